@@ -1,0 +1,179 @@
+/*
+ * libtide -- the per-denoise-step MoE expert layer of TIDE against a
+ * GPU-resident expert cache, the interval hit counter, and the top-B refresh
+ * with its host-to-device copy plan, for one AMD MI355X (gfx950).
+ *
+ * Paper vocabulary used below (Sec. 3.1, Sec. 3.3, Alg. 1):
+ *   E        routed experts per layer            k   experts per token
+ *   B        GPU expert budget (here: capacity)  tau refresh interval
+ *   H        hit counter: tokens each expert processed since the last refresh
+ *   E^GPU    resident set, E^CPU the rest (held by the caller in pinned host memory)
+ *
+ * Conventions
+ *   - Every entry point returns 0 (TIDE_OK) or a negative TIDE_E_* code;
+ *     tide_last_error() returns a text for the last failure on that context.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
+ *     addresses.  The library never frees caller memory and never keeps a
+ *     caller pointer beyond the call unless stated (registered expert blobs).
+ *   - bf16 = upper 16 bits of an IEEE fp32, carried as uint16_t.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls on one context must be issued in stream order on ONE stream: the
+ *     context owns a single workspace shared by all of its layers.
+ *   - Nothing is computed on the CPU: if no gfx950 device is usable,
+ *     tide_create fails with TIDE_E_HIP.
+ */
+#ifndef TIDE_H_
+#define TIDE_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TIDE_OK          0
+#define TIDE_E_INVAL    (-1)   /* null pointer, bad enum, bad layer index, size not supported   */
+#define TIDE_E_RANGE    (-2)   /* capacity / token count / expert id outside what ctx was built for */
+#define TIDE_E_STATE    (-3)   /* call order: experts not registered, placement not set, ...     */
+#define TIDE_E_HIP      (-4)   /* a HIP runtime call failed; text in tide_last_error             */
+#define TIDE_E_NOMEM    (-5)
+
+#define TIDE_GATING_SOFTMAX 0  /* softmax over E, weights renormalised over the k selected */
+#define TIDE_GATING_SIGMOID 1  /* sigmoid per expert, weights renormalised over the k selected */
+#define TIDE_BIAS_NONE   0
+#define TIDE_BIAS_LOGIT  1     /* bias added to the router logit before the gate */
+#define TIDE_BIAS_SELECT 2     /* bias added to the gate score for selection only, not to the weights */
+
+typedef struct tide_ctx tide_ctx;
+
+/* One token routed to an expert that is not resident ("miss", Alg. 1 token routing). */
+typedef struct { int32_t token; int32_t expert; float weight; } tide_miss;
+
+/* One host-to-device expert copy of a refresh (Alg. 1 refresh step). */
+typedef struct { int32_t expert; int32_t slot; uint64_t host_offset; uint64_t bytes; } tide_copy;
+
+typedef struct {
+    int32_t d;           /* hidden size; multiple of 64                                  */
+    int32_t n_experts;   /* E, 1..512                                                    */
+    int32_t top_k;       /* k, 1..min(E,32)                                              */
+    int32_t d_ff;        /* SwiGLU intermediate size I; multiple of 64                   */
+    int32_t n_shared;    /* 0 or 1 always-resident shared expert (weight 1, not counted) */
+    int32_t n_layers;    /* independent MoE layers, each with its own cache and counter  */
+    int32_t capacity;    /* cache slots per layer (the paper's B), 1..E                  */
+    int32_t max_tokens;  /* largest n_tokens a step may carry                            */
+    int32_t gating;      /* TIDE_GATING_*                                                */
+    int32_t bias_mode;   /* TIDE_BIAS_*                                                  */
+} tide_config;
+
+/* ---- set-up --------------------------------------------------------------------- */
+
+/* Allocates the context on the current HIP device: per layer `capacity` weight slots,
+ * the hit counter H[E] (zero), the placement tables (all slots empty), and one
+ * workspace sized by max_tokens.  Creates one side stream for refresh copies. */
+int tide_create(const tide_config* cfg, tide_ctx** out);
+int tide_destroy(tide_ctx* ctx);
+/* Text of the last error on ctx (ctx == NULL: last error of a failed tide_create). */
+const char* tide_last_error(const tide_ctx* ctx);
+
+/* Bytes of one packed expert blob: 3 * d * d_ff * 2. */
+uint64_t tide_expert_blob_bytes(const tide_config* cfg);
+
+/* Host-side packing of one expert e(x) = Wd (silu(Wg x) * (Wu x)) (Alg. 1, "output = e(x)")
+ * from row-major bf16 matrices wg[d_ff][d], wu[d_ff][d], wd[d][d_ff] (host) into the
+ * library's streaming layout at blob_host (host, tide_expert_blob_bytes bytes).
+ * The blob is what lives in pinned host memory and in a cache slot, byte for byte. */
+int tide_pack_expert(const tide_config* cfg, const uint16_t* wg_host, const uint16_t* wu_host,
+                     const uint16_t* wd_host, void* blob_host);
+
+/* Registers the host master copy of a layer's E packed blobs: expert e starts at
+ * host_blobs + e * blob_stride.  The memory must be pinned (hipHostMalloc / torch
+ * pin_memory) and stay valid and unchanged until tide_destroy: refresh copies read it
+ * asynchronously.  Borrowed, never written, never freed. */
+int tide_register_experts(tide_ctx* ctx, int layer, const void* host_blobs, uint64_t blob_stride);
+
+/* Copies one packed blob (host) into the layer's always-resident shared-expert slot.
+ * Synchronous.  Required before the first step when n_shared == 1. */
+int tide_set_shared(tide_ctx* ctx, int layer, const void* blob_host);
+
+/* Initial placement (the cold start E^GPU): expert experts_host[s] goes to slot s for
+ * s < n (n <= capacity; -1 leaves a slot empty; remaining slots are emptied).
+ * Copies from the registered host blobs, synchronous.  Does not touch H. */
+int tide_set_resident(tide_ctx* ctx, int layer, const int32_t* experts_host, int n);
+
+/* ---- the per-step hot path -------------------------------------------------------- */
+
+/* One MoE layer at one denoise step over n_tokens tokens (Alg. 1, token routing):
+ *   router logits z = X W_r^T (fp32), gate, top-k, routing weights renormalised over
+ *   the k selected; H[e] += tokens routed to e (all experts, resident or not);
+ *   out[n] = shared(x_n) + sum over the token's selected experts that are RESIDENT of
+ *            w * e(x_n)                      (bf16 operands, fp32 accumulation);
+ *   every selected expert that is not resident is appended to the miss list as
+ *   (token, expert, weight), ordered by token then by rank in the token's top-k list.
+ * Adding sum over the miss list of weight * e(x_token) to out reproduces the full MoE
+ * output: placement never changes what is computed (Sec. 3.3 "Lossless Inference").
+ *
+ *   hidden_dev      bf16 [n_tokens][d] row-major                               (in)
+ *   router_w_dev    fp32 [E][d] row-major                                      (in)
+ *   router_bias_dev fp32 [E], or NULL when bias_mode == TIDE_BIAS_NONE         (in)
+ *   out_dev         fp32 [n_tokens][d]                                         (out)
+ *   miss_dev        tide_miss[miss_cap], n_miss_dev int32[1]                   (out)
+ *                   *n_miss_dev is always the full number of misses; only the first
+ *                   miss_cap entries are written (miss_cap >= n_tokens*k never truncates)
+ *   topk_idx_dev    int32 [n_tokens][k], topk_w_dev fp32 [n_tokens][k]; may be NULL (out)
+ * Asynchronous on hip_stream.  If a refresh issued copies for this layer, the expert
+ * GEMMs of this call wait for them on the device; routing does not.
+ * n_tokens == 0 is allowed (writes *n_miss_dev = 0). */
+int tide_moe_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens,
+                  const float* router_w_dev, const float* router_bias_dev,
+                  float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
+                  int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream);
+
+/* The same step for token states that already carry their expert selections
+ * (Alg. 1 takes X = {(x, E_x)} as given): topk_idx_dev / topk_w_dev are INPUTS
+ * (expert ids must be in [0,E) and distinct per token).  Counts, split, expert
+ * evaluation, combine and miss list exactly as tide_moe_step. */
+int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens,
+                         const int32_t* topk_idx_dev, const float* topk_w_dev,
+                         float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
+                         void* hip_stream);
+
+/* ---- interval statistics and refresh ---------------------------------------------- */
+
+/* Copies the layer's hit counter H[E] (tokens per expert since the last reset; Fig. 1
+ * caption, Sec. 3.3 "global hit counter") to counts_host after all work queued on
+ * hip_stream; reset != 0 zeroes it afterwards.  Synchronises hip_stream. */
+int tide_interval_stats(tide_ctx* ctx, int layer, int32_t* counts_host, int reset, void* hip_stream);
+
+/* Refresh step (Alg. 1; Sec. 3.3: the GPU set becomes the current top-B by hits).
+ * Experts are ranked by (hits descending, currently resident first, lower id first);
+ * the first `capacity` form the new resident set.  Leaving experts, ordered by
+ * (hits ascending, id), free their slots; entering experts, ordered by (hits descending,
+ * id), take the freed slots in that order and then empty slots in ascending order.
+ * One copy per entering expert is queued on the context's side stream from the
+ * registered host blobs; eviction moves no bytes.  The tables change at once; the next
+ * step's expert GEMMs wait for the copies.
+ *   counts_host     int32 [E] to rank by, or NULL = the layer's own H               (in)
+ *   capacity        size of the new resident set, 0..ctx capacity                   (in)
+ *   reset_counts    != 0: zero H afterwards (per-interval counting)                 (in)
+ *   resident_out    int32 [ctx capacity]: expert in each slot after the refresh, -1 = empty (host, out, may be NULL)
+ *   plan_out        tide_copy [ctx capacity] (host, out, may be NULL), *n_copies_out entries
+ * Synchronises hip_stream (the plan is needed on the host to queue the copies). */
+int tide_refresh(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,
+                 int32_t* resident_out, tide_copy* plan_out, int* n_copies_out, void* hip_stream);
+
+/* Blocks until every refresh copy queued so far for the layer has landed. */
+int tide_wait_refresh(tide_ctx* ctx, int layer);
+
+/* Snapshot hooks (tests): placement table slot_of[E] (-1 = not resident) to host;
+ * raw bytes of a cache slot (slot == capacity: the shared expert) to host. */
+int tide_get_table(tide_ctx* ctx, int layer, int32_t* slot_of_host, void* hip_stream);
+int tide_read_slot(tide_ctx* ctx, int layer, int slot, void* blob_host);
+
+/* Per-call timing of the refresh copies of the LAST tide_refresh on the layer, in
+ * milliseconds between the first copy starting and the last one landing; waits for them. */
+int tide_refresh_copy_ms(tide_ctx* ctx, int layer, float* ms_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TIDE_H_ */

@@ -1,0 +1,196 @@
+"""ctypes binding of libtide's C ABI (include/tide.h): argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels; torch is used to
+own device memory and to supply the stream.  There is no CPU fallback: if the
+shared library is missing the import of this module raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtide.so")
+
+TIDE_OK, TIDE_E_INVAL, TIDE_E_RANGE, TIDE_E_STATE, TIDE_E_HIP, TIDE_E_NOMEM = 0, -1, -2, -3, -4, -5
+TIDE_GATING_SOFTMAX, TIDE_GATING_SIGMOID = 0, 1
+TIDE_BIAS_NONE, TIDE_BIAS_LOGIT, TIDE_BIAS_SELECT = 0, 1, 2
+
+EXPORTS = [
+    "tide_create", "tide_destroy", "tide_last_error", "tide_expert_blob_bytes", "tide_pack_expert",
+    "tide_register_experts", "tide_set_shared", "tide_set_resident", "tide_moe_step", "tide_moe_step_routed",
+    "tide_interval_stats", "tide_refresh", "tide_wait_refresh", "tide_get_table", "tide_read_slot",
+    "tide_refresh_copy_ms",
+]
+
+
+class tide_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("d", "n_experts", "top_k", "d_ff", "n_shared", "n_layers", "capacity",
+                                          "max_tokens", "gating", "bias_mode")]
+
+
+class tide_miss(C.Structure):
+    _fields_ = [("token", C.c_int32), ("expert", C.c_int32), ("weight", C.c_float)]
+
+
+class tide_copy(C.Structure):
+    _fields_ = [("expert", C.c_int32), ("slot", C.c_int32), ("host_offset", C.c_uint64), ("bytes", C.c_uint64)]
+
+
+MISS_DTYPE = np.dtype([("token", np.int32), ("expert", np.int32), ("weight", np.float32)])
+
+
+class TideError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("libtide error %d: %s" % (code, text))
+        self.code = code
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libtide.so is not built (%s); run `python -m paper_2605_20179_amd.build`. "
+                          "There is no fallback path." % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    vp, i32p, f32p = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float)
+    cfgp = C.POINTER(tide_config)
+    lib.tide_create.argtypes = [cfgp, C.POINTER(vp)]
+    lib.tide_destroy.argtypes = [vp]
+    lib.tide_last_error.argtypes = [vp]
+    lib.tide_last_error.restype = C.c_char_p
+    lib.tide_expert_blob_bytes.argtypes = [cfgp]
+    lib.tide_expert_blob_bytes.restype = C.c_uint64
+    lib.tide_pack_expert.argtypes = [cfgp, vp, vp, vp, vp]
+    lib.tide_register_experts.argtypes = [vp, C.c_int, vp, C.c_uint64]
+    lib.tide_set_shared.argtypes = [vp, C.c_int, vp]
+    lib.tide_set_resident.argtypes = [vp, C.c_int, vp, C.c_int]
+    lib.tide_moe_step.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp, vp, vp]
+    lib.tide_moe_step_routed.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp]
+    lib.tide_interval_stats.argtypes = [vp, C.c_int, vp, C.c_int, vp]
+    lib.tide_refresh.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, vp, vp, C.POINTER(C.c_int), vp]
+    lib.tide_wait_refresh.argtypes = [vp, C.c_int]
+    lib.tide_get_table.argtypes = [vp, C.c_int, vp, vp]
+    lib.tide_read_slot.argtypes = [vp, C.c_int, C.c_int, vp]
+    lib.tide_refresh_copy_ms.argtypes = [vp, C.c_int, C.POINTER(C.c_float)]
+    for name in EXPORTS:
+        if name not in ("tide_last_error", "tide_expert_blob_bytes"):
+            getattr(lib, name).restype = C.c_int
+    return lib
+
+
+lib = _load()
+
+
+def make_config(d, n_experts, top_k, d_ff, n_shared, n_layers, capacity, max_tokens, gating, bias_mode) -> tide_config:
+    return tide_config(d, n_experts, top_k, d_ff, n_shared, n_layers, capacity, max_tokens, gating, bias_mode)
+
+
+def _check(rc: int, ctx) -> None:
+    if rc != TIDE_OK:
+        raise TideError(rc, lib.tide_last_error(ctx).decode())
+
+
+def _ptr(t) -> Optional[int]:
+    """Address of a torch tensor, numpy array or None."""
+    if t is None:
+        return None
+    if isinstance(t, np.ndarray):
+        assert t.flags["C_CONTIGUOUS"]
+        return t.ctypes.data
+    assert t.is_contiguous()
+    return t.data_ptr()
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        return None
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def tide_expert_blob_bytes(cfg: tide_config) -> int:
+    return int(lib.tide_expert_blob_bytes(C.byref(cfg)))
+
+
+def tide_pack_expert(cfg: tide_config, wg: np.ndarray, wu: np.ndarray, wd: np.ndarray, blob) -> None:
+    """wg/wu [d_ff,d], wd [d,d_ff] uint16 (bf16 bits) host arrays -> packed blob (host uint8 buffer)."""
+    assert wg.dtype == np.uint16 and wg.shape == (cfg.d_ff, cfg.d) and wu.shape == wg.shape
+    assert wd.dtype == np.uint16 and wd.shape == (cfg.d, cfg.d_ff)
+    _check(lib.tide_pack_expert(C.byref(cfg), _ptr(np.ascontiguousarray(wg)), _ptr(np.ascontiguousarray(wu)),
+                                _ptr(np.ascontiguousarray(wd)), _ptr(blob)), None)
+
+
+def tide_create(cfg: tide_config) -> int:
+    h = C.c_void_p()
+    rc = lib.tide_create(C.byref(cfg), C.byref(h))
+    _check(rc, None)
+    return h.value
+
+
+def tide_destroy(ctx: int) -> None:
+    lib.tide_destroy(ctx)
+
+
+def tide_register_experts(ctx, layer: int, host_blobs, blob_stride: int) -> None:
+    _check(lib.tide_register_experts(ctx, layer, _ptr(host_blobs), blob_stride), ctx)
+
+
+def tide_set_shared(ctx, layer: int, blob_host) -> None:
+    _check(lib.tide_set_shared(ctx, layer, _ptr(blob_host)), ctx)
+
+
+def tide_set_resident(ctx, layer: int, experts: Sequence[int]) -> None:
+    a = np.ascontiguousarray(np.asarray(experts, dtype=np.int32))
+    _check(lib.tide_set_resident(ctx, layer, _ptr(a), len(a)), ctx)
+
+
+def tide_moe_step(ctx, layer: int, hidden, n_tokens: int, router_w, router_bias, out, miss, miss_cap: int, n_miss,
+                  topk_idx=None, topk_w=None, stream=None) -> None:
+    _check(lib.tide_moe_step(ctx, layer, _ptr(hidden), n_tokens, _ptr(router_w), _ptr(router_bias), _ptr(out),
+                             _ptr(miss), miss_cap, _ptr(n_miss), _ptr(topk_idx), _ptr(topk_w), _stream_ptr(stream)), ctx)
+
+
+def tide_moe_step_routed(ctx, layer: int, hidden, n_tokens: int, topk_idx, topk_w, out, miss, miss_cap: int, n_miss,
+                         stream=None) -> None:
+    _check(lib.tide_moe_step_routed(ctx, layer, _ptr(hidden), n_tokens, _ptr(topk_idx), _ptr(topk_w), _ptr(out),
+                                    _ptr(miss), miss_cap, _ptr(n_miss), _stream_ptr(stream)), ctx)
+
+
+def tide_interval_stats(ctx, layer: int, n_experts: int, reset: bool, stream=None) -> np.ndarray:
+    counts = np.zeros(n_experts, dtype=np.int32)
+    _check(lib.tide_interval_stats(ctx, layer, _ptr(counts), int(reset), _stream_ptr(stream)), ctx)
+    return counts
+
+
+def tide_refresh(ctx, layer: int, ctx_capacity: int, capacity: int, counts: Optional[np.ndarray] = None,
+                 reset_counts: bool = True, stream=None):
+    """Returns (expert_in_slot[ctx_capacity] int32, plan = list of (expert, slot, host_offset, bytes))."""
+    resident = np.full(ctx_capacity, -1, dtype=np.int32)
+    plan = (tide_copy * max(ctx_capacity, 1))()
+    n = C.c_int(0)
+    cnt = None if counts is None else np.ascontiguousarray(np.asarray(counts, dtype=np.int32))
+    _check(lib.tide_refresh(ctx, layer, _ptr(cnt), capacity, int(reset_counts), _ptr(resident),
+                            C.cast(plan, C.c_void_p), C.byref(n), _stream_ptr(stream)), ctx)
+    return resident, [(plan[i].expert, plan[i].slot, plan[i].host_offset, plan[i].bytes) for i in range(n.value)]
+
+
+def tide_wait_refresh(ctx, layer: int) -> None:
+    _check(lib.tide_wait_refresh(ctx, layer), ctx)
+
+
+def tide_refresh_copy_ms(ctx, layer: int) -> float:
+    ms = C.c_float(0)
+    _check(lib.tide_refresh_copy_ms(ctx, layer, C.byref(ms)), ctx)
+    return float(ms.value)
+
+
+def tide_get_table(ctx, layer: int, n_experts: int, stream=None) -> np.ndarray:
+    t = np.zeros(n_experts, dtype=np.int32)
+    _check(lib.tide_get_table(ctx, layer, _ptr(t), _stream_ptr(stream)), ctx)
+    return t
+
+
+def tide_read_slot(ctx, layer: int, slot: int, blob_bytes: int) -> np.ndarray:
+    b = np.zeros(blob_bytes, dtype=np.uint8)
+    _check(lib.tide_read_slot(ctx, layer, slot, _ptr(b)), ctx)
+    return b

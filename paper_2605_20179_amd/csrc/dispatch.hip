@@ -1,0 +1,160 @@
+// Hit/miss split of the step's (token, expert) pairs against the resident table,
+// canonical miss list, slot-sorted row lists and grouped-GEMM work items
+// (Alg. 1 token routing: pairs whose expert is in E^GPU are computed here, pairs whose
+// expert is in E^CPU are handed back).  No atomics: every list is produced by an
+// ordered block-level compaction, so results are identical from run to run.
+#include "tide_internal.h"
+
+namespace tide {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// Rank of this thread's flag among the block's set flags in thread order, and their total.
+__device__ inline int block_rank(bool flag, int& total, int* lds4) {
+    const unsigned long long b = __ballot(flag);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int r = __popcll(b & ((1ull << lane) - 1ull));
+    if (lane == 0) lds4[wv] = __popcll(b);
+    __syncthreads();
+    int base = 0;
+    total = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) {
+        const int c = lds4[w];
+        if (w < wv) base += c;
+        total += c;
+    }
+    __syncthreads();
+    return base + r;
+}
+
+__device__ inline int block_sum(int v, int* lds4) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int t = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) t += lds4[w];
+    __syncthreads();
+    return t;
+}
+
+// grid = capacity + 2 blocks: one per cache slot, one for the shared expert, one for the misses.
+__global__ __launch_bounds__(kThreads) void dispatch_kernel(
+    const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w, int n_tokens, int k, int capacity,
+    int n_shared, int n_experts, const int32_t* __restrict__ slot_of, const int32_t* __restrict__ expert_in_slot,
+    const int32_t* __restrict__ hist_step, int32_t* __restrict__ row_token, int32_t* __restrict__ pair_row,
+    int32_t* __restrict__ slot_off, Task* __restrict__ tasks, int32_t* __restrict__ n_tasks,
+    tide_miss* __restrict__ miss, int miss_cap, int32_t* __restrict__ n_miss) {
+    __shared__ int lds4[kThreads / 64];
+    const int s = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int n_pairs = n_tokens * k;
+
+    if (s == capacity + 1) {
+        // misses, ordered by token then rank
+        int running = 0;
+        for (int base = 0; base < n_pairs; base += kThreads) {
+            const int p = base + tid;
+            int e = -1;
+            bool flag = false;
+            if (p < n_pairs) {
+                e = topk_idx[p];
+                // an id outside [0,E) can only come from caller-supplied routing: report it as a miss
+                flag = (e < 0 || e >= n_experts) ? true : slot_of[e] < 0;
+            }
+            int total;
+            const int r = block_rank(flag, total, lds4);
+            if (flag) {
+                pair_row[p] = -1;
+                const int pos = running + r;
+                if (pos < miss_cap) {
+                    tide_miss m;
+                    m.token = p / k;
+                    m.expert = e;
+                    m.weight = topk_w[p];
+                    miss[pos] = m;
+                }
+            }
+            running += total;
+        }
+        if (tid == 0) *n_miss = running;
+        return;
+    }
+
+    // rows and work items that precede this slot
+    const int upto = s < capacity ? s : capacity;
+    int rows_before = 0, tasks_before = 0;
+    for (int q = tid; q < upto; q += kThreads) {
+        const int e = expert_in_slot[q];
+        const int m = e >= 0 ? hist_step[e] : 0;
+        rows_before += m;
+        tasks_before += (m + kRowsPerTask - 1) / kRowsPerTask;
+    }
+    rows_before = block_sum(rows_before, lds4);
+    tasks_before = block_sum(tasks_before, lds4);
+
+    if (s == capacity) {
+        // shared expert: every token, in token order
+        const int m = n_shared ? n_tokens : 0;
+        for (int n = tid; n < m; n += kThreads) row_token[rows_before + n] = n;
+        const int nt = (m + kRowsPerTask - 1) / kRowsPerTask;
+        for (int c = tid; c < nt; c += kThreads) {
+            Task t;
+            t.slot = capacity;
+            t.row0 = rows_before + c * kRowsPerTask;
+            t.nrows = min(kRowsPerTask, m - c * kRowsPerTask);
+            t.pad = 0;
+            tasks[tasks_before + c] = t;
+        }
+        if (tid == 0) {
+            slot_off[capacity] = rows_before;
+            slot_off[capacity + 1] = rows_before + m;
+            *n_tasks = tasks_before + nt;
+        }
+        return;
+    }
+
+    const int e = expert_in_slot[s];
+    const int m = e >= 0 ? hist_step[e] : 0;
+    if (tid == 0) slot_off[s] = rows_before;
+    if (m == 0) return;
+    const int nt = (m + kRowsPerTask - 1) / kRowsPerTask;
+    for (int c = tid; c < nt; c += kThreads) {
+        Task t;
+        t.slot = s;
+        t.row0 = rows_before + c * kRowsPerTask;
+        t.nrows = min(kRowsPerTask, m - c * kRowsPerTask);
+        t.pad = 0;
+        tasks[tasks_before + c] = t;
+    }
+    int running = 0;
+    for (int base = 0; base < n_pairs; base += kThreads) {
+        const int p = base + tid;
+        const bool flag = p < n_pairs && topk_idx[p] == e;
+        int total;
+        const int r = block_rank(flag, total, lds4);
+        if (flag) {
+            const int row = rows_before + running + r;
+            row_token[row] = p / k;
+            pair_row[p] = row;
+        }
+        running += total;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_dispatch(const Shape& s, const LayerTables& t, const Workspace& w, const int32_t* topk_idx,
+                           const float* topk_w, int n_tokens, tide_miss* miss, int miss_cap, int32_t* n_miss,
+                           hipStream_t stream) {
+    hipLaunchKernelGGL(dispatch_kernel, dim3(s.capacity + 2), dim3(kThreads), 0, stream, topk_idx, topk_w,
+                       n_tokens, s.k, s.capacity, s.n_shared, s.E, t.slot_of, t.expert_in_slot, w.hist_step,
+                       w.row_token, w.pair_row, w.slot_off, w.tasks, w.n_tasks, miss, miss_cap, n_miss);
+    return hipGetLastError();
+}
+
+}  // namespace tide

@@ -1,0 +1,426 @@
+// C-ABI of libtide: context, expert packing, placement, the per-step call sequence,
+// interval statistics and the refresh with its side-stream host-to-device copies.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "tide_internal.h"
+
+using namespace tide;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+struct Layer {
+    LayerTables t{};
+    uint16_t* slots_owned = nullptr;     // capacity+1 blobs
+    const uint8_t* host_blobs = nullptr;
+    uint64_t host_stride = 0;
+    bool shared_set = false;
+    bool placed = false;
+    hipEvent_t copies_begin = nullptr, copies_done = nullptr;
+    bool copies_pending = false;         // a step must wait on copies_done before its GEMMs
+    bool copies_recorded = false;
+    RefreshOut* plan = nullptr;          // pinned, device-visible
+};
+
+}  // namespace
+
+struct tide_ctx {
+    tide_config cfg{};
+    Shape shape{};
+    int device = 0;
+    Workspace ws{};
+    std::vector<void*> ws_allocs;
+    std::vector<Layer> layers;
+    hipStream_t side = nullptr;
+    hipEvent_t compute_mark = nullptr;
+    int max_rows = 0, max_tasks = 0;
+    std::string err;
+};
+
+namespace {
+
+int fail(tide_ctx* ctx, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf; else g_create_error = buf;
+    return code;
+}
+
+#define TIDE_HIP(ctx, call)                                                                          \
+    do {                                                                                             \
+        hipError_t e_ = (call);                                                                      \
+        if (e_ != hipSuccess) return fail(ctx, TIDE_E_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+int check_cfg(const tide_config* c) {
+    if (!c) return fail(nullptr, TIDE_E_INVAL, "config is null");
+    if (c->d <= 0 || c->d % 64) return fail(nullptr, TIDE_E_INVAL, "d must be a positive multiple of 64");
+    if (c->d_ff <= 0 || c->d_ff % 64) return fail(nullptr, TIDE_E_INVAL, "d_ff must be a positive multiple of 64");
+    if (c->n_experts < 1 || c->n_experts > kMaxExperts) return fail(nullptr, TIDE_E_INVAL, "n_experts must be 1..%d", kMaxExperts);
+    if (c->top_k < 1 || c->top_k > kMaxTopK || c->top_k > c->n_experts) return fail(nullptr, TIDE_E_INVAL, "top_k must be 1..min(E,%d)", kMaxTopK);
+    if (c->n_shared < 0 || c->n_shared > 1) return fail(nullptr, TIDE_E_INVAL, "n_shared must be 0 or 1");
+    if (c->n_layers < 1) return fail(nullptr, TIDE_E_INVAL, "n_layers must be >= 1");
+    if (c->capacity < 1 || c->capacity > c->n_experts) return fail(nullptr, TIDE_E_RANGE, "capacity must be 1..E");
+    if (c->max_tokens < 1 || (int64_t)c->max_tokens * c->top_k > (1 << 26)) return fail(nullptr, TIDE_E_RANGE, "max_tokens out of range");
+    if (c->gating != TIDE_GATING_SOFTMAX && c->gating != TIDE_GATING_SIGMOID) return fail(nullptr, TIDE_E_INVAL, "bad gating");
+    if (c->bias_mode < TIDE_BIAS_NONE || c->bias_mode > TIDE_BIAS_SELECT) return fail(nullptr, TIDE_E_INVAL, "bad bias_mode");
+    return TIDE_OK;
+}
+
+template <typename T>
+int ws_alloc(tide_ctx* ctx, T** p, size_t count) {
+    void* q = nullptr;
+    hipError_t e = hipMalloc(&q, count * sizeof(T) + 256);
+    if (e != hipSuccess) return fail(ctx, TIDE_E_NOMEM, "hipMalloc(%zu bytes): %s", count * sizeof(T), hipGetErrorString(e));
+    ctx->ws_allocs.push_back(q);
+    *p = static_cast<T*>(q);
+    return TIDE_OK;
+}
+
+int layer_ok(tide_ctx* ctx, int layer) {
+    if (!ctx) return TIDE_E_INVAL;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, TIDE_E_INVAL, "layer %d outside 0..%d", layer, ctx->cfg.n_layers - 1);
+    return TIDE_OK;
+}
+
+uint16_t* slot_ptr(tide_ctx* ctx, Layer& L, int slot) { return L.slots_owned + (int64_t)slot * ctx->shape.blob_elems; }
+
+void pack_matrix(const uint16_t* src, int rows, int cols, uint16_t* dst) {
+    // tile (rt, kc) of 16 rows x 32 columns -> 512 contiguous elements, lane-major:
+    // lane l holds row rt*16 + l%16, columns kc*32 + (l/16)*8 .. +7
+    const int kchunks = cols / 32;
+    for (int rt = 0; rt < rows / 16; ++rt)
+        for (int kc = 0; kc < kchunks; ++kc) {
+            uint16_t* tile = dst + ((int64_t)rt * kchunks + kc) * 512;
+            for (int l = 0; l < 64; ++l)
+                memcpy(tile + l * 8, src + (int64_t)(rt * 16 + (l & 15)) * cols + kc * 32 + (l >> 4) * 8, 16);
+        }
+}
+
+int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const int32_t* idx,
+                const float* w, float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
+                hipStream_t stream) {
+    Layer& L = ctx->layers[layer];
+    TIDE_HIP(ctx, launch_dispatch(ctx->shape, L.t, ctx->ws, idx, w, n_tokens, miss_dev, miss_cap, n_miss_dev, stream));
+    if (L.copies_pending) {
+        TIDE_HIP(ctx, hipStreamWaitEvent(stream, L.copies_done, 0));
+        L.copies_pending = false;
+    }
+    const int rows = n_tokens * ctx->cfg.top_k + (ctx->cfg.n_shared ? n_tokens : 0);
+    const int max_tasks = ctx->cfg.capacity + 1 + rows / kRowsPerTask + 1;
+    TIDE_HIP(ctx, launch_expert_gemms(ctx->shape, L.t, ctx->ws, static_cast<const uint16_t*>(hidden_dev), n_tokens,
+                                      max_tasks, stream));
+    TIDE_HIP(ctx, launch_combine(ctx->shape, ctx->ws, w, n_tokens, out_dev, stream));
+    return TIDE_OK;
+}
+
+int step_args_ok(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, float* out_dev,
+                 tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    if (n_tokens < 0 || n_tokens > ctx->cfg.max_tokens) return fail(ctx, TIDE_E_RANGE, "n_tokens %d outside 0..max_tokens=%d", n_tokens, ctx->cfg.max_tokens);
+    if (!n_miss_dev) return fail(ctx, TIDE_E_INVAL, "n_miss_dev is null");
+    if (miss_cap < 0 || (miss_cap > 0 && !miss_dev)) return fail(ctx, TIDE_E_INVAL, "miss_dev is null with miss_cap > 0");
+    if (n_tokens > 0 && (!hidden_dev || !out_dev)) return fail(ctx, TIDE_E_INVAL, "hidden_dev / out_dev is null");
+    if (((uintptr_t)hidden_dev & 15) || ((uintptr_t)out_dev & 15)) return fail(ctx, TIDE_E_INVAL, "hidden_dev / out_dev must be 16-byte aligned");
+    Layer& L = ctx->layers[layer];
+    if (!L.placed) return fail(ctx, TIDE_E_STATE, "layer %d has no placement: call tide_set_resident first", layer);
+    if (ctx->cfg.n_shared && !L.shared_set) return fail(ctx, TIDE_E_STATE, "layer %d: shared expert not set", layer);
+    return TIDE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* tide_last_error(const tide_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+uint64_t tide_expert_blob_bytes(const tide_config* cfg) {
+    if (!cfg) return 0;
+    return 3ull * (uint64_t)cfg->d * (uint64_t)cfg->d_ff * 2ull;
+}
+
+int tide_pack_expert(const tide_config* cfg, const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, void* blob) {
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    if (!wg || !wu || !wd || !blob) return fail(nullptr, TIDE_E_INVAL, "null matrix or blob");
+    uint16_t* b = static_cast<uint16_t*>(blob);
+    const int64_t n = (int64_t)cfg->d * cfg->d_ff;
+    pack_matrix(wg, cfg->d_ff, cfg->d, b);
+    pack_matrix(wu, cfg->d_ff, cfg->d, b + n);
+    pack_matrix(wd, cfg->d, cfg->d_ff, b + 2 * n);
+    return TIDE_OK;
+}
+
+int tide_create(const tide_config* cfg, tide_ctx** out) {
+    if (!out) return fail(nullptr, TIDE_E_INVAL, "out is null");
+    *out = nullptr;
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess || ndev < 1)
+        return fail(nullptr, TIDE_E_HIP, "no HIP device: %s", e == hipSuccess ? "device count is 0" : hipGetErrorString(e));
+    tide_ctx* ctx = new (std::nothrow) tide_ctx();
+    if (!ctx) return fail(nullptr, TIDE_E_NOMEM, "out of host memory");
+    ctx->cfg = *cfg;
+    Shape& s = ctx->shape;
+    s.d = cfg->d; s.E = cfg->n_experts; s.k = cfg->top_k; s.I = cfg->d_ff; s.n_shared = cfg->n_shared;
+    s.capacity = cfg->capacity; s.gating = cfg->gating; s.bias_mode = cfg->bias_mode;
+    s.blob_elems = 3ll * cfg->d * cfg->d_ff;
+    auto bail = [&](int code) { g_create_error = ctx->err; tide_destroy(ctx); return code; };
+    if (hipGetDevice(&ctx->device) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "hipGetDevice failed"));
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, ctx->device) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "hipGetDeviceProperties failed"));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return bail(fail(ctx, TIDE_E_HIP, "device is %s; libtide is built for gfx950 only", prop.gcnArchName));
+
+    const int64_t N = cfg->max_tokens, P = N * cfg->top_k;
+    ctx->max_rows = (int)(P + (cfg->n_shared ? N : 0));
+    ctx->max_tasks = cfg->capacity + 1 + ctx->max_rows / kRowsPerTask + 1;
+    Workspace& w = ctx->ws;
+    if ((rc = ws_alloc(ctx, &w.logits, N * s.E)) || (rc = ws_alloc(ctx, &w.topk_idx, P)) ||
+        (rc = ws_alloc(ctx, &w.topk_w, P)) || (rc = ws_alloc(ctx, &w.hist_step, s.E)) ||
+        (rc = ws_alloc(ctx, &w.row_token, ctx->max_rows)) || (rc = ws_alloc(ctx, &w.pair_row, P)) ||
+        (rc = ws_alloc(ctx, &w.slot_off, s.capacity + 2)) || (rc = ws_alloc(ctx, &w.tasks, ctx->max_tasks)) ||
+        (rc = ws_alloc(ctx, &w.n_tasks, 1)) || (rc = ws_alloc(ctx, &w.act, (int64_t)ctx->max_rows * s.I)) ||
+        (rc = ws_alloc(ctx, &w.y, (int64_t)ctx->max_rows * s.d)) || (rc = ws_alloc(ctx, &w.counts_tmp, s.E)))
+        return bail(rc);
+    if (hipMemset(w.n_tasks, 0, sizeof(int32_t)) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "hipMemset failed"));
+
+    if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "side stream"));
+    if (hipEventCreateWithFlags(&ctx->compute_mark, hipEventDisableTiming) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "event"));
+
+    ctx->layers.resize(cfg->n_layers);
+    for (Layer& L : ctx->layers) {
+        int32_t *hits, *slot_of, *eis;
+        if ((rc = ws_alloc(ctx, &hits, s.E)) || (rc = ws_alloc(ctx, &slot_of, s.E)) || (rc = ws_alloc(ctx, &eis, s.capacity)))
+            return bail(rc);
+        if (hipMemset(hits, 0, s.E * 4) != hipSuccess || hipMemset(slot_of, 0xFF, s.E * 4) != hipSuccess ||
+            hipMemset(eis, 0xFF, s.capacity * 4) != hipSuccess)
+            return bail(fail(ctx, TIDE_E_HIP, "hipMemset failed"));
+        if ((rc = ws_alloc(ctx, &L.slots_owned, (int64_t)(s.capacity + 1) * s.blob_elems))) return bail(rc);
+        L.t.hits = hits; L.t.slot_of = slot_of; L.t.expert_in_slot = eis; L.t.slots = L.slots_owned;
+        if (hipEventCreate(&L.copies_begin) != hipSuccess || hipEventCreate(&L.copies_done) != hipSuccess)
+            return bail(fail(ctx, TIDE_E_HIP, "event"));
+        void* plan = nullptr;
+        if (hipHostMalloc(&plan, sizeof(RefreshOut), hipHostMallocDefault) != hipSuccess) return bail(fail(ctx, TIDE_E_NOMEM, "pinned plan buffer"));
+        L.plan = static_cast<RefreshOut*>(plan);
+        memset(L.plan, 0, sizeof(RefreshOut));
+    }
+    if (hipDeviceSynchronize() != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "synchronize after set-up failed"));
+    *out = ctx;
+    return TIDE_OK;
+}
+
+int tide_destroy(tide_ctx* ctx) {
+    if (!ctx) return TIDE_OK;
+    (void)hipDeviceSynchronize();
+    for (Layer& L : ctx->layers) {
+        if (L.copies_begin) (void)hipEventDestroy(L.copies_begin);
+        if (L.copies_done) (void)hipEventDestroy(L.copies_done);
+        if (L.plan) (void)hipHostFree(L.plan);
+    }
+    if (ctx->compute_mark) (void)hipEventDestroy(ctx->compute_mark);
+    if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    for (void* p : ctx->ws_allocs) (void)hipFree(p);
+    delete ctx;
+    return TIDE_OK;
+}
+
+int tide_register_experts(tide_ctx* ctx, int layer, const void* host_blobs, uint64_t blob_stride) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    if (!host_blobs) return fail(ctx, TIDE_E_INVAL, "host_blobs is null");
+    if (blob_stride < tide_expert_blob_bytes(&ctx->cfg) || (blob_stride & 15) || ((uintptr_t)host_blobs & 15))
+        return fail(ctx, TIDE_E_INVAL, "blob_stride must be >= blob bytes; base and stride 16-byte aligned");
+    ctx->layers[layer].host_blobs = static_cast<const uint8_t*>(host_blobs);
+    ctx->layers[layer].host_stride = blob_stride;
+    return TIDE_OK;
+}
+
+int tide_set_shared(tide_ctx* ctx, int layer, const void* blob_host) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    if (!ctx->cfg.n_shared) return fail(ctx, TIDE_E_STATE, "context was created with n_shared = 0");
+    if (!blob_host) return fail(ctx, TIDE_E_INVAL, "blob_host is null");
+    Layer& L = ctx->layers[layer];
+    TIDE_HIP(ctx, hipDeviceSynchronize());
+    TIDE_HIP(ctx, hipMemcpy(slot_ptr(ctx, L, ctx->cfg.capacity), blob_host, tide_expert_blob_bytes(&ctx->cfg), hipMemcpyHostToDevice));
+    L.shared_set = true;
+    return TIDE_OK;
+}
+
+int tide_set_resident(tide_ctx* ctx, int layer, const int32_t* experts, int n) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    const int C = ctx->cfg.capacity, E = ctx->cfg.n_experts;
+    if (n < 0 || n > C) return fail(ctx, TIDE_E_RANGE, "n = %d outside 0..capacity", n);
+    if (n > 0 && !experts) return fail(ctx, TIDE_E_INVAL, "experts is null");
+    Layer& L = ctx->layers[layer];
+    if (!L.host_blobs) return fail(ctx, TIDE_E_STATE, "layer %d: experts not registered", layer);
+    std::vector<int32_t> slot_of(E, -1), eis(C, -1);
+    for (int s = 0; s < n; ++s) {
+        const int e = experts[s];
+        if (e == -1) continue;
+        if (e < 0 || e >= E) return fail(ctx, TIDE_E_RANGE, "expert id %d outside 0..E-1", e);
+        if (slot_of[e] >= 0) return fail(ctx, TIDE_E_INVAL, "expert %d listed twice", e);
+        slot_of[e] = s;
+        eis[s] = e;
+    }
+    TIDE_HIP(ctx, hipDeviceSynchronize());
+    const uint64_t bytes = tide_expert_blob_bytes(&ctx->cfg);
+    for (int s = 0; s < C; ++s)
+        if (eis[s] >= 0)
+            TIDE_HIP(ctx, hipMemcpy(slot_ptr(ctx, L, s), L.host_blobs + (uint64_t)eis[s] * L.host_stride, bytes, hipMemcpyHostToDevice));
+    TIDE_HIP(ctx, hipMemcpy(L.t.slot_of, slot_of.data(), E * 4, hipMemcpyHostToDevice));
+    TIDE_HIP(ctx, hipMemcpy(L.t.expert_in_slot, eis.data(), C * 4, hipMemcpyHostToDevice));
+    L.placed = true;
+    L.copies_pending = false;
+    return TIDE_OK;
+}
+
+int tide_moe_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const float* router_w_dev,
+                  const float* router_bias_dev, float* out_dev, tide_miss* miss_dev, int miss_cap,
+                  int32_t* n_miss_dev, int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream) {
+    int rc = step_args_ok(ctx, layer, hidden_dev, n_tokens, out_dev, miss_dev, miss_cap, n_miss_dev);
+    if (rc) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (n_tokens == 0) {
+        TIDE_HIP(ctx, launch_clear_i32(n_miss_dev, 1, stream));
+        return TIDE_OK;
+    }
+    if (!router_w_dev) return fail(ctx, TIDE_E_INVAL, "router_w_dev is null");
+    if (ctx->cfg.bias_mode != TIDE_BIAS_NONE && !router_bias_dev) return fail(ctx, TIDE_E_INVAL, "router_bias_dev is null but bias_mode != NONE");
+    if ((uintptr_t)router_w_dev & 15) return fail(ctx, TIDE_E_INVAL, "router_w_dev must be 16-byte aligned");
+    Layer& L = ctx->layers[layer];
+    const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
+    TIDE_HIP(ctx, launch_router_logits(ctx->shape, x, n_tokens, router_w_dev, ctx->ws.logits, ctx->ws.hist_step, stream));
+    TIDE_HIP(ctx, launch_topk_gate(ctx->shape, ctx->ws.logits, router_bias_dev, n_tokens, ctx->ws.topk_idx, ctx->ws.topk_w,
+                                   ctx->ws.hist_step, L.t.hits, topk_idx_dev, topk_w_dev, stream));
+    return common_step(ctx, layer, hidden_dev, n_tokens, ctx->ws.topk_idx, ctx->ws.topk_w, out_dev, miss_dev, miss_cap,
+                       n_miss_dev, stream);
+}
+
+int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const int32_t* topk_idx_dev,
+                         const float* topk_w_dev, float* out_dev, tide_miss* miss_dev, int miss_cap,
+                         int32_t* n_miss_dev, void* hip_stream) {
+    int rc = step_args_ok(ctx, layer, hidden_dev, n_tokens, out_dev, miss_dev, miss_cap, n_miss_dev);
+    if (rc) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (n_tokens == 0) {
+        TIDE_HIP(ctx, launch_clear_i32(n_miss_dev, 1, stream));
+        return TIDE_OK;
+    }
+    if (!topk_idx_dev || !topk_w_dev) return fail(ctx, TIDE_E_INVAL, "topk_idx_dev / topk_w_dev is null");
+    Layer& L = ctx->layers[layer];
+    TIDE_HIP(ctx, launch_count_pairs(ctx->shape, topk_idx_dev, n_tokens, ctx->ws.hist_step, L.t.hits, stream));
+    return common_step(ctx, layer, hidden_dev, n_tokens, topk_idx_dev, topk_w_dev, out_dev, miss_dev, miss_cap,
+                       n_miss_dev, stream);
+}
+
+int tide_interval_stats(tide_ctx* ctx, int layer, int32_t* counts_host, int reset, void* hip_stream) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    if (!counts_host) return fail(ctx, TIDE_E_INVAL, "counts_host is null");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    Layer& L = ctx->layers[layer];
+    TIDE_HIP(ctx, hipMemcpyAsync(counts_host, L.t.hits, ctx->cfg.n_experts * 4, hipMemcpyDeviceToHost, stream));
+    if (reset) TIDE_HIP(ctx, launch_clear_i32(L.t.hits, ctx->cfg.n_experts, stream));
+    TIDE_HIP(ctx, hipStreamSynchronize(stream));
+    return TIDE_OK;
+}
+
+int tide_refresh(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,
+                 int32_t* resident_out, tide_copy* plan_out, int* n_copies_out, void* hip_stream) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    if (capacity < 0 || capacity > ctx->cfg.capacity) return fail(ctx, TIDE_E_RANGE, "capacity %d outside 0..%d", capacity, ctx->cfg.capacity);
+    Layer& L = ctx->layers[layer];
+    if (!L.host_blobs) return fail(ctx, TIDE_E_STATE, "layer %d: experts not registered", layer);
+    if (!L.placed) return fail(ctx, TIDE_E_STATE, "layer %d has no placement: call tide_set_resident first", layer);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int32_t* counts = L.t.hits;
+    if (counts_host) {
+        TIDE_HIP(ctx, hipMemcpyAsync(ctx->ws.counts_tmp, counts_host, ctx->cfg.n_experts * 4, hipMemcpyHostToDevice, stream));
+        counts = ctx->ws.counts_tmp;
+    }
+    // copies of an earlier refresh must have landed before their slots can be given away again
+    if (L.copies_recorded) TIDE_HIP(ctx, hipStreamWaitEvent(stream, L.copies_done, 0));
+    TIDE_HIP(ctx, launch_refresh_select(ctx->shape, L.t, counts, capacity, reset_counts, L.plan, stream));
+    // the plan is needed here to queue the copies; this also means every earlier step that
+    // could still read a slot about to be overwritten has finished
+    TIDE_HIP(ctx, hipStreamSynchronize(stream));
+    const int n = L.plan->n_copies;
+    const uint64_t bytes = tide_expert_blob_bytes(&ctx->cfg);
+    TIDE_HIP(ctx, hipEventRecord(L.copies_begin, ctx->side));
+    for (int i = 0; i < n; ++i) {
+        const int e = L.plan->expert[i], s = L.plan->slot[i];
+        TIDE_HIP(ctx, hipMemcpyAsync(slot_ptr(ctx, L, s), L.host_blobs + (uint64_t)e * L.host_stride, bytes, hipMemcpyHostToDevice, ctx->side));
+        if (plan_out) {
+            plan_out[i].expert = e;
+            plan_out[i].slot = s;
+            plan_out[i].host_offset = (uint64_t)e * L.host_stride;
+            plan_out[i].bytes = bytes;
+        }
+    }
+    TIDE_HIP(ctx, hipEventRecord(L.copies_done, ctx->side));
+    L.copies_recorded = true;
+    L.copies_pending = n > 0;
+    if (n_copies_out) *n_copies_out = n;
+    if (resident_out) memcpy(resident_out, L.plan->expert_in_slot, ctx->cfg.capacity * sizeof(int32_t));
+    return TIDE_OK;
+}
+
+int tide_wait_refresh(tide_ctx* ctx, int layer) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    Layer& L = ctx->layers[layer];
+    if (L.copies_recorded) TIDE_HIP(ctx, hipEventSynchronize(L.copies_done));
+    return TIDE_OK;
+}
+
+int tide_refresh_copy_ms(tide_ctx* ctx, int layer, float* ms_out) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    if (!ms_out) return fail(ctx, TIDE_E_INVAL, "ms_out is null");
+    Layer& L = ctx->layers[layer];
+    if (!L.copies_recorded) return fail(ctx, TIDE_E_STATE, "no refresh has run on layer %d", layer);
+    TIDE_HIP(ctx, hipEventSynchronize(L.copies_done));
+    TIDE_HIP(ctx, hipEventElapsedTime(ms_out, L.copies_begin, L.copies_done));
+    return TIDE_OK;
+}
+
+int tide_get_table(tide_ctx* ctx, int layer, int32_t* slot_of_host, void* hip_stream) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    if (!slot_of_host) return fail(ctx, TIDE_E_INVAL, "slot_of_host is null");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    TIDE_HIP(ctx, hipMemcpyAsync(slot_of_host, ctx->layers[layer].t.slot_of, ctx->cfg.n_experts * 4, hipMemcpyDeviceToHost, stream));
+    TIDE_HIP(ctx, hipStreamSynchronize(stream));
+    return TIDE_OK;
+}
+
+int tide_read_slot(tide_ctx* ctx, int layer, int slot, void* blob_host) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    if (slot < 0 || slot > ctx->cfg.capacity) return fail(ctx, TIDE_E_RANGE, "slot %d outside 0..capacity", slot);
+    if (!blob_host) return fail(ctx, TIDE_E_INVAL, "blob_host is null");
+    Layer& L = ctx->layers[layer];
+    TIDE_HIP(ctx, hipDeviceSynchronize());
+    TIDE_HIP(ctx, hipMemcpy(blob_host, slot_ptr(ctx, L, slot), tide_expert_blob_bytes(&ctx->cfg), hipMemcpyDeviceToHost));
+    return TIDE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,90 @@
+// Internal declarations shared by the kernel translation units of libtide.
+// Every launcher enqueues on `stream` and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tide.h"
+
+namespace tide {
+
+constexpr int kMaxExperts = 512;        // E limit: 8 router scores per lane of a 64-wide wave
+constexpr int kMaxTopK = 32;
+constexpr int kRowsPerTask = 64;        // token rows one expert-GEMM work item covers
+
+// One grouped-GEMM work item: rows [row0, row0+nrows) of the slot-sorted row space
+// all belong to cache slot `slot` (slot == capacity means the shared expert).
+struct Task {
+    int32_t slot;
+    int32_t row0;
+    int32_t nrows;
+    int32_t pad;
+};
+
+// Device-side workspace of one context (shared by its layers; one step at a time).
+struct Workspace {
+    float*   logits;      // [max_tokens][E]
+    int32_t* topk_idx;    // [max_tokens][k]
+    float*   topk_w;      // [max_tokens][k]
+    int32_t* hist_step;   // [E] hits of the step in flight
+    int32_t* row_token;   // [max_rows] token of each slot-sorted row
+    int32_t* pair_row;    // [max_tokens*k] row of each (token, rank) pair, -1 = miss
+    int32_t* slot_off;    // [capacity+2] first row of each slot (shared slot last), then total rows
+    Task*    tasks;       // [max_tasks]
+    int32_t* n_tasks;     // [1]
+    uint16_t* act;        // [max_rows][d_ff] bf16 SwiGLU activations
+    float*   y;           // [max_rows][d] per-row expert outputs
+    int32_t* counts_tmp;  // [E] caller-provided counts for a refresh
+};
+
+struct LayerTables {
+    int32_t* hits;            // H[E]
+    int32_t* slot_of;         // [E]  slot of each expert, -1 = not resident
+    int32_t* expert_in_slot;  // [capacity] expert in each slot, -1 = empty
+    const uint16_t* slots;    // capacity (+1 shared) packed blobs, blob_elems apart
+};
+
+struct Shape {
+    int d, E, k, I, n_shared, capacity, gating, bias_mode;
+    int64_t blob_elems;       // 3*d*I
+};
+
+// a1: z[n][e] = <x_n, W_r[e]>  (fp32)
+hipError_t launch_router_logits(const Shape& s, const uint16_t* x, int n_tokens, const float* w_r,
+                                float* logits, int32_t* hist_step_to_clear, hipStream_t stream);
+// a2 + a3: gate, top-k, weights; hist_step[e] += 1 and hits[e] += 1 per selected pair
+hipError_t launch_topk_gate(const Shape& s, const float* logits, const float* bias, int n_tokens,
+                            int32_t* topk_idx, float* topk_w, int32_t* hist_step, int32_t* hits,
+                            int32_t* idx_copy, float* w_copy, hipStream_t stream);
+// a3 for token states that arrive routed: clear + count
+hipError_t launch_count_pairs(const Shape& s, const int32_t* topk_idx, int n_tokens, int32_t* hist_step,
+                              int32_t* hits, hipStream_t stream);
+// p[0..n) = 0 by a fill kernel (safe inside a captured graph, unlike a memset node)
+hipError_t launch_clear_i32(int32_t* p, int n, hipStream_t stream);
+// a4 + a5: hit/miss split, canonical miss list, slot-sorted rows, work items
+hipError_t launch_dispatch(const Shape& s, const LayerTables& t, const Workspace& w, const int32_t* topk_idx,
+                           const float* topk_w, int n_tokens, tide_miss* miss, int miss_cap, int32_t* n_miss,
+                           hipStream_t stream);
+// a6 / a7 / a8: grouped SwiGLU expert GEMMs over the work items
+hipError_t launch_expert_gemms(const Shape& s, const LayerTables& t, const Workspace& w, const uint16_t* x,
+                               int n_tokens, int max_tasks, hipStream_t stream);
+// a9: out[n] = shared row + sum over hit pairs in rank order of w * y[row]
+hipError_t launch_combine(const Shape& s, const Workspace& w, const float* topk_w, int n_tokens, float* out,
+                          hipStream_t stream);
+// a11: top-capacity selection + slot plan, tables updated in place
+struct RefreshOut {           // lives in pinned host memory the kernel writes directly
+    int32_t n_copies;
+    int32_t pad;
+    int32_t expert[kMaxExperts];
+    int32_t slot[kMaxExperts];
+    int32_t expert_in_slot[kMaxExperts];
+};
+hipError_t launch_refresh_select(const Shape& s, const LayerTables& t, const int32_t* counts, int capacity,
+                                 int reset_counts, RefreshOut* out_hostmapped, hipStream_t stream);
+
+// number of packed elements before each matrix inside a blob
+inline int64_t blob_off_gate(const Shape&) { return 0; }
+inline int64_t blob_off_up(const Shape& s) { return (int64_t)s.d * s.I; }
+inline int64_t blob_off_down(const Shape& s) { return 2 * (int64_t)s.d * s.I; }
+
+}  // namespace tide

@@ -1,0 +1,81 @@
+"""Host-side checks of libtide that need no GPU: the library loads, exports every
+symbol include/tide.h declares, validates configurations, packs expert weights into
+the documented tile order, and refuses to create a context without a device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def tb():
+    from paper_2605_20179_amd import binding
+    return binding
+
+
+def test_every_declared_symbol_is_exported(tb):
+    header = open(os.path.join(ROOT, "include", "tide.h")).read()
+    declared = set(re.findall(r"\b(tide_[a-z_0-9]+)\s*\(", header))
+    declared -= {"tide_ctx"}
+    assert declared, "no declarations found"
+    lib = ctypes.CDLL(tb.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), "libtide.so does not export %s" % name
+    assert declared == set(tb.EXPORTS)
+
+
+def test_struct_layouts_match_the_header(tb):
+    assert ctypes.sizeof(tb.tide_miss) == 12
+    assert ctypes.sizeof(tb.tide_copy) == 24
+    assert ctypes.sizeof(tb.tide_config) == 40
+    assert tb.MISS_DTYPE.itemsize == 12
+
+
+def test_pack_layout(tb):
+    """Tile (rt, kc) of 16 rows x 32 columns is 512 contiguous elements; lane l holds row
+    rt*16 + l%16, columns kc*32 + (l/16)*8 .. +7; gate, up, down matrices follow each other."""
+    d, I = 128, 64
+    cfg = tb.make_config(d, 8, 2, I, 0, 1, 4, 8, 0, 0)
+    wg = np.arange(I * d, dtype=np.uint16).reshape(I, d)
+    wu = (np.arange(I * d, dtype=np.uint32) + 20000).astype(np.uint16).reshape(I, d)
+    wd = (np.arange(I * d, dtype=np.uint32) + 40000).astype(np.uint16).reshape(d, I)
+    blob = np.zeros(tb.tide_expert_blob_bytes(cfg), dtype=np.uint8)
+    assert blob.size == 3 * d * I * 2
+    tb.tide_pack_expert(cfg, wg, wu, wd, blob)
+    b = blob.view(np.uint16)
+    for mat, rows, cols, base in ((wg, I, d, 0), (wu, I, d, I * d), (wd, d, I, 2 * I * d)):
+        kch = cols // 32
+        for rt in range(rows // 16):
+            for kc in range(kch):
+                tile = b[base + (rt * kch + kc) * 512: base + (rt * kch + kc + 1) * 512].reshape(64, 8)
+                for l in (0, 1, 15, 16, 37, 63):
+                    want = mat[rt * 16 + l % 16, kc * 32 + (l // 16) * 8: kc * 32 + (l // 16) * 8 + 8]
+                    assert np.array_equal(tile[l], want)
+    # a permutation: nothing lost, nothing duplicated
+    assert np.array_equal(np.sort(b), np.sort(np.concatenate([wg.ravel(), wu.ravel(), wd.ravel()])))
+
+
+def test_config_validation_and_no_device(tb):
+    ok = dict(d=256, n_experts=16, top_k=2, d_ff=128, n_shared=0, n_layers=1, capacity=8, max_tokens=8, gating=0, bias_mode=0)
+    blob = np.zeros(3 * 256 * 128 * 2, dtype=np.uint8)
+    w = np.zeros((128, 256), dtype=np.uint16)
+    for bad, code in ((dict(d=100), tb.TIDE_E_INVAL), (dict(d_ff=96), tb.TIDE_E_INVAL), (dict(n_experts=0), tb.TIDE_E_INVAL),
+                      (dict(n_experts=513), tb.TIDE_E_INVAL), (dict(top_k=17), tb.TIDE_E_INVAL), (dict(top_k=0), tb.TIDE_E_INVAL),
+                      (dict(capacity=17), tb.TIDE_E_RANGE), (dict(capacity=0), tb.TIDE_E_RANGE), (dict(n_shared=2), tb.TIDE_E_INVAL),
+                      (dict(gating=5), tb.TIDE_E_INVAL), (dict(bias_mode=3), tb.TIDE_E_INVAL), (dict(max_tokens=0), tb.TIDE_E_RANGE)):
+        cfg = tb.make_config(**{**ok, **bad})
+        rc = tb.lib.tide_pack_expert(ctypes.byref(cfg), w.ctypes.data, w.ctypes.data, w.ctypes.data, blob.ctypes.data)
+        assert rc == code, (bad, rc)
+        assert tb.lib.tide_last_error(None)
+    import torch
+    if not torch.cuda.is_available():
+        with pytest.raises(tb.TideError) as ei:
+            tb.tide_create(tb.make_config(**ok))
+        assert ei.value.code == tb.TIDE_E_HIP        # no silent CPU path
+        from paper_2605_20179_amd.session import TideSession
+        with pytest.raises(RuntimeError):
+            TideSession(256, 16, 2, 128, 0, 8, 8, 0, 0)
