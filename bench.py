@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the TIDE MoE-step hot path on one MI355X.
+
+A "step" is one denoise step of one MoE layer: (every tau-th step) the refresh --
+top-B selection, plan, pinned-host -> HBM expert copies -- followed by tide_moe_step
+(router, top-k, hit counts, hit/miss split + miss list, grouped SwiGLU expert GEMMs
+over the resident experts, weighted combine).  The workload is the LLaDA2.0-mini-shaped
+single layer (block of 32 tokens, batch 1, 256 experts top-8 + shared, capacity 64,
+refresh interval 4) on seeded synthetic weights and drifting hidden states; the 32
+hidden-state tensors of the block are resident in HBM before timing starts and the
+block is replayed cyclically.
+
+Prints ONE JSON line.  `value` is tokens/s over the whole timed region (refreshes
+included).  `roofline` is for the dominant kernel (grouped gate/up GEMM + SwiGLU):
+algorithmic bytes per launch / its mean duration between the start and stop HIP events
+that each launch stamps on its own stream inside the timed region.  `cpu_baseline` is the CPU oracle timed on a
+bounded sample of the same workload on this host."""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(wl, ti, sample_steps=6):
+    """The oracle as it stands, on `sample_steps` consecutive denoise steps (all tokens,
+    cold-start placement) of the benchmark workload."""
+    import numpy as np
+    from oracle import tide_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    store = orc.ExpertStore(lambda e: ti.expert_weights(wl, 0, e), max_cached=wl.E + 1)
+    shared = tuple(orc.bf16_to_f64(m) for m in ti.expert_weights(wl, 0, wl.E)) if wl.n_shared else None
+    hidden = list(ti.hidden_stream(wl, 0, sample_steps))
+    wr, b = ti.router_weights(wl, 0), ti.router_bias(wl, 0)
+    t0 = time.perf_counter()
+    orc.run_block(hidden, wr, b, wl.gating, wl.bias_mode, wl.k, wl.E, wl.C, wl.K, ti.initial_resident(wl),
+                  weights=store, shared=shared)
+    dt = time.perf_counter() - t0
+    return {"value": wl.N * sample_steps / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d denoise steps x %d tokens of the same layer, routing + resident and full outputs in fp64, "
+                      "%.1f s (includes bf16->fp64 weight conversion on first use)" % (sample_steps, wl.N, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--config", type=int, default=1, help="workload id (1 = the headline layer; 3 = flash-shaped layer)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)." % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import tide_inputs as ti
+    from paper_2605_20179_amd import binding as tb
+    from paper_2605_20179_amd.session import TideSession
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU path.", file=sys.stderr)
+        sys.exit(2)
+    wl = ti.CONFIGS[args.config]
+    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode)
+    sess.load_layer(0, lambda e: ti.expert_weights(wl, 0, e), ti.router_weights(wl, 0), ti.router_bias(wl, 0),
+                    ti.initial_resident(wl), workers=16)
+    hidden = [sess.to_device_bf16(h) for h in ti.hidden_stream(wl, 0)]
+    torch.cuda.synchronize()
+
+    state = {"t": 0, "refresh_s": 0.0, "copies": 0, "copy_ms": 0.0, "refreshes": 0}
+
+    def one_step(timed):
+        t = state["t"] % wl.S
+        if t > 0 and t % wl.K == 0:
+            r0 = time.perf_counter()
+            _, plan = sess.refresh(0)
+            if timed:
+                state["refresh_s"] += time.perf_counter() - r0
+                state["copies"] += len(plan)
+                state["refreshes"] += 1
+                state["pending_copy_timing"] = bool(plan)
+        sess.step(0, hidden[t], want_topk=False)
+        state["t"] += 1
+
+    for _ in range(args.warmup):
+        one_step(False)
+    torch.cuda.synchronize()
+    tb.tide_counters(sess.ctx, reset=True)
+    if not args.no_kernel_events:
+        tb.tide_profile(sess.ctx, True)
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    prof = tb.tide_profile_read(sess.ctx) if not args.no_kernel_events else {}
+    tb.tide_profile(sess.ctx, False)
+    cnt = tb.tide_counters(sess.ctx)
+    assert cnt["steps"] == args.steps
+
+    # detail only: the same steps with the placement frozen (no refresh, no event brackets)
+    torch.cuda.synchronize()
+    s0 = time.perf_counter()
+    for i in range(args.steps):
+        sess.step(0, hidden[i % wl.S], want_topk=False)
+    torch.cuda.synchronize()
+    step_only_s = (time.perf_counter() - s0) / args.steps
+
+    # measured separately (outside the timed region): pinned-host -> HBM rate of one refresh's copies
+    h2d = None
+    probe = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode)
+    probe.host_blobs[0] = sess.host_blobs[0]
+    tb.tide_register_experts(probe.ctx, 0, sess.host_blobs[0], sess.blob_bytes)
+    tb.tide_set_resident(probe.ctx, 0, list(range(wl.C)))
+    counts = np.zeros(wl.E, dtype=np.int32)
+    counts[wl.C:2 * wl.C] = 1                      # swaps in `capacity` new experts
+    _, plan = probe.refresh(0, counts=counts)
+    ms = tb.tide_refresh_copy_ms(probe.ctx, 0)
+    if plan and ms > 0:
+        h2d = {"GB/s": len(plan) * sess.blob_bytes / ms / 1e6, "copies": len(plan), "MiB_each": sess.blob_bytes / 2 ** 20}
+    probe.close()
+
+    tokens = wl.N * args.steps
+    value = tokens / dt
+    blob = sess.blob_bytes
+    roofline = None
+    kernels = {}
+    if prof:
+        # avg_us: mean time between the start and stop events each launch stamps on its own stream
+        for name, (ms_sum, n) in prof.items():
+            if n:
+                kernels[name] = {"avg_us": 1e3 * ms_sum / n, "launches": n}
+        ms_sum, n = prof["gate_up_swiglu"]
+        # algorithmic bytes of one gate/up launch: the gate and up matrices (2/3 of a blob) of every cache
+        # slot that has a token this step (shared expert included), the step's hidden states once, and the
+        # bf16 activations written
+        active_per_launch = cnt["active_slots"] / cnt["steps"]
+        rows_per_launch = cnt["rows"] / cnt["steps"]
+        bytes_per_launch = active_per_launch * (2 * blob / 3) + wl.N * wl.d * 2 + rows_per_launch * wl.I * 2
+        avg_s = 1e-3 * ms_sum / n
+        achieved = bytes_per_launch / avg_s / 1e9
+        roofline = {"bound": "hbm", "kernel": "expert_gemm_kernel<0> (grouped gate/up GEMM + SwiGLU)",
+                    "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                    "traffic": None, "avg_kernel_us": avg_s * 1e6, "algorithmic_bytes_per_launch": bytes_per_launch,
+                    "active_slots_per_launch": active_per_launch}
+        ms2, n2 = prof["down"]
+        if n2:
+            b2 = active_per_launch * (blob / 3) + rows_per_launch * wl.I * 2 + rows_per_launch * wl.d * 4
+            roofline["down_kernel"] = {"achieved": b2 / (1e-3 * ms2 / n2) / 1e9, "frac": b2 / (1e-3 * ms2 / n2) / 1e9 / HBM_PEAK_GBS,
+                                       "avg_kernel_us": 1e3 * ms2 / n2}
+
+    step_bytes = (cnt["active_slots"] / cnt["steps"]) * blob + wl.E * wl.d * 4 + wl.N * wl.d * 2 + wl.N * wl.d * 4
+    out = {
+        "metric": "MoE-layer tokens/s per denoise step", "value": value, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "d": wl.d, "experts": wl.E, "top_k": wl.k, "d_ff": wl.I, "shared_experts": wl.n_shared,
+                   "tokens_per_step": wl.N, "capacity": wl.C, "refresh_interval": wl.K, "steps_per_block": wl.S, "layers": 1},
+        "roofline": roofline,
+        "detail": {
+            "kernels": kernels,
+            "step_hbm_roofline_us": step_bytes / (HBM_PEAK_GBS * 1e9) * 1e6,
+            "hit_rate": 1.0 - cnt["misses"] / (tokens * wl.k),
+            "refreshes": state["refreshes"], "experts_copied": state["copies"],
+            "refresh_host_s": state["refresh_s"],
+            "frozen_placement_us_per_step": step_only_s * 1e6,
+            "frozen_placement_tokens_per_s": wl.N / step_only_s,
+            "h2d_probe": h2d,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, ti)
+    sess.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

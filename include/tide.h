@@ -55,7 +55,7 @@ typedef struct { int32_t expert; int32_t slot; uint64_t host_offset; uint64_t by
 typedef struct {
     int32_t d;           /* hidden size; multiple of 64                                  */
     int32_t n_experts;   /* E, 1..512                                                    */
-    int32_t top_k;       /* k, 1..min(E,32)                                              */
+    int32_t top_k;       /* k, 1..min(E,16)                                              */
     int32_t d_ff;        /* SwiGLU intermediate size I; multiple of 64                   */
     int32_t n_shared;    /* 0 or 1 always-resident shared expert (weight 1, not counted) */
     int32_t n_layers;    /* independent MoE layers, each with its own cache and counter  */
@@ -172,6 +172,30 @@ int tide_read_slot(tide_ctx* ctx, int layer, int slot, void* blob_host);
 /* Per-call timing of the refresh copies of the LAST tide_refresh on the layer, in
  * milliseconds between the first copy starting and the last one landing; waits for them. */
 int tide_refresh_copy_ms(tide_ctx* ctx, int layer, float* ms_out);
+
+/* ---- measurement hooks ---------------------------------------------------------------- */
+
+/* Kernels of one step, in launch order (ids for tide_profile_read). */
+#define TIDE_K_ROUTER   0   /* router logits                          */
+#define TIDE_K_TOPK     1   /* gate + top-k + hit counts              */
+#define TIDE_K_DISPATCH 2   /* hit/miss split, miss list, row lists   */
+#define TIDE_K_GATE_UP  3   /* grouped gate/up GEMM + SwiGLU          */
+#define TIDE_K_DOWN     4   /* grouped down GEMM                      */
+#define TIDE_K_COMBINE  5   /* weighted combine                       */
+#define TIDE_K_COUNT    6
+
+/* enable != 0: from now on every kernel launch of a step carries a start and a stop HIP
+ * event that the dispatch itself stamps when it begins and ends on its stream (no extra
+ * packets between the kernels).  Synchronises the device and drops earlier samples. */
+int tide_profile(tide_ctx* ctx, int enable);
+/* Waits for the device, then writes per kernel id the summed start-to-stop time in
+ * milliseconds (ms_sum_host[TIDE_K_COUNT]) and the number of launches
+ * (launches_host[TIDE_K_COUNT]) since the last read, and clears the samples. */
+int tide_profile_read(tide_ctx* ctx, double* ms_sum_host, int64_t* launches_host);
+/* Running totals kept on the device by the step itself: out4_host = {steps, cache slots
+ * (shared expert included) that had at least one token, expert rows evaluated, misses}.
+ * Synchronises hip_stream; reset != 0 zeroes them afterwards. */
+int tide_counters(tide_ctx* ctx, int64_t* out4_host, int reset, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -22,8 +22,9 @@ EXPORTS = [
     "tide_create", "tide_destroy", "tide_last_error", "tide_expert_blob_bytes", "tide_pack_expert",
     "tide_register_experts", "tide_set_shared", "tide_set_resident", "tide_moe_step", "tide_moe_step_routed",
     "tide_interval_stats", "tide_refresh", "tide_wait_refresh", "tide_get_table", "tide_read_slot",
-    "tide_refresh_copy_ms",
+    "tide_refresh_copy_ms", "tide_profile", "tide_profile_read", "tide_counters",
 ]
+KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine"]
 
 
 class tide_config(C.Structure):
@@ -73,6 +74,9 @@ def _load() -> C.CDLL:
     lib.tide_get_table.argtypes = [vp, C.c_int, vp, vp]
     lib.tide_read_slot.argtypes = [vp, C.c_int, C.c_int, vp]
     lib.tide_refresh_copy_ms.argtypes = [vp, C.c_int, C.POINTER(C.c_float)]
+    lib.tide_profile.argtypes = [vp, C.c_int]
+    lib.tide_profile_read.argtypes = [vp, vp, vp]
+    lib.tide_counters.argtypes = [vp, vp, C.c_int, vp]
     for name in EXPORTS:
         if name not in ("tide_last_error", "tide_expert_blob_bytes"):
             getattr(lib, name).restype = C.c_int
@@ -194,3 +198,22 @@ def tide_read_slot(ctx, layer: int, slot: int, blob_bytes: int) -> np.ndarray:
     b = np.zeros(blob_bytes, dtype=np.uint8)
     _check(lib.tide_read_slot(ctx, layer, slot, _ptr(b)), ctx)
     return b
+
+
+def tide_profile(ctx, enable: bool) -> None:
+    _check(lib.tide_profile(ctx, int(enable)), ctx)
+
+
+def tide_profile_read(ctx):
+    """Returns {kernel name: (summed ms, launches)} since the last read."""
+    ms = np.zeros(len(KERNEL_NAMES), dtype=np.float64)
+    n = np.zeros(len(KERNEL_NAMES), dtype=np.int64)
+    _check(lib.tide_profile_read(ctx, _ptr(ms), _ptr(n)), ctx)
+    return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(KERNEL_NAMES)}
+
+
+def tide_counters(ctx, reset: bool = False, stream=None):
+    """Returns dict(steps, active_slots, rows, misses): running totals kept by the step kernels."""
+    out = np.zeros(4, dtype=np.int64)
+    _check(lib.tide_counters(ctx, _ptr(out), int(reset), _stream_ptr(stream)), ctx)
+    return dict(steps=int(out[0]), active_slots=int(out[1]), rows=int(out[2]), misses=int(out[3]))

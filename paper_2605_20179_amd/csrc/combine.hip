@@ -37,9 +37,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 }  // namespace
 
 hipError_t launch_combine(const Shape& s, const Workspace& w, const float* topk_w, int n_tokens, float* out,
-                          hipStream_t stream) {
+                          hipStream_t stream, LaunchEvents ev) {
     dim3 grid((s.d + 1023) / 1024, n_tokens);
-    hipLaunchKernelGGL(combine_kernel, grid, dim3(256), 0, stream, w.y, w.pair_row, topk_w, w.slot_off, s.capacity,
+    TIDE_LAUNCH(combine_kernel, grid, dim3(256), stream, ev, w.y, w.pair_row, topk_w, w.slot_off, s.capacity,
                        s.n_shared, s.k, s.d, out);
     return hipGetLastError();
 }

@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     int n_shared, int n_experts, const int32_t* __restrict__ slot_of, const int32_t* __restrict__ expert_in_slot,
     const int32_t* __restrict__ hist_step, int32_t* __restrict__ row_token, int32_t* __restrict__ pair_row,
     int32_t* __restrict__ slot_off, Task* __restrict__ tasks, int32_t* __restrict__ n_tasks,
-    tide_miss* __restrict__ miss, int miss_cap, int32_t* __restrict__ n_miss) {
+    tide_miss* __restrict__ miss, int miss_cap, int32_t* __restrict__ n_miss, int64_t* __restrict__ counters) {
     __shared__ int lds4[kThreads / 64];
     const int s = blockIdx.x;
     const int tid = threadIdx.x;
@@ -81,18 +81,22 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
             }
             running += total;
         }
-        if (tid == 0) *n_miss = running;
+        if (tid == 0) {
+            *n_miss = running;
+            counters[3] += running;
+        }
         return;
     }
 
     // rows and work items that precede this slot
     const int upto = s < capacity ? s : capacity;
-    int rows_before = 0, tasks_before = 0;
+    int rows_before = 0, tasks_before = 0, active_before = 0;
     for (int q = tid; q < upto; q += kThreads) {
         const int e = expert_in_slot[q];
         const int m = e >= 0 ? hist_step[e] : 0;
         rows_before += m;
         tasks_before += (m + kRowsPerTask - 1) / kRowsPerTask;
+        active_before += m > 0 ? 1 : 0;
     }
     rows_before = block_sum(rows_before, lds4);
     tasks_before = block_sum(tasks_before, lds4);
@@ -114,6 +118,13 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
             slot_off[capacity] = rows_before;
             slot_off[capacity + 1] = rows_before + m;
             *n_tasks = tasks_before + nt;
+        }
+        active_before = block_sum(active_before, lds4);
+        if (tid == 0) {
+            // running totals for throughput accounting; only this block of this kernel writes them
+            counters[0] += 1;
+            counters[1] += active_before + (m > 0 ? 1 : 0);
+            counters[2] += rows_before + m;
         }
         return;
     }
@@ -150,10 +161,10 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
 
 hipError_t launch_dispatch(const Shape& s, const LayerTables& t, const Workspace& w, const int32_t* topk_idx,
                            const float* topk_w, int n_tokens, tide_miss* miss, int miss_cap, int32_t* n_miss,
-                           hipStream_t stream) {
-    hipLaunchKernelGGL(dispatch_kernel, dim3(s.capacity + 2), dim3(kThreads), 0, stream, topk_idx, topk_w,
+                           hipStream_t stream, LaunchEvents ev) {
+    TIDE_LAUNCH(dispatch_kernel, dim3(s.capacity + 2), dim3(kThreads), stream, ev, topk_idx, topk_w,
                        n_tokens, s.k, s.capacity, s.n_shared, s.E, t.slot_of, t.expert_in_slot, w.hist_step,
-                       w.row_token, w.pair_row, w.slot_off, w.tasks, w.n_tasks, miss, miss_cap, n_miss);
+                       w.row_token, w.pair_row, w.slot_off, w.tasks, w.n_tasks, miss, miss_cap, n_miss, w.counters);
     return hipGetLastError();
 }
 

@@ -9,85 +9,96 @@ namespace {
 
 constexpr int kThreads = kMaxExperts;
 
+// Orders are expressed as packed 64-bit keys so that each all-pairs pass is one LDS read
+// and one compare per candidate:
+//   placement rank (larger key first):  hits | resident bit | reversed id
+//   leaving order  (smaller key first): hits | id
+//   entering order (larger key first):  hits | reversed id
 __global__ __launch_bounds__(kThreads) void refresh_select_kernel(int n_experts, int n_slots, int capacity,
                                                                   const int32_t* __restrict__ counts,
                                                                   int32_t* __restrict__ hits_to_reset,
                                                                   int32_t* __restrict__ slot_of,
                                                                   int32_t* __restrict__ expert_in_slot,
                                                                   RefreshOut* __restrict__ out) {
-    __shared__ int h[kMaxExperts];          // hits
-    __shared__ int slot[kMaxExperts];       // slot of expert or -1
-    __shared__ int cls[kMaxExperts];        // 0 stays out / stays in, 1 leaving, 2 entering
-    __shared__ int free_slot[kMaxExperts];  // freed slots in leaving order, then empty slots ascending
+    __shared__ unsigned long long rank_key[kMaxExperts];
+    __shared__ unsigned long long leave_key[kMaxExperts];   // ~0 for experts that are not leaving
+    __shared__ unsigned long long enter_key[kMaxExperts];   // 0 for experts that are not entering
+    __shared__ int free_slot[kMaxExperts];   // freed slots in leaving order, then empty slots ascending
+    __shared__ int plan_expert[kMaxExperts], plan_slot[kMaxExperts];
+    __shared__ int empty_flag[kMaxExperts];
     __shared__ int n_leaving_s, n_entering_s;
     const int e = threadIdx.x;
     const bool live = e < n_experts;
+    unsigned long long h = 0;
+    int my_slot = -1;
     if (live) {
-        h[e] = counts[e];
-        slot[e] = slot_of[e];
+        h = (unsigned long long)(unsigned int)counts[e];
+        my_slot = slot_of[e];
     }
+    rank_key[e] = live ? ((h << 10) | (my_slot >= 0 ? 512ull : 0ull) | (unsigned long long)(kMaxExperts - 1 - e)) : 0ull;
+    empty_flag[e] = (e < n_slots && expert_in_slot[e] < 0) ? 1 : 0;
     if (e == 0) { n_leaving_s = 0; n_entering_s = 0; }
     __syncthreads();
 
-    // rank under (hits descending, resident first, lower id first)
-    int my_cls = 0;
+    int my_cls = 0;            // 1 leaving, 2 entering
     if (live) {
-        const int he = h[e];
-        const int re = slot[e] >= 0 ? 0 : 1;
+        const unsigned long long mine = rank_key[e];
         int rank = 0;
-        for (int o = 0; o < n_experts; ++o) {
-            const int ho = h[o];
-            const int ro = slot[o] >= 0 ? 0 : 1;
-            const bool before = (ho > he) || (ho == he && (ro < re || (ro == re && o < e)));
-            rank += before ? 1 : 0;
-        }
+#pragma unroll 8
+        for (int o = 0; o < n_experts; ++o) rank += rank_key[o] > mine ? 1 : 0;
         const bool in_new = rank < capacity;
-        if (re == 0 && !in_new) my_cls = 1;
-        if (re == 1 && in_new) my_cls = 2;
-        cls[e] = my_cls;
+        if (my_slot >= 0 && !in_new) my_cls = 1;
+        if (my_slot < 0 && in_new) my_cls = 2;
     }
-    __syncthreads();
-
-    // order inside the leaving set: (hits ascending, id); inside the entering set: (hits descending, id)
-    int my_pos = -1;
-    if (live && my_cls != 0) {
-        const int he = h[e];
-        int pos = 0;
-        for (int o = 0; o < n_experts; ++o) {
-            if (cls[o] != my_cls) continue;
-            const int ho = h[o];
-            const bool before = (my_cls == 1) ? ((ho < he) || (ho == he && o < e)) : ((ho > he) || (ho == he && o < e));
-            pos += before ? 1 : 0;
-        }
-        my_pos = pos;
-        atomicAdd(my_cls == 1 ? &n_leaving_s : &n_entering_s, 1);
-    }
+    leave_key[e] = my_cls == 1 ? ((h << 10) | (unsigned long long)e) : ~0ull;
+    enter_key[e] = my_cls == 2 ? ((h << 10) | (unsigned long long)(kMaxExperts - 1 - e) | (1ull << 62)) : 0ull;
+    if (my_cls == 1) atomicAdd(&n_leaving_s, 1);
+    if (my_cls == 2) atomicAdd(&n_entering_s, 1);
     __syncthreads();
     const int n_leaving = n_leaving_s, n_entering = n_entering_s;
 
-    if (live && my_cls == 1) free_slot[my_pos] = slot[e];
+    int my_pos = -1;
+    if (my_cls == 1) {
+        const unsigned long long mine = leave_key[e];
+        int pos = 0;
+#pragma unroll 8
+        for (int o = 0; o < n_experts; ++o) pos += leave_key[o] < mine ? 1 : 0;
+        my_pos = pos;
+        free_slot[pos] = my_slot;
+    } else if (my_cls == 2) {
+        const unsigned long long mine = enter_key[e];
+        int pos = 0;
+#pragma unroll 8
+        for (int o = 0; o < n_experts; ++o) pos += enter_key[o] > mine ? 1 : 0;
+        my_pos = pos;
+    }
     // thread s < n_slots looks at slot s: originally empty slots follow the freed ones
-    if (e < n_slots && expert_in_slot[e] < 0) {
+    if (e < n_slots && empty_flag[e]) {
         int before = 0;
-        for (int q = 0; q < e; ++q) before += expert_in_slot[q] < 0 ? 1 : 0;
+        for (int q = 0; q < e; ++q) before += empty_flag[q];
         free_slot[n_leaving + before] = e;
     }
     __syncthreads();
 
-    if (live && my_cls == 1) {
-        expert_in_slot[slot[e]] = -1;
+    if (my_cls == 1) {
+        expert_in_slot[my_slot] = -1;
         slot_of[e] = -1;
     }
     __syncthreads();
-    if (live && my_cls == 2) {
+    if (my_cls == 2) {
         const int s = free_slot[my_pos];
         expert_in_slot[s] = e;
         slot_of[e] = s;
-        out->expert[my_pos] = e;
-        out->slot[my_pos] = s;
+        plan_expert[my_pos] = e;
+        plan_slot[my_pos] = s;
     }
     if (live && hits_to_reset != nullptr) hits_to_reset[e] = 0;
     __syncthreads();
+    // results go to host-visible memory in thread order (coalesced stores)
+    if (e < n_entering) {
+        out->expert[e] = plan_expert[e];
+        out->slot[e] = plan_slot[e];
+    }
     if (e < n_slots) out->expert_in_slot[e] = expert_in_slot[e];
     if (e == 0) {
         out->n_copies = n_entering;

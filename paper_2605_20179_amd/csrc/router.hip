@@ -1,4 +1,5 @@
-// Router: fp32 logits, gate, in-register top-k with wavefront shuffles, and the
+// Router: fp32-faithful logits on the bf16 matrix cores, gate, in-register top-k with
+// wavefront shuffles, and the
 // per-step / per-interval hit counts (Sec. 3.1: k of E experts per token;
 // Fig. 1 caption: hits = number of tokens each expert has processed).
 #include "tide_internal.h"
@@ -7,79 +8,168 @@ namespace tide {
 
 namespace {
 
-constexpr int kTokPerWave = 8;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-__device__ inline float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+constexpr int kRouterWaves = 4;
 
-// One wave per (expert, group of 8 tokens): the router row is read once per group,
-// each lane owns 4 consecutive columns per 256-column stripe.
-__global__ __launch_bounds__(64) void router_logits_kernel(const uint16_t* __restrict__ x, int n_tokens, int d,
-                                                           int n_experts, const float* __restrict__ w_r,
-                                                           float* __restrict__ logits,
-                                                           int32_t* __restrict__ hist_step_to_clear) {
-    const int e = blockIdx.x;
-    const int n0 = blockIdx.y * kTokPerWave;
-    const int lane = threadIdx.x;
+// An fp32 number is the exact sum of three bf16 numbers (its mantissa cut into 8-bit
+// pieces); the hidden states are bf16 already.  So the fp32 router product
+// x * w = x*hi + x*mid + x*lo runs on the bf16 matrix cores with every product exact in
+// fp32 and only the accumulation rounded -- the same error class as an fp32 FMA chain.
+__device__ inline void split3(float w, uint32_t& hi, uint32_t& mid, uint32_t& lo) {
+    const uint32_t wb = __float_as_uint(w);
+    hi = wb & 0xFFFF0000u;
+    const float r1 = w - __uint_as_float(hi);
+    mid = __float_as_uint(r1) & 0xFFFF0000u;
+    const float r2 = r1 - __uint_as_float(mid);
+    lo = __float_as_uint(r2) & 0xFFFF0000u;
+}
+
+__device__ inline bf16x8 pack8(const uint32_t (&v)[8]) {
+    u32x4 p;
+    p[0] = (v[0] >> 16) | v[1];
+    p[1] = (v[2] >> 16) | v[3];
+    p[2] = (v[4] >> 16) | v[5];
+    p[3] = (v[6] >> 16) | v[7];
+    return __builtin_bit_cast(bf16x8, p);
+}
+
+// z_part[ks][n][e] = sum over the ks-th slice of the hidden dimension of x[n][j] * W_r[e][j].
+// grid.x = expert tile (16 experts) * k_splits + ks, grid.y = token tile (NT*16 tokens);
+// the 4 waves of a workgroup interleave over the slice's 32-column chunks and are summed
+// through LDS in a fixed order.  MFMA layout: experts on the 16-row side, tokens on the
+// 16-column side.
+template <int NT>
+__global__ __launch_bounds__(kRouterWaves * 64) void router_logits_kernel(
+    const uint16_t* __restrict__ x, int n_tokens, int d, int n_experts, int e_pad, int k_splits,
+    const float* __restrict__ w_r, float* __restrict__ z_part, int32_t* __restrict__ hist_step_to_clear) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int etile = blockIdx.x / k_splits, ks = blockIdx.x % k_splits;
+    const int n0 = blockIdx.y * (NT * 16);
     if (blockIdx.x == 0 && blockIdx.y == 0 && hist_step_to_clear != nullptr) {
-        for (int i = lane; i < n_experts; i += 64) hist_step_to_clear[i] = 0;
+        for (int i = threadIdx.x; i < n_experts; i += kRouterWaves * 64) hist_step_to_clear[i] = 0;
     }
-    float acc[kTokPerWave];
+    const int chunks_per_split = (d >> 5) / k_splits;
+    const int c_begin = ks * chunks_per_split, c_end = c_begin + chunks_per_split;
+    const int erow = min(etile * 16 + (lane & 15), n_experts - 1);           // clamp: padded rows are never stored
+    const float* wrow = w_r + (int64_t)erow * d + (lane >> 4) * 8;
+    const uint16_t* xrow[NT];
 #pragma unroll
-    for (int t = 0; t < kTokPerWave; ++t) acc[t] = 0.f;
-    const float* wrow = w_r + (int64_t)e * d;
-    for (int j = lane * 4; j < d; j += 256) {
-        const float4 wv = *reinterpret_cast<const float4*>(wrow + j);
+    for (int t = 0; t < NT; ++t) {
+        const int n = min(n0 + t * 16 + (lane & 15), n_tokens - 1);
+        xrow[t] = x + (int64_t)n * d + (lane >> 4) * 8;
+    }
+    f32x4 acc[NT];
 #pragma unroll
-        for (int t = 0; t < kTokPerWave; ++t) {
-            const int n = n0 + t;
-            if (n < n_tokens) {
-                const uint2 xv = *reinterpret_cast<const uint2*>(x + (int64_t)n * d + j);
-                acc[t] = fmaf(bf16_bits_to_float(xv.x & 0xFFFFu), wv.x, acc[t]);
-                acc[t] = fmaf(bf16_bits_to_float(xv.x >> 16), wv.y, acc[t]);
-                acc[t] = fmaf(bf16_bits_to_float(xv.y & 0xFFFFu), wv.z, acc[t]);
-                acc[t] = fmaf(bf16_bits_to_float(xv.y >> 16), wv.w, acc[t]);
+    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int c = c_begin + wave; c < c_end; c += kRouterWaves) {
+        const float4 w0 = *reinterpret_cast<const float4*>(wrow + c * 32);
+        const float4 w1 = *reinterpret_cast<const float4*>(wrow + c * 32 + 4);
+        bf16x8 b[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) b[t] = *reinterpret_cast<const bf16x8*>(xrow[t] + c * 32);
+        const float wv[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+        uint32_t hi[8], mid[8], lo[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) split3(wv[i], hi[i], mid[i], lo[i]);
+        const bf16x8 a_hi = pack8(hi), a_mid = pack8(mid), a_lo = pack8(lo);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, b[t], acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_mid, b[t], acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, b[t], acc[t], 0, 0, 0);
+        }
+    }
+    __shared__ f32x4 red[kRouterWaves][NT][64];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) red[wave][t][lane] = acc[t];
+    __syncthreads();
+    // wave w finishes token tiles w, w+4, ...
+    for (int t = wave; t < NT; t += kRouterWaves) {
+        const f32x4 v = red[0][t][lane] + red[1][t][lane] + red[2][t][lane] + red[3][t][lane];
+        const int n = n0 + t * 16 + (lane & 15);
+        const int e = etile * 16 + (lane >> 4) * 4;
+        if (n < n_tokens)
+            *reinterpret_cast<float4*>(z_part + ((int64_t)ks * n_tokens + n) * e_pad + e) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+}
+
+// Cross-lane moves inside a row of 16 lanes by DPP rotation (no LDS round trip).  Four
+// rotate-and-combine steps (by 8, 4, 2, 1) leave every lane with the combination of all 16.
+template <int N>
+__device__ inline int row_ror_i(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x120 + N, 0xF, 0xF, false); }
+template <int N>
+__device__ inline float row_ror_f(float v) { return __int_as_float(row_ror_i<N>(__float_as_int(v))); }
+
+__device__ inline float group16_sum(float v) {
+    v += row_ror_f<8>(v);
+    v += row_ror_f<4>(v);
+    v += row_ror_f<2>(v);
+    v += row_ror_f<1>(v);
+    return v;
+}
+__device__ inline float group16_max(float v) {
+    v = fmaxf(v, row_ror_f<8>(v));
+    v = fmaxf(v, row_ror_f<4>(v));
+    v = fmaxf(v, row_ror_f<2>(v));
+    v = fmaxf(v, row_ror_f<1>(v));
+    return v;
+}
+// best = larger key, equal keys: lower expert id; the winner's logit rides along
+template <int N>
+__device__ inline void argmax_step(float& best, int& be, float& bz) {
+    const float ob = row_ror_f<N>(best);
+    const int oe = row_ror_i<N>(be);
+    const float oz = row_ror_f<N>(bz);
+    if (ob > best || (ob == best && oe < be)) { best = ob; be = oe; bz = oz; }
+}
+
+// Sixteen lanes per token, sixteen tokens per workgroup.  Sub-lane s holds the scores of
+// experts s, s+16, ...; each of the k rounds takes the group-wide maximum (equal values:
+// lower expert id) and retires it.  The slices of z_part are summed in slice order.
+template <int V>
+__global__ __launch_bounds__(256) void topk_gate_kernel(const float* __restrict__ z_part, int k_splits, int e_pad,
+                                                        const float* __restrict__ bias, int n_tokens, int n_experts,
+                                                        int k, int gating, int bias_mode,
+                                                        int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                        int32_t* __restrict__ hist_step, int32_t* __restrict__ hits,
+                                                        int32_t* __restrict__ idx_copy, float* __restrict__ w_copy) {
+    const int s = threadIdx.x & 15;
+    const int n_raw = blockIdx.x * 16 + (threadIdx.x >> 4);
+    const bool valid = n_raw < n_tokens;
+    const int n = valid ? n_raw : n_tokens - 1;
+    const float NEG = -__builtin_huge_valf();
+    // sub-lane s owns experts s*4..s*4+3 of every group of 64, so that one 16-byte load per
+    // group and slice fetches them; value j of the lane is expert EXPERT_OF(j)
+#define EXPERT_OF(j) ((((j) >> 2) << 6) + s * 4 + ((j) & 3))
+    float z[V], key[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) z[j] = 0.f;
+#pragma unroll
+    for (int p = 0; p < kMaxRouterSplits; ++p) {
+        if (p < k_splits) {
+            const float* row = z_part + ((int64_t)p * n_tokens + n) * e_pad + s * 4;
+            float4 part[V / 4];
+#pragma unroll
+            for (int g = 0; g < V / 4; ++g)
+                part[g] = (g * 64 + s * 4 < e_pad) ? *reinterpret_cast<const float4*>(row + g * 64) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int g = 0; g < V / 4; ++g) {
+                z[g * 4 + 0] += part[g].x;
+                z[g * 4 + 1] += part[g].y;
+                z[g * 4 + 2] += part[g].z;
+                z[g * 4 + 3] += part[g].w;
             }
         }
     }
 #pragma unroll
-    for (int t = 0; t < kTokPerWave; ++t) {
-        float v = acc[t];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-        if (lane == 0 && n0 + t < n_tokens) logits[(int64_t)(n0 + t) * n_experts + e] = v;
-    }
-}
-
-__device__ inline float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    return v;
-}
-__device__ inline float wave_max(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
-    return v;
-}
-
-// One wave per token.  Lane l holds the scores of experts l, l+64, ...; each of the k
-// rounds takes the wave-wide maximum (equal values: lower expert id) and retires it.
-template <int V>
-__global__ __launch_bounds__(64) void topk_gate_kernel(const float* __restrict__ logits,
-                                                       const float* __restrict__ bias, int n_experts, int k,
-                                                       int gating, int bias_mode, int32_t* __restrict__ topk_idx,
-                                                       float* __restrict__ topk_w, int32_t* __restrict__ hist_step,
-                                                       int32_t* __restrict__ hits, int32_t* __restrict__ idx_copy,
-                                                       float* __restrict__ w_copy) {
-    const int n = blockIdx.x;
-    const int lane = threadIdx.x;
-    const float NEG = -__builtin_huge_valf();
-    float z[V], key[V];
-#pragma unroll
     for (int j = 0; j < V; ++j) {
-        const int e = j * 64 + lane;
+        const int e = EXPERT_OF(j);
         float v = NEG;
         if (e < n_experts) {
-            v = logits[(int64_t)n * n_experts + e];
+            v = z[j];
             if (bias_mode == TIDE_BIAS_LOGIT) v += bias[e];
         }
         z[j] = v;
@@ -90,71 +180,66 @@ __global__ __launch_bounds__(64) void topk_gate_kernel(const float* __restrict__
         float m = NEG;
 #pragma unroll
         for (int j = 0; j < V; ++j) m = fmaxf(m, z[j]);
-        m = wave_max(m);
-        float p[V], sum = 0.f;
+        m = group16_max(m);
+        float sum = 0.f;
 #pragma unroll
         for (int j = 0; j < V; ++j) {
-            const int e = j * 64 + lane;
-            p[j] = 0.f;
+            const int e = EXPERT_OF(j);
             if (e < n_experts) {
-                p[j] = (gating == TIDE_GATING_SOFTMAX) ? expf(z[j] - m) : 1.f / (1.f + expf(-z[j]));
-                sum += p[j];
+                key[j] = (gating == TIDE_GATING_SOFTMAX) ? expf(z[j] - m) : 1.f / (1.f + expf(-z[j]));
+                sum += key[j];
             }
         }
-        sum = wave_sum(sum);
+        sum = group16_sum(sum);
 #pragma unroll
         for (int j = 0; j < V; ++j) {
-            const int e = j * 64 + lane;
-            if (e < n_experts) key[j] = ((gating == TIDE_GATING_SOFTMAX) ? p[j] / sum : p[j]) + bias[e];
+            const int e = EXPERT_OF(j);
+            if (e < n_experts) key[j] = ((gating == TIDE_GATING_SOFTMAX) ? key[j] / sum : key[j]) + bias[e];
         }
     }
 
-    int my_e = -1;      // lane i < k keeps the i-th selection
+    int my_e = 0;       // sub-lane i < k keeps the i-th selection
     float my_z = 0.f;
     for (int i = 0; i < k; ++i) {
-        float best = NEG;
+        float best = NEG, bz = 0.f;
         int be = 0x7fffffff;
 #pragma unroll
         for (int j = 0; j < V; ++j) {
-            const int e = j * 64 + lane;
-            if (e < n_experts && key[j] > best) { best = key[j]; be = e; }
+            const int e = EXPERT_OF(j);
+            if (e < n_experts && key[j] > best) { best = key[j]; be = e; bz = z[j]; }
         }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            const float ob = __shfl_xor(best, off);
-            const int oe = __shfl_xor(be, off);
-            if (ob > best || (ob == best && oe < be)) { best = ob; be = oe; }
-        }
+        argmax_step<8>(best, be, bz);
+        argmax_step<4>(best, be, bz);
+        argmax_step<2>(best, be, bz);
+        argmax_step<1>(best, be, bz);
         if (be == 0x7fffffff) be = 0;     // only with non-finite logits; keeps indexing in range
-        float zown = 0.f;
+        if (s == ((be >> 2) & 15)) {
 #pragma unroll
-        for (int j = 0; j < V; ++j) {
-            if (j == (be >> 6)) {
-                zown = z[j];
-                if (lane == (be & 63)) key[j] = NEG;
-            }
+            for (int j = 0; j < V; ++j)
+                if (j == ((be >> 6) << 2) + (be & 3)) key[j] = NEG;
         }
-        const float zsel = __shfl(zown, be & 63);
-        if (lane == i) { my_e = be; my_z = zsel; }
+        const float zsel = bz;
+        if (s == i) { my_e = be; my_z = zsel; }
     }
 
-    float s = 0.f;
+    float sc = 0.f;
     if (gating == TIDE_GATING_SOFTMAX) {
-        const float m = wave_max(lane < k ? my_z : NEG);
-        if (lane < k) s = expf(my_z - m);
+        const float m = group16_max(s < k ? my_z : NEG);
+        if (s < k) sc = expf(my_z - m);
     } else {
-        if (lane < k) s = 1.f / (1.f + expf(-my_z));
+        if (s < k) sc = 1.f / (1.f + expf(-my_z));
     }
-    const float tot = wave_sum(s);
-    if (lane < k) {
-        const float w = s / tot;
-        topk_idx[(int64_t)n * k + lane] = my_e;
-        topk_w[(int64_t)n * k + lane] = w;
-        if (idx_copy) idx_copy[(int64_t)n * k + lane] = my_e;
-        if (w_copy) w_copy[(int64_t)n * k + lane] = w;
+    const float tot = group16_sum(sc);
+    if (valid && s < k) {
+        const float w = sc / tot;
+        topk_idx[(int64_t)n * k + s] = my_e;
+        topk_w[(int64_t)n * k + s] = w;
+        if (idx_copy) idx_copy[(int64_t)n * k + s] = my_e;
+        if (w_copy) w_copy[(int64_t)n * k + s] = w;
         atomicAdd(&hist_step[my_e], 1);
         atomicAdd(&hits[my_e], 1);
     }
+#undef EXPERT_OF
 }
 
 __global__ void clear_i32_kernel(int32_t* p, int n) {
@@ -175,22 +260,43 @@ __global__ void count_pairs_kernel(const int32_t* __restrict__ topk_idx, int n_p
 
 }  // namespace
 
-hipError_t launch_router_logits(const Shape& s, const uint16_t* x, int n_tokens, const float* w_r, float* logits,
-                                int32_t* hist_step_to_clear, hipStream_t stream) {
-    dim3 grid(s.E, (n_tokens + kTokPerWave - 1) / kTokPerWave);
-    hipLaunchKernelGGL(router_logits_kernel, grid, dim3(64), 0, stream, x, n_tokens, s.d, s.E, w_r, logits,
-                       hist_step_to_clear);
+int router_k_splits(const Shape& s, int n_tokens) {
+    // enough workgroups to spread the router matrix over the chip when the token count is small
+    const int nt16 = n_tokens >= 256 ? 4 : 2;
+    const int base = ((s.E + 15) / 16) * ((n_tokens + nt16 * 16 - 1) / (nt16 * 16));
+    const int chunks = s.d / 32;
+    int ks = 1;
+    while (ks < kMaxRouterSplits && base * ks < 64 && chunks % (ks * 2) == 0 && chunks / (ks * 2) >= kRouterWaves) ks *= 2;
+    return ks;
+}
+
+hipError_t launch_router_logits(const Shape& s, const uint16_t* x, int n_tokens, const float* w_r, float* z_part,
+                                int32_t* hist_step_to_clear, hipStream_t stream, LaunchEvents ev) {
+    const int ks = router_k_splits(s, n_tokens);
+    const int e_pad = (s.E + 15) / 16 * 16;
+    if (n_tokens >= 256) {
+        dim3 grid(((s.E + 15) / 16) * ks, (n_tokens + 63) / 64);
+        TIDE_LAUNCH(router_logits_kernel<4>, grid, dim3(kRouterWaves * 64), stream, ev, x, n_tokens, s.d, s.E,
+                           e_pad, ks, w_r, z_part, hist_step_to_clear);
+    } else {
+        dim3 grid(((s.E + 15) / 16) * ks, (n_tokens + 31) / 32);
+        TIDE_LAUNCH(router_logits_kernel<2>, grid, dim3(kRouterWaves * 64), stream, ev, x, n_tokens, s.d, s.E,
+                           e_pad, ks, w_r, z_part, hist_step_to_clear);
+    }
     return hipGetLastError();
 }
 
-hipError_t launch_topk_gate(const Shape& s, const float* logits, const float* bias, int n_tokens,
+hipError_t launch_topk_gate(const Shape& s, const float* z_part, const float* bias, int n_tokens,
                             int32_t* topk_idx, float* topk_w, int32_t* hist_step, int32_t* hits,
-                            int32_t* idx_copy, float* w_copy, hipStream_t stream) {
+                            int32_t* idx_copy, float* w_copy, hipStream_t stream, LaunchEvents ev) {
+    const int ks = router_k_splits(s, n_tokens);
+    const int e_pad = (s.E + 15) / 16 * 16;
+    dim3 grid((n_tokens + 15) / 16);
     if (s.E <= 256) {
-        hipLaunchKernelGGL(topk_gate_kernel<4>, dim3(n_tokens), dim3(64), 0, stream, logits, bias, s.E, s.k,
+        TIDE_LAUNCH(topk_gate_kernel<16>, grid, dim3(256), stream, ev, z_part, ks, e_pad, bias, n_tokens, s.E, s.k,
                            s.gating, s.bias_mode, topk_idx, topk_w, hist_step, hits, idx_copy, w_copy);
     } else {
-        hipLaunchKernelGGL(topk_gate_kernel<8>, dim3(n_tokens), dim3(64), 0, stream, logits, bias, s.E, s.k,
+        TIDE_LAUNCH(topk_gate_kernel<32>, grid, dim3(256), stream, ev, z_part, ks, e_pad, bias, n_tokens, s.E, s.k,
                            s.gating, s.bias_mode, topk_idx, topk_w, hist_step, hits, idx_copy, w_copy);
     }
     return hipGetLastError();

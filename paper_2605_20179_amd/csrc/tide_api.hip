@@ -43,6 +43,12 @@ struct tide_ctx {
     hipEvent_t compute_mark = nullptr;
     int max_rows = 0, max_tasks = 0;
     std::string err;
+    // optional per-kernel timing: every kernel launch of a step stamps a start and a stop event
+    bool profiling = false;
+    std::vector<hipEvent_t> prof_pool;      // created on demand, reused
+    size_t prof_used = 0;
+    std::vector<std::pair<int, std::pair<hipEvent_t, hipEvent_t>>> prof_spans;   // (kernel id, begin, end)
+    int64_t steps_issued = 0;
 };
 
 namespace {
@@ -62,6 +68,29 @@ int fail(tide_ctx* ctx, int code, const char* fmt, ...) {
         hipError_t e_ = (call);                                                                      \
         if (e_ != hipSuccess) return fail(ctx, TIDE_E_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
     } while (0)
+
+hipEvent_t prof_event(tide_ctx* ctx) {
+    if (ctx->prof_used == ctx->prof_pool.size()) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        ctx->prof_pool.push_back(e);
+    }
+    return ctx->prof_pool[ctx->prof_used++];
+}
+
+// Runs `launch(ev)`; when profiling, ev carries two events that the launch stamps with the
+// dispatch's begin and end times.
+template <typename F>
+hipError_t timed(tide_ctx* ctx, int kernel_id, F&& launch) {
+    LaunchEvents ev;
+    if (!ctx->profiling) return launch(ev);
+    ev.start = prof_event(ctx);
+    ev.stop = prof_event(ctx);
+    if (!ev.start || !ev.stop) return hipErrorOutOfMemory;
+    hipError_t rc = launch(ev);
+    if (rc == hipSuccess) ctx->prof_spans.push_back({kernel_id, {ev.start, ev.stop}});
+    return rc;
+}
 
 int check_cfg(const tide_config* c) {
     if (!c) return fail(nullptr, TIDE_E_INVAL, "config is null");
@@ -112,16 +141,22 @@ int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, 
                 const float* w, float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
                 hipStream_t stream) {
     Layer& L = ctx->layers[layer];
-    TIDE_HIP(ctx, launch_dispatch(ctx->shape, L.t, ctx->ws, idx, w, n_tokens, miss_dev, miss_cap, n_miss_dev, stream));
+    TIDE_HIP(ctx, timed(ctx, TIDE_K_DISPATCH, [&](LaunchEvents ev) {
+        return launch_dispatch(ctx->shape, L.t, ctx->ws, idx, w, n_tokens, miss_dev, miss_cap, n_miss_dev, stream, ev); }));
     if (L.copies_pending) {
         TIDE_HIP(ctx, hipStreamWaitEvent(stream, L.copies_done, 0));
         L.copies_pending = false;
     }
     const int rows = n_tokens * ctx->cfg.top_k + (ctx->cfg.n_shared ? n_tokens : 0);
     const int max_tasks = ctx->cfg.capacity + 1 + rows / kRowsPerTask + 1;
-    TIDE_HIP(ctx, launch_expert_gemms(ctx->shape, L.t, ctx->ws, static_cast<const uint16_t*>(hidden_dev), n_tokens,
-                                      max_tasks, stream));
-    TIDE_HIP(ctx, launch_combine(ctx->shape, ctx->ws, w, n_tokens, out_dev, stream));
+    const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
+    TIDE_HIP(ctx, timed(ctx, TIDE_K_GATE_UP, [&](LaunchEvents ev) {
+        return launch_expert_gemm(0, ctx->shape, L.t, ctx->ws, x, n_tokens, max_tasks, stream, ev); }));
+    TIDE_HIP(ctx, timed(ctx, TIDE_K_DOWN, [&](LaunchEvents ev) {
+        return launch_expert_gemm(1, ctx->shape, L.t, ctx->ws, x, n_tokens, max_tasks, stream, ev); }));
+    TIDE_HIP(ctx, timed(ctx, TIDE_K_COMBINE, [&](LaunchEvents ev) {
+        return launch_combine(ctx->shape, ctx->ws, w, n_tokens, out_dev, stream, ev); }));
+    ctx->steps_issued++;
     return TIDE_OK;
 }
 
@@ -190,14 +225,16 @@ int tide_create(const tide_config* cfg, tide_ctx** out) {
     ctx->max_rows = (int)(P + (cfg->n_shared ? N : 0));
     ctx->max_tasks = cfg->capacity + 1 + ctx->max_rows / kRowsPerTask + 1;
     Workspace& w = ctx->ws;
-    if ((rc = ws_alloc(ctx, &w.logits, N * s.E)) || (rc = ws_alloc(ctx, &w.topk_idx, P)) ||
+    if ((rc = ws_alloc(ctx, &w.logits, (int64_t)kMaxRouterSplits * N * ((s.E + 15) / 16 * 16))) || (rc = ws_alloc(ctx, &w.topk_idx, P)) ||
         (rc = ws_alloc(ctx, &w.topk_w, P)) || (rc = ws_alloc(ctx, &w.hist_step, s.E)) ||
         (rc = ws_alloc(ctx, &w.row_token, ctx->max_rows)) || (rc = ws_alloc(ctx, &w.pair_row, P)) ||
         (rc = ws_alloc(ctx, &w.slot_off, s.capacity + 2)) || (rc = ws_alloc(ctx, &w.tasks, ctx->max_tasks)) ||
         (rc = ws_alloc(ctx, &w.n_tasks, 1)) || (rc = ws_alloc(ctx, &w.act, (int64_t)ctx->max_rows * s.I)) ||
-        (rc = ws_alloc(ctx, &w.y, (int64_t)ctx->max_rows * s.d)) || (rc = ws_alloc(ctx, &w.counts_tmp, s.E)))
+        (rc = ws_alloc(ctx, &w.y, (int64_t)ctx->max_rows * s.d)) || (rc = ws_alloc(ctx, &w.counts_tmp, s.E)) ||
+        (rc = ws_alloc(ctx, &w.counters, 4)))
         return bail(rc);
-    if (hipMemset(w.n_tasks, 0, sizeof(int32_t)) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "hipMemset failed"));
+    if (hipMemset(w.n_tasks, 0, sizeof(int32_t)) != hipSuccess || hipMemset(w.counters, 0, 4 * sizeof(int64_t)) != hipSuccess)
+        return bail(fail(ctx, TIDE_E_HIP, "hipMemset failed"));
 
     if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "side stream"));
     if (hipEventCreateWithFlags(&ctx->compute_mark, hipEventDisableTiming) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "event"));
@@ -232,6 +269,7 @@ int tide_destroy(tide_ctx* ctx) {
         if (L.copies_done) (void)hipEventDestroy(L.copies_done);
         if (L.plan) (void)hipHostFree(L.plan);
     }
+    for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
     if (ctx->compute_mark) (void)hipEventDestroy(ctx->compute_mark);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
     for (void* p : ctx->ws_allocs) (void)hipFree(p);
@@ -306,9 +344,11 @@ int tide_moe_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens
     if ((uintptr_t)router_w_dev & 15) return fail(ctx, TIDE_E_INVAL, "router_w_dev must be 16-byte aligned");
     Layer& L = ctx->layers[layer];
     const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
-    TIDE_HIP(ctx, launch_router_logits(ctx->shape, x, n_tokens, router_w_dev, ctx->ws.logits, ctx->ws.hist_step, stream));
-    TIDE_HIP(ctx, launch_topk_gate(ctx->shape, ctx->ws.logits, router_bias_dev, n_tokens, ctx->ws.topk_idx, ctx->ws.topk_w,
-                                   ctx->ws.hist_step, L.t.hits, topk_idx_dev, topk_w_dev, stream));
+    TIDE_HIP(ctx, timed(ctx, TIDE_K_ROUTER, [&](LaunchEvents ev) {
+        return launch_router_logits(ctx->shape, x, n_tokens, router_w_dev, ctx->ws.logits, ctx->ws.hist_step, stream, ev); }));
+    TIDE_HIP(ctx, timed(ctx, TIDE_K_TOPK, [&](LaunchEvents ev) {
+        return launch_topk_gate(ctx->shape, ctx->ws.logits, router_bias_dev, n_tokens, ctx->ws.topk_idx, ctx->ws.topk_w,
+                                ctx->ws.hist_step, L.t.hits, topk_idx_dev, topk_w_dev, stream, ev); }));
     return common_step(ctx, layer, hidden_dev, n_tokens, ctx->ws.topk_idx, ctx->ws.topk_w, out_dev, miss_dev, miss_cap,
                        n_miss_dev, stream);
 }
@@ -420,6 +460,39 @@ int tide_read_slot(tide_ctx* ctx, int layer, int slot, void* blob_host) {
     Layer& L = ctx->layers[layer];
     TIDE_HIP(ctx, hipDeviceSynchronize());
     TIDE_HIP(ctx, hipMemcpy(blob_host, slot_ptr(ctx, L, slot), tide_expert_blob_bytes(&ctx->cfg), hipMemcpyDeviceToHost));
+    return TIDE_OK;
+}
+
+int tide_profile(tide_ctx* ctx, int enable) {
+    if (!ctx) return TIDE_E_INVAL;
+    TIDE_HIP(ctx, hipDeviceSynchronize());
+    ctx->profiling = enable != 0;
+    ctx->prof_spans.clear();
+    ctx->prof_used = 0;
+    return TIDE_OK;
+}
+
+int tide_profile_read(tide_ctx* ctx, double* ms_sum, int64_t* launches) {
+    if (!ctx || !ms_sum || !launches) return ctx ? fail(ctx, TIDE_E_INVAL, "null output") : TIDE_E_INVAL;
+    TIDE_HIP(ctx, hipDeviceSynchronize());
+    for (int i = 0; i < TIDE_K_COUNT; ++i) { ms_sum[i] = 0.0; launches[i] = 0; }
+    for (auto& sp : ctx->prof_spans) {
+        float ms = 0.f;
+        TIDE_HIP(ctx, hipEventElapsedTime(&ms, sp.second.first, sp.second.second));
+        ms_sum[sp.first] += ms;
+        launches[sp.first] += 1;
+    }
+    ctx->prof_spans.clear();
+    ctx->prof_used = 0;
+    return TIDE_OK;
+}
+
+int tide_counters(tide_ctx* ctx, int64_t* out4, int reset, void* hip_stream) {
+    if (!ctx || !out4) return ctx ? fail(ctx, TIDE_E_INVAL, "null output") : TIDE_E_INVAL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    TIDE_HIP(ctx, hipMemcpyAsync(out4, ctx->ws.counters, 4 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+    if (reset) TIDE_HIP(ctx, launch_clear_i32(reinterpret_cast<int32_t*>(ctx->ws.counters), 8, stream));
+    TIDE_HIP(ctx, hipStreamSynchronize(stream));
     return TIDE_OK;
 }
 

@@ -2,6 +2,7 @@
 // Every launcher enqueues on `stream` and returns the hipError_t of the launch.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "tide.h"
@@ -9,8 +10,9 @@
 namespace tide {
 
 constexpr int kMaxExperts = 512;        // E limit: 8 router scores per lane of a 64-wide wave
-constexpr int kMaxTopK = 32;
-constexpr int kRowsPerTask = 64;        // token rows one expert-GEMM work item covers
+constexpr int kMaxTopK = 16;             // one selection per lane of a 16-lane group
+constexpr int kMaxRouterSplits = 8;      // slices of the hidden dimension the router logits are computed in
+constexpr int kRowsPerTask = 32;        // token rows one expert-GEMM work item covers
 
 // One grouped-GEMM work item: rows [row0, row0+nrows) of the slot-sorted row space
 // all belong to cache slot `slot` (slot == capacity means the shared expert).
@@ -23,7 +25,7 @@ struct Task {
 
 // Device-side workspace of one context (shared by its layers; one step at a time).
 struct Workspace {
-    float*   logits;      // [max_tokens][E]
+    float*   logits;      // [kMaxRouterSplits][max_tokens][E padded to 16] partial router logits
     int32_t* topk_idx;    // [max_tokens][k]
     float*   topk_w;      // [max_tokens][k]
     int32_t* hist_step;   // [E] hits of the step in flight
@@ -35,6 +37,7 @@ struct Workspace {
     uint16_t* act;        // [max_rows][d_ff] bf16 SwiGLU activations
     float*   y;           // [max_rows][d] per-row expert outputs
     int32_t* counts_tmp;  // [E] caller-provided counts for a refresh
+    int64_t* counters;    // [4] running totals: steps, active slots (shared included), rows, misses
 };
 
 struct LayerTables {
@@ -44,6 +47,21 @@ struct LayerTables {
     const uint16_t* slots;    // capacity (+1 shared) packed blobs, blob_elems apart
 };
 
+// Optional timing of one kernel launch: when both events are set the launch goes through
+// hipExtLaunchKernelGGL, which stamps them with the dispatch's own begin and end times
+// (no extra barrier packets in the stream, the kernel's neighbours are not disturbed).
+struct LaunchEvents {
+    hipEvent_t start = nullptr;
+    hipEvent_t stop = nullptr;
+};
+#define TIDE_LAUNCH(kernel, grid, block, stream, ev, ...)                                                   \
+    do {                                                                                                    \
+        if ((ev).start && (ev).stop)                                                                        \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, (ev).start, (ev).stop, 0, __VA_ARGS__);   \
+        else                                                                                                \
+            hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                                \
+    } while (0)
+
 struct Shape {
     int d, E, k, I, n_shared, capacity, gating, bias_mode;
     int64_t blob_elems;       // 3*d*I
@@ -51,11 +69,11 @@ struct Shape {
 
 // a1: z[n][e] = <x_n, W_r[e]>  (fp32)
 hipError_t launch_router_logits(const Shape& s, const uint16_t* x, int n_tokens, const float* w_r,
-                                float* logits, int32_t* hist_step_to_clear, hipStream_t stream);
+                                float* logits, int32_t* hist_step_to_clear, hipStream_t stream, LaunchEvents ev = {});
 // a2 + a3: gate, top-k, weights; hist_step[e] += 1 and hits[e] += 1 per selected pair
 hipError_t launch_topk_gate(const Shape& s, const float* logits, const float* bias, int n_tokens,
                             int32_t* topk_idx, float* topk_w, int32_t* hist_step, int32_t* hits,
-                            int32_t* idx_copy, float* w_copy, hipStream_t stream);
+                            int32_t* idx_copy, float* w_copy, hipStream_t stream, LaunchEvents ev = {});
 // a3 for token states that arrive routed: clear + count
 hipError_t launch_count_pairs(const Shape& s, const int32_t* topk_idx, int n_tokens, int32_t* hist_step,
                               int32_t* hits, hipStream_t stream);
@@ -64,13 +82,14 @@ hipError_t launch_clear_i32(int32_t* p, int n, hipStream_t stream);
 // a4 + a5: hit/miss split, canonical miss list, slot-sorted rows, work items
 hipError_t launch_dispatch(const Shape& s, const LayerTables& t, const Workspace& w, const int32_t* topk_idx,
                            const float* topk_w, int n_tokens, tide_miss* miss, int miss_cap, int32_t* n_miss,
-                           hipStream_t stream);
+                           hipStream_t stream, LaunchEvents ev = {});
 // a6 / a7 / a8: grouped SwiGLU expert GEMMs over the work items
-hipError_t launch_expert_gemms(const Shape& s, const LayerTables& t, const Workspace& w, const uint16_t* x,
-                               int n_tokens, int max_tasks, hipStream_t stream);
+// pass 0 = gate/up + SwiGLU -> act; pass 1 = down -> y
+hipError_t launch_expert_gemm(int pass, const Shape& s, const LayerTables& t, const Workspace& w, const uint16_t* x,
+                              int n_tokens, int max_tasks, hipStream_t stream, LaunchEvents ev = {});
 // a9: out[n] = shared row + sum over hit pairs in rank order of w * y[row]
 hipError_t launch_combine(const Shape& s, const Workspace& w, const float* topk_w, int n_tokens, float* out,
-                          hipStream_t stream);
+                          hipStream_t stream, LaunchEvents ev = {});
 // a11: top-capacity selection + slot plan, tables updated in place
 struct RefreshOut {           // lives in pinned host memory the kernel writes directly
     int32_t n_copies;

@@ -1,0 +1,37 @@
+"""Summarise a rocprofv3 --kernel-trace CSV of a bench.py run: per kernel, launches and
+mean/min/max duration over (a) every launch and (b) the launches of bench.py's timed region
+(launch numbers warmup .. warmup+steps-1 of each step kernel).
+
+usage: python -m paper_2605_20179_amd.profile_summary <kernel_trace.csv> --warmup W --steps K"""
+import argparse
+import csv
+import collections
+
+
+def short(name: str) -> str:
+    name = name.replace("tide::(anonymous namespace)::", "").replace("void ", "")
+    return name.split("(")[0]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("trace")
+    ap.add_argument("--warmup", type=int, required=True)
+    ap.add_argument("--steps", type=int, required=True)
+    a = ap.parse_args()
+    rows = collections.defaultdict(list)
+    with open(a.trace) as f:
+        for r in csv.DictReader(f):
+            rows[short(r["Kernel_Name"])].append((int(r["Start_Timestamp"]), int(r["End_Timestamp"])))
+    print("%-34s %8s %12s | %8s %12s %10s %10s" % ("kernel", "launches", "mean_us(all)", "timed", "mean_us", "min_us", "max_us"))
+    for k, v in sorted(rows.items(), key=lambda kv: -sum(e - s for s, e in kv[1])):
+        v.sort()
+        d = [(e - s) / 1e3 for s, e in v]
+        t = d[a.warmup:a.warmup + a.steps] if len(d) >= a.warmup + a.steps else []
+        line = "%-34s %8d %12.2f | " % (k[:34], len(d), sum(d) / len(d))
+        line += "%8d %12.2f %10.2f %10.2f" % (len(t), sum(t) / len(t), min(t), max(t)) if t else "%8s" % "-"
+        print(line)
+
+
+if __name__ == "__main__":
+    main()
