@@ -148,6 +148,8 @@ def main():
             if n:
                 kernels[name] = {"avg_us": 1e3 * ms_sum / n, "launches": n}
         ms_sum, n = prof["gate_up_swiglu"]
+        ms_big, n_big = prof.get("gate_up_swiglu_big", (0.0, 0))
+        ms_sum += ms_big        # slots with more than 32 rows run in a second launch of the same GEMM
         # algorithmic bytes of one gate/up launch: the gate and up matrices (2/3 of a blob) of every cache
         # slot that has a token this step (shared expert included), the step's hidden states once, and the
         # bf16 activations written
@@ -156,11 +158,12 @@ def main():
         bytes_per_launch = active_per_launch * (2 * blob / 3) + wl.N * wl.d * 2 + rows_per_launch * wl.I * 2
         avg_s = 1e-3 * ms_sum / n
         achieved = bytes_per_launch / avg_s / 1e9
-        roofline = {"bound": "hbm", "kernel": "expert_gemm_kernel<0> (grouped gate/up GEMM + SwiGLU)",
+        roofline = {"bound": "hbm", "kernel": "expert_gemm_kernel<0>%s (grouped gate/up GEMM + SwiGLU)" % (" + expert_gemm_big_kernel<0>" if n_big else ""),
                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                     "traffic": None, "avg_kernel_us": avg_s * 1e6, "algorithmic_bytes_per_launch": bytes_per_launch,
                     "active_slots_per_launch": active_per_launch}
         ms2, n2 = prof["down"]
+        ms2 += prof.get("down_big", (0.0, 0))[0]
         if n2:
             b2 = active_per_launch * (blob / 3) + rows_per_launch * wl.I * 2 + rows_per_launch * wl.d * 4
             roofline["down_kernel"] = {"achieved": b2 / (1e-3 * ms2 / n2) / 1e9, "frac": b2 / (1e-3 * ms2 / n2) / 1e9 / HBM_PEAK_GBS,

@@ -69,7 +69,8 @@ typedef struct {
 
 /* Allocates the context on the current HIP device: per layer `capacity` weight slots,
  * the hit counter H[E] (zero), the placement tables (all slots empty), and one
- * workspace sized by max_tokens.  Creates one side stream for refresh copies. */
+ * workspace sized by max_tokens.  Creates two streams of default priority: one for
+ * refresh copies, one on which a step's large work items run beside the small ones. */
 int tide_create(const tide_config* cfg, tide_ctx** out);
 int tide_destroy(tide_ctx* ctx);
 /* Text of the last error on ctx (ctx == NULL: last error of a failed tide_create). */
@@ -182,7 +183,9 @@ int tide_refresh_copy_ms(tide_ctx* ctx, int layer, float* ms_out);
 #define TIDE_K_GATE_UP  3   /* grouped gate/up GEMM + SwiGLU          */
 #define TIDE_K_DOWN     4   /* grouped down GEMM                      */
 #define TIDE_K_COMBINE  5   /* weighted combine                       */
-#define TIDE_K_COUNT    6
+#define TIDE_K_GATE_UP_BIG 6 /* the same two GEMMs over work items of up to 128 rows   */
+#define TIDE_K_DOWN_BIG    7 /* (slots with more than 32 rows; not launched at <= 32 tokens) */
+#define TIDE_K_COUNT    8
 
 /* enable != 0: from now on every kernel launch of a step carries a start and a stop HIP
  * event that the dispatch itself stamps when it begins and ends on its stream (no extra

@@ -24,7 +24,7 @@ EXPORTS = [
     "tide_interval_stats", "tide_refresh", "tide_wait_refresh", "tide_get_table", "tide_read_slot",
     "tide_refresh_copy_ms", "tide_profile", "tide_profile_read", "tide_counters",
 ]
-KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine"]
+KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
 
 class tide_config(C.Structure):

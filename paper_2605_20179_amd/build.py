@@ -17,6 +17,8 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+if os.environ.get("TIDE_EXTRA_DEFINES"):          # e.g. "-DTIDE_BIG_MIN_ROWS=128" for tuning builds
+    FLAGS += os.environ["TIDE_EXTRA_DEFINES"].split()
 
 
 def _hipcc() -> str:

@@ -42,13 +42,43 @@ __device__ inline int block_sum(int v, int* lds4) {
     return t;
 }
 
+// Work items of one slot whose m rows start at row0.
+__device__ inline void emit_tasks(int slot, int row0, int m, Task* small_out, Task* big_out, int big_room) {
+    if (m <= 0) return;
+    if (m <= kBigMinRows) {
+        const int ns = (m + kRowsPerTask - 1) / kRowsPerTask;
+        for (int c = threadIdx.x; c < ns; c += kThreads) {
+            Task t;
+            t.slot = slot;
+            t.row0 = row0 + c * kRowsPerTask;
+            t.nrows = min(kRowsPerTask, m - c * kRowsPerTask);
+            t.pad = 0;
+            small_out[c] = t;
+        }
+        return;
+    }
+    const int nb = (m + kRowsPerBigTask - 1) / kRowsPerBigTask;
+    // big_room < nb only if the caller's routing repeats an expert inside a token (not allowed):
+    // the surplus rows are then left uncomputed rather than written out of bounds
+    for (int c = threadIdx.x; c < nb && c < big_room; c += kThreads) {
+        Task t;
+        t.slot = slot;
+        t.row0 = row0 + c * kRowsPerBigTask;
+        t.nrows = min(kRowsPerBigTask, m - c * kRowsPerBigTask);
+        t.pad = 0;
+        big_out[c] = t;
+    }
+}
+
 // grid = capacity + 2 blocks: one per cache slot, one for the shared expert, one for the misses.
 __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w, int n_tokens, int k, int capacity,
     int n_shared, int n_experts, const int32_t* __restrict__ slot_of, const int32_t* __restrict__ expert_in_slot,
     const int32_t* __restrict__ hist_step, int32_t* __restrict__ row_token, int32_t* __restrict__ pair_row,
-    int32_t* __restrict__ slot_off, Task* __restrict__ tasks, int32_t* __restrict__ n_tasks,
-    tide_miss* __restrict__ miss, int miss_cap, int32_t* __restrict__ n_miss, int64_t* __restrict__ counters) {
+    int32_t* __restrict__ slot_off, Task* __restrict__ tasks, Task* __restrict__ big_tasks,
+    int32_t* __restrict__ n_tasks,
+    tide_miss* __restrict__ miss, int miss_cap, int32_t* __restrict__ n_miss, int64_t* __restrict__ counters,
+    int max_big) {
     __shared__ int lds4[kThreads / 64];
     const int s = blockIdx.x;
     const int tid = threadIdx.x;
@@ -90,34 +120,32 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
 
     // rows and work items that precede this slot
     const int upto = s < capacity ? s : capacity;
-    int rows_before = 0, tasks_before = 0, active_before = 0;
+    // a slot with up to kBigMinRows rows is cut into small work items of 32 rows, a fuller one into large ones of 128
+    int rows_before = 0, tasks_before = 0, big_before = 0, active_before = 0;
     for (int q = tid; q < upto; q += kThreads) {
         const int e = expert_in_slot[q];
         const int m = e >= 0 ? hist_step[e] : 0;
         rows_before += m;
-        tasks_before += (m + kRowsPerTask - 1) / kRowsPerTask;
+        tasks_before += m <= kBigMinRows ? (m + kRowsPerTask - 1) / kRowsPerTask : 0;
+        big_before += m > kBigMinRows ? (m + kRowsPerBigTask - 1) / kRowsPerBigTask : 0;
         active_before += m > 0 ? 1 : 0;
     }
     rows_before = block_sum(rows_before, lds4);
     tasks_before = block_sum(tasks_before, lds4);
+    big_before = block_sum(big_before, lds4);
 
     if (s == capacity) {
         // shared expert: every token, in token order
         const int m = n_shared ? n_tokens : 0;
         for (int n = tid; n < m; n += kThreads) row_token[rows_before + n] = n;
-        const int nt = (m + kRowsPerTask - 1) / kRowsPerTask;
-        for (int c = tid; c < nt; c += kThreads) {
-            Task t;
-            t.slot = capacity;
-            t.row0 = rows_before + c * kRowsPerTask;
-            t.nrows = min(kRowsPerTask, m - c * kRowsPerTask);
-            t.pad = 0;
-            tasks[tasks_before + c] = t;
-        }
+        const int n_small = m <= kBigMinRows ? (m + kRowsPerTask - 1) / kRowsPerTask : 0;
+        const int n_big = m > kBigMinRows ? (m + kRowsPerBigTask - 1) / kRowsPerBigTask : 0;
+        emit_tasks(capacity, rows_before, m, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
         if (tid == 0) {
             slot_off[capacity] = rows_before;
             slot_off[capacity + 1] = rows_before + m;
-            *n_tasks = tasks_before + nt;
+            n_tasks[0] = tasks_before + n_small;
+            n_tasks[1] = min(big_before + n_big, max_big);
         }
         active_before = block_sum(active_before, lds4);
         if (tid == 0) {
@@ -133,15 +161,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     const int m = e >= 0 ? hist_step[e] : 0;
     if (tid == 0) slot_off[s] = rows_before;
     if (m == 0) return;
-    const int nt = (m + kRowsPerTask - 1) / kRowsPerTask;
-    for (int c = tid; c < nt; c += kThreads) {
-        Task t;
-        t.slot = s;
-        t.row0 = rows_before + c * kRowsPerTask;
-        t.nrows = min(kRowsPerTask, m - c * kRowsPerTask);
-        t.pad = 0;
-        tasks[tasks_before + c] = t;
-    }
+    emit_tasks(s, rows_before, m, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
     int running = 0;
     for (int base = 0; base < n_pairs; base += kThreads) {
         const int p = base + tid;
@@ -164,7 +184,8 @@ hipError_t launch_dispatch(const Shape& s, const LayerTables& t, const Workspace
                            hipStream_t stream, LaunchEvents ev) {
     TIDE_LAUNCH(dispatch_kernel, dim3(s.capacity + 2), dim3(kThreads), stream, ev, topk_idx, topk_w,
                        n_tokens, s.k, s.capacity, s.n_shared, s.E, t.slot_of, t.expert_in_slot, w.hist_step,
-                       w.row_token, w.pair_row, w.slot_off, w.tasks, w.n_tasks, miss, miss_cap, n_miss, w.counters);
+                       w.row_token, w.pair_row, w.slot_off, w.tasks, w.big_tasks, w.n_tasks, miss, miss_cap, n_miss, w.counters,
+                max_big_tasks_for(s, n_tokens));
     return hipGetLastError();
 }
 

@@ -31,69 +31,91 @@ __device__ inline uint32_t f32_to_bf16_rne(float f) {
 
 __device__ inline float silu(float g) { return g / (1.f + __expf(-g)); }
 
-constexpr int kPhaseCols = 512;                 // activation columns staged in LDS at a time
-constexpr int kPhaseChunks = kPhaseCols / 32;
-constexpr int kLdsRowElems = kPhaseCols + 8;    // +16 B per row: the 16 rows of a fragment read hit distinct banks
-
-// grid.x = feature tile, grid.y = work item (blocks past *n_tasks leave at once).
-// PASS 0 (RT = 2): wave w of feature tile ft owns SwiGLU columns (4*ft + w)*16 .. +15: one gate
-//         tile and the matching up tile; K = d; activations gathered from hidden[row_token[row]].
-// PASS 1 (RT = 4): wave w owns output columns (4*ft + w)*64 .. +63: four down tiles; K = d_ff;
-//         activations = act[row].
+// Shared skeleton of the small (<= 32 rows) and large (<= 128 rows) work-item kernels.
 //
-// Weights: every wave streams its own row tiles from HBM straight into a ring of registers
-// that runs D chunks (D * RT KiB) ahead of the matrix cores -- what hides HBM latency when each
-// weight byte is used once.  Activations: the work item's token rows are shared by the
-// workgroup's waves, so they are staged through LDS, 512 columns at a time; the next stage's
-// rows are already in flight while the current one is consumed.
-template <int PASS, int NT, int D>
-__device__ inline void gemm_task(const uint16_t* const (&wt)[PASS == 0 ? 2 : 4], bool active, const Task& task,
-                                 const uint16_t* __restrict__ act_in, const int32_t* __restrict__ row_token, int K,
-                                 int n_out, int col0, uint16_t* __restrict__ act_out, float* __restrict__ y_out,
-                                 uint16_t* lds) {
-    constexpr int RT = PASS == 0 ? 2 : 4;
-    constexpr int kPieces = NT * 4;                  // 16-byte pieces each thread stages per phase
+//   PASS 0: a wave owns G gate stripes and the G matching up stripes (RT = 2G weight stripes of
+//           16 rows), i.e. SwiGLU columns wtile*16G .. +16G-1; K = d; activations are gathered
+//           from hidden[row_token[row]].
+//   PASS 1: a wave owns RT consecutive down stripes, i.e. output columns wtile*16RT .. ; K = d_ff;
+//           activations = act[row].
+//
+// Weights: every wave streams its own stripes from HBM (or L2, when several work items share a
+// slot) straight into a ring of registers that runs D chunks ahead of the matrix cores -- what
+// hides memory latency when each weight byte is used once.  Activations: the work item's token
+// rows are shared by the workgroup's four waves, so they are staged through LDS, PC chunks of 32
+// columns at a time; the next stage's rows are already in flight while the current one is used.
+// Tokens sit on the MFMA's 16-wide N side, NT token tiles per work item.
+template <int PASS, int RT, int NT, int D, int PC, int NBUF>
+__device__ inline void gemm_task(const uint16_t* blob, int64_t off_a, int64_t off_b, int wtile, bool active,
+                                 const Task& task, const uint16_t* __restrict__ act_in,
+                                 const int32_t* __restrict__ row_token, int K, int n_out,
+                                 uint16_t* __restrict__ act_out, float* __restrict__ y_out, uint16_t* lds) {
+    static_assert(PC % D == 0, "the ring must turn over a whole number of times per stage");
+    constexpr int G = RT / 2;                        // PASS 0: gate stripes per wave
+    constexpr int kCols = PC * 32;                   // columns per stage
+    constexpr int kRowElems = kCols + 8;             // +16 B per LDS row: a fragment's 16 rows hit distinct banks
+    constexpr int kPPR = PC * 4;                     // 16-byte pieces per staged row
+    constexpr int kPieces = NT * 16 * kPPR / 256;    // pieces each thread stages
+    static_assert(NT * 16 * kPPR % 256 == 0, "staging must divide evenly over the workgroup");
+    constexpr int kBufElems = NT * 16 * kRowElems;   // one staging buffer
     const int lane = threadIdx.x & 63;
     const int kchunks = K >> 5;
+    const int64_t stripe = (int64_t)kchunks * kTileElems;        // one 16-row stripe across all of K
+    const int col0 = wtile * 16 * (PASS == 0 ? G : RT);
 
-    // staging map: piece q = tid + 256*j covers row q/64 of the item, columns (q%64)*8 .. +7 of the phase
+    // a spare wave (columns past n_out) streams the last valid wave's stripes and stores nothing:
+    // it stays in step with the barriers without a predicate around the loop
+    const int wsrc = active ? wtile : (n_out / (16 * (PASS == 0 ? G : RT)) - 1);
+    const uint16_t* wt[RT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+        if (PASS == 0)
+            wt[r] = blob + (r < G ? off_a : off_b) + (int64_t)(wsrc * G + (r % G)) * stripe + lane * 8;
+        else
+            wt[r] = blob + off_a + (int64_t)(wsrc * RT + r) * stripe + lane * 8;
+    }
+
+    // staging map: piece q = tid + 256*j covers row q / kPPR of the item, columns (q % kPPR)*8 .. +7 of the stage
     const uint16_t* xsrc[kPieces];
 #pragma unroll
     for (int j = 0; j < kPieces; ++j) {
         const int q = threadIdx.x + 256 * j;
-        int r = q >> 6;
+        int r = q / kPPR;
         if (r >= task.nrows) r = 0;                  // padding rows mirror a valid row; never stored
         const int row = task.row0 + r;
         const int64_t src = (PASS == 0) ? (int64_t)row_token[row] : (int64_t)row;
-        xsrc[j] = act_in + src * K + (q & 63) * 8;
+        xsrc[j] = act_in + src * K + (q % kPPR) * 8;
     }
     uint4 xr[kPieces];
-    auto fetch_phase = [&](int phase) {
-        const int width = min(kPhaseCols, K - phase * kPhaseCols);
+    auto fetch_stage = [&](int stage) {
+        const int width = min(kCols, K - stage * kCols);
 #pragma unroll
         for (int j = 0; j < kPieces; ++j) {
-            const int c8 = ((threadIdx.x + 256 * j) & 63) * 8;
-            xr[j] = (c8 < width) ? *reinterpret_cast<const uint4*>(xsrc[j] + phase * kPhaseCols) : make_uint4(0, 0, 0, 0);
+            const int c8 = ((threadIdx.x + 256 * j) % kPPR) * 8;
+            xr[j] = (c8 < width) ? *reinterpret_cast<const uint4*>(xsrc[j] + stage * kCols) : make_uint4(0, 0, 0, 0);
         }
     };
-    auto store_phase = [&]() {
+    auto store_stage = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < kPieces; ++j) {
             const int q = threadIdx.x + 256 * j;
-            *reinterpret_cast<uint4*>(lds + (q >> 6) * kLdsRowElems + (q & 63) * 8) = xr[j];
+            *reinterpret_cast<uint4*>(lds + buf * kBufElems + (q / kPPR) * kRowElems + (q % kPPR) * 8) = xr[j];
         }
     };
-    fetch_phase(0);
+    fetch_stage(0);
+    if (NBUF == 2) {
+        // two buffers: stage s is written while stage s-1 is consumed, one barrier per stage
+        store_stage(0);
+        if (PC < kchunks) fetch_stage(1);
+    }
 
+    // ring prologue (chunk indices past the end are clamped: a redundant in-bounds load, never used)
     bf16x8 a[D][RT];
-    if (active) {
 #pragma unroll
-        for (int i = 0; i < D; ++i)
-            if (i < kchunks) {
+    for (int i = 0; i < D; ++i) {
+        const int ci = min(i, kchunks - 1);
 #pragma unroll
-                for (int r = 0; r < RT; ++r)
-                    a[i][r] = *reinterpret_cast<const bf16x8*>(wt[r] + (int64_t)i * kTileElems + lane * 8);
-            }
+        for (int r = 0; r < RT; ++r) a[i][r] = *reinterpret_cast<const bf16x8*>(wt[r] + (int64_t)ci * kTileElems);
     }
     f32x4 acc[RT][NT];
 #pragma unroll
@@ -101,44 +123,56 @@ __device__ inline void gemm_task(const uint16_t* const (&wt)[PASS == 0 ? 2 : 4],
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // this lane's fragment position inside a staged row block
-    const uint16_t* frag = lds + (lane & 15) * kLdsRowElems + (lane >> 4) * 8;
+    // this lane's fragment position inside a staged 16-row block
+    const uint16_t* frag = lds + (lane & 15) * kRowElems + (lane >> 4) * 8;
 
-    for (int base = 0; base < kchunks; base += D) {
-        if ((base & (kPhaseChunks - 1)) == 0) {
-            const int phase = base / kPhaseChunks;
-            if (phase) __syncthreads();              // everyone is done reading the previous stage
-            store_phase();
+    auto stage_switch = [&](int base) {
+        const int stage = base / PC;
+        if (NBUF == 1) {
+            if (stage) __syncthreads();              // everyone is done reading the previous stage
+            store_stage(0);
             __syncthreads();
-            if ((phase + 1) * kPhaseChunks < kchunks) fetch_phase(phase + 1);
-        }
-        if (active) {
-#pragma unroll
-            for (int i = 0; i < D; ++i) {
-                const int c = base + i;
-                if (c < kchunks) {
-                    bf16x8 b[NT];
-#pragma unroll
-                    for (int t = 0; t < NT; ++t)
-                        b[t] = *reinterpret_cast<const bf16x8*>(frag + t * 16 * kLdsRowElems + (c & (kPhaseChunks - 1)) * 32);
-#pragma unroll
-                    for (int r = 0; r < RT; ++r)
-#pragma unroll
-                        for (int t = 0; t < NT; ++t)
-                            acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][r], b[t], acc[r][t], 0, 0, 0);
-                    const int cn = c + D;
-                    if (cn < kchunks) {
-#pragma unroll
-                        for (int r = 0; r < RT; ++r)
-                            a[i][r] = *reinterpret_cast<const bf16x8*>(wt[r] + (int64_t)cn * kTileElems + lane * 8);
-                    }
-                }
+            if ((stage + 1) * PC < kchunks) fetch_stage(stage + 1);
+        } else {
+            __syncthreads();                         // stage's buffer is complete; the other one is free again
+            if ((stage + 1) * PC < kchunks) {
+                store_stage((stage + 1) & 1);
+                if ((stage + 2) * PC < kchunks) fetch_stage(stage + 2);
             }
         }
+    };
+    // chunk c: MFMAs from ring slot i and the staged fragments, then refill the slot D chunks ahead
+    auto chunk = [&](int c, int i) {
+        bf16x8 b[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+            b[t] = *reinterpret_cast<const bf16x8*>(frag + (NBUF == 2 ? ((c / PC) & 1) * kBufElems : 0) + t * 16 * kRowElems + (c % PC) * 32);
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][r], b[t], acc[r][t], 0, 0, 0);
+        const int cn = min(c + D, kchunks - 1);
+#pragma unroll
+        for (int r = 0; r < RT; ++r) a[i][r] = *reinterpret_cast<const bf16x8*>(wt[r] + (int64_t)cn * kTileElems);
+    };
+
+    // the main loop is straight-line (no per-chunk predicates): whole turns of the ring
+    int base = 0;
+    for (; base + D <= kchunks; base += D) {
+        if (base % PC == 0) stage_switch(base);
+#pragma unroll
+        for (int i = 0; i < D; ++i) chunk(base + i, i);
+    }
+    if (base < kchunks) {                            // a last partial turn (K not a multiple of 32*D)
+        if (base % PC == 0) stage_switch(base);
+#pragma unroll
+        for (int i = 0; i < D; ++i)
+            if (base + i < kchunks) chunk(base + i, i);
     }
     if (!active) return;
 
-    // MFMA result layout: lane holds token column lane%16, feature rows (lane/16)*4 .. +3 of each tile.
+    // MFMA result layout: lane holds token column lane%16, feature rows (lane/16)*4 .. +3 of each stripe.
     const int f4 = (lane >> 4) * 4;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -146,15 +180,18 @@ __device__ inline void gemm_task(const uint16_t* const (&wt)[PASS == 0 ? 2 : 4],
         if (rr >= task.nrows) continue;
         const int64_t row = task.row0 + rr;
         if (PASS == 0) {
-            const f32x4 g = acc[0][t], u = acc[1][t];
-            const uint32_t a0 = f32_to_bf16_rne(silu(g[0]) * u[0]);
-            const uint32_t a1 = f32_to_bf16_rne(silu(g[1]) * u[1]);
-            const uint32_t a2 = f32_to_bf16_rne(silu(g[2]) * u[2]);
-            const uint32_t a3 = f32_to_bf16_rne(silu(g[3]) * u[3]);
-            uint2 pk;
-            pk.x = a0 | (a1 << 16);
-            pk.y = a2 | (a3 << 16);
-            *reinterpret_cast<uint2*>(act_out + row * n_out + col0 + f4) = pk;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const f32x4 gt = acc[g][t], up = acc[g + G][t];
+                const uint32_t a0 = f32_to_bf16_rne(silu(gt[0]) * up[0]);
+                const uint32_t a1 = f32_to_bf16_rne(silu(gt[1]) * up[1]);
+                const uint32_t a2 = f32_to_bf16_rne(silu(gt[2]) * up[2]);
+                const uint32_t a3 = f32_to_bf16_rne(silu(gt[3]) * up[3]);
+                uint2 pk;
+                pk.x = a0 | (a1 << 16);
+                pk.y = a2 | (a3 << 16);
+                *reinterpret_cast<uint2*>(act_out + row * n_out + col0 + g * 16 + f4) = pk;
+            }
         } else {
 #pragma unroll
             for (int r = 0; r < RT; ++r) {
@@ -165,6 +202,9 @@ __device__ inline void gemm_task(const uint16_t* const (&wt)[PASS == 0 ? 2 : 4],
     }
 }
 
+// Small work items: up to 32 rows of one slot (the whole slot at block 32 / batch 1).
+// grid.x = feature tile, grid.y = work item (blocks past n_tasks[0] leave at once).
+constexpr int kSmallPC = 16;       // 512 columns per stage
 template <int PASS>
 __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
     const uint16_t* __restrict__ slots, int64_t blob_elems, int64_t off_a, int64_t off_b,
@@ -172,48 +212,94 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
     const int32_t* __restrict__ row_token, int K, int n_out, uint16_t* __restrict__ act_out,
     float* __restrict__ y_out) {
     constexpr int RT = PASS == 0 ? 2 : 4;
-    __shared__ __attribute__((aligned(16))) uint16_t lds[kRowsPerTask * kLdsRowElems];
+    constexpr int D = PASS == 0 ? 8 : 4;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[kRowsPerTask * (kSmallPC * 32 + 8)];
     const int task_id = blockIdx.y;
-    if (task_id >= *n_tasks) return;
-    const int wave = threadIdx.x >> 6;
-    const int wtile = blockIdx.x * kWaves + wave;            // this wave's group of RT row tiles
-    const int col0 = wtile * (PASS == 0 ? 16 : 64);          // first output column of the wave
-    const bool active = col0 < n_out;                        // spare waves still help staging
+    if (task_id >= n_tasks[0]) return;
+    const int wtile = blockIdx.x * kWaves + (threadIdx.x >> 6);
+    const bool active = wtile * 16 * (PASS == 0 ? RT / 2 : RT) < n_out;      // spare waves still help staging
     const Task task = tasks[task_id];
-    const int kchunks = K >> 5;
     const uint16_t* blob = slots + (int64_t)task.slot * blob_elems;
-    const int64_t tile_stride = (int64_t)kchunks * kTileElems;   // one 16-row tile across all of K
-
-    const uint16_t* wt[RT];
-    if (PASS == 0) {
-        wt[0] = blob + off_a + (int64_t)wtile * tile_stride;
-        wt[1] = blob + off_b + (int64_t)wtile * tile_stride;
-    } else {
-#pragma unroll
-        for (int r = 0; r < RT; ++r) wt[r] = blob + off_a + (int64_t)(wtile * 4 + r) * tile_stride;
-    }
-    const int nt = (task.nrows + 15) >> 4;
-    static_assert(kRowsPerTask == 32, "one or two 16-token tiles per work item");
-    if (nt == 1)
-        gemm_task<PASS, 1, (PASS == 0 ? 8 : 4)>(wt, active, task, act_in, row_token, K, n_out, col0, act_out, y_out, lds);
+    static_assert(kRowsPerTask == 32, "one or two 16-token tiles per small work item");
+    if (task.nrows <= 16)
+        gemm_task<PASS, RT, 1, D, kSmallPC, 1>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
     else
-        gemm_task<PASS, 2, (PASS == 0 ? 8 : 4)>(wt, active, task, act_in, row_token, K, n_out, col0, act_out, y_out, lds);
+        gemm_task<PASS, RT, 2, D, kSmallPC, 1>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
+}
+
+// Large work items: up to 128 rows of a slot that holds more than 32.  Each weight fragment now
+// feeds eight token tiles (32 MFMAs per wave and chunk), so a hot expert is bound by the matrix
+// cores rather than by weight traffic; the other work items of the same slot find the weights in L2.
+constexpr int kBigPC = 8;          // 256 columns per stage, two staging buffers
+constexpr int kXcds = 8;           // accelerator complex dies, each with its own L2
+template <int PASS>
+__global__ __launch_bounds__(kWaves * 64) void expert_gemm_big_kernel(
+    const uint16_t* __restrict__ slots, int64_t blob_elems, int64_t off_a, int64_t off_b,
+    const Task* __restrict__ tasks, const int32_t* __restrict__ n_tasks, const uint16_t* __restrict__ act_in,
+    const int32_t* __restrict__ row_token, int K, int n_out, uint16_t* __restrict__ act_out,
+    float* __restrict__ y_out, int n_ftiles) {
+    constexpr int RT = 4;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * kRowsPerBigTask * (kBigPC * 32 + 8)];
+    // Work units (work item, feature tile) are listed slot by slot, row chunk by row chunk, feature
+    // tile fastest, so neighbours share weight stripes or token rows.  Workgroups are handed to
+    // the chip's 8 XCDs round-robin by their linear id; XCD x takes the x-th contiguous eighth of
+    // the list in order, so the units in flight on one XCD find each other's data in its L2.
+    const int n_units = n_tasks[1] * n_ftiles;
+    const int seg = (n_units + kXcds - 1) / kXcds;
+    const int xcd = blockIdx.x % kXcds, j = blockIdx.x / kXcds;
+    const int unit = xcd * seg + j;
+    if (j >= seg || unit >= n_units) return;
+    const int task_id = unit / n_ftiles;
+    const int wtile = (unit % n_ftiles) * kWaves + (threadIdx.x >> 6);
+    const bool active = wtile * 16 * (PASS == 0 ? RT / 2 : RT) < n_out;
+    const Task task = tasks[task_id];
+    const uint16_t* blob = slots + (int64_t)task.slot * blob_elems;
+    static_assert(kRowsPerBigTask == 128, "eight 16-token tiles per large work item");
+    // only as many 16-token tiles as the item has rows: a 40-row item costs 3/8 of a full one
+#define TIDE_BIG_CASE(NT_)                                                                                              \
+    case NT_:                                                                                                           \
+        gemm_task<PASS, RT, NT_, 8, kBigPC, 2>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K, n_out,  \
+                                               act_out, y_out, lds);                                                   \
+        break;
+    switch ((task.nrows + 15) >> 4) {
+        TIDE_BIG_CASE(1) TIDE_BIG_CASE(2) TIDE_BIG_CASE(3) TIDE_BIG_CASE(4) TIDE_BIG_CASE(5) TIDE_BIG_CASE(6) TIDE_BIG_CASE(7)
+        default:
+            gemm_task<PASS, RT, 8, 8, kBigPC, 2>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K, n_out,
+                                                 act_out, y_out, lds);
+    }
+#undef TIDE_BIG_CASE
 }
 
 }  // namespace
 
 hipError_t launch_expert_gemm(int pass, const Shape& s, const LayerTables& t, const Workspace& w, const uint16_t* x,
-                              int n_tokens, int max_tasks, hipStream_t stream, LaunchEvents ev) {
-    (void)n_tokens;
+                              int max_tasks, hipStream_t stream, LaunchEvents ev) {
     dim3 block(kWaves * 64);
     if (pass == 0) {
         TIDE_LAUNCH(expert_gemm_kernel<0>, dim3((s.I + 63) / 64, max_tasks), block, stream, ev, t.slots, s.blob_elems,
-                           blob_off_gate(s), blob_off_up(s), w.tasks, w.n_tasks, x, w.row_token, s.d, s.I, w.act,
-                           (float*)nullptr);
+                    blob_off_gate(s), blob_off_up(s), w.tasks, w.n_tasks, x, w.row_token, s.d, s.I, w.act,
+                    (float*)nullptr);
     } else {
         TIDE_LAUNCH(expert_gemm_kernel<1>, dim3((s.d + 255) / 256, max_tasks), block, stream, ev, t.slots, s.blob_elems,
-                           blob_off_down(s), (int64_t)0, w.tasks, w.n_tasks, w.act, w.row_token, s.I, s.d,
-                           (uint16_t*)nullptr, w.y);
+                    blob_off_down(s), (int64_t)0, w.tasks, w.n_tasks, w.act, w.row_token, s.I, s.d,
+                    (uint16_t*)nullptr, w.y);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_expert_gemm_big(int pass, const Shape& s, const LayerTables& t, const Workspace& w,
+                                  const uint16_t* x, int max_big_tasks, hipStream_t stream, LaunchEvents ev) {
+    dim3 block(kWaves * 64);
+    if (pass == 0) {
+        const int ft = (s.I + 127) / 128;
+        TIDE_LAUNCH(expert_gemm_big_kernel<0>, dim3((max_big_tasks * ft + kXcds - 1) / kXcds * kXcds), block, stream, ev,
+                    t.slots, s.blob_elems, blob_off_gate(s), blob_off_up(s), w.big_tasks, w.n_tasks, x, w.row_token, s.d,
+                    s.I, w.act, (float*)nullptr, ft);
+    } else {
+        const int ft = (s.d + 255) / 256;
+        TIDE_LAUNCH(expert_gemm_big_kernel<1>, dim3((max_big_tasks * ft + kXcds - 1) / kXcds * kXcds), block, stream, ev,
+                    t.slots, s.blob_elems, blob_off_down(s), (int64_t)0, w.big_tasks, w.n_tasks, w.act, w.row_token, s.I,
+                    s.d, (uint16_t*)nullptr, w.y, ft);
     }
     return hipGetLastError();
 }

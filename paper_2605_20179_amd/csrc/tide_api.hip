@@ -39,7 +39,9 @@ struct tide_ctx {
     Workspace ws{};
     std::vector<void*> ws_allocs;
     std::vector<Layer> layers;
-    hipStream_t side = nullptr;
+    hipStream_t side = nullptr;             // refresh copies
+    hipStream_t aux = nullptr;              // large work items run here, beside the small ones
+    hipEvent_t fork_ev = nullptr, join_ev = nullptr;
     hipEvent_t compute_mark = nullptr;
     int max_rows = 0, max_tasks = 0;
     std::string err;
@@ -147,13 +149,25 @@ int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, 
         TIDE_HIP(ctx, hipStreamWaitEvent(stream, L.copies_done, 0));
         L.copies_pending = false;
     }
-    const int rows = n_tokens * ctx->cfg.top_k + (ctx->cfg.n_shared ? n_tokens : 0);
-    const int max_tasks = ctx->cfg.capacity + 1 + rows / kRowsPerTask + 1;
+    const int max_tasks = max_small_tasks_for(ctx->shape, n_tokens);
+    const int max_big = max_big_tasks_for(ctx->shape, n_tokens);
     const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
+    // Small and large work items touch disjoint rows: the large ones run on a second stream so that
+    // the two kinds of kernels overlap on the chip (fork after the split, join before the combine).
+    if (max_big > 0) {
+        TIDE_HIP(ctx, hipEventRecord(ctx->fork_ev, stream));
+        TIDE_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_ev, 0));
+        TIDE_HIP(ctx, timed(ctx, TIDE_K_GATE_UP_BIG, [&](LaunchEvents ev) {
+            return launch_expert_gemm_big(0, ctx->shape, L.t, ctx->ws, x, max_big, ctx->aux, ev); }));
+        TIDE_HIP(ctx, timed(ctx, TIDE_K_DOWN_BIG, [&](LaunchEvents ev) {
+            return launch_expert_gemm_big(1, ctx->shape, L.t, ctx->ws, x, max_big, ctx->aux, ev); }));
+        TIDE_HIP(ctx, hipEventRecord(ctx->join_ev, ctx->aux));
+    }
     TIDE_HIP(ctx, timed(ctx, TIDE_K_GATE_UP, [&](LaunchEvents ev) {
-        return launch_expert_gemm(0, ctx->shape, L.t, ctx->ws, x, n_tokens, max_tasks, stream, ev); }));
+        return launch_expert_gemm(0, ctx->shape, L.t, ctx->ws, x, max_tasks, stream, ev); }));
     TIDE_HIP(ctx, timed(ctx, TIDE_K_DOWN, [&](LaunchEvents ev) {
-        return launch_expert_gemm(1, ctx->shape, L.t, ctx->ws, x, n_tokens, max_tasks, stream, ev); }));
+        return launch_expert_gemm(1, ctx->shape, L.t, ctx->ws, x, max_tasks, stream, ev); }));
+    if (max_big > 0) TIDE_HIP(ctx, hipStreamWaitEvent(stream, ctx->join_ev, 0));
     TIDE_HIP(ctx, timed(ctx, TIDE_K_COMBINE, [&](LaunchEvents ev) {
         return launch_combine(ctx->shape, ctx->ws, w, n_tokens, out_dev, stream, ev); }));
     ctx->steps_issued++;
@@ -223,21 +237,27 @@ int tide_create(const tide_config* cfg, tide_ctx** out) {
 
     const int64_t N = cfg->max_tokens, P = N * cfg->top_k;
     ctx->max_rows = (int)(P + (cfg->n_shared ? N : 0));
-    ctx->max_tasks = cfg->capacity + 1 + ctx->max_rows / kRowsPerTask + 1;
+    ctx->max_tasks = max_small_tasks_for(s, cfg->max_tokens);
+    const int max_big = max_big_tasks_for(s, cfg->max_tokens);
     Workspace& w = ctx->ws;
     if ((rc = ws_alloc(ctx, &w.logits, (int64_t)kMaxRouterSplits * N * ((s.E + 15) / 16 * 16))) || (rc = ws_alloc(ctx, &w.topk_idx, P)) ||
         (rc = ws_alloc(ctx, &w.topk_w, P)) || (rc = ws_alloc(ctx, &w.hist_step, s.E)) ||
         (rc = ws_alloc(ctx, &w.row_token, ctx->max_rows)) || (rc = ws_alloc(ctx, &w.pair_row, P)) ||
         (rc = ws_alloc(ctx, &w.slot_off, s.capacity + 2)) || (rc = ws_alloc(ctx, &w.tasks, ctx->max_tasks)) ||
-        (rc = ws_alloc(ctx, &w.n_tasks, 1)) || (rc = ws_alloc(ctx, &w.act, (int64_t)ctx->max_rows * s.I)) ||
+        (rc = ws_alloc(ctx, &w.big_tasks, max_big + 1)) || (rc = ws_alloc(ctx, &w.n_tasks, 2)) || (rc = ws_alloc(ctx, &w.act, (int64_t)ctx->max_rows * s.I)) ||
         (rc = ws_alloc(ctx, &w.y, (int64_t)ctx->max_rows * s.d)) || (rc = ws_alloc(ctx, &w.counts_tmp, s.E)) ||
         (rc = ws_alloc(ctx, &w.counters, 4)))
         return bail(rc);
-    if (hipMemset(w.n_tasks, 0, sizeof(int32_t)) != hipSuccess || hipMemset(w.counters, 0, 4 * sizeof(int64_t)) != hipSuccess)
+    if (hipMemset(w.n_tasks, 0, 2 * sizeof(int32_t)) != hipSuccess || hipMemset(w.counters, 0, 4 * sizeof(int64_t)) != hipSuccess)
         return bail(fail(ctx, TIDE_E_HIP, "hipMemset failed"));
 
-    if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "side stream"));
-    if (hipEventCreateWithFlags(&ctx->compute_mark, hipEventDisableTiming) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "event"));
+    if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
+        hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking) != hipSuccess)
+        return bail(fail(ctx, TIDE_E_HIP, "stream creation failed"));
+    if (hipEventCreateWithFlags(&ctx->compute_mark, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->fork_ev, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->join_ev, hipEventDisableTiming) != hipSuccess)
+        return bail(fail(ctx, TIDE_E_HIP, "event creation failed"));
 
     ctx->layers.resize(cfg->n_layers);
     for (Layer& L : ctx->layers) {
@@ -271,7 +291,10 @@ int tide_destroy(tide_ctx* ctx) {
     }
     for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
     if (ctx->compute_mark) (void)hipEventDestroy(ctx->compute_mark);
+    if (ctx->fork_ev) (void)hipEventDestroy(ctx->fork_ev);
+    if (ctx->join_ev) (void)hipEventDestroy(ctx->join_ev);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    if (ctx->aux) (void)hipStreamDestroy(ctx->aux);
     for (void* p : ctx->ws_allocs) (void)hipFree(p);
     delete ctx;
     return TIDE_OK;

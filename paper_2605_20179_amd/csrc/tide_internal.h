@@ -12,7 +12,12 @@ namespace tide {
 constexpr int kMaxExperts = 512;        // E limit: 8 router scores per lane of a 64-wide wave
 constexpr int kMaxTopK = 16;             // one selection per lane of a 16-lane group
 constexpr int kMaxRouterSplits = 8;      // slices of the hidden dimension the router logits are computed in
-constexpr int kRowsPerTask = 32;        // token rows one expert-GEMM work item covers
+constexpr int kRowsPerTask = 32;        // rows of a small work item
+constexpr int kRowsPerBigTask = 128;    // rows of a large work item
+#ifndef TIDE_BIG_MIN_ROWS
+#define TIDE_BIG_MIN_ROWS 32
+#endif
+constexpr int kBigMinRows = TIDE_BIG_MIN_ROWS;   // a slot with more rows than this is cut into large work items, else into small ones
 
 // One grouped-GEMM work item: rows [row0, row0+nrows) of the slot-sorted row space
 // all belong to cache slot `slot` (slot == capacity means the shared expert).
@@ -32,8 +37,9 @@ struct Workspace {
     int32_t* row_token;   // [max_rows] token of each slot-sorted row
     int32_t* pair_row;    // [max_tokens*k] row of each (token, rank) pair, -1 = miss
     int32_t* slot_off;    // [capacity+2] first row of each slot (shared slot last), then total rows
-    Task*    tasks;       // [max_tasks]
-    int32_t* n_tasks;     // [1]
+    Task*    tasks;       // [max_small_tasks] small work items
+    Task*    big_tasks;   // [max_big_tasks] large work items
+    int32_t* n_tasks;     // [2] number of small, large work items
     uint16_t* act;        // [max_rows][d_ff] bf16 SwiGLU activations
     float*   y;           // [max_rows][d] per-row expert outputs
     int32_t* counts_tmp;  // [E] caller-provided counts for a refresh
@@ -84,9 +90,24 @@ hipError_t launch_dispatch(const Shape& s, const LayerTables& t, const Workspace
                            const float* topk_w, int n_tokens, tide_miss* miss, int miss_cap, int32_t* n_miss,
                            hipStream_t stream, LaunchEvents ev = {});
 // a6 / a7 / a8: grouped SwiGLU expert GEMMs over the work items
-// pass 0 = gate/up + SwiGLU -> act; pass 1 = down -> y
+// pass 0 = gate/up + SwiGLU -> act; pass 1 = down -> y; small and large work items
 hipError_t launch_expert_gemm(int pass, const Shape& s, const LayerTables& t, const Workspace& w, const uint16_t* x,
-                              int n_tokens, int max_tasks, hipStream_t stream, LaunchEvents ev = {});
+                              int max_tasks, hipStream_t stream, LaunchEvents ev = {});
+hipError_t launch_expert_gemm_big(int pass, const Shape& s, const LayerTables& t, const Workspace& w,
+                                  const uint16_t* x, int max_big_tasks, hipStream_t stream, LaunchEvents ev = {});
+// upper bound of the number of large work items a step over n_tokens tokens can produce
+inline int max_big_tasks_for(const Shape& s, int n_tokens) {
+    if (n_tokens <= kBigMinRows) return 0;
+    const int rows = n_tokens * s.k + (s.n_shared ? n_tokens : 0);
+    const int slots = s.capacity + 1;
+    const int busy = rows / (kBigMinRows + 1);           // slots that can exceed the small limit at once
+    return rows / kRowsPerBigTask + (busy < slots ? busy : slots);
+}
+// upper bound of the number of small work items
+inline int max_small_tasks_for(const Shape& s, int n_tokens) {
+    const int rows = n_tokens * s.k + (s.n_shared ? n_tokens : 0);
+    return s.capacity + 1 + rows / kRowsPerTask;
+}
 // a9: out[n] = shared row + sum over hit pairs in rank order of w * y[row]
 hipError_t launch_combine(const Shape& s, const Workspace& w, const float* topk_w, int n_tokens, float* out,
                           hipStream_t stream, LaunchEvents ev = {});
