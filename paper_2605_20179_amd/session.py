@@ -37,8 +37,9 @@ class TideSession:
         self.router_b: List[Optional[torch.Tensor]] = [None] * n_layers
 
     # ------------------------------------------------------------------ set-up
-    def load_layer(self, layer: int, expert_bits: ExpertBits, router_w: np.ndarray, router_bias: Optional[np.ndarray],
-                   resident: Sequence[int], workers: int = 8) -> None:
+    def pack_layer(self, expert_bits: ExpertBits, workers: int = 8):
+        """Packs a layer's E routed experts into one pinned tensor [E, blob_bytes] and the shared
+        expert (if any) into a host array.  The result can be attached to several sessions."""
         blobs = torch.empty((self.E, self.blob_bytes), dtype=torch.uint8, pin_memory=True)
         np_blobs = blobs.numpy()
 
@@ -48,11 +49,19 @@ class TideSession:
 
         with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as ex:
             list(ex.map(one, range(self.E)))
-        self.host_blobs[layer] = blobs
-        tb.tide_register_experts(self.ctx, layer, blobs, self.blob_bytes)
+        sh = None
         if self.n_shared:
             sh = np.empty(self.blob_bytes, dtype=np.uint8)
             tb.tide_pack_expert(self.cfg, *expert_bits(self.E), sh)
+        return blobs, sh
+
+    def load_layer(self, layer: int, expert_bits: Optional[ExpertBits], router_w: np.ndarray,
+                   router_bias: Optional[np.ndarray], resident: Sequence[int], workers: int = 8, packed=None) -> None:
+        blobs, sh = packed if packed is not None else self.pack_layer(expert_bits, workers)
+        assert tuple(blobs.shape) == (self.E, self.blob_bytes) and blobs.is_pinned()
+        self.host_blobs[layer] = blobs
+        tb.tide_register_experts(self.ctx, layer, blobs, self.blob_bytes)
+        if self.n_shared:
             tb.tide_set_shared(self.ctx, layer, sh)
         tb.tide_set_resident(self.ctx, layer, resident)
         self.router_w[layer] = torch.from_numpy(np.ascontiguousarray(router_w, dtype=np.float32)).to(self.device)
@@ -86,8 +95,9 @@ class TideSession:
         idx = self.topk_idx[:n_tokens].cpu().numpy()
         w = self.topk_w[:n_tokens].cpu().numpy()
         n_miss = int(self.n_miss.item())
-        raw = self.miss[:min(n_miss, self.miss.shape[0])].cpu().numpy()
-        miss = [(int(r[0]), int(r[1]), float(np.int32(r[2]).view(np.float32))) for r in raw]
+        raw = np.ascontiguousarray(self.miss[:min(n_miss, self.miss.shape[0])].cpu().numpy())
+        wts = raw[:, 2].copy().view(np.float32)
+        miss = [(int(r[0]), int(r[1]), float(x)) for r, x in zip(raw, wts)]
         return out, idx, w, miss, n_miss
 
     def stats(self, layer: int, reset: bool = False) -> np.ndarray:

@@ -111,7 +111,9 @@ def run_block_on_gpu(wl, layer, sess, log, hidden, forced, out_steps, tokens=Non
 
 
 def oracle_block(wl, layer, out_steps, tokens=None):
-    store = orc.ExpertStore(lambda e: ti.expert_weights(wl, layer, e), max_cached=wl.E + 1)
+    # fp64 copies of the experts the sampled tokens touch, capped at about 4 GB of host memory
+    store = orc.ExpertStore(lambda e: ti.expert_weights(wl, layer, e),
+                            max_cached=min(wl.E + 1, max(8, int(4e9 // (wl.expert_elems * 8)))))
     shared = tuple(orc.bf16_to_f64(m) for m in ti.expert_weights(wl, layer, wl.E)) if wl.n_shared else None
     hidden = list(ti.hidden_stream(wl, layer))
     log = orc.run_block(hidden, ti.router_weights(wl, layer), ti.router_bias(wl, layer), wl.gating, wl.bias_mode,
