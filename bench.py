@@ -28,7 +28,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
-def cpu_baseline(wl, ti, sample_steps=6):
+def cpu_baseline(wl, ti, sample_steps=20):
     """The oracle as it stands, on `sample_steps` consecutive denoise steps (all tokens,
     cold-start placement) of the benchmark workload."""
     import numpy as np
@@ -51,6 +51,22 @@ def cpu_baseline(wl, ti, sample_steps=6):
                       "%.1f s (includes bf16->fp64 weight conversion on first use)" % (sample_steps, wl.N, dt)}
 
 
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "cfg1_mini_layer_hbm_traffic.md")
+
+
+def read_traffic_summary():
+    """HBM bytes per launch of the dominant kernel as measured by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (scaled by a plain copy of known size); the measurement is kept as text under profiles/ because
+    a benchmark run cannot collect hardware counters on itself."""
+    try:
+        for line in open(TRAFFIC_SUMMARY):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1]), os.path.relpath(TRAFFIC_SUMMARY, ROOT)
+    except OSError:
+        pass
+    return None, None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +75,8 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload id (1 = the headline layer; 3 = flash-shaped layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run 8 plain device copies of 1 GiB (what rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled by) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)." % args.gpus,
@@ -74,6 +92,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; there is no CPU path.", file=sys.stderr)
         sys.exit(2)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")        # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(8):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 8}}))
+        return
     wl = ti.CONFIGS[args.config]
     sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode)
     sess.load_layer(0, lambda e: ti.expert_weights(wl, 0, e), ti.router_weights(wl, 0), ti.router_bias(wl, 0),
@@ -169,6 +195,8 @@ def main():
             roofline["down_kernel"] = {"achieved": b2 / (1e-3 * ms2 / n2) / 1e9, "frac": b2 / (1e-3 * ms2 / n2) / 1e9 / HBM_PEAK_GBS,
                                        "avg_kernel_us": 1e3 * ms2 / n2}
 
+    if roofline is not None and args.config == 1:
+        roofline["traffic"], roofline["traffic_source"] = read_traffic_summary()
     step_bytes = (cnt["active_slots"] / cnt["steps"]) * blob + wl.E * wl.d * 4 + wl.N * wl.d * 2 + wl.N * wl.d * 4
     out = {
         "metric": "MoE-layer tokens/s per denoise step", "value": value, "unit": "tokens/s", "n_gpus": 1,

@@ -205,14 +205,28 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_a, int64_t of
 // Small work items: up to 32 rows of one slot (the whole slot at block 32 / batch 1).
 // grid.x = feature tile, grid.y = work item (blocks past n_tasks[0] leave at once).
 constexpr int kSmallPC = 16;       // 512 columns per stage
+#ifndef TIDE_P0_RT
+#define TIDE_P0_RT 2
+#endif
+#ifndef TIDE_P0_D
+#define TIDE_P0_D 8
+#endif
+#ifndef TIDE_P1_RT
+#define TIDE_P1_RT 4
+#endif
+#ifndef TIDE_P1_D
+#define TIDE_P1_D 4
+#endif
+constexpr int kSmallRT0 = TIDE_P0_RT, kSmallD0 = TIDE_P0_D;   // gate/up: weight stripes per wave, ring depth
+constexpr int kSmallRT1 = TIDE_P1_RT, kSmallD1 = TIDE_P1_D;   // down
 template <int PASS>
 __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
     const uint16_t* __restrict__ slots, int64_t blob_elems, int64_t off_a, int64_t off_b,
     const Task* __restrict__ tasks, const int32_t* __restrict__ n_tasks, const uint16_t* __restrict__ act_in,
     const int32_t* __restrict__ row_token, int K, int n_out, uint16_t* __restrict__ act_out,
     float* __restrict__ y_out) {
-    constexpr int RT = PASS == 0 ? 2 : 4;
-    constexpr int D = PASS == 0 ? 8 : 4;
+    constexpr int RT = PASS == 0 ? kSmallRT0 : kSmallRT1;
+    constexpr int D = PASS == 0 ? kSmallD0 : kSmallD1;
     __shared__ __attribute__((aligned(16))) uint16_t lds[kRowsPerTask * (kSmallPC * 32 + 8)];
     const int task_id = blockIdx.y;
     if (task_id >= n_tasks[0]) return;
@@ -276,11 +290,11 @@ hipError_t launch_expert_gemm(int pass, const Shape& s, const LayerTables& t, co
                               int max_tasks, hipStream_t stream, LaunchEvents ev) {
     dim3 block(kWaves * 64);
     if (pass == 0) {
-        TIDE_LAUNCH(expert_gemm_kernel<0>, dim3((s.I + 63) / 64, max_tasks), block, stream, ev, t.slots, s.blob_elems,
+        TIDE_LAUNCH(expert_gemm_kernel<0>, dim3((s.I + 32 * kSmallRT0 - 1) / (32 * kSmallRT0), max_tasks), block, stream, ev, t.slots, s.blob_elems,
                     blob_off_gate(s), blob_off_up(s), w.tasks, w.n_tasks, x, w.row_token, s.d, s.I, w.act,
                     (float*)nullptr);
     } else {
-        TIDE_LAUNCH(expert_gemm_kernel<1>, dim3((s.d + 255) / 256, max_tasks), block, stream, ev, t.slots, s.blob_elems,
+        TIDE_LAUNCH(expert_gemm_kernel<1>, dim3((s.d + 64 * kSmallRT1 - 1) / (64 * kSmallRT1), max_tasks), block, stream, ev, t.slots, s.blob_elems,
                     blob_off_down(s), (int64_t)0, w.tasks, w.n_tasks, w.act, w.row_token, s.I, s.d,
                     (uint16_t*)nullptr, w.y);
     }

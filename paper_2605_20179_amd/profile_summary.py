@@ -2,7 +2,8 @@
 mean/min/max duration over (a) every launch and (b) the launches of bench.py's timed region
 (launch numbers warmup .. warmup+steps-1 of each step kernel).
 
-usage: python -m paper_2605_20179_amd.profile_summary <kernel_trace.csv> --warmup W --steps K"""
+usage: python -m paper_2605_20179_amd.profile_summary <kernel_trace.csv> --warmup W --steps K
+       python -m paper_2605_20179_amd.profile_summary <counter_collection.csv> --pmc --warmup W --steps K"""
 import argparse
 import csv
 import collections
@@ -13,12 +14,32 @@ def short(name: str) -> str:
     return name.split("(")[0]
 
 
+def pmc(path: str, warmup: int, steps: int) -> None:
+    """Per kernel and counter: mean over all dispatches and over the timed-region dispatches."""
+    rows = collections.defaultdict(lambda: collections.defaultdict(list))
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            rows[short(r["Kernel_Name"])][r["Counter_Name"]].append((int(r["Dispatch_Id"]), float(r["Counter_Value"])))
+    print("%-40s %-14s %8s %16s | %8s %16s" % ("kernel", "counter", "launches", "mean(all)", "timed", "mean(timed)"))
+    for k, d in sorted(rows.items()):
+        for c, v in sorted(d.items()):
+            v.sort()
+            x = [val for _, val in v]
+            t = x[warmup:warmup + steps] if len(x) >= warmup + steps else []
+            print("%-40s %-14s %8d %16.1f | %8d %16s" % (k[:40], c, len(x), sum(x) / len(x), len(t),
+                                                           "%.1f" % (sum(t) / len(t)) if t else "-"))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("trace")
     ap.add_argument("--warmup", type=int, required=True)
     ap.add_argument("--steps", type=int, required=True)
+    ap.add_argument("--pmc", action="store_true", help="the file is a rocprofv3 --pmc counter_collection CSV")
     a = ap.parse_args()
+    if a.pmc:
+        pmc(a.trace, a.warmup, a.steps)
+        return
     rows = collections.defaultdict(list)
     with open(a.trace) as f:
         for r in csv.DictReader(f):
