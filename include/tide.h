@@ -178,8 +178,8 @@ int tide_refresh_copy_ms(tide_ctx* ctx, int layer, float* ms_out);
 
 /* Kernels of one step, in launch order (ids for tide_profile_read). */
 #define TIDE_K_ROUTER   0   /* router logits                          */
-#define TIDE_K_TOPK     1   /* gate + top-k + hit counts              */
-#define TIDE_K_DISPATCH 2   /* hit/miss split, miss list, row lists   */
+#define TIDE_K_TOPK     1   /* gate + top-k + hit counts (at <= 32 tokens also the split below, in one workgroup) */
+#define TIDE_K_DISPATCH 2   /* hit/miss split, miss list, row lists (own launch above 32 tokens) */
 #define TIDE_K_GATE_UP  3   /* grouped gate/up GEMM + SwiGLU          */
 #define TIDE_K_DOWN     4   /* grouped down GEMM                      */
 #define TIDE_K_COMBINE  5   /* weighted combine                       */

@@ -2,6 +2,7 @@
 // wavefront shuffles, and the
 // per-step / per-interval hit counts (Sec. 3.1: k of E experts per token;
 // Fig. 1 caption: hits = number of tokens each expert has processed).
+#include "dispatch_small.h"
 #include "tide_internal.h"
 
 namespace tide {
@@ -123,12 +124,193 @@ __device__ inline void argmax_step(float& best, int& be, float& bz) {
     const float ob = row_ror_f<N>(best);
     const int oe = row_ror_i<N>(be);
     const float oz = row_ror_f<N>(bz);
-    if (ob > best || (ob == best && oe < be)) { best = ob; be = oe; bz = oz; }
+    const bool take = (ob > best) | ((ob == best) & (oe < be));      // branch-free selects
+    best = take ? ob : best;
+    be = take ? oe : be;
+    bz = take ? oz : bz;
 }
 
-// Sixteen lanes per token, sixteen tokens per workgroup.  Sub-lane s holds the scores of
-// experts s, s+16, ...; each of the k rounds takes the group-wide maximum (equal values:
-// lower expert id) and retires it.  The slices of z_part are summed in slice order.
+// sub-lane s owns experts s*4..s*4+3 of every group of 64, so that one 16-byte load per group and
+// slice fetches them; value j of the lane is expert EXPERT_OF(j)
+#define EXPERT_OF(j) ((((j) >> 2) << 6) + s * 4 + ((j) & 3))
+
+// Logits of 16 tokens (token n_base + tid/16), summed over the KS slices in slice order, plus the
+// logit bias.  Every load is unconditional and independent, so they are all in flight together:
+// one memory round trip instead of one per slice.
+template <int V, int KS>
+__device__ inline void load_logits16(int n_base, const float* __restrict__ z_part, int e_pad,
+                                     const float* __restrict__ bias, int bias_mode, int n_tokens, int n_experts,
+                                     float (&z)[V]) {
+    const int s = threadIdx.x & 15;
+    const int n = min(n_base + (int)(threadIdx.x >> 4), n_tokens - 1);
+    float4 part[KS][V / 4];
+#pragma unroll
+    for (int p = 0; p < KS; ++p) {
+        const float* row = z_part + ((int64_t)p * n_tokens + n) * e_pad;
+#pragma unroll
+        for (int g = 0; g < V / 4; ++g) {
+            const int col = min(g * 64 + s * 4, e_pad - 4);          // clamped: columns past E are masked below
+            part[p][g] = *reinterpret_cast<const float4*>(row + col);
+        }
+    }
+    float b[V];
+    if (bias_mode == TIDE_BIAS_LOGIT) {              // one uniform branch around all the loads
+#pragma unroll
+        for (int j = 0; j < V; ++j) b[j] = bias[min(EXPERT_OF(j), n_experts - 1)];
+    } else {
+#pragma unroll
+        for (int j = 0; j < V; ++j) b[j] = 0.f;
+    }
+#pragma unroll
+    for (int g = 0; g < V / 4; ++g) {
+        float4 acc = part[0][g];
+#pragma unroll
+        for (int p = 1; p < KS; ++p) {
+            acc.x += part[p][g].x;
+            acc.y += part[p][g].y;
+            acc.z += part[p][g].z;
+            acc.w += part[p][g].w;
+        }
+        z[g * 4 + 0] = acc.x + b[g * 4 + 0];
+        z[g * 4 + 1] = acc.y + b[g * 4 + 1];
+        z[g * 4 + 2] = acc.z + b[g * 4 + 2];
+        z[g * 4 + 3] = acc.w + b[g * 4 + 3];
+    }
+}
+
+template <int V>
+__device__ inline void load_logits16_any(int k_splits, int n_base, const float* __restrict__ z_part, int e_pad,
+                                         const float* __restrict__ bias, int bias_mode, int n_tokens, int n_experts,
+                                         float (&z)[V]) {
+    switch (k_splits) {
+        case 1: load_logits16<V, 1>(n_base, z_part, e_pad, bias, bias_mode, n_tokens, n_experts, z); break;
+        case 2: load_logits16<V, 2>(n_base, z_part, e_pad, bias, bias_mode, n_tokens, n_experts, z); break;
+        case 4: load_logits16<V, 4>(n_base, z_part, e_pad, bias, bias_mode, n_tokens, n_experts, z); break;
+        default: load_logits16<V, 8>(n_base, z_part, e_pad, bias, bias_mode, n_tokens, n_experts, z); break;
+    }
+}
+
+// Gate, top-k and weights of the 16 tokens whose (biased) logits are in z.
+// SMALL = true: the caller is the single workgroup that routes the whole step; selections are
+// mirrored into LDS (s_idx, s_w) and counted in an LDS histogram instead of global atomics.
+template <int V, bool SMALL, int NG>
+__device__ inline void select16(int n_base, float (&z)[NG][V], const float* __restrict__ bias, int n_tokens,
+                                int n_experts, int k, int gating, int bias_mode, int32_t* __restrict__ topk_idx,
+                                float* __restrict__ topk_w, int32_t* __restrict__ hist_step,
+                                int32_t* __restrict__ hits, int32_t* __restrict__ idx_copy,
+                                float* __restrict__ w_copy, unsigned* s_mask, int* s_idx, float* s_w) {
+    // NG groups of 16 tokens are worked on side by side: their dependency chains are independent,
+    // so the single wave per SIMD always has an instruction ready to issue
+    const int s = threadIdx.x & 15;
+    const float NEG = -__builtin_huge_valf();
+    int n[NG];
+    bool valid[NG];
+    float key[NG][V];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int n_raw = n_base + g * 16 + (threadIdx.x >> 4);
+        valid[g] = n_raw < n_tokens;
+        n[g] = valid[g] ? n_raw : n_tokens - 1;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            if (EXPERT_OF(j) >= n_experts) z[g][j] = NEG;
+            key[g][j] = z[g][j];      // both gates are monotone in the logit: select on it directly
+        }
+    }
+    if (bias_mode == TIDE_BIAS_SELECT) {
+        // selection score = gate score + bias
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            float m = NEG;
+#pragma unroll
+            for (int j = 0; j < V; ++j) m = fmaxf(m, z[g][j]);
+            m = group16_max(m);
+            float sum = 0.f;
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                if (EXPERT_OF(j) < n_experts) {
+                    key[g][j] = (gating == TIDE_GATING_SOFTMAX) ? expf(z[g][j] - m) : 1.f / (1.f + expf(-z[g][j]));
+                    sum += key[g][j];
+                }
+            }
+            sum = group16_sum(sum);
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const int e = EXPERT_OF(j);
+                if (e < n_experts) key[g][j] = ((gating == TIDE_GATING_SOFTMAX) ? key[g][j] / sum : key[g][j]) + bias[e];
+            }
+        }
+    }
+
+    int my_e[NG];       // sub-lane i < k keeps the i-th selection
+    float my_z[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) { my_e[g] = 0; my_z[g] = 0.f; }
+    for (int i = 0; i < k; ++i) {
+        // per-lane scan in ascending expert id with a strict compare keeps the lowest id among equals;
+        // experts past E hold -inf and never win; everything is select instructions, no branches
+        float best[NG], bz[NG];
+        int be[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) { best[g] = NEG; bz[g] = 0.f; be[g] = 0x7fffffff; }
+#pragma unroll
+        for (int j = 0; j < V; ++j)
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                const bool better = key[g][j] > best[g];
+                best[g] = better ? key[g][j] : best[g];
+                be[g] = better ? EXPERT_OF(j) : be[g];
+                bz[g] = better ? z[g][j] : bz[g];
+            }
+#pragma unroll
+        for (int g = 0; g < NG; ++g) argmax_step<8>(best[g], be[g], bz[g]);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) argmax_step<4>(best[g], be[g], bz[g]);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) argmax_step<2>(best[g], be[g], bz[g]);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) argmax_step<1>(best[g], be[g], bz[g]);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            be[g] = (be[g] == 0x7fffffff) ? 0 : be[g];     // only with non-finite logits; keeps indexing in range
+            const bool mine = s == ((be[g] >> 2) & 15);
+            const int jsel = ((be[g] >> 6) << 2) + (be[g] & 3);
+#pragma unroll
+            for (int j = 0; j < V; ++j) key[g][j] = (mine & (j == jsel)) ? NEG : key[g][j];
+            my_e[g] = (s == i) ? be[g] : my_e[g];
+            my_z[g] = (s == i) ? bz[g] : my_z[g];
+        }
+    }
+
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        float sc = 0.f;
+        if (gating == TIDE_GATING_SOFTMAX) {
+            const float m = group16_max(s < k ? my_z[g] : NEG);
+            if (s < k) sc = expf(my_z[g] - m);
+        } else {
+            if (s < k) sc = 1.f / (1.f + expf(-my_z[g]));
+        }
+        const float tot = group16_sum(sc);
+        if (valid[g] && s < k) {
+            const float w = sc / tot;
+            const int64_t p = (int64_t)n[g] * k + s;
+            topk_idx[p] = my_e[g];
+            topk_w[p] = w;
+            if (idx_copy) idx_copy[p] = my_e[g];
+            if (w_copy) w_copy[p] = w;
+            if (SMALL) {
+                atomicOr(&s_mask[my_e[g]], 1u << n[g]);      // which tokens chose the expert (order-free)
+                s_idx[p] = my_e[g];
+                s_w[p] = w;
+            } else {
+                atomicAdd(&hist_step[my_e[g]], 1);
+                atomicAdd(&hits[my_e[g]], 1);
+            }
+        }
+    }
+}
+
 template <int V>
 __global__ __launch_bounds__(256) void topk_gate_kernel(const float* __restrict__ z_part, int k_splits, int e_pad,
                                                         const float* __restrict__ bias, int n_tokens, int n_experts,
@@ -136,111 +318,56 @@ __global__ __launch_bounds__(256) void topk_gate_kernel(const float* __restrict_
                                                         int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
                                                         int32_t* __restrict__ hist_step, int32_t* __restrict__ hits,
                                                         int32_t* __restrict__ idx_copy, float* __restrict__ w_copy) {
-    const int s = threadIdx.x & 15;
-    const int n_raw = blockIdx.x * 16 + (threadIdx.x >> 4);
-    const bool valid = n_raw < n_tokens;
-    const int n = valid ? n_raw : n_tokens - 1;
-    const float NEG = -__builtin_huge_valf();
-    // sub-lane s owns experts s*4..s*4+3 of every group of 64, so that one 16-byte load per
-    // group and slice fetches them; value j of the lane is expert EXPERT_OF(j)
-#define EXPERT_OF(j) ((((j) >> 2) << 6) + s * 4 + ((j) & 3))
-    float z[V], key[V];
-#pragma unroll
-    for (int j = 0; j < V; ++j) z[j] = 0.f;
-#pragma unroll
-    for (int p = 0; p < kMaxRouterSplits; ++p) {
-        if (p < k_splits) {
-            const float* row = z_part + ((int64_t)p * n_tokens + n) * e_pad + s * 4;
-            float4 part[V / 4];
-#pragma unroll
-            for (int g = 0; g < V / 4; ++g)
-                part[g] = (g * 64 + s * 4 < e_pad) ? *reinterpret_cast<const float4*>(row + g * 64) : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-            for (int g = 0; g < V / 4; ++g) {
-                z[g * 4 + 0] += part[g].x;
-                z[g * 4 + 1] += part[g].y;
-                z[g * 4 + 2] += part[g].z;
-                z[g * 4 + 3] += part[g].w;
-            }
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < V; ++j) {
-        const int e = EXPERT_OF(j);
-        float v = NEG;
-        if (e < n_experts) {
-            v = z[j];
-            if (bias_mode == TIDE_BIAS_LOGIT) v += bias[e];
-        }
-        z[j] = v;
-        key[j] = v;      // both gates are monotone in the logit: select on it directly
-    }
-    if (bias_mode == TIDE_BIAS_SELECT) {
-        // selection score = gate score + bias
-        float m = NEG;
-#pragma unroll
-        for (int j = 0; j < V; ++j) m = fmaxf(m, z[j]);
-        m = group16_max(m);
-        float sum = 0.f;
-#pragma unroll
-        for (int j = 0; j < V; ++j) {
-            const int e = EXPERT_OF(j);
-            if (e < n_experts) {
-                key[j] = (gating == TIDE_GATING_SOFTMAX) ? expf(z[j] - m) : 1.f / (1.f + expf(-z[j]));
-                sum += key[j];
-            }
-        }
-        sum = group16_sum(sum);
-#pragma unroll
-        for (int j = 0; j < V; ++j) {
-            const int e = EXPERT_OF(j);
-            if (e < n_experts) key[j] = ((gating == TIDE_GATING_SOFTMAX) ? key[j] / sum : key[j]) + bias[e];
-        }
-    }
-
-    int my_e = 0;       // sub-lane i < k keeps the i-th selection
-    float my_z = 0.f;
-    for (int i = 0; i < k; ++i) {
-        float best = NEG, bz = 0.f;
-        int be = 0x7fffffff;
-#pragma unroll
-        for (int j = 0; j < V; ++j) {
-            const int e = EXPERT_OF(j);
-            if (e < n_experts && key[j] > best) { best = key[j]; be = e; bz = z[j]; }
-        }
-        argmax_step<8>(best, be, bz);
-        argmax_step<4>(best, be, bz);
-        argmax_step<2>(best, be, bz);
-        argmax_step<1>(best, be, bz);
-        if (be == 0x7fffffff) be = 0;     // only with non-finite logits; keeps indexing in range
-        if (s == ((be >> 2) & 15)) {
-#pragma unroll
-            for (int j = 0; j < V; ++j)
-                if (j == ((be >> 6) << 2) + (be & 3)) key[j] = NEG;
-        }
-        const float zsel = bz;
-        if (s == i) { my_e = be; my_z = zsel; }
-    }
-
-    float sc = 0.f;
-    if (gating == TIDE_GATING_SOFTMAX) {
-        const float m = group16_max(s < k ? my_z : NEG);
-        if (s < k) sc = expf(my_z - m);
-    } else {
-        if (s < k) sc = 1.f / (1.f + expf(-my_z));
-    }
-    const float tot = group16_sum(sc);
-    if (valid && s < k) {
-        const float w = sc / tot;
-        topk_idx[(int64_t)n * k + s] = my_e;
-        topk_w[(int64_t)n * k + s] = w;
-        if (idx_copy) idx_copy[(int64_t)n * k + s] = my_e;
-        if (w_copy) w_copy[(int64_t)n * k + s] = w;
-        atomicAdd(&hist_step[my_e], 1);
-        atomicAdd(&hits[my_e], 1);
-    }
-#undef EXPERT_OF
+    float z[1][V];
+    load_logits16_any<V>(k_splits, blockIdx.x * 16, z_part, e_pad, bias, bias_mode, n_tokens, n_experts, z[0]);
+    select16<V, false, 1>(blockIdx.x * 16, z, bias, n_tokens, n_experts, k, gating, bias_mode, topk_idx, topk_w,
+                          hist_step, hits, idx_copy, w_copy, nullptr, nullptr, nullptr);
 }
+
+// A step of at most 32 tokens is routed by ONE workgroup: top-k of every token, the step's
+// histogram (in LDS), H += histogram, then the hit/miss split -- all without leaving the CU, so
+// nothing has to travel through memory between routing and split and no launch separates them.
+template <int V>
+__global__ __launch_bounds__(256) void route_small_kernel(const float* __restrict__ z_part, int k_splits, int e_pad,
+                                                          const float* __restrict__ bias, int n_experts, int gating,
+                                                          int bias_mode, int32_t* __restrict__ topk_idx,
+                                                          float* __restrict__ topk_w, int32_t* __restrict__ hits,
+                                                          int32_t* __restrict__ idx_copy, float* __restrict__ w_copy,
+                                                          DispatchArgs da) {
+    __shared__ unsigned s_mask[kMaxExperts];     // per expert: bit n set when token n selected it
+    __shared__ int s_slot_of[kMaxExperts];
+    __shared__ int s_eis[kMaxExperts];
+    __shared__ int s_idx[kSmallDispatchMaxPairs];
+    __shared__ float s_w[kSmallDispatchMaxPairs];
+    __shared__ int s_work[kSmallDispatchLdsInts];
+    // everything the workgroup needs from memory is requested up front -- the placement tables and the
+    // logits of both groups of 16 tokens -- because each dependent round trip to memory costs microseconds
+    int t_slot[kMaxExperts / 256], t_eis[kMaxExperts / 256];
+#pragma unroll
+    for (int q = 0; q < kMaxExperts / 256; ++q) {
+        const int e = threadIdx.x + 256 * q;
+        t_slot[q] = da.slot_of[min(e, n_experts - 1)];
+        t_eis[q] = da.expert_in_slot[min(e, da.capacity - 1)];
+    }
+    float z[2][V];
+    load_logits16_any<V>(k_splits, 0, z_part, e_pad, bias, bias_mode, da.n_tokens, n_experts, z[0]);
+    load_logits16_any<V>(k_splits, 16, z_part, e_pad, bias, bias_mode, da.n_tokens, n_experts, z[1]);
+#pragma unroll
+    for (int q = 0; q < kMaxExperts / 256; ++q) {
+        const int e = threadIdx.x + 256 * q;
+        s_mask[e] = 0u;
+        s_slot_of[e] = t_slot[q];
+        s_eis[e] = t_eis[q];
+    }
+    __syncthreads();
+    select16<V, true, 2>(0, z, bias, da.n_tokens, n_experts, da.k, gating, bias_mode, topk_idx, topk_w, nullptr, hits,
+                         idx_copy, w_copy, s_mask, s_idx, s_w);
+    __syncthreads();
+    for (int e = threadIdx.x; e < n_experts; e += 256)
+        if (s_mask[e]) hits[e] += __popc(s_mask[e]);     // this workgroup is the step's only writer of H
+    dispatch_small(da, s_mask, s_slot_of, s_eis, s_idx, s_w, s_work);
+}
+#undef EXPERT_OF
 
 __global__ void clear_i32_kernel(int32_t* p, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -299,6 +426,29 @@ hipError_t launch_topk_gate(const Shape& s, const float* z_part, const float* bi
         TIDE_LAUNCH(topk_gate_kernel<32>, grid, dim3(256), stream, ev, z_part, ks, e_pad, bias, n_tokens, s.E, s.k,
                            s.gating, s.bias_mode, topk_idx, topk_w, hist_step, hits, idx_copy, w_copy);
     }
+    return hipGetLastError();
+}
+
+bool routes_in_one_workgroup(const Shape& s, int n_tokens) {
+    return n_tokens <= kSmallDispatchMaxTokens && n_tokens * s.k <= kSmallDispatchMaxPairs;
+}
+
+hipError_t launch_route_small(const Shape& s, const LayerTables& t, const Workspace& w, const float* bias, int n_tokens,
+                              int32_t* idx_copy, float* w_copy, tide_miss* miss, int miss_cap, int32_t* n_miss,
+                              hipStream_t stream, LaunchEvents ev) {
+    const int ks = router_k_splits(s, n_tokens);
+    const int e_pad = (s.E + 15) / 16 * 16;
+    DispatchArgs da;
+    da.n_tokens = n_tokens; da.k = s.k; da.capacity = s.capacity; da.n_shared = s.n_shared; da.n_experts = s.E;
+    da.slot_of = t.slot_of; da.expert_in_slot = t.expert_in_slot; da.row_token = w.row_token; da.pair_row = w.pair_row;
+    da.slot_off = w.slot_off; da.tasks = w.tasks; da.n_tasks = w.n_tasks; da.miss = miss; da.miss_cap = miss_cap;
+    da.n_miss = n_miss; da.counters = w.counters;
+    if (s.E <= 256)
+        TIDE_LAUNCH(route_small_kernel<16>, dim3(1), dim3(256), stream, ev, w.logits, ks, e_pad, bias, s.E, s.gating,
+                    s.bias_mode, w.topk_idx, w.topk_w, t.hits, idx_copy, w_copy, da);
+    else
+        TIDE_LAUNCH(route_small_kernel<32>, dim3(1), dim3(256), stream, ev, w.logits, ks, e_pad, bias, s.E, s.gating,
+                    s.bias_mode, w.topk_idx, w.topk_w, t.hits, idx_copy, w_copy, da);
     return hipGetLastError();
 }
 

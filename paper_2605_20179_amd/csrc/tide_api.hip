@@ -141,10 +141,11 @@ void pack_matrix(const uint16_t* src, int rows, int cols, uint16_t* dst) {
 
 int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const int32_t* idx,
                 const float* w, float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
-                hipStream_t stream) {
+                hipStream_t stream, bool split_done) {
     Layer& L = ctx->layers[layer];
-    TIDE_HIP(ctx, timed(ctx, TIDE_K_DISPATCH, [&](LaunchEvents ev) {
-        return launch_dispatch(ctx->shape, L.t, ctx->ws, idx, w, n_tokens, miss_dev, miss_cap, n_miss_dev, stream, ev); }));
+    if (!split_done)
+        TIDE_HIP(ctx, timed(ctx, TIDE_K_DISPATCH, [&](LaunchEvents ev) {
+            return launch_dispatch(ctx->shape, L.t, ctx->ws, idx, w, n_tokens, miss_dev, miss_cap, n_miss_dev, stream, ev); }));
     if (L.copies_pending) {
         TIDE_HIP(ctx, hipStreamWaitEvent(stream, L.copies_done, 0));
         L.copies_pending = false;
@@ -369,11 +370,18 @@ int tide_moe_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens
     const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
     TIDE_HIP(ctx, timed(ctx, TIDE_K_ROUTER, [&](LaunchEvents ev) {
         return launch_router_logits(ctx->shape, x, n_tokens, router_w_dev, ctx->ws.logits, ctx->ws.hist_step, stream, ev); }));
-    TIDE_HIP(ctx, timed(ctx, TIDE_K_TOPK, [&](LaunchEvents ev) {
-        return launch_topk_gate(ctx->shape, ctx->ws.logits, router_bias_dev, n_tokens, ctx->ws.topk_idx, ctx->ws.topk_w,
-                                ctx->ws.hist_step, L.t.hits, topk_idx_dev, topk_w_dev, stream, ev); }));
+    const bool one_wg = routes_in_one_workgroup(ctx->shape, n_tokens);
+    if (one_wg) {
+        TIDE_HIP(ctx, timed(ctx, TIDE_K_TOPK, [&](LaunchEvents ev) {
+            return launch_route_small(ctx->shape, L.t, ctx->ws, router_bias_dev, n_tokens, topk_idx_dev, topk_w_dev, miss_dev,
+                                      miss_cap, n_miss_dev, stream, ev); }));
+    } else {
+        TIDE_HIP(ctx, timed(ctx, TIDE_K_TOPK, [&](LaunchEvents ev) {
+            return launch_topk_gate(ctx->shape, ctx->ws.logits, router_bias_dev, n_tokens, ctx->ws.topk_idx, ctx->ws.topk_w,
+                                    ctx->ws.hist_step, L.t.hits, topk_idx_dev, topk_w_dev, stream, ev); }));
+    }
     return common_step(ctx, layer, hidden_dev, n_tokens, ctx->ws.topk_idx, ctx->ws.topk_w, out_dev, miss_dev, miss_cap,
-                       n_miss_dev, stream);
+                       n_miss_dev, stream, one_wg);
 }
 
 int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const int32_t* topk_idx_dev,
@@ -390,7 +398,7 @@ int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n
     Layer& L = ctx->layers[layer];
     TIDE_HIP(ctx, launch_count_pairs(ctx->shape, topk_idx_dev, n_tokens, ctx->ws.hist_step, L.t.hits, stream));
     return common_step(ctx, layer, hidden_dev, n_tokens, topk_idx_dev, topk_w_dev, out_dev, miss_dev, miss_cap,
-                       n_miss_dev, stream);
+                       n_miss_dev, stream, false);
 }
 
 int tide_interval_stats(tide_ctx* ctx, int layer, int32_t* counts_host, int reset, void* hip_stream) {

@@ -80,6 +80,11 @@ hipError_t launch_router_logits(const Shape& s, const uint16_t* x, int n_tokens,
 hipError_t launch_topk_gate(const Shape& s, const float* logits, const float* bias, int n_tokens,
                             int32_t* topk_idx, float* topk_w, int32_t* hist_step, int32_t* hits,
                             int32_t* idx_copy, float* w_copy, hipStream_t stream, LaunchEvents ev = {});
+// a2..a5 for a step of at most 32 tokens, in one workgroup: top-k, weights, counts, hit/miss split
+bool routes_in_one_workgroup(const Shape& s, int n_tokens);
+hipError_t launch_route_small(const Shape& s, const LayerTables& t, const Workspace& w, const float* bias, int n_tokens,
+                              int32_t* idx_copy, float* w_copy, tide_miss* miss, int miss_cap, int32_t* n_miss,
+                              hipStream_t stream, LaunchEvents ev = {});
 // a3 for token states that arrive routed: clear + count
 hipError_t launch_count_pairs(const Shape& s, const int32_t* topk_idx, int n_tokens, int32_t* hist_step,
                               int32_t* hits, hipStream_t stream);
