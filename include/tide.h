@@ -131,7 +131,7 @@ int tide_moe_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens
 
 /* The same step for token states that already carry their expert selections
  * (Alg. 1 takes X = {(x, E_x)} as given): topk_idx_dev / topk_w_dev are INPUTS
- * (expert ids must be in [0,E) and distinct per token).  Counts, split, expert
+ * (expert ids must be in [0,E) and distinct per token; topk_idx_dev 16-byte aligned).  Counts, split, expert
  * evaluation, combine and miss list exactly as tide_moe_step. */
 int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens,
                          const int32_t* topk_idx_dev, const float* topk_w_dev,

@@ -11,25 +11,6 @@ namespace {
 
 constexpr int kThreads = 256;
 
-// Rank of this thread's flag among the block's set flags in thread order, and their total.
-__device__ inline int block_rank(bool flag, int& total, int* lds4) {
-    const unsigned long long b = __ballot(flag);
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int r = __popcll(b & ((1ull << lane) - 1ull));
-    if (lane == 0) lds4[wv] = __popcll(b);
-    __syncthreads();
-    int base = 0;
-    total = 0;
-#pragma unroll
-    for (int w = 0; w < kThreads / 64; ++w) {
-        const int c = lds4[w];
-        if (w < wv) base += c;
-        total += c;
-    }
-    __syncthreads();
-    return base + r;
-}
-
 __device__ inline int block_sum(int v, int* lds4) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
@@ -40,6 +21,40 @@ __device__ inline int block_sum(int v, int* lds4) {
     for (int w = 0; w < kThreads / 64; ++w) t += lds4[w];
     __syncthreads();
     return t;
+}
+
+// ids[0..3] = idx[p0 .. p0+3] (16-byte load when the four are in range; idx is 16-byte aligned).
+__device__ inline void load4(const int32_t* __restrict__ idx, int p0, int n, int (&ids)[4]) {
+    if (p0 + 3 < n) {
+        const int4 v = *reinterpret_cast<const int4*>(idx + p0);
+        ids[0] = v.x; ids[1] = v.y; ids[2] = v.z; ids[3] = v.w;
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) ids[q] = p0 + q < n ? idx[p0 + q] : -1;
+    }
+}
+
+// Exclusive prefix sum of v over the block in thread order, and the block total.
+__device__ inline int block_scan_excl(int v, int& total, int* lds4) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(inc, off);
+        if (lane >= off) inc += o;
+    }
+    if (lane == 63) lds4[wv] = inc;
+    __syncthreads();
+    int base = 0;
+    total = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) {
+        const int c = lds4[w];
+        if (w < wv) base += c;
+        total += c;
+    }
+    __syncthreads();
+    return base + inc - v;
 }
 
 // Work items of one slot whose m rows start at row0.
@@ -85,28 +100,35 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     const int n_pairs = n_tokens * k;
 
     if (s == capacity + 1) {
-        // misses, ordered by token then rank
+        // misses, ordered by token then rank; each thread takes 4 consecutive pairs per pass
         int running = 0;
-        for (int base = 0; base < n_pairs; base += kThreads) {
-            const int p = base + tid;
-            int e = -1;
-            bool flag = false;
-            if (p < n_pairs) {
-                e = topk_idx[p];
+        for (int base = 0; base < n_pairs; base += 4 * kThreads) {
+            const int p0 = base + 4 * tid;
+            int e[4];
+            bool flag[4];
+            load4(topk_idx, p0, n_pairs, e);
+            int c = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
                 // an id outside [0,E) can only come from caller-supplied routing: report it as a miss
-                flag = (e < 0 || e >= n_experts) ? true : slot_of[e] < 0;
+                flag[q] = p0 + q < n_pairs && ((e[q] < 0 || e[q] >= n_experts) ? true : slot_of[e[q]] < 0);
+                c += flag[q] ? 1 : 0;
             }
             int total;
-            const int r = block_rank(flag, total, lds4);
-            if (flag) {
-                pair_row[p] = -1;
-                const int pos = running + r;
-                if (pos < miss_cap) {
-                    tide_miss m;
-                    m.token = p / k;
-                    m.expert = e;
-                    m.weight = topk_w[p];
-                    miss[pos] = m;
+            int pos = running + block_scan_excl(c, total, lds4);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (flag[q]) {
+                    const int p = p0 + q;
+                    pair_row[p] = -1;
+                    if (pos < miss_cap) {
+                        tide_miss m;
+                        m.token = p / k;
+                        m.expert = e[q];
+                        m.weight = topk_w[p];
+                        miss[pos] = m;
+                    }
+                    ++pos;
                 }
             }
             running += total;
@@ -163,15 +185,30 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     if (m == 0) return;
     emit_tasks(s, rows_before, m, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
     int running = 0;
-    for (int base = 0; base < n_pairs; base += kThreads) {
-        const int p = base + tid;
-        const bool flag = p < n_pairs && topk_idx[p] == e;
+    int next[4];
+    load4(topk_idx, 4 * tid, n_pairs, next);                 // the next pass's ids are always in flight
+    for (int base = 0; base < n_pairs; base += 4 * kThreads) {
+        const int p0 = base + 4 * tid;
+        int ids[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) ids[q] = next[q];
+        load4(topk_idx, p0 + 4 * kThreads, n_pairs, next);
+        bool flag[4];
+        int c = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            flag[q] = p0 + q < n_pairs && ids[q] == e;
+            c += flag[q] ? 1 : 0;
+        }
         int total;
-        const int r = block_rank(flag, total, lds4);
-        if (flag) {
-            const int row = rows_before + running + r;
-            row_token[row] = p / k;
-            pair_row[p] = row;
+        int row = rows_before + running + block_scan_excl(c, total, lds4);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (flag[q]) {
+                row_token[row] = (p0 + q) / k;
+                pair_row[p0 + q] = row;
+                ++row;
+            }
         }
         running += total;
     }

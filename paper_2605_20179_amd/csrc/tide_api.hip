@@ -395,6 +395,7 @@ int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n
         return TIDE_OK;
     }
     if (!topk_idx_dev || !topk_w_dev) return fail(ctx, TIDE_E_INVAL, "topk_idx_dev / topk_w_dev is null");
+    if ((uintptr_t)topk_idx_dev & 15) return fail(ctx, TIDE_E_INVAL, "topk_idx_dev must be 16-byte aligned");
     Layer& L = ctx->layers[layer];
     TIDE_HIP(ctx, launch_count_pairs(ctx->shape, topk_idx_dev, n_tokens, ctx->ws.hist_step, L.t.hits, stream));
     return common_step(ctx, layer, hidden_dev, n_tokens, topk_idx_dev, topk_w_dev, out_dev, miss_dev, miss_cap,
