@@ -138,6 +138,22 @@ int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n
                          float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
                          void* hip_stream);
 
+/* Evaluates a step's misses on the GPU and adds them to out_dev, which then holds the FULL MoE
+ * output: out[token] += weight * e_expert(x_token) for every listed miss, in list order.  The
+ * missed experts are not copied into the cache and the placement does not change: the expert
+ * GEMMs read the weights in place from the registered pinned host blobs across the host link
+ * (Sec. 3.3 sends such tokens to CPU experts instead; the result is the same by the lossless
+ * property, the cost is one pass over each missed expert's weights at host-link speed).
+ *   hidden_dev  the step's input, as passed to tide_moe_step                      (in)
+ *   miss_dev / miss_cap / n_miss_dev  the list that step returned; min(*n_miss_dev, miss_cap)
+ *               entries are used                                                   (in)
+ *   out_dev     fp32 [n_tokens][d], the step's resident-partial output             (in/out)
+ * Asynchronous on hip_stream; must follow the step on the same stream (it reuses the context's
+ * workspace).  Does not touch H or the tables. */
+int tide_moe_apply_misses(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens,
+                          const tide_miss* miss_dev, int miss_cap, const int32_t* n_miss_dev,
+                          float* out_dev, void* hip_stream);
+
 /* ---- interval statistics and refresh ---------------------------------------------- */
 
 /* Copies the layer's hit counter H[E] (tokens per expert since the last reset; Fig. 1

@@ -22,7 +22,7 @@ EXPORTS = [
     "tide_create", "tide_destroy", "tide_last_error", "tide_expert_blob_bytes", "tide_pack_expert",
     "tide_register_experts", "tide_set_shared", "tide_set_resident", "tide_moe_step", "tide_moe_step_routed",
     "tide_interval_stats", "tide_refresh", "tide_wait_refresh", "tide_get_table", "tide_read_slot",
-    "tide_refresh_copy_ms", "tide_profile", "tide_profile_read", "tide_counters",
+    "tide_refresh_copy_ms", "tide_profile", "tide_profile_read", "tide_counters", "tide_moe_apply_misses",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -68,6 +68,7 @@ def _load() -> C.CDLL:
     lib.tide_set_resident.argtypes = [vp, C.c_int, vp, C.c_int]
     lib.tide_moe_step.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp, vp, vp]
     lib.tide_moe_step_routed.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp]
+    lib.tide_moe_apply_misses.argtypes = [vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, vp, vp]
     lib.tide_interval_stats.argtypes = [vp, C.c_int, vp, C.c_int, vp]
     lib.tide_refresh.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, vp, vp, C.POINTER(C.c_int), vp]
     lib.tide_wait_refresh.argtypes = [vp, C.c_int]
@@ -158,6 +159,11 @@ def tide_moe_step_routed(ctx, layer: int, hidden, n_tokens: int, topk_idx, topk_
                          stream=None) -> None:
     _check(lib.tide_moe_step_routed(ctx, layer, _ptr(hidden), n_tokens, _ptr(topk_idx), _ptr(topk_w), _ptr(out),
                                     _ptr(miss), miss_cap, _ptr(n_miss), _stream_ptr(stream)), ctx)
+
+
+def tide_moe_apply_misses(ctx, layer: int, hidden, n_tokens: int, miss, miss_cap: int, n_miss, out, stream=None) -> None:
+    _check(lib.tide_moe_apply_misses(ctx, layer, _ptr(hidden), n_tokens, _ptr(miss), miss_cap, _ptr(n_miss), _ptr(out),
+                                     _stream_ptr(stream)), ctx)
 
 
 def tide_interval_stats(ctx, layer: int, n_experts: int, reset: bool, stream=None) -> np.ndarray:

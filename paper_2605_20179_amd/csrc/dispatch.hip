@@ -85,6 +85,43 @@ __device__ inline void emit_tasks(int slot, int row0, int m, Task* small_out, Ta
     }
 }
 
+// Rows of one group: the pairs p (in pair order) whose expert id is e get rows row_begin, row_begin+1, ...
+// PAIR_TOKEN: the token of pair p is pair_token[p] (a miss list) instead of p / k (a routing table).
+template <bool PAIR_TOKEN>
+__device__ inline void collect_rows(const int32_t* __restrict__ idx, const int32_t* __restrict__ pair_token, int n_pairs,
+                                    int k, int e, int row_begin, int32_t* __restrict__ row_token,
+                                    int32_t* __restrict__ pair_row, int* lds4) {
+    const int tid = threadIdx.x;
+    int running = 0;
+    int next[4];
+    load4(idx, 4 * tid, n_pairs, next);                      // the next pass's ids are always in flight
+    for (int base = 0; base < n_pairs; base += 4 * kThreads) {
+        const int p0 = base + 4 * tid;
+        int ids[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) ids[q] = next[q];
+        load4(idx, p0 + 4 * kThreads, n_pairs, next);
+        bool flag[4];
+        int c = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            flag[q] = p0 + q < n_pairs && ids[q] == e;
+            c += flag[q] ? 1 : 0;
+        }
+        int total;
+        int row = row_begin + running + block_scan_excl(c, total, lds4);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (flag[q]) {
+                row_token[row] = PAIR_TOKEN ? pair_token[p0 + q] : (p0 + q) / k;
+                pair_row[p0 + q] = row;
+                ++row;
+            }
+        }
+        running += total;
+    }
+}
+
 // grid = capacity + 2 blocks: one per cache slot, one for the shared expert, one for the misses.
 __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w, int n_tokens, int k, int capacity,
@@ -184,37 +221,114 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     if (tid == 0) slot_off[s] = rows_before;
     if (m == 0) return;
     emit_tasks(s, rows_before, m, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
-    int running = 0;
-    int next[4];
-    load4(topk_idx, 4 * tid, n_pairs, next);                 // the next pass's ids are always in flight
-    for (int base = 0; base < n_pairs; base += 4 * kThreads) {
-        const int p0 = base + 4 * tid;
-        int ids[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) ids[q] = next[q];
-        load4(topk_idx, p0 + 4 * kThreads, n_pairs, next);
-        bool flag[4];
-        int c = 0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            flag[q] = p0 + q < n_pairs && ids[q] == e;
-            c += flag[q] ? 1 : 0;
-        }
-        int total;
-        int row = rows_before + running + block_scan_excl(c, total, lds4);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (flag[q]) {
-                row_token[row] = (p0 + q) / k;
-                pair_row[p0 + q] = row;
-                ++row;
-            }
-        }
-        running += total;
+    collect_rows<false>(topk_idx, nullptr, n_pairs, k, e, rows_before, row_token, pair_row, lds4);
+}
+
+// ---- miss pass: the miss list of a step, evaluated from the host-resident expert blobs -------------
+
+// Struct-of-arrays copy of the (possibly truncated) miss list and the number of misses per expert.
+__global__ __launch_bounds__(kThreads) void miss_prepare_kernel(const tide_miss* __restrict__ miss, int miss_cap,
+                                                               const int32_t* __restrict__ n_miss, int n_experts,
+                                                               int32_t* __restrict__ m_idx, int32_t* __restrict__ m_tok,
+                                                               float* __restrict__ m_w, int32_t* __restrict__ miss_hist,
+                                                               int32_t* __restrict__ m_count) {
+    const int n = min(*n_miss, miss_cap);
+    const int p = blockIdx.x * kThreads + threadIdx.x;
+    if (p == 0) *m_count = n;
+    if (p >= n) return;
+    const tide_miss m = miss[p];
+    const bool ok = m.expert >= 0 && m.expert < n_experts;
+    m_idx[p] = ok ? m.expert : -1;                           // an id outside [0,E) is skipped
+    m_tok[p] = m.token;
+    m_w[p] = m.weight;
+    if (ok) atomicAdd(&miss_hist[m.expert], 1);
+}
+
+// grid = E + 1 blocks: block e lists the rows of expert e (the "slot" of a miss-pass work item is the
+// expert id, its weights are the expert's host blob); the last block publishes the work-item counts.
+__global__ __launch_bounds__(kThreads) void miss_group_kernel(const int32_t* __restrict__ m_idx,
+                                                             const int32_t* __restrict__ m_tok,
+                                                             const int32_t* __restrict__ m_count, int n_experts,
+                                                             const int32_t* __restrict__ miss_hist,
+                                                             int32_t* __restrict__ row_token,
+                                                             int32_t* __restrict__ pair_row, Task* __restrict__ tasks,
+                                                             Task* __restrict__ big_tasks, int32_t* __restrict__ n_tasks,
+                                                             int max_big) {
+    __shared__ int lds4[kThreads / 64];
+    const int e = blockIdx.x, tid = threadIdx.x;
+    const int upto = e < n_experts ? e : n_experts;
+    int rows_before = 0, tasks_before = 0, big_before = 0;
+    for (int q = tid; q < upto; q += kThreads) {
+        const int m = miss_hist[q];
+        rows_before += m;
+        tasks_before += m <= kBigMinRows ? (m + kRowsPerTask - 1) / kRowsPerTask : 0;
+        big_before += m > kBigMinRows ? (m + kRowsPerBigTask - 1) / kRowsPerBigTask : 0;
     }
+    rows_before = block_sum(rows_before, lds4);
+    tasks_before = block_sum(tasks_before, lds4);
+    big_before = block_sum(big_before, lds4);
+    if (e == n_experts) {
+        if (tid == 0) {
+            n_tasks[0] = tasks_before;
+            n_tasks[1] = min(big_before, max_big);
+        }
+        return;
+    }
+    const int m = miss_hist[e];
+    if (m == 0) return;
+    emit_tasks(e, rows_before, m, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
+    collect_rows<true>(m_idx, m_tok, *m_count, 1, e, rows_before, row_token, pair_row, lds4);
+}
+
+// out[n] += sum over the token's misses, in list order, of weight * y[row]; the list is sorted by token,
+// so a token's misses are one contiguous range found by bisection.  grid = (ceil(d/1024), n_tokens).
+__global__ __launch_bounds__(256) void miss_combine_kernel(const float* __restrict__ y, const int32_t* __restrict__ m_idx,
+                                                           const int32_t* __restrict__ m_tok,
+                                                           const float* __restrict__ m_w,
+                                                           const int32_t* __restrict__ pair_row,
+                                                           const int32_t* __restrict__ m_count, int d,
+                                                           float* __restrict__ out) {
+    const int n = blockIdx.y;
+    const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (c >= d) return;
+    const int total = *m_count;
+    int lo = 0, hi = total;                                  // first entry with token >= n
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (m_tok[mid] < n) lo = mid + 1; else hi = mid;
+    }
+    float4 acc = *reinterpret_cast<const float4*>(out + (int64_t)n * d + c);
+    bool any = false;
+    for (int p = lo; p < total && m_tok[p] == n; ++p) {
+        if (m_idx[p] < 0) continue;
+        const float w = m_w[p];
+        const float4 v = *reinterpret_cast<const float4*>(y + (int64_t)pair_row[p] * d + c);
+        acc.x = fmaf(w, v.x, acc.x);
+        acc.y = fmaf(w, v.y, acc.y);
+        acc.z = fmaf(w, v.z, acc.z);
+        acc.w = fmaf(w, v.w, acc.w);
+        any = true;
+    }
+    if (any) *reinterpret_cast<float4*>(out + (int64_t)n * d + c) = acc;
 }
 
 }  // namespace
+
+hipError_t launch_miss_group(const Shape& s, const Workspace& w, const tide_miss* miss, int miss_cap,
+                             const int32_t* n_miss, int max_big, hipStream_t stream) {
+    if (miss_cap <= 0) return hipSuccess;
+    hipLaunchKernelGGL(miss_prepare_kernel, dim3((miss_cap + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, miss,
+                       miss_cap, n_miss, s.E, w.m_idx, w.m_tok, w.m_w, w.miss_hist, w.m_count);
+    hipLaunchKernelGGL(miss_group_kernel, dim3(s.E + 1), dim3(kThreads), 0, stream, w.m_idx, w.m_tok, w.m_count, s.E,
+                       w.miss_hist, w.row_token, w.pair_row, w.tasks, w.big_tasks, w.n_tasks, max_big);
+    return hipGetLastError();
+}
+
+hipError_t launch_miss_combine(const Shape& s, const Workspace& w, int n_tokens, float* out, hipStream_t stream) {
+    hipLaunchKernelGGL(miss_combine_kernel, dim3((s.d + 1023) / 1024, n_tokens), dim3(256), 0, stream, w.y, w.m_idx,
+                       w.m_tok, w.m_w, w.pair_row, w.m_count, s.d, out);
+    return hipGetLastError();
+}
 
 hipError_t launch_dispatch(const Shape& s, const LayerTables& t, const Workspace& w, const int32_t* topk_idx,
                            const float* topk_w, int n_tokens, tide_miss* miss, int miss_cap, int32_t* n_miss,

@@ -288,6 +288,7 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_big_kernel(
 
 hipError_t launch_expert_gemm(int pass, const Shape& s, const LayerTables& t, const Workspace& w, const uint16_t* x,
                               int max_tasks, hipStream_t stream, LaunchEvents ev) {
+    if (max_tasks <= 0) return hipSuccess;
     dim3 block(kWaves * 64);
     if (pass == 0) {
         TIDE_LAUNCH(expert_gemm_kernel<0>, dim3((s.I + 32 * kSmallRT0 - 1) / (32 * kSmallRT0), max_tasks), block, stream, ev, t.slots, s.blob_elems,

@@ -2,6 +2,7 @@
 // interval statistics and the refresh with its side-stream host-to-device copies.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -238,8 +239,8 @@ int tide_create(const tide_config* cfg, tide_ctx** out) {
 
     const int64_t N = cfg->max_tokens, P = N * cfg->top_k;
     ctx->max_rows = (int)(P + (cfg->n_shared ? N : 0));
-    ctx->max_tasks = max_small_tasks_for(s, cfg->max_tokens);
-    const int max_big = max_big_tasks_for(s, cfg->max_tokens);
+    ctx->max_tasks = std::max(max_small_tasks_for(s, cfg->max_tokens), max_miss_small_tasks_for(s, cfg->max_tokens));
+    const int max_big = std::max(max_big_tasks_for(s, cfg->max_tokens), max_miss_big_tasks_for(s, cfg->max_tokens));
     Workspace& w = ctx->ws;
     if ((rc = ws_alloc(ctx, &w.logits, (int64_t)kMaxRouterSplits * N * ((s.E + 15) / 16 * 16))) || (rc = ws_alloc(ctx, &w.topk_idx, P)) ||
         (rc = ws_alloc(ctx, &w.topk_w, P)) || (rc = ws_alloc(ctx, &w.hist_step, s.E)) ||
@@ -247,7 +248,8 @@ int tide_create(const tide_config* cfg, tide_ctx** out) {
         (rc = ws_alloc(ctx, &w.slot_off, s.capacity + 2)) || (rc = ws_alloc(ctx, &w.tasks, ctx->max_tasks)) ||
         (rc = ws_alloc(ctx, &w.big_tasks, max_big + 1)) || (rc = ws_alloc(ctx, &w.n_tasks, 2)) || (rc = ws_alloc(ctx, &w.act, (int64_t)ctx->max_rows * s.I)) ||
         (rc = ws_alloc(ctx, &w.y, (int64_t)ctx->max_rows * s.d)) || (rc = ws_alloc(ctx, &w.counts_tmp, s.E)) ||
-        (rc = ws_alloc(ctx, &w.counters, 4)))
+        (rc = ws_alloc(ctx, &w.counters, 4)) || (rc = ws_alloc(ctx, &w.m_idx, P)) || (rc = ws_alloc(ctx, &w.m_tok, P)) ||
+        (rc = ws_alloc(ctx, &w.m_w, P)) || (rc = ws_alloc(ctx, &w.miss_hist, s.E)) || (rc = ws_alloc(ctx, &w.m_count, 1)))
         return bail(rc);
     if (hipMemset(w.n_tasks, 0, 2 * sizeof(int32_t)) != hipSuccess || hipMemset(w.counters, 0, 4 * sizeof(int64_t)) != hipSuccess)
         return bail(fail(ctx, TIDE_E_HIP, "hipMemset failed"));
@@ -400,6 +402,37 @@ int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n
     TIDE_HIP(ctx, launch_count_pairs(ctx->shape, topk_idx_dev, n_tokens, ctx->ws.hist_step, L.t.hits, stream));
     return common_step(ctx, layer, hidden_dev, n_tokens, topk_idx_dev, topk_w_dev, out_dev, miss_dev, miss_cap,
                        n_miss_dev, stream, false);
+}
+
+int tide_moe_apply_misses(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const tide_miss* miss_dev,
+                          int miss_cap, const int32_t* n_miss_dev, float* out_dev, void* hip_stream) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    if (n_tokens < 0 || n_tokens > ctx->cfg.max_tokens) return fail(ctx, TIDE_E_RANGE, "n_tokens %d outside 0..max_tokens=%d", n_tokens, ctx->cfg.max_tokens);
+    if (n_tokens == 0 || miss_cap == 0) return TIDE_OK;
+    if (!hidden_dev || !out_dev || !miss_dev || !n_miss_dev) return fail(ctx, TIDE_E_INVAL, "null argument");
+    if (miss_cap < 0 || (int64_t)miss_cap > (int64_t)ctx->cfg.max_tokens * ctx->cfg.top_k) return fail(ctx, TIDE_E_RANGE, "miss_cap outside 0..max_tokens*k");
+    if (((uintptr_t)hidden_dev & 15) || ((uintptr_t)out_dev & 15)) return fail(ctx, TIDE_E_INVAL, "hidden_dev / out_dev must be 16-byte aligned");
+    Layer& L = ctx->layers[layer];
+    if (!L.host_blobs) return fail(ctx, TIDE_E_STATE, "layer %d: experts not registered", layer);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
+    // the work items' "slots" are expert ids and their weights the experts' pinned host blobs, which the
+    // GEMM kernels read in place across the host link
+    LayerTables host_view = L.t;
+    host_view.slots = reinterpret_cast<const uint16_t*>(L.host_blobs);
+    Shape shape = ctx->shape;
+    shape.blob_elems = (int64_t)(L.host_stride / 2);
+    const int max_small = max_miss_small_tasks_for(ctx->shape, n_tokens);
+    const int max_big = max_miss_big_tasks_for(ctx->shape, n_tokens);
+    TIDE_HIP(ctx, launch_clear_i32(ctx->ws.miss_hist, ctx->cfg.n_experts, stream));
+    TIDE_HIP(ctx, launch_miss_group(ctx->shape, ctx->ws, miss_dev, miss_cap, n_miss_dev, max_big, stream));
+    TIDE_HIP(ctx, launch_expert_gemm(0, shape, host_view, ctx->ws, x, max_small, stream));
+    if (max_big > 0) TIDE_HIP(ctx, launch_expert_gemm_big(0, shape, host_view, ctx->ws, x, max_big, stream));
+    TIDE_HIP(ctx, launch_expert_gemm(1, shape, host_view, ctx->ws, x, max_small, stream));
+    if (max_big > 0) TIDE_HIP(ctx, launch_expert_gemm_big(1, shape, host_view, ctx->ws, x, max_big, stream));
+    TIDE_HIP(ctx, launch_miss_combine(ctx->shape, ctx->ws, n_tokens, out_dev, stream));
+    return TIDE_OK;
 }
 
 int tide_interval_stats(tide_ctx* ctx, int layer, int32_t* counts_host, int reset, void* hip_stream) {

@@ -44,6 +44,11 @@ struct Workspace {
     float*   y;           // [max_rows][d] per-row expert outputs
     int32_t* counts_tmp;  // [E] caller-provided counts for a refresh
     int64_t* counters;    // [4] running totals: steps, active slots (shared included), rows, misses
+    int32_t* m_idx;       // [max_tokens*k] miss pass: expert, token and weight of each listed miss
+    int32_t* m_tok;
+    float*   m_w;
+    int32_t* miss_hist;   // [E] listed misses per expert
+    int32_t* m_count;     // [1] number of listed misses
 };
 
 struct LayerTables {
@@ -113,6 +118,19 @@ inline int max_small_tasks_for(const Shape& s, int n_tokens) {
     const int rows = n_tokens * s.k + (s.n_shared ? n_tokens : 0);
     return s.capacity + 1 + rows / kRowsPerTask;
 }
+// the same bounds for a miss pass, whose groups are the E experts instead of the cache slots
+inline int max_miss_small_tasks_for(const Shape& s, int n_tokens) { return s.E + n_tokens * s.k / kRowsPerTask; }
+inline int max_miss_big_tasks_for(const Shape& s, int n_tokens) {
+    if (n_tokens <= kBigMinRows) return 0;
+    const int rows = n_tokens * s.k;
+    const int busy = rows / (kBigMinRows + 1);
+    return rows / kRowsPerBigTask + (busy < s.E ? busy : s.E);
+}
+// miss pass (the step's misses evaluated from the host-resident blobs): group the list by expert into
+// rows and work items whose "slot" is the expert id; add the weighted results to out
+hipError_t launch_miss_group(const Shape& s, const Workspace& w, const tide_miss* miss, int miss_cap,
+                             const int32_t* n_miss, int max_big, hipStream_t stream);
+hipError_t launch_miss_combine(const Shape& s, const Workspace& w, int n_tokens, float* out, hipStream_t stream);
 // a9: out[n] = shared row + sum over hit pairs in rank order of w * y[row]
 hipError_t launch_combine(const Shape& s, const Workspace& w, const float* topk_w, int n_tokens, float* out,
                           hipStream_t stream, LaunchEvents ev = {});

@@ -104,6 +104,13 @@ def run_block_on_gpu(wl, layer, sess, log, hidden, forced, out_steps, tokens=Non
             assert np.array_equal(sess.table(layer), rec["slot_of"]), "step %d: table" % t
             if "y_res" in rec and t in out_steps:
                 worst = max(worst, check_out(out, rec["y_res"], rows=tokens))
+                # the miss pass (weights read in place from pinned host memory) completes the output:
+                # resident part + misses == the full MoE layer, whatever the placement (lossless)
+                sess.apply_misses(layer, x)
+                torch.cuda.synchronize()
+                full = sess.out[:wl.N].cpu().numpy()
+                worst = max(worst, check_out(full, rec["y_full"], rows=tokens))
+                assert np.array_equal(sess.stats(layer), rec["hits"].astype(np.int32)), "miss pass must not count"
         else:
             start = (t // wl.K) * wl.K          # first step of the interval in progress
             assert sess.stats(layer).sum() == sum(int(r["hist"].sum()) for r in log[start:t + 1])
