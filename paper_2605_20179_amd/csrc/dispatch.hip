@@ -72,14 +72,17 @@ __device__ inline void emit_tasks(int slot, int row0, int m, Task* small_out, Ta
         }
         return;
     }
+    // the fewest large work items that hold m rows, of even size (a whole number of 16-token tiles):
+    // 300 rows become 160 + 140, not 256 + 44, so the slot's work items finish together
     const int nb = (m + kRowsPerBigTask - 1) / kRowsPerBigTask;
+    const int per = ((m + nb - 1) / nb + 15) / 16 * 16;      // <= kRowsPerBigTask, and (nb-1)*per < m
     // big_room < nb only if the caller's routing repeats an expert inside a token (not allowed):
     // the surplus rows are then left uncomputed rather than written out of bounds
     for (int c = threadIdx.x; c < nb && c < big_room; c += kThreads) {
         Task t;
         t.slot = slot;
-        t.row0 = row0 + c * kRowsPerBigTask;
-        t.nrows = min(kRowsPerBigTask, m - c * kRowsPerBigTask);
+        t.row0 = row0 + c * per;
+        t.nrows = min(per, m - c * per);
         t.pad = 0;
         big_out[c] = t;
     }
@@ -179,7 +182,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
 
     // rows and work items that precede this slot
     const int upto = s < capacity ? s : capacity;
-    // a slot with up to kBigMinRows rows is cut into small work items of 32 rows, a fuller one into large ones of 128
+    // a slot with up to kBigMinRows rows is cut into small work items of 32 rows, a fuller one into large ones of up to 256
     int rows_before = 0, tasks_before = 0, big_before = 0, active_before = 0;
     for (int q = tid; q < upto; q += kThreads) {
         const int e = expert_in_slot[q];

@@ -13,12 +13,15 @@
 // no LDS staging for weights.  Tokens sit on the MFMA's 16-wide N side.
 #include "tide_internal.h"
 
+#include <type_traits>
+
 namespace tide {
 
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kWaves = 4;            // independent waves per workgroup, each streaming its own weight rows
 constexpr int kTileElems = 16 * 32;  // one packed tile
@@ -50,7 +53,7 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_a, int64_t of
                                  const Task& task, const uint16_t* __restrict__ act_in,
                                  const int32_t* __restrict__ row_token, int K, int n_out,
                                  uint16_t* __restrict__ act_out, float* __restrict__ y_out, uint16_t* lds) {
-    static_assert(PC % D == 0, "the ring must turn over a whole number of times per stage");
+    static_assert(PC % D == 0 || (NBUF == 2 && D % PC == 0), "stage boundaries must fall on whole chunks of a ring turn");
     constexpr int G = RT / 2;                        // PASS 0: gate stripes per wave
     constexpr int kCols = PC * 32;                   // columns per stage
     constexpr int kRowElems = kCols + 8;             // +16 B per LDS row: a fragment's 16 rows hit distinct banks
@@ -75,38 +78,40 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_a, int64_t of
             wt[r] = blob + off_a + (int64_t)(wsrc * RT + r) * stripe + lane * 8;
     }
 
-    // staging map: piece q = tid + 256*j covers row q / kPPR of the item, columns (q % kPPR)*8 .. +7 of the stage
+    // staging map: piece q = tid + 256*j covers row q / kPPR of the item, columns (q % kPPR)*8 .. +7 of the
+    // stage; kPPR divides 256, so a thread's pieces all sit at the same columns
+    static_assert(256 % kPPR == 0, "a thread stages the same columns of each of its rows");
+    const int xcol = (threadIdx.x % kPPR) * 8;
     const uint16_t* xsrc[kPieces];
 #pragma unroll
     for (int j = 0; j < kPieces; ++j) {
-        const int q = threadIdx.x + 256 * j;
-        int r = q / kPPR;
+        int r = (threadIdx.x + 256 * j) / kPPR;
         if (r >= task.nrows) r = 0;                  // padding rows mirror a valid row; never stored
         const int row = task.row0 + r;
         const int64_t src = (PASS == 0) ? (int64_t)row_token[row] : (int64_t)row;
-        xsrc[j] = act_in + src * K + (q % kPPR) * 8;
+        xsrc[j] = act_in + src * K;
     }
-    uint4 xr[kPieces];
+    u32x4 xr[kPieces];
+    // columns past K (a last, partial stage) are clamped to the row's last piece: loaded, staged, never
+    // read by an MFMA -- the loop body stays free of branches
     auto fetch_stage = [&](int stage) {
-        const int width = min(kCols, K - stage * kCols);
+        const int col = min(stage * kCols + xcol, K - 8);
 #pragma unroll
-        for (int j = 0; j < kPieces; ++j) {
-            const int c8 = ((threadIdx.x + 256 * j) % kPPR) * 8;
-            xr[j] = (c8 < width) ? *reinterpret_cast<const uint4*>(xsrc[j] + stage * kCols) : make_uint4(0, 0, 0, 0);
-        }
+        for (int j = 0; j < kPieces; ++j) xr[j] = *reinterpret_cast<const u32x4*>(xsrc[j] + col);
     };
     auto store_stage = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < kPieces; ++j) {
             const int q = threadIdx.x + 256 * j;
-            *reinterpret_cast<uint4*>(lds + buf * kBufElems + (q / kPPR) * kRowElems + (q % kPPR) * 8) = xr[j];
+            *reinterpret_cast<u32x4*>(lds + buf * kBufElems + (q / kPPR) * kRowElems + (q % kPPR) * 8) = xr[j];
         }
     };
+    const int last_stage = (kchunks - 1) / PC;
     fetch_stage(0);
     if (NBUF == 2) {
-        // two buffers: stage s is written while stage s-1 is consumed, one barrier per stage
+        // two buffers: stage s+1 is written while stage s is consumed, one barrier per stage
         store_stage(0);
-        if (PC < kchunks) fetch_stage(1);
+        fetch_stage(min(1, last_stage));
     }
 
     // ring prologue (chunk indices past the end are clamped: a redundant in-bounds load, never used)
@@ -125,50 +130,104 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_a, int64_t of
 
     // this lane's fragment position inside a staged 16-row block
     const uint16_t* frag = lds + (lane & 15) * kRowElems + (lane >> 4) * 8;
-
-    auto stage_switch = [&](int base) {
-        const int stage = base / PC;
-        if (NBUF == 1) {
-            if (stage) __syncthreads();              // everyone is done reading the previous stage
-            store_stage(0);
-            __syncthreads();
-            if ((stage + 1) * PC < kchunks) fetch_stage(stage + 1);
-        } else {
-            __syncthreads();                         // stage's buffer is complete; the other one is free again
-            if ((stage + 1) * PC < kchunks) {
-                store_stage((stage + 1) & 1);
-                if ((stage + 2) * PC < kchunks) fetch_stage(stage + 2);
-            }
-        }
-    };
-    // chunk c: MFMAs from ring slot i and the staged fragments, then refill the slot D chunks ahead
-    auto chunk = [&](int c, int i) {
-        bf16x8 b[NT];
+    // fragments of token tiles t0 .. t0+CNT-1 for chunk c
+    auto read_frags = [&](bf16x8* b, int c, int t0, auto cnt) {
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
-            b[t] = *reinterpret_cast<const bf16x8*>(frag + (NBUF == 2 ? ((c / PC) & 1) * kBufElems : 0) + t * 16 * kRowElems + (c % PC) * 32);
+        for (int t = 0; t < decltype(cnt)::value; ++t)
+            b[t] = *reinterpret_cast<const bf16x8*>(frag + (NBUF == 2 ? ((c / PC) & 1) * kBufElems : 0) + (t0 + t) * 16 * kRowElems + (c % PC) * 32);
+    };
+    auto mfmas = [&](const bf16x8* b, int i, int t0, auto cnt) {
 #pragma unroll
         for (int r = 0; r < RT; ++r)
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][r], b[t], acc[r][t], 0, 0, 0);
+            for (int t = 0; t < decltype(cnt)::value; ++t)
+                acc[r][t0 + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][r], b[t], acc[r][t0 + t], 0, 0, 0);
+    };
+    auto refill = [&](int c, int i) {
         const int cn = min(c + D, kchunks - 1);
 #pragma unroll
         for (int r = 0; r < RT; ++r) a[i][r] = *reinterpret_cast<const bf16x8*>(wt[r] + (int64_t)cn * kTileElems);
     };
+    using all_tiles = std::integral_constant<int, NT>;
 
-    // the main loop is straight-line (no per-chunk predicates): whole turns of the ring
-    int base = 0;
-    for (; base + D <= kchunks; base += D) {
-        if (base % PC == 0) stage_switch(base);
+    if constexpr (NBUF == 1) {
+        auto stage_switch = [&](int base) {
+            const int stage = base / PC;
+            if (stage) __syncthreads();              // everyone is done reading the previous stage
+            store_stage(0);
+            __syncthreads();
+            if ((stage + 1) * PC < kchunks) fetch_stage(stage + 1);
+        };
+        // chunk c: MFMAs from ring slot i and the staged fragments, then refill the slot D chunks ahead
+        auto chunk = [&](int c, int i) {
+            bf16x8 b[NT];
+            read_frags(b, c, 0, all_tiles{});
+            mfmas(b, i, 0, all_tiles{});
+            refill(c, i);
+        };
+        // the main loop is straight-line (no per-chunk predicates): whole turns of the ring
+        int base = 0;
+        for (; base + D <= kchunks; base += D) {
+            if (base % PC == 0) stage_switch(base);
 #pragma unroll
-        for (int i = 0; i < D; ++i) chunk(base + i, i);
-    }
-    if (base < kchunks) {                            // a last partial turn (K not a multiple of 32*D)
-        if (base % PC == 0) stage_switch(base);
+            for (int i = 0; i < D; ++i) chunk(base + i, i);
+        }
+        if (base < kchunks) {                        // a last partial turn (K not a multiple of 32*D)
+            if (base % PC == 0) stage_switch(base);
 #pragma unroll
-        for (int i = 0; i < D; ++i)
-            if (base + i < kchunks) chunk(base + i, i);
+            for (int i = 0; i < D; ++i)
+                if (base + i < kchunks) chunk(base + i, i);
+        }
+    } else {
+        // Fragments are double-buffered in registers too: the next set is read from LDS while the current
+        // one feeds the MFMAs.  More than 8 token tiles are handled as two half sets per chunk, so the
+        // fragment registers stay at 2 x 8 tiles.  The stage barrier sits right ahead of the read of the
+        // next stage's first fragments, in the stage's last chunk: by then every thread has written its
+        // part of the next stage (at the stage's first chunk) and every wave has read the stage before
+        // this one to the end, so the buffer written at the next stage's first chunk is free.
+        constexpr int NH = NT > 8 ? 2 : 1;           // half sets per chunk
+        constexpr int NTH = NT / NH;
+        static_assert(NT % NH == 0 && D % 2 == 0, "fragment buffers alternate with the step's parity");
+        static_assert(PC % D == 0 || D % PC == 0, "stage boundaries must fall on whole chunks of a ring turn");
+        using half_tiles = std::integral_constant<int, NTH>;
+        bf16x8 b[2][NTH];
+        __syncthreads();                             // stage 0 is complete
+        read_frags(b[0], 0, 0, half_tiles{});
+        auto chunk = [&](int c, int i) {
+            if (c % PC == 0) {
+                // no branches in the loop body: past the last stage this stores a stage nobody reads into
+                // the buffer that is free, and fetches the last stage once more
+                const int stage = c / PC;
+                store_stage((stage + 1) & 1);
+                fetch_stage(min(stage + 2, last_stage));
+            }
+            // scheduling fences: the next fragments are requested before the current MFMAs start, and
+            // each chunk's weight loads stay with its MFMAs, so the ring stays D chunks ahead
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                const int q = NH == 2 ? h : (i & 1);     // parity of this step
+                if (h == NH - 1) {
+                    if (c % PC == PC - 1) __syncthreads();
+                    read_frags(b[q ^ 1], min(c + 1, kchunks - 1), 0, half_tiles{});
+                } else {
+                    read_frags(b[q ^ 1], c, NTH, half_tiles{});
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                mfmas(b[q], i, h * NTH, half_tiles{});
+                if (h == NH - 1) refill(c, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        int base = 0;
+        for (; base + D <= kchunks; base += D) {
+#pragma unroll
+            for (int i = 0; i < D; ++i) chunk(base + i, i);
+        }
+        if (base < kchunks) {
+#pragma unroll
+            for (int i = 0; i < D; ++i)
+                if (base + i < kchunks) chunk(base + i, i);
+        }
     }
     if (!active) return;
 
@@ -241,10 +300,15 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
         gemm_task<PASS, RT, 2, D, kSmallPC, 1>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
 }
 
-// Large work items: up to 128 rows of a slot that holds more than 32.  Each weight fragment now
-// feeds eight token tiles (32 MFMAs per wave and chunk), so a hot expert is bound by the matrix
-// cores rather than by weight traffic; the other work items of the same slot find the weights in L2.
-constexpr int kBigPC = 8;          // 256 columns per stage, two staging buffers
+// Large work items: up to 256 rows of a slot that holds more than 32.  A workgroup's tile is 256
+// weight rows x up to 256 tokens: what bounds these kernels is the rate at which a compute unit's
+// vector cache can be filled, so the tile is as large as the accumulators allow (256 of a wave's 512
+// registers).  Up to 128 rows: eight token tiles, 256-column stages, ring depth 8.  Above: up to 16
+// token tiles in two half sets, 64-column stages, ring depth 4 (the same lead in MFMA time).
+constexpr int kBigPC = 8, kBigD = 8;       // <= 8 token tiles
+constexpr int kWidePC = 4, kWideD = 4;     // 9..16 token tiles
+constexpr int kBigLdsElems = 2 * 128 * (kBigPC * 32 + 8) > 2 * 256 * (kWidePC * 32 + 8) ? 2 * 128 * (kBigPC * 32 + 8)
+                                                                                      : 2 * 256 * (kWidePC * 32 + 8);
 constexpr int kXcds = 8;           // accelerator complex dies, each with its own L2
 template <int PASS>
 __global__ __launch_bounds__(kWaves * 64) void expert_gemm_big_kernel(
@@ -253,7 +317,7 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_big_kernel(
     const int32_t* __restrict__ row_token, int K, int n_out, uint16_t* __restrict__ act_out,
     float* __restrict__ y_out, int n_ftiles) {
     constexpr int RT = 4;
-    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * kRowsPerBigTask * (kBigPC * 32 + 8)];
+    __shared__ __attribute__((aligned(16))) uint16_t lds[kBigLdsElems];
     // Work units (work item, feature tile) are listed slot by slot, row chunk by row chunk, feature
     // tile fastest, so neighbours share weight stripes or token rows.  Workgroups are handed to
     // the chip's 8 XCDs round-robin by their linear id; XCD x takes the x-th contiguous eighth of
@@ -268,20 +332,28 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_big_kernel(
     const bool active = wtile * 16 * (PASS == 0 ? RT / 2 : RT) < n_out;
     const Task task = tasks[task_id];
     const uint16_t* blob = slots + (int64_t)task.slot * blob_elems;
-    static_assert(kRowsPerBigTask == 128, "eight 16-token tiles per large work item");
-    // only as many 16-token tiles as the item has rows: a 40-row item costs 3/8 of a full one
+    static_assert(kRowsPerBigTask == 256, "sixteen 16-token tiles per large work item");
+    // only as many 16-token tiles as the item has rows: a 40-row item costs 3/8 of a 128-row one
 #define TIDE_BIG_CASE(NT_)                                                                                              \
     case NT_:                                                                                                           \
-        gemm_task<PASS, RT, NT_, 8, kBigPC, 2>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K, n_out,  \
-                                               act_out, y_out, lds);                                                   \
+        gemm_task<PASS, RT, NT_, kBigD, kBigPC, 2>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K, n_out, \
+                                                   act_out, y_out, lds);                                               \
+        break;
+#define TIDE_WIDE_CASE(NT_)                                                                                             \
+    case NT_ - 1:                                                                                                       \
+    case NT_:                                                                                                           \
+        gemm_task<PASS, RT, NT_, kWideD, kWidePC, 2>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K,    \
+                                                     n_out, act_out, y_out, lds);                                      \
         break;
     switch ((task.nrows + 15) >> 4) {
         TIDE_BIG_CASE(1) TIDE_BIG_CASE(2) TIDE_BIG_CASE(3) TIDE_BIG_CASE(4) TIDE_BIG_CASE(5) TIDE_BIG_CASE(6) TIDE_BIG_CASE(7)
+        TIDE_BIG_CASE(8) TIDE_WIDE_CASE(10) TIDE_WIDE_CASE(12) TIDE_WIDE_CASE(14)
         default:
-            gemm_task<PASS, RT, 8, 8, kBigPC, 2>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K, n_out,
-                                                 act_out, y_out, lds);
+            gemm_task<PASS, RT, 16, kWideD, kWidePC, 2>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K,
+                                                        n_out, act_out, y_out, lds);
     }
 #undef TIDE_BIG_CASE
+#undef TIDE_WIDE_CASE
 }
 
 }  // namespace

@@ -13,7 +13,7 @@ constexpr int kMaxExperts = 512;        // E limit: 8 router scores per lane of 
 constexpr int kMaxTopK = 16;             // one selection per lane of a 16-lane group
 constexpr int kMaxRouterSplits = 8;      // slices of the hidden dimension the router logits are computed in
 constexpr int kRowsPerTask = 32;        // rows of a small work item
-constexpr int kRowsPerBigTask = 128;    // rows of a large work item
+constexpr int kRowsPerBigTask = 256;    // rows of a large work item
 #ifndef TIDE_BIG_MIN_ROWS
 #define TIDE_BIG_MIN_ROWS 32
 #endif
