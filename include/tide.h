@@ -82,7 +82,13 @@ uint64_t tide_expert_blob_bytes(const tide_config* cfg);
 /* Host-side packing of one expert e(x) = Wd (silu(Wg x) * (Wu x)) (Alg. 1, "output = e(x)")
  * from row-major bf16 matrices wg[d_ff][d], wu[d_ff][d], wd[d][d_ff] (host) into the
  * library's streaming layout at blob_host (host, tide_expert_blob_bytes bytes).
- * The blob is what lives in pinned host memory and in a cache slot, byte for byte. */
+ * The blob is what lives in pinned host memory and in a cache slot, byte for byte.
+ * Layout: 16-row x 32-column tiles of 512 elements, lane-major (lane l: row l%16 of the
+ * tile, columns (l/16)*8..+7).  First the gate and up matrices interleaved: groups of 8
+ * SwiGLU column blocks (16 rows of Wg and of Wu each); inside a group, for each K chunk
+ * of 32 columns, the group's gate tiles then its up tiles.  Then the down matrix: groups
+ * of 16 row stripes; inside a group, for each K chunk, the group's tiles.  A last group
+ * with fewer blocks or stripes is laid out the same way. */
 int tide_pack_expert(const tide_config* cfg, const uint16_t* wg_host, const uint16_t* wu_host,
                      const uint16_t* wd_host, void* blob_host);
 

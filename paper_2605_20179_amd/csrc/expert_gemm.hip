@@ -10,7 +10,10 @@
 // 16-row x 32-column bf16 tile is 1 KiB, lane l's 16 bytes are the A operand of
 // v_mfma_f32_16x16x32_bf16 for row l%16, columns (l/16)*8..+7.  A wave therefore
 // fetches each tile with one fully coalesced 1 KiB load straight into registers --
-// no LDS staging for weights.  Tokens sit on the MFMA's 16-wide N side.
+// no LDS staging for weights.  The tiles of the stripes a workgroup consumes together
+// are stored K chunk by K chunk, so the workgroup reads one contiguous region front to
+// back (all memory channels in turn) instead of 16 streams 128 KiB apart.  Tokens sit
+// on the MFMA's 16-wide N side.
 #include "tide_internal.h"
 
 #include <type_traits>
@@ -49,7 +52,7 @@ __device__ inline float silu(float g) { return g / (1.f + __expf(-g)); }
 // columns at a time; the next stage's rows are already in flight while the current one is used.
 // Tokens sit on the MFMA's 16-wide N side, NT token tiles per work item.
 template <int PASS, int RT, int NT, int D, int PC, int NBUF>
-__device__ inline void gemm_task(const uint16_t* blob, int64_t off_a, int64_t off_b, int wtile, bool active,
+__device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile, bool active,
                                  const Task& task, const uint16_t* __restrict__ act_in,
                                  const int32_t* __restrict__ row_token, int K, int n_out,
                                  uint16_t* __restrict__ act_out, float* __restrict__ y_out, uint16_t* lds) {
@@ -63,19 +66,33 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_a, int64_t of
     constexpr int kBufElems = NT * 16 * kRowElems;   // one staging buffer
     const int lane = threadIdx.x & 63;
     const int kchunks = K >> 5;
-    const int64_t stripe = (int64_t)kchunks * kTileElems;        // one 16-row stripe across all of K
     const int col0 = wtile * 16 * (PASS == 0 ? G : RT);
 
     // a spare wave (columns past n_out) streams the last valid wave's stripes and stores nothing:
     // it stays in step with the barriers without a predicate around the loop
     const int wsrc = active ? wtile : (n_out / (16 * (PASS == 0 ? G : RT)) - 1);
+    // A wave's stripes all lie in one group of the packed layout; inside the group the K chunk is the
+    // slow index, so chunk c of stripe r sits at wt[r] + c * cstep.
     const uint16_t* wt[RT];
+    int64_t cstep;
+    if (PASS == 0) {
+        static_assert(PASS != 0 || kGateUpGroup % (RT / 2) == 0, "a wave's column blocks share a group");
+        const int first = wsrc * G;                                  // the wave's first SwiGLU column block
+        const int g = first / kGateUpGroup, j0 = first % kGateUpGroup;
+        const int ng = min(kGateUpGroup, n_out / 16 - g * kGateUpGroup);
+        const uint16_t* base = blob + off_w + (int64_t)g * 2 * kGateUpGroup * kchunks * kTileElems + lane * 8;
+        cstep = (int64_t)2 * ng * kTileElems;
 #pragma unroll
-    for (int r = 0; r < RT; ++r) {
-        if (PASS == 0)
-            wt[r] = blob + (r < G ? off_a : off_b) + (int64_t)(wsrc * G + (r % G)) * stripe + lane * 8;
-        else
-            wt[r] = blob + off_a + (int64_t)(wsrc * RT + r) * stripe + lane * 8;
+        for (int r = 0; r < RT; ++r) wt[r] = base + ((r < G ? 0 : ng) + j0 + (r % G)) * kTileElems;
+    } else {
+        static_assert(PASS == 0 || kDownGroup % RT == 0, "a wave's stripes share a group");
+        const int first = wsrc * RT;
+        const int g = first / kDownGroup, j0 = first % kDownGroup;
+        const int ng = min(kDownGroup, n_out / 16 - g * kDownGroup);
+        const uint16_t* base = blob + off_w + (int64_t)g * kDownGroup * kchunks * kTileElems + lane * 8;
+        cstep = (int64_t)ng * kTileElems;
+#pragma unroll
+        for (int r = 0; r < RT; ++r) wt[r] = base + (j0 + r) * kTileElems;
     }
 
     // staging map: piece q = tid + 256*j covers row q / kPPR of the item, columns (q % kPPR)*8 .. +7 of the
@@ -120,7 +137,7 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_a, int64_t of
     for (int i = 0; i < D; ++i) {
         const int ci = min(i, kchunks - 1);
 #pragma unroll
-        for (int r = 0; r < RT; ++r) a[i][r] = *reinterpret_cast<const bf16x8*>(wt[r] + (int64_t)ci * kTileElems);
+        for (int r = 0; r < RT; ++r) a[i][r] = *reinterpret_cast<const bf16x8*>(wt[r] + ci * cstep);
     }
     f32x4 acc[RT][NT];
 #pragma unroll
@@ -146,7 +163,7 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_a, int64_t of
     auto refill = [&](int c, int i) {
         const int cn = min(c + D, kchunks - 1);
 #pragma unroll
-        for (int r = 0; r < RT; ++r) a[i][r] = *reinterpret_cast<const bf16x8*>(wt[r] + (int64_t)cn * kTileElems);
+        for (int r = 0; r < RT; ++r) a[i][r] = *reinterpret_cast<const bf16x8*>(wt[r] + cn * cstep);
     };
     using all_tiles = std::integral_constant<int, NT>;
 
@@ -280,7 +297,7 @@ constexpr int kSmallRT0 = TIDE_P0_RT, kSmallD0 = TIDE_P0_D;   // gate/up: weight
 constexpr int kSmallRT1 = TIDE_P1_RT, kSmallD1 = TIDE_P1_D;   // down
 template <int PASS>
 __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
-    const uint16_t* __restrict__ slots, int64_t blob_elems, int64_t off_a, int64_t off_b,
+    const uint16_t* __restrict__ slots, int64_t blob_elems, int64_t off_w,
     const Task* __restrict__ tasks, const int32_t* __restrict__ n_tasks, const uint16_t* __restrict__ act_in,
     const int32_t* __restrict__ row_token, int K, int n_out, uint16_t* __restrict__ act_out,
     float* __restrict__ y_out) {
@@ -295,9 +312,9 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
     const uint16_t* blob = slots + (int64_t)task.slot * blob_elems;
     static_assert(kRowsPerTask == 32, "one or two 16-token tiles per small work item");
     if (task.nrows <= 16)
-        gemm_task<PASS, RT, 1, D, kSmallPC, 1>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
+        gemm_task<PASS, RT, 1, D, kSmallPC, 1>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
     else
-        gemm_task<PASS, RT, 2, D, kSmallPC, 1>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
+        gemm_task<PASS, RT, 2, D, kSmallPC, 1>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
 }
 
 // Large work items: up to 256 rows of a slot that holds more than 32.  A workgroup's tile is 256
@@ -312,7 +329,7 @@ constexpr int kBigLdsElems = 2 * 128 * (kBigPC * 32 + 8) > 2 * 256 * (kWidePC * 
 constexpr int kXcds = 8;           // accelerator complex dies, each with its own L2
 template <int PASS>
 __global__ __launch_bounds__(kWaves * 64) void expert_gemm_big_kernel(
-    const uint16_t* __restrict__ slots, int64_t blob_elems, int64_t off_a, int64_t off_b,
+    const uint16_t* __restrict__ slots, int64_t blob_elems, int64_t off_w,
     const Task* __restrict__ tasks, const int32_t* __restrict__ n_tasks, const uint16_t* __restrict__ act_in,
     const int32_t* __restrict__ row_token, int K, int n_out, uint16_t* __restrict__ act_out,
     float* __restrict__ y_out, int n_ftiles) {
@@ -336,20 +353,20 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_big_kernel(
     // only as many 16-token tiles as the item has rows: a 40-row item costs 3/8 of a 128-row one
 #define TIDE_BIG_CASE(NT_)                                                                                              \
     case NT_:                                                                                                           \
-        gemm_task<PASS, RT, NT_, kBigD, kBigPC, 2>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K, n_out, \
+        gemm_task<PASS, RT, NT_, kBigD, kBigPC, 2>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, \
                                                    act_out, y_out, lds);                                               \
         break;
 #define TIDE_WIDE_CASE(NT_)                                                                                             \
     case NT_ - 1:                                                                                                       \
     case NT_:                                                                                                           \
-        gemm_task<PASS, RT, NT_, kWideD, kWidePC, 2>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K,    \
+        gemm_task<PASS, RT, NT_, kWideD, kWidePC, 2>(blob, off_w, wtile, active, task, act_in, row_token, K,    \
                                                      n_out, act_out, y_out, lds);                                      \
         break;
     switch ((task.nrows + 15) >> 4) {
         TIDE_BIG_CASE(1) TIDE_BIG_CASE(2) TIDE_BIG_CASE(3) TIDE_BIG_CASE(4) TIDE_BIG_CASE(5) TIDE_BIG_CASE(6) TIDE_BIG_CASE(7)
         TIDE_BIG_CASE(8) TIDE_WIDE_CASE(10) TIDE_WIDE_CASE(12) TIDE_WIDE_CASE(14)
         default:
-            gemm_task<PASS, RT, 16, kWideD, kWidePC, 2>(blob, off_a, off_b, wtile, active, task, act_in, row_token, K,
+            gemm_task<PASS, RT, 16, kWideD, kWidePC, 2>(blob, off_w, wtile, active, task, act_in, row_token, K,
                                                         n_out, act_out, y_out, lds);
     }
 #undef TIDE_BIG_CASE
@@ -364,11 +381,11 @@ hipError_t launch_expert_gemm(int pass, const Shape& s, const LayerTables& t, co
     dim3 block(kWaves * 64);
     if (pass == 0) {
         TIDE_LAUNCH(expert_gemm_kernel<0>, dim3((s.I + 32 * kSmallRT0 - 1) / (32 * kSmallRT0), max_tasks), block, stream, ev, t.slots, s.blob_elems,
-                    blob_off_gate(s), blob_off_up(s), w.tasks, w.n_tasks, x, w.row_token, s.d, s.I, w.act,
+                    blob_off_gate_up(s), w.tasks, w.n_tasks, x, w.row_token, s.d, s.I, w.act,
                     (float*)nullptr);
     } else {
         TIDE_LAUNCH(expert_gemm_kernel<1>, dim3((s.d + 64 * kSmallRT1 - 1) / (64 * kSmallRT1), max_tasks), block, stream, ev, t.slots, s.blob_elems,
-                    blob_off_down(s), (int64_t)0, w.tasks, w.n_tasks, w.act, w.row_token, s.I, s.d,
+                    blob_off_down(s), w.tasks, w.n_tasks, w.act, w.row_token, s.I, s.d,
                     (uint16_t*)nullptr, w.y);
     }
     return hipGetLastError();
@@ -380,12 +397,12 @@ hipError_t launch_expert_gemm_big(int pass, const Shape& s, const LayerTables& t
     if (pass == 0) {
         const int ft = (s.I + 127) / 128;
         TIDE_LAUNCH(expert_gemm_big_kernel<0>, dim3((max_big_tasks * ft + kXcds - 1) / kXcds * kXcds), block, stream, ev,
-                    t.slots, s.blob_elems, blob_off_gate(s), blob_off_up(s), w.big_tasks, w.n_tasks, x, w.row_token, s.d,
+                    t.slots, s.blob_elems, blob_off_gate_up(s), w.big_tasks, w.n_tasks, x, w.row_token, s.d,
                     s.I, w.act, (float*)nullptr, ft);
     } else {
         const int ft = (s.d + 255) / 256;
         TIDE_LAUNCH(expert_gemm_big_kernel<1>, dim3((max_big_tasks * ft + kXcds - 1) / kXcds * kXcds), block, stream, ev,
-                    t.slots, s.blob_elems, blob_off_down(s), (int64_t)0, w.big_tasks, w.n_tasks, w.act, w.row_token, s.I,
+                    t.slots, s.blob_elems, blob_off_down(s), w.big_tasks, w.n_tasks, w.act, w.row_token, s.I,
                     s.d, (uint16_t*)nullptr, w.y, ft);
     }
     return hipGetLastError();

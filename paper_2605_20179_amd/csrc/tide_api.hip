@@ -128,16 +128,39 @@ int layer_ok(tide_ctx* ctx, int layer) {
 
 uint16_t* slot_ptr(tide_ctx* ctx, Layer& L, int slot) { return L.slots_owned + (int64_t)slot * ctx->shape.blob_elems; }
 
-void pack_matrix(const uint16_t* src, int rows, int cols, uint16_t* dst) {
-    // tile (rt, kc) of 16 rows x 32 columns -> 512 contiguous elements, lane-major:
-    // lane l holds row rt*16 + l%16, columns kc*32 + (l/16)*8 .. +7
-    const int kchunks = cols / 32;
-    for (int rt = 0; rt < rows / 16; ++rt)
-        for (int kc = 0; kc < kchunks; ++kc) {
-            uint16_t* tile = dst + ((int64_t)rt * kchunks + kc) * 512;
-            for (int l = 0; l < 64; ++l)
-                memcpy(tile + l * 8, src + (int64_t)(rt * 16 + (l & 15)) * cols + kc * 32 + (l >> 4) * 8, 16);
-        }
+// One 16-row x 32-column tile of a row-major matrix -> 512 contiguous elements, lane-major:
+// lane l holds row stripe*16 + l%16, columns kc*32 + (l/16)*8 .. +7 (the A operand of the 16x16x32 MFMA).
+void pack_tile(const uint16_t* src, int cols, int stripe, int kc, uint16_t* tile) {
+    for (int l = 0; l < 64; ++l)
+        memcpy(tile + l * 8, src + (int64_t)(stripe * 16 + (l & 15)) * cols + kc * 32 + (l >> 4) * 8, 16);
+}
+
+// Streaming order of the tiles.  The 16-row stripes of a matrix are taken in groups -- the stripes one
+// workgroup of the GEMM kernels consumes together -- and inside a group the K chunk is the slow index,
+// so a workgroup walks one contiguous region front to back (16 KiB per chunk for a full group).
+//   gate/up: a group is 8 SwiGLU column blocks = their 8 gate stripes, then their 8 up stripes
+//   down:    a group is 16 stripes (256 output columns)
+// A last, partial group holds fewer stripes and is laid out the same way.
+void pack_gate_up(const uint16_t* wg, const uint16_t* wu, int d_ff, int d, uint16_t* dst) {
+    const int kchunks = d / 32, blocks = d_ff / 16;
+    for (int g = 0; g * kGateUpGroup < blocks; ++g) {
+        const int ng = std::min(kGateUpGroup, blocks - g * kGateUpGroup);
+        uint16_t* base = dst + (int64_t)g * 2 * kGateUpGroup * kchunks * 512;
+        for (int kc = 0; kc < kchunks; ++kc)
+            for (int j = 0; j < ng; ++j) {
+                pack_tile(wg, d, g * kGateUpGroup + j, kc, base + ((int64_t)kc * 2 * ng + j) * 512);
+                pack_tile(wu, d, g * kGateUpGroup + j, kc, base + ((int64_t)kc * 2 * ng + ng + j) * 512);
+            }
+    }
+}
+void pack_down(const uint16_t* wd, int d, int d_ff, uint16_t* dst) {
+    const int kchunks = d_ff / 32, stripes = d / 16;
+    for (int g = 0; g * kDownGroup < stripes; ++g) {
+        const int ng = std::min(kDownGroup, stripes - g * kDownGroup);
+        uint16_t* base = dst + (int64_t)g * kDownGroup * kchunks * 512;
+        for (int kc = 0; kc < kchunks; ++kc)
+            for (int j = 0; j < ng; ++j) pack_tile(wd, d_ff, g * kDownGroup + j, kc, base + ((int64_t)kc * ng + j) * 512);
+    }
 }
 
 int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const int32_t* idx,
@@ -208,9 +231,8 @@ int tide_pack_expert(const tide_config* cfg, const uint16_t* wg, const uint16_t*
     if (!wg || !wu || !wd || !blob) return fail(nullptr, TIDE_E_INVAL, "null matrix or blob");
     uint16_t* b = static_cast<uint16_t*>(blob);
     const int64_t n = (int64_t)cfg->d * cfg->d_ff;
-    pack_matrix(wg, cfg->d_ff, cfg->d, b);
-    pack_matrix(wu, cfg->d_ff, cfg->d, b + n);
-    pack_matrix(wd, cfg->d, cfg->d_ff, b + 2 * n);
+    pack_gate_up(wg, wu, cfg->d_ff, cfg->d, b);
+    pack_down(wd, cfg->d, cfg->d_ff, b + 2 * n);
     return TIDE_OK;
 }
 

@@ -145,9 +145,11 @@ struct RefreshOut {           // lives in pinned host memory the kernel writes d
 hipError_t launch_refresh_select(const Shape& s, const LayerTables& t, const int32_t* counts, int capacity,
                                  int reset_counts, RefreshOut* out_hostmapped, hipStream_t stream);
 
-// number of packed elements before each matrix inside a blob
-inline int64_t blob_off_gate(const Shape&) { return 0; }
-inline int64_t blob_off_up(const Shape& s) { return (int64_t)s.d * s.I; }
+// Packed blob: the gate and up matrices interleaved (2*d*I elements), then the down matrix (d*I).
+// Stripes (16 matrix rows) are stored in groups, K chunk slow inside a group (tide_pack_expert).
+constexpr int kGateUpGroup = 8;     // SwiGLU column blocks (a gate and an up stripe each) per group
+constexpr int kDownGroup = 16;      // down stripes per group
+inline int64_t blob_off_gate_up(const Shape&) { return 0; }
 inline int64_t blob_off_down(const Shape& s) { return 2 * (int64_t)s.d * s.I; }
 
 }  // namespace tide

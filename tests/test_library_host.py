@@ -36,25 +36,39 @@ def test_struct_layouts_match_the_header(tb):
 
 
 def test_pack_layout(tb):
-    """Tile (rt, kc) of 16 rows x 32 columns is 512 contiguous elements; lane l holds row
-    rt*16 + l%16, columns kc*32 + (l/16)*8 .. +7; gate, up, down matrices follow each other."""
-    d, I = 128, 64
+    """A tile of 16 rows x 32 columns is 512 contiguous elements; lane l holds row stripe*16 + l%16,
+    columns kc*32 + (l/16)*8 .. +7.  Stripes are stored in groups, K chunk slow inside a group:
+    gate/up groups hold 8 SwiGLU column blocks (their gate stripes, then their up stripes), down
+    groups 16 stripes; a last partial group holds fewer.  The down matrix follows gate/up."""
+    d, I = 320, 192          # 10 K chunks; 12 column blocks (8 + 4); 20 down stripes (16 + 4)
     cfg = tb.make_config(d, 8, 2, I, 0, 1, 4, 8, 0, 0)
-    wg = np.arange(I * d, dtype=np.uint16).reshape(I, d)
-    wu = (np.arange(I * d, dtype=np.uint32) + 20000).astype(np.uint16).reshape(I, d)
-    wd = (np.arange(I * d, dtype=np.uint32) + 40000).astype(np.uint16).reshape(d, I)
+    rng = np.random.default_rng(3)
+    wg, wu = (rng.integers(0, 2 ** 16, size=(I, d), dtype=np.uint16) for _ in range(2))
+    wd = rng.integers(0, 2 ** 16, size=(d, I), dtype=np.uint16)
     blob = np.zeros(tb.tide_expert_blob_bytes(cfg), dtype=np.uint8)
     assert blob.size == 3 * d * I * 2
     tb.tide_pack_expert(cfg, wg, wu, wd, blob)
     b = blob.view(np.uint16)
-    for mat, rows, cols, base in ((wg, I, d, 0), (wu, I, d, I * d), (wd, d, I, 2 * I * d)):
-        kch = cols // 32
-        for rt in range(rows // 16):
-            for kc in range(kch):
-                tile = b[base + (rt * kch + kc) * 512: base + (rt * kch + kc + 1) * 512].reshape(64, 8)
-                for l in (0, 1, 15, 16, 37, 63):
-                    want = mat[rt * 16 + l % 16, kc * 32 + (l // 16) * 8: kc * 32 + (l // 16) * 8 + 8]
-                    assert np.array_equal(tile[l], want)
+
+    def check_tile(at, mat, stripe, kc):
+        tile = b[at * 512:(at + 1) * 512].reshape(64, 8)
+        for l in (0, 1, 15, 16, 37, 63):
+            want = mat[stripe * 16 + l % 16, kc * 32 + (l // 16) * 8: kc * 32 + (l // 16) * 8 + 8]
+            assert np.array_equal(tile[l], want), (at, stripe, kc, l)
+
+    kch, blocks = d // 32, I // 16
+    for g in range((blocks + 7) // 8):
+        ng = min(8, blocks - 8 * g)
+        for kc in range(kch):
+            for j in range(ng):
+                check_tile(g * 16 * kch + kc * 2 * ng + j, wg, 8 * g + j, kc)
+                check_tile(g * 16 * kch + kc * 2 * ng + ng + j, wu, 8 * g + j, kc)
+    kch, stripes, base = I // 32, d // 16, 2 * d * I // 512
+    for g in range((stripes + 15) // 16):
+        ng = min(16, stripes - 16 * g)
+        for kc in range(kch):
+            for j in range(ng):
+                check_tile(base + g * 16 * kch + kc * ng + j, wd, 16 * g + j, kc)
     # a permutation: nothing lost, nothing duplicated
     assert np.array_equal(np.sort(b), np.sort(np.concatenate([wg.ravel(), wu.ravel(), wd.ravel()])))
 
