@@ -327,24 +327,57 @@ constexpr int kWidePC = 4, kWideD = 4;     // 9..16 token tiles
 constexpr int kBigLdsElems = 2 * 128 * (kBigPC * 32 + 8) > 2 * 256 * (kWidePC * 32 + 8) ? 2 * 128 * (kBigPC * 32 + 8)
                                                                                       : 2 * 256 * (kWidePC * 32 + 8);
 constexpr int kXcds = 8;           // accelerator complex dies, each with its own L2
+
+// Order of the large work.  The work items are ranked heaviest first (plan_big_kernel) and dealt to
+// eight lists, one per XCD, in serpentine order (ranks 0..7 to lists 0..7, ranks 8..15 to lists 7..0,
+// ...), so the lists hold about equal work.  Workgroups are handed to the XCDs round-robin by linear
+// id and started in id order as compute units fall free: workgroup b runs on XCD b % 8 and takes unit
+// b / 8 of that XCD's list (its work items in rank order, feature tile fastest).  Heavy units start
+// first, the light ones fill the end of the launch; the units of a work item share their token rows
+// through the XCD's L2.
+__device__ inline int list_tasks(int x, int n) {         // work items in list x when n are ranked
+    const int lo = x, hi = 2 * kXcds - 1 - x;
+    return (n > lo ? (n - lo + 2 * kXcds - 1) / (2 * kXcds) : 0) + (n > hi ? (n - hi + 2 * kXcds - 1) / (2 * kXcds) : 0);
+}
+__device__ inline int list_rank(int x, int j) {          // rank of list x's j-th work item
+    return (j >> 1) * 2 * kXcds + ((j & 1) ? 2 * kXcds - 1 - x : x);
+}
+
+constexpr int kPlanThreads = 256;
+constexpr int kTileClasses = kRowsPerBigTask / 16;       // work items are ranked by their number of 16-token tiles
+__global__ __launch_bounds__(kPlanThreads) void plan_big_kernel(const Task* __restrict__ tasks,
+                                                               const int32_t* __restrict__ n_tasks,
+                                                               int32_t* __restrict__ order) {
+    __shared__ int count[kTileClasses + 1], first[kTileClasses + 1];
+    const int tid = threadIdx.x, n = n_tasks[1];
+    if (tid <= kTileClasses) count[tid] = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += kPlanThreads) atomicAdd(&count[min((tasks[i].nrows + 15) >> 4, kTileClasses)], 1);
+    __syncthreads();
+    if (tid == 0) {
+        int at = 0;
+        for (int c = kTileClasses; c >= 0; --c) {
+            first[c] = at;
+            at += count[c];
+        }
+    }
+    __syncthreads();
+    // the order inside a class does not matter (equal cost); every rank 0..n-1 is written exactly once
+    for (int i = tid; i < n; i += kPlanThreads) order[atomicAdd(&first[min((tasks[i].nrows + 15) >> 4, kTileClasses)], 1)] = i;
+}
+
 template <int PASS>
 __global__ __launch_bounds__(kWaves * 64) void expert_gemm_big_kernel(
-    const uint16_t* __restrict__ slots, int64_t blob_elems, int64_t off_w,
-    const Task* __restrict__ tasks, const int32_t* __restrict__ n_tasks, const uint16_t* __restrict__ act_in,
+    const uint16_t* __restrict__ slots, int64_t blob_elems, int64_t off_w, const Task* __restrict__ tasks,
+    const int32_t* __restrict__ n_tasks, const int32_t* __restrict__ order, const uint16_t* __restrict__ act_in,
     const int32_t* __restrict__ row_token, int K, int n_out, uint16_t* __restrict__ act_out,
     float* __restrict__ y_out, int n_ftiles) {
     constexpr int RT = 4;
     __shared__ __attribute__((aligned(16))) uint16_t lds[kBigLdsElems];
-    // Work units (work item, feature tile) are listed slot by slot, row chunk by row chunk, feature
-    // tile fastest, so neighbours share weight stripes or token rows.  Workgroups are handed to
-    // the chip's 8 XCDs round-robin by their linear id; XCD x takes the x-th contiguous eighth of
-    // the list in order, so the units in flight on one XCD find each other's data in its L2.
-    const int n_units = n_tasks[1] * n_ftiles;
-    const int seg = (n_units + kXcds - 1) / kXcds;
-    const int xcd = blockIdx.x % kXcds, j = blockIdx.x / kXcds;
-    const int unit = xcd * seg + j;
-    if (j >= seg || unit >= n_units) return;
-    const int task_id = unit / n_ftiles;
+    const int n_big = n_tasks[1];
+    const int xcd = blockIdx.x % kXcds, unit = blockIdx.x / kXcds;
+    if (unit >= list_tasks(xcd, n_big) * n_ftiles) return;
+    const int task_id = order[list_rank(xcd, unit / n_ftiles)];
     const int wtile = (unit % n_ftiles) * kWaves + (threadIdx.x >> 6);
     const bool active = wtile * 16 * (PASS == 0 ? RT / 2 : RT) < n_out;
     const Task task = tasks[task_id];
@@ -391,19 +424,25 @@ hipError_t launch_expert_gemm(int pass, const Shape& s, const LayerTables& t, co
     return hipGetLastError();
 }
 
+hipError_t launch_plan_big(const Workspace& w, int max_big_tasks, hipStream_t stream) {
+    if (max_big_tasks <= 0) return hipSuccess;
+    hipLaunchKernelGGL(plan_big_kernel, dim3(1), dim3(kPlanThreads), 0, stream, w.big_tasks, w.n_tasks, w.big_order);
+    return hipGetLastError();
+}
+
 hipError_t launch_expert_gemm_big(int pass, const Shape& s, const LayerTables& t, const Workspace& w,
                                   const uint16_t* x, int max_big_tasks, hipStream_t stream, LaunchEvents ev) {
+    if (max_big_tasks <= 0) return hipSuccess;
     dim3 block(kWaves * 64);
+    const int ft = pass == 0 ? (s.I + 127) / 128 : (s.d + 255) / 256;
+    // the longest list holds 2 * ceil(n / 16) work items
+    const dim3 grid((unsigned)((max_big_tasks + 2 * kXcds - 1) / (2 * kXcds) * 2 * ft * kXcds));
     if (pass == 0) {
-        const int ft = (s.I + 127) / 128;
-        TIDE_LAUNCH(expert_gemm_big_kernel<0>, dim3((max_big_tasks * ft + kXcds - 1) / kXcds * kXcds), block, stream, ev,
-                    t.slots, s.blob_elems, blob_off_gate_up(s), w.big_tasks, w.n_tasks, x, w.row_token, s.d,
-                    s.I, w.act, (float*)nullptr, ft);
+        TIDE_LAUNCH(expert_gemm_big_kernel<0>, grid, block, stream, ev, t.slots, s.blob_elems, blob_off_gate_up(s),
+                    w.big_tasks, w.n_tasks, w.big_order, x, w.row_token, s.d, s.I, w.act, (float*)nullptr, ft);
     } else {
-        const int ft = (s.d + 255) / 256;
-        TIDE_LAUNCH(expert_gemm_big_kernel<1>, dim3((max_big_tasks * ft + kXcds - 1) / kXcds * kXcds), block, stream, ev,
-                    t.slots, s.blob_elems, blob_off_down(s), w.big_tasks, w.n_tasks, w.act, w.row_token, s.I,
-                    s.d, (uint16_t*)nullptr, w.y, ft);
+        TIDE_LAUNCH(expert_gemm_big_kernel<1>, grid, block, stream, ev, t.slots, s.blob_elems, blob_off_down(s),
+                    w.big_tasks, w.n_tasks, w.big_order, w.act, w.row_token, s.I, s.d, (uint16_t*)nullptr, w.y, ft);
     }
     return hipGetLastError();
 }

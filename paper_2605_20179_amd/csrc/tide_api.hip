@@ -180,6 +180,7 @@ int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, 
     // Small and large work items touch disjoint rows: the large ones run on a second stream so that
     // the two kinds of kernels overlap on the chip (fork after the split, join before the combine).
     if (max_big > 0) {
+        TIDE_HIP(ctx, launch_plan_big(ctx->ws, max_big, stream));
         TIDE_HIP(ctx, hipEventRecord(ctx->fork_ev, stream));
         TIDE_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_ev, 0));
         TIDE_HIP(ctx, timed(ctx, TIDE_K_GATE_UP_BIG, [&](LaunchEvents ev) {
@@ -268,7 +269,8 @@ int tide_create(const tide_config* cfg, tide_ctx** out) {
         (rc = ws_alloc(ctx, &w.topk_w, P)) || (rc = ws_alloc(ctx, &w.hist_step, s.E)) ||
         (rc = ws_alloc(ctx, &w.row_token, ctx->max_rows)) || (rc = ws_alloc(ctx, &w.pair_row, P)) ||
         (rc = ws_alloc(ctx, &w.slot_off, s.capacity + 2)) || (rc = ws_alloc(ctx, &w.tasks, ctx->max_tasks)) ||
-        (rc = ws_alloc(ctx, &w.big_tasks, max_big + 1)) || (rc = ws_alloc(ctx, &w.n_tasks, 2)) || (rc = ws_alloc(ctx, &w.act, (int64_t)ctx->max_rows * s.I)) ||
+        (rc = ws_alloc(ctx, &w.big_tasks, max_big + 1)) || (rc = ws_alloc(ctx, &w.n_tasks, 2)) ||
+        (rc = ws_alloc(ctx, &w.big_order, max_big + 1)) || (rc = ws_alloc(ctx, &w.act, (int64_t)ctx->max_rows * s.I)) ||
         (rc = ws_alloc(ctx, &w.y, (int64_t)ctx->max_rows * s.d)) || (rc = ws_alloc(ctx, &w.counts_tmp, s.E)) ||
         (rc = ws_alloc(ctx, &w.counters, 4)) || (rc = ws_alloc(ctx, &w.m_idx, P)) || (rc = ws_alloc(ctx, &w.m_tok, P)) ||
         (rc = ws_alloc(ctx, &w.m_w, P)) || (rc = ws_alloc(ctx, &w.miss_hist, s.E)) || (rc = ws_alloc(ctx, &w.m_count, 1)))
@@ -450,6 +452,7 @@ int tide_moe_apply_misses(tide_ctx* ctx, int layer, const void* hidden_dev, int 
     TIDE_HIP(ctx, launch_clear_i32(ctx->ws.miss_hist, ctx->cfg.n_experts, stream));
     TIDE_HIP(ctx, launch_miss_group(ctx->shape, ctx->ws, miss_dev, miss_cap, n_miss_dev, max_big, stream));
     TIDE_HIP(ctx, launch_expert_gemm(0, shape, host_view, ctx->ws, x, max_small, stream));
+    if (max_big > 0) TIDE_HIP(ctx, launch_plan_big(ctx->ws, max_big, stream));
     if (max_big > 0) TIDE_HIP(ctx, launch_expert_gemm_big(0, shape, host_view, ctx->ws, x, max_big, stream));
     TIDE_HIP(ctx, launch_expert_gemm(1, shape, host_view, ctx->ws, x, max_small, stream));
     if (max_big > 0) TIDE_HIP(ctx, launch_expert_gemm_big(1, shape, host_view, ctx->ws, x, max_big, stream));

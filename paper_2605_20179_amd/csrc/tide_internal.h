@@ -40,6 +40,7 @@ struct Workspace {
     Task*    tasks;       // [max_small_tasks] small work items
     Task*    big_tasks;   // [max_big_tasks] large work items
     int32_t* n_tasks;     // [2] number of small, large work items
+    int32_t* big_order;   // [max_big_tasks] large work items, heaviest first
     uint16_t* act;        // [max_rows][d_ff] bf16 SwiGLU activations
     float*   y;           // [max_rows][d] per-row expert outputs
     int32_t* counts_tmp;  // [E] caller-provided counts for a refresh
@@ -105,6 +106,9 @@ hipError_t launch_expert_gemm(int pass, const Shape& s, const LayerTables& t, co
                               int max_tasks, hipStream_t stream, LaunchEvents ev = {});
 hipError_t launch_expert_gemm_big(int pass, const Shape& s, const LayerTables& t, const Workspace& w,
                                   const uint16_t* x, int max_big_tasks, hipStream_t stream, LaunchEvents ev = {});
+// ranks the large work items heaviest first (w.big_order); runs after the work items are written and
+// before launch_expert_gemm_big
+hipError_t launch_plan_big(const Workspace& w, int max_big_tasks, hipStream_t stream);
 // upper bound of the number of large work items a step over n_tokens tokens can produce
 inline int max_big_tasks_for(const Shape& s, int n_tokens) {
     if (n_tokens <= kBigMinRows) return 0;
