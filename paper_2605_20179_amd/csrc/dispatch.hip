@@ -9,7 +9,7 @@ namespace tide {
 
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 1024;
 
 __device__ inline int block_sum(int v, int* lds4) {
 #pragma unroll
