@@ -129,8 +129,8 @@ __device__ inline void collect_rows(const int32_t* __restrict__ idx, const int32
 __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w, int n_tokens, int k, int capacity,
     int n_shared, int n_experts, const int32_t* __restrict__ slot_of, const int32_t* __restrict__ expert_in_slot,
-    const int32_t* __restrict__ hist_step, int32_t* __restrict__ row_token, int32_t* __restrict__ pair_row,
-    int32_t* __restrict__ slot_off, Task* __restrict__ tasks, Task* __restrict__ big_tasks,
+    const int32_t* __restrict__ hist_step, int32_t* __restrict__ hits, int32_t* __restrict__ row_token,
+    int32_t* __restrict__ pair_row, int32_t* __restrict__ slot_off, Task* __restrict__ tasks, Task* __restrict__ big_tasks,
     int32_t* __restrict__ n_tasks,
     tide_miss* __restrict__ miss, int miss_cap, int32_t* __restrict__ n_miss, int64_t* __restrict__ counters,
     int max_big) {
@@ -197,6 +197,9 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     big_before = block_sum(big_before, lds4);
 
     if (s == capacity) {
+        // the interval counter takes the step's histogram (Fig. 1 caption: every selected expert counts,
+        // resident or not); this block is the step's only writer of H
+        for (int e = tid; e < n_experts; e += kThreads) hits[e] += hist_step[e];
         // shared expert: every token, in token order
         const int m = n_shared ? n_tokens : 0;
         for (int n = tid; n < m; n += kThreads) row_token[rows_before + n] = n;
@@ -337,7 +340,7 @@ hipError_t launch_dispatch(const Shape& s, const LayerTables& t, const Workspace
                            const float* topk_w, int n_tokens, tide_miss* miss, int miss_cap, int32_t* n_miss,
                            hipStream_t stream, LaunchEvents ev) {
     TIDE_LAUNCH(dispatch_kernel, dim3(s.capacity + 2), dim3(kThreads), stream, ev, topk_idx, topk_w,
-                       n_tokens, s.k, s.capacity, s.n_shared, s.E, t.slot_of, t.expert_in_slot, w.hist_step,
+                       n_tokens, s.k, s.capacity, s.n_shared, s.E, t.slot_of, t.expert_in_slot, w.hist_step, t.hits,
                        w.row_token, w.pair_row, w.slot_off, w.tasks, w.big_tasks, w.n_tasks, miss, miss_cap, n_miss, w.counters,
                 max_big_tasks_for(s, n_tokens));
     return hipGetLastError();

@@ -398,8 +398,7 @@ __device__ inline void select16(int n_base, float (&z)[NG][V], const float* __re
                 s_idx[p] = my_e[g];
                 s_w[p] = w;
             } else {
-                atomicAdd(&hist_step[my_e[g]], 1);
-                atomicAdd(&hits[my_e[g]], 1);
+                atomicAdd(&hist_step[my_e[g]], 1);    // H += hist_step follows in the split kernel (one writer)
             }
         }
     }
@@ -474,8 +473,7 @@ __global__ void count_pairs_kernel(const int32_t* __restrict__ topk_idx, int n_p
     if (p < n_pairs) {
         const int e = topk_idx[p];
         if (e < 0 || e >= n_experts) return;
-        atomicAdd(&hist_step[e], 1);
-        atomicAdd(&hits[e], 1);
+        atomicAdd(&hist_step[e], 1);              // H += hist_step follows in the split kernel (one writer)
     }
 }
 
