@@ -222,6 +222,41 @@ int tide_profile_read(tide_ctx* ctx, double* ms_sum_host, int64_t* launches_host
  * Synchronises hip_stream; reset != 0 zeroes them afterwards. */
 int tide_counters(tide_ctx* ctx, int64_t* out4_host, int reset, void* hip_stream);
 
+/* ---- refresh-interval analysis (Sec. 3.2; Sec. 3.3 "Interval-based Expert Refresh", Eq. 4-7) ---- */
+
+/* Copies the last step's activation vector -- counts_host[e] = number of tokens that selected
+ * expert e in the most recent tide_moe_step / tide_moe_step_routed on this context (Fig. 1a's
+ * per-step vectors) -- to host memory.  n_experts must equal the configuration's.  Synchronises
+ * hip_stream. */
+int tide_step_histogram(tide_ctx* ctx, int32_t* counts_host, int n_experts, void* hip_stream);
+/* Routing stability of a run of steps from their activation vectors counts_dev[n_steps][n_experts]
+ * (device, int32, row-major).  Any output may be NULL.
+ *   sim_dev[n_steps][n_steps] (device, fp64): cosine similarity of steps i and j (Sec. 3.2); a step with
+ *     no activations has similarity 0 with every step;
+ *   unique_dev[n_steps] (device, int32): distinct experts activated at each step (Fig. 2a);
+ *   drift_dev[n_steps] (device, fp64): Eq. 4, d_t = |Delta K_t| / budget, where K_t is the top-`budget`
+ *     set of step t's own counts (count descending, lower expert first) and Delta K_t the experts of
+ *     K_t that are not in K_{t-1}; d_0 = 0.
+ * 1 <= n_experts <= 512, 1 <= budget <= n_experts, n_steps >= 1.  Enqueued on hip_stream, not
+ * synchronised.  ctx may be NULL (then errors carry no text). */
+int tide_routing_stability(tide_ctx* ctx, const int32_t* counts_dev, int n_steps, int n_experts, int budget,
+                           double* sim_dev, int32_t* unique_dev, double* drift_dev, void* hip_stream);
+/* The cost model for every candidate interval tau = 1 .. n_steps-1 (host arrays of n_steps-1 doubles):
+ *   lat_io_host[tau-1]  = c_io  * (budget * n_steps / tau) * (1 - (1-d)^tau)      (Eq. 5)
+ *   lat_cpu_host[tau-1] = c_cpu * n_steps * budget * f_host[tau-1]                (Eq. 6, f_host[tau-1] = f(tau))
+ * Pure host arithmetic in fp64; needs no device.  0 <= d <= 1, n_steps >= 2. */
+int tide_interval_costs(int budget, int n_steps, double d, double c_io, double c_cpu, const double* f_host,
+                        double* lat_io_host, double* lat_cpu_host);
+/* Eq. 7 read as min over tau in 1..n_steps-1 of lat_io + lat_cpu, by scanning all candidates (equal totals:
+ * the smaller tau): *tau_host = the minimiser, *cost_host = its total.  Host only. */
+int tide_optimal_interval(int budget, int n_steps, double d, double c_io, double c_cpu, const double* f_host,
+                          int* tau_host, double* cost_host);
+
+/* The constant drift rate for which Eq. 5 reproduces a measured number of migrated experts over n_steps
+ * steps at interval tau: *d_host = 1 - (1 - migrations*tau/(budget*n_steps))^(1/tau), the fraction clamped
+ * to [0, 1].  Host only. */
+int tide_fit_drift(double migrations, int budget, int n_steps, int tau, double* d_host);
+
 #ifdef __cplusplus
 }
 #endif

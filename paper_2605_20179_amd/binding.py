@@ -23,6 +23,7 @@ EXPORTS = [
     "tide_register_experts", "tide_set_shared", "tide_set_resident", "tide_moe_step", "tide_moe_step_routed",
     "tide_interval_stats", "tide_refresh", "tide_wait_refresh", "tide_get_table", "tide_read_slot",
     "tide_refresh_copy_ms", "tide_profile", "tide_profile_read", "tide_counters", "tide_moe_apply_misses",
+    "tide_step_histogram", "tide_routing_stability", "tide_interval_costs", "tide_optimal_interval", "tide_fit_drift",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -78,6 +79,12 @@ def _load() -> C.CDLL:
     lib.tide_profile.argtypes = [vp, C.c_int]
     lib.tide_profile_read.argtypes = [vp, vp, vp]
     lib.tide_counters.argtypes = [vp, vp, C.c_int, vp]
+    lib.tide_step_histogram.argtypes = [vp, vp, C.c_int, vp]
+    lib.tide_routing_stability.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp]
+    lib.tide_interval_costs.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, vp, vp, vp]
+    lib.tide_fit_drift.argtypes = [C.c_double, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double)]
+    lib.tide_optimal_interval.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, vp, C.POINTER(C.c_int),
+                                          C.POINTER(C.c_double)]
     for name in EXPORTS:
         if name not in ("tide_last_error", "tide_expert_blob_bytes"):
             getattr(lib, name).restype = C.c_int
@@ -223,3 +230,40 @@ def tide_counters(ctx, reset: bool = False, stream=None):
     out = np.zeros(4, dtype=np.int64)
     _check(lib.tide_counters(ctx, _ptr(out), int(reset), _stream_ptr(stream)), ctx)
     return dict(steps=int(out[0]), active_slots=int(out[1]), rows=int(out[2]), misses=int(out[3]))
+
+
+def tide_step_histogram(ctx, n_experts: int, stream=None) -> np.ndarray:
+    """The last step's activation vector (tokens per expert) as a host array."""
+    out = np.zeros(n_experts, dtype=np.int32)
+    _check(lib.tide_step_histogram(ctx, _ptr(out), n_experts, _stream_ptr(stream)), ctx)
+    return out
+
+
+def tide_routing_stability(ctx, counts_dev, n_steps: int, n_experts: int, budget: int, sim_dev, unique_dev, drift_dev,
+                           stream=None) -> None:
+    _check(lib.tide_routing_stability(ctx, _ptr(counts_dev), n_steps, n_experts, budget, _ptr(sim_dev), _ptr(unique_dev),
+                                      _ptr(drift_dev), _stream_ptr(stream)), ctx)
+
+
+def tide_interval_costs(budget: int, n_steps: int, d: float, c_io: float, c_cpu: float, f):
+    """(lat_io[tau-1], lat_cpu[tau-1]) for tau = 1..n_steps-1."""
+    f = np.ascontiguousarray(f, dtype=np.float64)
+    assert n_steps < 2 or f.size == n_steps - 1
+    io, cpu = np.zeros(n_steps - 1), np.zeros(n_steps - 1)
+    _check(lib.tide_interval_costs(budget, n_steps, d, c_io, c_cpu, _ptr(f), _ptr(io), _ptr(cpu)), None)
+    return io, cpu
+
+
+def tide_optimal_interval(budget: int, n_steps: int, d: float, c_io: float, c_cpu: float, f):
+    """(tau, total cost) minimising lat_io + lat_cpu over tau = 1..n_steps-1."""
+    f = np.ascontiguousarray(f, dtype=np.float64)
+    assert n_steps < 2 or f.size == n_steps - 1
+    tau, cost = C.c_int(0), C.c_double(0.0)
+    _check(lib.tide_optimal_interval(budget, n_steps, d, c_io, c_cpu, _ptr(f), C.byref(tau), C.byref(cost)), None)
+    return tau.value, cost.value
+
+
+def tide_fit_drift(migrations: float, budget: int, n_steps: int, tau: int) -> float:
+    d = C.c_double(0.0)
+    _check(lib.tide_fit_drift(migrations, budget, n_steps, tau, C.byref(d)), None)
+    return d.value

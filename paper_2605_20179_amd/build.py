@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtide.so")
 
-SOURCES = ["router.hip", "dispatch.hip", "expert_gemm.hip", "combine.hip", "refresh.hip", "tide_api.hip"]
+SOURCES = ["router.hip", "dispatch.hip", "expert_gemm.hip", "combine.hip", "refresh.hip", "analysis.hip", "tide_api.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          # keep the compiler from forming packed-fp32 instructions

@@ -424,7 +424,8 @@ template <int V>
 __global__ __launch_bounds__(256) void route_small_kernel(const float* __restrict__ z_part, int k_splits, int e_pad,
                                                           const float* __restrict__ bias, int n_experts, int gating,
                                                           int bias_mode, int32_t* __restrict__ topk_idx,
-                                                          float* __restrict__ topk_w, int32_t* __restrict__ hits,
+                                                          float* __restrict__ topk_w, int32_t* __restrict__ hist_step,
+                                                          int32_t* __restrict__ hits,
                                                           int32_t* __restrict__ idx_copy, float* __restrict__ w_copy,
                                                           DispatchArgs da) {
     __shared__ unsigned s_mask[kMaxExperts];     // per expert: bit n set when token n selected it
@@ -456,8 +457,11 @@ __global__ __launch_bounds__(256) void route_small_kernel(const float* __restric
     select16<V, true, 2>(0, z, bias, da.n_tokens, n_experts, da.k, gating, bias_mode, topk_idx, topk_w, nullptr, hits,
                          idx_copy, w_copy, s_mask, s_idx, s_w);
     __syncthreads();
-    for (int e = threadIdx.x; e < n_experts; e += 256)
-        if (s_mask[e]) hits[e] += __popc(s_mask[e]);     // this workgroup is the step's only writer of H
+    for (int e = threadIdx.x; e < n_experts; e += 256) {
+        const int c = __popc(s_mask[e]);
+        hist_step[e] = c;                                // the step's activation vector
+        if (c) hits[e] += c;                             // this workgroup is the step's only writer of H
+    }
     dispatch_small(da, s_mask, s_slot_of, s_eis, s_idx, s_w, s_work);
 }
 #undef EXPERT_OF
@@ -548,10 +552,10 @@ hipError_t launch_route_small(const Shape& s, const LayerTables& t, const Worksp
     da.n_miss = n_miss; da.counters = w.counters;
     if (s.E <= 256)
         TIDE_LAUNCH(route_small_kernel<16>, dim3(1), dim3(256), stream, ev, w.logits, ks, e_pad, bias, s.E, s.gating,
-                    s.bias_mode, w.topk_idx, w.topk_w, t.hits, idx_copy, w_copy, da);
+                    s.bias_mode, w.topk_idx, w.topk_w, w.hist_step, t.hits, idx_copy, w_copy, da);
     else
         TIDE_LAUNCH(route_small_kernel<32>, dim3(1), dim3(256), stream, ev, w.logits, ks, e_pad, bias, s.E, s.gating,
-                    s.bias_mode, w.topk_idx, w.topk_w, t.hits, idx_copy, w_copy, da);
+                    s.bias_mode, w.topk_idx, w.topk_w, w.hist_step, t.hits, idx_copy, w_copy, da);
     return hipGetLastError();
 }
 

@@ -586,4 +586,58 @@ int tide_counters(tide_ctx* ctx, int64_t* out4, int reset, void* hip_stream) {
     return TIDE_OK;
 }
 
+int tide_step_histogram(tide_ctx* ctx, int32_t* counts_host, int n_experts, void* hip_stream) {
+    if (!ctx || !counts_host) return ctx ? fail(ctx, TIDE_E_INVAL, "null output") : TIDE_E_INVAL;
+    if (n_experts != ctx->cfg.n_experts) return fail(ctx, TIDE_E_RANGE, "n_experts %d != configured %d", n_experts, ctx->cfg.n_experts);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    TIDE_HIP(ctx, hipMemcpyAsync(counts_host, ctx->ws.hist_step, (size_t)n_experts * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    TIDE_HIP(ctx, hipStreamSynchronize(stream));
+    return TIDE_OK;
+}
+
+int tide_routing_stability(tide_ctx* ctx, const int32_t* counts_dev, int n_steps, int n_experts, int budget,
+                           double* sim_dev, int32_t* unique_dev, double* drift_dev, void* hip_stream) {
+    if (!counts_dev) return fail(ctx, TIDE_E_INVAL, "counts_dev is null");
+    if (n_steps < 1 || n_steps > 65535) return fail(ctx, TIDE_E_RANGE, "n_steps must be 1..65535");
+    if (n_experts < 1 || n_experts > kMaxExperts) return fail(ctx, TIDE_E_RANGE, "n_experts must be 1..%d", kMaxExperts);
+    if (drift_dev && (budget < 1 || budget > n_experts)) return fail(ctx, TIDE_E_RANGE, "budget must be 1..n_experts");
+    hipError_t e = launch_routing_stability(counts_dev, n_steps, n_experts, budget, sim_dev, unique_dev, drift_dev,
+                                            static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(ctx, TIDE_E_HIP, "routing stability kernels: %s", hipGetErrorString(e));
+    return TIDE_OK;
+}
+
+int tide_interval_costs(int budget, int n_steps, double d, double c_io, double c_cpu, const double* f_host,
+                        double* lat_io_host, double* lat_cpu_host) {
+    if (!f_host || !lat_io_host || !lat_cpu_host) return fail(nullptr, TIDE_E_INVAL, "null array");
+    if (budget < 1 || n_steps < 2) return fail(nullptr, TIDE_E_RANGE, "budget must be >= 1 and n_steps >= 2");
+    if (!(d >= 0.0 && d <= 1.0)) return fail(nullptr, TIDE_E_RANGE, "drift rate must be in [0, 1]");
+    interval_costs(budget, n_steps, d, c_io, c_cpu, f_host, lat_io_host, lat_cpu_host);
+    return TIDE_OK;
+}
+
+int tide_optimal_interval(int budget, int n_steps, double d, double c_io, double c_cpu, const double* f_host,
+                          int* tau_host, double* cost_host) {
+    if (!f_host || !tau_host || !cost_host) return fail(nullptr, TIDE_E_INVAL, "null argument");
+    if (budget < 1 || n_steps < 2) return fail(nullptr, TIDE_E_RANGE, "budget must be >= 1 and n_steps >= 2");
+    if (!(d >= 0.0 && d <= 1.0)) return fail(nullptr, TIDE_E_RANGE, "drift rate must be in [0, 1]");
+    std::vector<double> io(n_steps - 1), cpu(n_steps - 1);
+    interval_costs(budget, n_steps, d, c_io, c_cpu, f_host, io.data(), cpu.data());
+    int best = 0;
+    for (int i = 1; i < n_steps - 1; ++i)
+        if (io[i] + cpu[i] < io[best] + cpu[best]) best = i;
+    *tau_host = best + 1;
+    *cost_host = io[best] + cpu[best];
+    return TIDE_OK;
+}
+
+int tide_fit_drift(double migrations, int budget, int n_steps, int tau, double* d_host) {
+    if (!d_host) return fail(nullptr, TIDE_E_INVAL, "null output");
+    if (budget < 1 || n_steps < 1 || tau < 1) return fail(nullptr, TIDE_E_RANGE, "budget, n_steps and tau must be >= 1");
+    double frac = migrations * (double)tau / (double)((int64_t)budget * n_steps);
+    frac = std::min(std::max(frac, 0.0), 1.0);
+    *d_host = 1.0 - std::pow(1.0 - frac, 1.0 / (double)tau);
+    return TIDE_OK;
+}
+
 }  // extern "C"

@@ -149,6 +149,12 @@ struct RefreshOut {           // lives in pinned host memory the kernel writes d
 hipError_t launch_refresh_select(const Shape& s, const LayerTables& t, const int32_t* counts, int capacity,
                                  int reset_counts, RefreshOut* out_hostmapped, hipStream_t stream);
 
+// interval analysis (Sec. 3.2, Eq. 4-7): similarity / distinct experts / drift on the device, cost model on the host
+hipError_t launch_routing_stability(const int32_t* counts, int n_steps, int n_experts, int budget, double* sim,
+                                    int32_t* unique, double* drift, hipStream_t stream);
+void interval_costs(int budget, int n_steps, double d, double c_io, double c_cpu, const double* f, double* lat_io,
+                    double* lat_cpu);
+
 // Packed blob: the gate and up matrices interleaved (2*d*I elements), then the down matrix (d*I).
 // Stripes (16 matrix rows) are stored in groups, K chunk slow inside a group (tide_pack_expert).
 constexpr int kGateUpGroup = 8;     // SwiGLU column blocks (a gate and an up stripe each) per group
