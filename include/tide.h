@@ -187,6 +187,12 @@ int tide_refresh(tide_ctx* ctx, int layer, const int32_t* counts_host, int capac
 /* Blocks until every refresh copy queued so far for the layer has landed. */
 int tide_wait_refresh(tide_ctx* ctx, int layer);
 
+/* Policy variant of the counter (the paper clears H at a refresh; Sec. 5 names counters with a longer
+ * memory as future work): H[e] <- floor(H[e] * num / den) for every expert of the layer, on hip_stream.
+ * Called after tide_refresh(reset_counts = 0) it turns H into an exponentially fading count.
+ * 0 <= num <= den, den >= 1 (num == den leaves H as it is: a cumulative counter). */
+int tide_scale_counts(tide_ctx* ctx, int layer, int num, int den, void* hip_stream);
+
 /* Snapshot hooks (tests): placement table slot_of[E] (-1 = not resident) to host;
  * raw bytes of a cache slot (slot == capacity: the shared expert) to host. */
 int tide_get_table(tide_ctx* ctx, int layer, int32_t* slot_of_host, void* hip_stream);

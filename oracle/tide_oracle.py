@@ -21,7 +21,8 @@ Parity pins (tests/test_oracle_pins.py): every function below is pinned by at
 least one of: brute-force full sort, scipy's expit / softmax, numpy bincount,
 an independently written dense all-experts masked sum in torch fp64, the
 lossless identity, hand-worked fixtures in tests/golden/, and brute-force
-refresh rules.  No function is "parity unpinned".
+refresh rules; the policy driver is pinned to the Alg. 1 driver and to direct
+statements of each counter rule.  No function is "parity unpinned".
 
 Readings of points on which the paper is silent are marked R1..R12 and listed
 in the design document.
@@ -283,6 +284,63 @@ def run_block(hidden_steps, w_r, bias, gating: int, bias_mode: int, k: int, n_ex
             rec.update(y_res=y_res, y_full=y_full, tokens=toks)
         log.append(rec)
     return log
+
+
+# --------------------------------------------------------------------------
+# placement policies on the same layer (Sec. 4: the static and every-step baselines;
+# Sec. 5 limitations: counters that outlive an interval or a block)
+# --------------------------------------------------------------------------
+def run_block_policy(hidden_steps, w_r, bias, gating: int, bias_mode: int, k: int, n_experts: int,
+                     capacity: int, initial_expert_in_slot: np.ndarray, interval: Optional[int],
+                     counter: str = "interval", decay: Tuple[int, int] = (1, 2), warm_start: bool = False,
+                     initial_hits: Optional[np.ndarray] = None):
+    """Routing, counter, placement and miss lists of one block under a placement policy.
+
+    interval = None: static placement, never refreshed (the Fiddler-like baseline); interval = 1:
+    refresh before every step (the Mixtral-Offload-like baseline); otherwise Alg. 1.
+    counter: what happens to H when a refresh has used it --
+      "interval"    cleared (Alg. 1 as read in R4),
+      "cumulative"  kept (hits since the start of the run),
+      "decay"       H <- floor(H * num / den) with decay = (num, den): an exponentially fading memory.
+    warm_start: step 0 is routed once on the initial placement only to count its hits, the placement is
+    refreshed from them and the counter cleared (only with counter = "interval"), and step 0 is run again
+    on the new placement, which counts it into the interval that starts there.
+    initial_hits: H carried over from an earlier block (with initial_expert_in_slot its last placement).
+    Returns (log, final expert_in_slot, final hits); log[t] has idx, w, hist, hits, expert_in_slot,
+    slot_of, plan, miss like run_block's."""
+    if warm_start and counter != "interval":
+        raise ValueError("warm start is defined for the per-interval counter only")
+    eis = np.asarray(initial_expert_in_slot, dtype=np.int32).copy()
+    hits = np.zeros(n_experts, dtype=np.int64) if initial_hits is None else np.asarray(initial_hits, dtype=np.int64).copy()
+
+    def after_refresh(h):
+        if counter == "interval":
+            h[:] = 0
+        elif counter == "decay":
+            h[:] = (h * decay[0]) // decay[1]
+        elif counter != "cumulative":
+            raise ValueError(counter)
+
+    log = []
+    for t, x_bits in enumerate(hidden_steps):
+        rec: Dict = {"t": t, "plan": None}
+        idx, w, amb, key = route(x_bits, w_r, bias, gating, bias_mode, k)
+        hist = step_histogram(idx, n_experts)
+        if t == 0 and warm_start:
+            hits += hist
+            eis, rec["plan"] = refresh(hits, eis, capacity)
+            after_refresh(hits)
+        elif interval is not None and t > 0 and t % interval == 0:
+            eis, rec["plan"] = refresh(hits, eis, capacity)
+            after_refresh(hits)
+        slot_of = slot_table(eis, n_experts)
+        hits += hist
+        rec.update(idx=idx, w=w, ambiguous=amb, key=key, hist=hist, hits=hits.copy(), expert_in_slot=eis.copy(),
+                   slot_of=slot_of)
+        rec["miss"] = [(n, int(idx[n, i]), float(w[n, i]))
+                       for n in range(idx.shape[0]) for i in range(k) if slot_of[int(idx[n, i])] < 0]
+        log.append(rec)
+    return log, eis, hits
 
 
 class ExpertStore:

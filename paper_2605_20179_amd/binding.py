@@ -23,7 +23,7 @@ EXPORTS = [
     "tide_register_experts", "tide_set_shared", "tide_set_resident", "tide_moe_step", "tide_moe_step_routed",
     "tide_interval_stats", "tide_refresh", "tide_wait_refresh", "tide_get_table", "tide_read_slot",
     "tide_refresh_copy_ms", "tide_profile", "tide_profile_read", "tide_counters", "tide_moe_apply_misses",
-    "tide_step_histogram", "tide_routing_stability", "tide_interval_costs", "tide_optimal_interval", "tide_fit_drift",
+    "tide_step_histogram", "tide_routing_stability", "tide_interval_costs", "tide_optimal_interval", "tide_fit_drift", "tide_scale_counts",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -82,6 +82,7 @@ def _load() -> C.CDLL:
     lib.tide_step_histogram.argtypes = [vp, vp, C.c_int, vp]
     lib.tide_routing_stability.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp]
     lib.tide_interval_costs.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, vp, vp, vp]
+    lib.tide_scale_counts.argtypes = [vp, C.c_int, C.c_int, C.c_int, vp]
     lib.tide_fit_drift.argtypes = [C.c_double, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double)]
     lib.tide_optimal_interval.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, vp, C.POINTER(C.c_int),
                                           C.POINTER(C.c_double)]
@@ -267,3 +268,7 @@ def tide_fit_drift(migrations: float, budget: int, n_steps: int, tau: int) -> fl
     d = C.c_double(0.0)
     _check(lib.tide_fit_drift(migrations, budget, n_steps, tau, C.byref(d)), None)
     return d.value
+
+
+def tide_scale_counts(ctx, layer: int, num: int, den: int, stream=None) -> None:
+    _check(lib.tide_scale_counts(ctx, layer, num, den, _stream_ptr(stream)), ctx)

@@ -115,4 +115,16 @@ hipError_t launch_refresh_select(const Shape& s, const LayerTables& t, const int
     return hipGetLastError();
 }
 
+namespace {
+__global__ void scale_counts_kernel(int32_t* hits, int n, int num, int den) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < n) hits[e] = (int32_t)(((int64_t)hits[e] * num) / den);
+}
+}  // namespace
+
+hipError_t launch_scale_counts(int32_t* hits, int n_experts, int num, int den, hipStream_t stream) {
+    hipLaunchKernelGGL(scale_counts_kernel, dim3((n_experts + 255) / 256), dim3(256), 0, stream, hits, n_experts, num, den);
+    return hipGetLastError();
+}
+
 }  // namespace tide

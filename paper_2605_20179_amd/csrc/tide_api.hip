@@ -586,6 +586,14 @@ int tide_counters(tide_ctx* ctx, int64_t* out4, int reset, void* hip_stream) {
     return TIDE_OK;
 }
 
+int tide_scale_counts(tide_ctx* ctx, int layer, int num, int den, void* hip_stream) {
+    if (!ctx) return TIDE_E_INVAL;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, TIDE_E_RANGE, "layer %d out of range", layer);
+    if (den < 1 || num < 0 || num > den) return fail(ctx, TIDE_E_RANGE, "need 0 <= num <= den, den >= 1");
+    TIDE_HIP(ctx, launch_scale_counts(ctx->layers[layer].t.hits, ctx->cfg.n_experts, num, den, static_cast<hipStream_t>(hip_stream)));
+    return TIDE_OK;
+}
+
 int tide_step_histogram(tide_ctx* ctx, int32_t* counts_host, int n_experts, void* hip_stream) {
     if (!ctx || !counts_host) return ctx ? fail(ctx, TIDE_E_INVAL, "null output") : TIDE_E_INVAL;
     if (n_experts != ctx->cfg.n_experts) return fail(ctx, TIDE_E_RANGE, "n_experts %d != configured %d", n_experts, ctx->cfg.n_experts);

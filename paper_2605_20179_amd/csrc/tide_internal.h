@@ -149,6 +149,8 @@ struct RefreshOut {           // lives in pinned host memory the kernel writes d
 hipError_t launch_refresh_select(const Shape& s, const LayerTables& t, const int32_t* counts, int capacity,
                                  int reset_counts, RefreshOut* out_hostmapped, hipStream_t stream);
 
+// H[e] <- floor(H[e] * num / den)
+hipError_t launch_scale_counts(int32_t* hits, int n_experts, int num, int den, hipStream_t stream);
 // interval analysis (Sec. 3.2, Eq. 4-7): similarity / distinct experts / drift on the device, cost model on the host
 hipError_t launch_routing_stability(const int32_t* counts, int n_steps, int n_experts, int budget, double* sim,
                                     int32_t* unique, double* drift, hipStream_t stream);

@@ -413,3 +413,65 @@ def test_inputs_are_seeded_and_shaped():
     # drift keeps neighbouring steps close
     cos = (h0 * h1).sum() / np.linalg.norm(h0) / np.linalg.norm(h1)
     assert cos > 0.99
+
+
+# ------------------------------------------------------------------ placement policies
+def _policy_inputs(steps=12):
+    wl = ti.CONFIGS[0].replace(S=steps)
+    hidden = list(ti.hidden_stream(wl, 0))
+    args = (hidden, ti.router_weights(wl, 0), ti.router_bias(wl, 0), wl.gating, wl.bias_mode, wl.k, wl.E, wl.C,
+            ti.initial_resident(wl))
+    return wl, hidden, args
+
+
+def test_policy_interval_equals_alg1_driver_and_static_never_moves():
+    wl, hidden, args = _policy_inputs()
+    for K in (1, 2, 5):
+        log, _, _ = orc.run_block_policy(*args, interval=K)
+        ref = orc.run_block(hidden, *args[1:8], K, args[8])
+        for a, b in zip(log, ref):
+            assert a["expert_in_slot"].tolist() == b["expert_in_slot"].tolist() and a["plan"] == b["plan"]
+            assert np.array_equal(a["hits"], b["hits"]) and a["miss"] == b["miss"]
+    log, eis, hits = orc.run_block_policy(*args, interval=None)
+    assert all(r["plan"] is None and r["expert_in_slot"].tolist() == list(args[8]) for r in log)
+    assert np.array_equal(hits, sum(r["hist"] for r in log))
+
+
+def test_policy_counters_follow_their_definitions():
+    wl, hidden, args = _policy_inputs()
+    hists = [orc.step_histogram(orc.route(h, *args[1:6])[0], wl.E) for h in hidden]
+    K = 3
+    log, _, _ = orc.run_block_policy(*args, interval=K, counter="cumulative")
+    for t, r in enumerate(log):
+        assert np.array_equal(r["hits"], sum(hists[:t + 1]))
+        if t > 0 and t % K == 0:                      # placement = top-C of everything seen so far
+            assert set(r["expert_in_slot"].tolist()) == set(orc.refresh(sum(hists[:t]), log[t - 1]["expert_in_slot"], wl.C)[0].tolist())
+    log, _, _ = orc.run_block_policy(*args, interval=K, counter="decay", decay=(1, 2))
+    h = np.zeros(wl.E, dtype=np.int64)
+    for t, r in enumerate(log):
+        if t > 0 and t % K == 0:
+            h = h // 2
+        h = h + hists[t]
+        assert np.array_equal(r["hits"], h)
+    with pytest.raises(ValueError):
+        orc.run_block_policy(*args, interval=K, counter="nonsense")
+
+
+def test_policy_warm_start_and_carry_over():
+    wl, hidden, args = _policy_inputs()
+    hist0 = orc.step_histogram(orc.route(hidden[0], *args[1:6])[0], wl.E)
+    log, _, _ = orc.run_block_policy(*args, interval=4, warm_start=True)
+    want, plan = orc.refresh(hist0, np.asarray(args[8]), wl.C)
+    assert log[0]["expert_in_slot"].tolist() == want.tolist() and log[0]["plan"] == plan
+    assert np.array_equal(log[0]["hits"], hist0)       # counted once into the interval that starts at step 0
+    # the warm placement holds step 0's most-hit experts: no other set of C experts has fewer misses at step 0
+    served = sum(int(hist0[e]) for e in want if e >= 0)
+    assert served == int(np.sort(hist0)[::-1][:wl.C].sum())
+    # two blocks with carry-over == one run over the concatenated steps when the first block's length is a
+    # multiple of the interval (the second block's step 0 is then a refresh step of the long run)
+    first, eis, hits = orc.run_block_policy(*args, interval=4, counter="cumulative")
+    second, _, _ = orc.run_block_policy(hidden, *args[1:8], eis, interval=4, counter="cumulative", initial_hits=hits)
+    long_log, _, _ = orc.run_block_policy(hidden + hidden, *args[1:], interval=4, counter="cumulative")
+    for a, b in zip(second[1:], long_log[len(hidden) + 1:]):
+        assert np.array_equal(a["hits"], b["hits"])
+    assert np.array_equal(second[0]["hits"], long_log[len(hidden)]["hits"])
