@@ -184,6 +184,20 @@ int tide_interval_stats(tide_ctx* ctx, int layer, int32_t* counts_host, int rese
 int tide_refresh(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,
                  int32_t* resident_out, tide_copy* plan_out, int* n_copies_out, void* hip_stream);
 
+/* The same refresh with its effect deferred, so that the host-link copies overlap with the steps that
+ * follow instead of holding up the next one: the selection, the plan, the counter reset and the copies are
+ * as above, but the newcomers land in staging blobs owned by the layer (allocated on first use: `ctx
+ * capacity` blobs) and the layer keeps serving from the OLD placement -- tide_moe_step, tide_get_table and
+ * the miss lists see no change -- until tide_commit.  resident_out / plan_out describe the placement that
+ * the commit will install.  Until then tide_refresh and tide_refresh_deferred on the layer return
+ * TIDE_E_STATE; tide_set_resident cancels the pending refresh. */
+int tide_refresh_deferred(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,
+                          int32_t* resident_out, tide_copy* plan_out, int* n_copies_out, void* hip_stream);
+/* Installs the placement of the pending deferred refresh: hip_stream waits for the staged copies, then (in
+ * stream order, i.e. after every step already queued) the staged blobs move into their slots inside HBM and
+ * the tables are swapped.  Does not synchronise.  TIDE_E_STATE if nothing is pending. */
+int tide_commit(tide_ctx* ctx, int layer, void* hip_stream);
+
 /* Blocks until every refresh copy queued so far for the layer has landed. */
 int tide_wait_refresh(tide_ctx* ctx, int layer);
 

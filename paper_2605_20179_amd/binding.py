@@ -23,7 +23,7 @@ EXPORTS = [
     "tide_register_experts", "tide_set_shared", "tide_set_resident", "tide_moe_step", "tide_moe_step_routed",
     "tide_interval_stats", "tide_refresh", "tide_wait_refresh", "tide_get_table", "tide_read_slot",
     "tide_refresh_copy_ms", "tide_profile", "tide_profile_read", "tide_counters", "tide_moe_apply_misses",
-    "tide_step_histogram", "tide_routing_stability", "tide_interval_costs", "tide_optimal_interval", "tide_fit_drift", "tide_scale_counts",
+    "tide_step_histogram", "tide_routing_stability", "tide_interval_costs", "tide_optimal_interval", "tide_fit_drift", "tide_scale_counts", "tide_refresh_deferred", "tide_commit",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -72,6 +72,8 @@ def _load() -> C.CDLL:
     lib.tide_moe_apply_misses.argtypes = [vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, vp, vp]
     lib.tide_interval_stats.argtypes = [vp, C.c_int, vp, C.c_int, vp]
     lib.tide_refresh.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, vp, vp, C.POINTER(C.c_int), vp]
+    lib.tide_refresh_deferred.argtypes = lib.tide_refresh.argtypes
+    lib.tide_commit.argtypes = [vp, C.c_int, vp]
     lib.tide_wait_refresh.argtypes = [vp, C.c_int]
     lib.tide_get_table.argtypes = [vp, C.c_int, vp, vp]
     lib.tide_read_slot.argtypes = [vp, C.c_int, C.c_int, vp]
@@ -181,14 +183,16 @@ def tide_interval_stats(ctx, layer: int, n_experts: int, reset: bool, stream=Non
 
 
 def tide_refresh(ctx, layer: int, ctx_capacity: int, capacity: int, counts: Optional[np.ndarray] = None,
-                 reset_counts: bool = True, stream=None):
-    """Returns (expert_in_slot[ctx_capacity] int32, plan = list of (expert, slot, host_offset, bytes))."""
+                 reset_counts: bool = True, stream=None, deferred: bool = False):
+    """Returns (expert_in_slot[ctx_capacity] int32, plan = list of (expert, slot, host_offset, bytes)).
+    deferred: tide_refresh_deferred (the placement takes effect at tide_commit)."""
     resident = np.full(ctx_capacity, -1, dtype=np.int32)
     plan = (tide_copy * max(ctx_capacity, 1))()
     n = C.c_int(0)
     cnt = None if counts is None else np.ascontiguousarray(np.asarray(counts, dtype=np.int32))
-    _check(lib.tide_refresh(ctx, layer, _ptr(cnt), capacity, int(reset_counts), _ptr(resident),
-                            C.cast(plan, C.c_void_p), C.byref(n), _stream_ptr(stream)), ctx)
+    fn = lib.tide_refresh_deferred if deferred else lib.tide_refresh
+    _check(fn(ctx, layer, _ptr(cnt), capacity, int(reset_counts), _ptr(resident),
+              C.cast(plan, C.c_void_p), C.byref(n), _stream_ptr(stream)), ctx)
     return resident, [(plan[i].expert, plan[i].slot, plan[i].host_offset, plan[i].bytes) for i in range(n.value)]
 
 
@@ -272,3 +276,7 @@ def tide_fit_drift(migrations: float, budget: int, n_steps: int, tau: int) -> fl
 
 def tide_scale_counts(ctx, layer: int, num: int, den: int, stream=None) -> None:
     _check(lib.tide_scale_counts(ctx, layer, num, den, _stream_ptr(stream)), ctx)
+
+
+def tide_commit(ctx, layer: int, stream=None) -> None:
+    _check(lib.tide_commit(ctx, layer, _stream_ptr(stream)), ctx)

@@ -29,6 +29,12 @@ struct Layer {
     bool copies_pending = false;         // a step must wait on copies_done before its GEMMs
     bool copies_recorded = false;
     RefreshOut* plan = nullptr;          // pinned, device-visible
+    // deferred refresh: staging blobs, the tables the selection wrote, the slots the staged blobs go to
+    uint8_t* staging = nullptr;
+    int32_t* pend_slot_of = nullptr;
+    int32_t* pend_eis = nullptr;
+    std::vector<int> pend_slots;
+    bool deferred_pending = false;
 };
 
 }  // namespace
@@ -315,6 +321,8 @@ int tide_destroy(tide_ctx* ctx) {
         if (L.copies_begin) (void)hipEventDestroy(L.copies_begin);
         if (L.copies_done) (void)hipEventDestroy(L.copies_done);
         if (L.plan) (void)hipHostFree(L.plan);
+        if (L.staging) (void)hipFree(L.staging);
+        if (L.pend_slot_of) (void)hipFree(L.pend_slot_of);
     }
     for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
     if (ctx->compute_mark) (void)hipEventDestroy(ctx->compute_mark);
@@ -376,6 +384,8 @@ int tide_set_resident(tide_ctx* ctx, int layer, const int32_t* experts, int n) {
     TIDE_HIP(ctx, hipMemcpy(L.t.expert_in_slot, eis.data(), C * 4, hipMemcpyHostToDevice));
     L.placed = true;
     L.copies_pending = false;
+    L.deferred_pending = false;          // a placement set by hand supersedes a refresh that was not committed
+    L.pend_slots.clear();
     return TIDE_OK;
 }
 
@@ -472,15 +482,35 @@ int tide_interval_stats(tide_ctx* ctx, int layer, int32_t* counts_host, int rese
     return TIDE_OK;
 }
 
-int tide_refresh(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,
-                 int32_t* resident_out, tide_copy* plan_out, int* n_copies_out, void* hip_stream) {
+namespace {
+// tide_refresh and tide_refresh_deferred.  Deferred: the selection runs on a copy of the tables, the
+// newcomers are copied into staging blobs, and the layer keeps serving from the old placement until
+// tide_commit moves the staged blobs into their slots and swaps the tables.
+int refresh_impl(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,
+                 int32_t* resident_out, tide_copy* plan_out, int* n_copies_out, void* hip_stream, bool deferred) {
     int rc = layer_ok(ctx, layer);
     if (rc) return rc;
     if (capacity < 0 || capacity > ctx->cfg.capacity) return fail(ctx, TIDE_E_RANGE, "capacity %d outside 0..%d", capacity, ctx->cfg.capacity);
     Layer& L = ctx->layers[layer];
     if (!L.host_blobs) return fail(ctx, TIDE_E_STATE, "layer %d: experts not registered", layer);
     if (!L.placed) return fail(ctx, TIDE_E_STATE, "layer %d has no placement: call tide_set_resident first", layer);
+    if (L.deferred_pending) return fail(ctx, TIDE_E_STATE, "layer %d: a deferred refresh awaits tide_commit", layer);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const uint64_t bytes = tide_expert_blob_bytes(&ctx->cfg);
+    if (deferred && !L.staging) {
+        void* p = nullptr;
+        if (hipMalloc(&p, bytes * (uint64_t)ctx->cfg.capacity) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ctx, TIDE_E_NOMEM, "out of device memory for %d staging blobs", ctx->cfg.capacity);
+        }
+        L.staging = static_cast<uint8_t*>(p);
+        if (hipMalloc(&p, (size_t)(ctx->cfg.n_experts + ctx->cfg.capacity) * sizeof(int32_t)) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ctx, TIDE_E_NOMEM, "out of device memory for the pending tables");
+        }
+        L.pend_slot_of = static_cast<int32_t*>(p);
+        L.pend_eis = L.pend_slot_of + ctx->cfg.n_experts;
+    }
     const int32_t* counts = L.t.hits;
     if (counts_host) {
         TIDE_HIP(ctx, hipMemcpyAsync(ctx->ws.counts_tmp, counts_host, ctx->cfg.n_experts * 4, hipMemcpyHostToDevice, stream));
@@ -488,28 +518,66 @@ int tide_refresh(tide_ctx* ctx, int layer, const int32_t* counts_host, int capac
     }
     // copies of an earlier refresh must have landed before their slots can be given away again
     if (L.copies_recorded) TIDE_HIP(ctx, hipStreamWaitEvent(stream, L.copies_done, 0));
-    TIDE_HIP(ctx, launch_refresh_select(ctx->shape, L.t, counts, capacity, reset_counts, L.plan, stream));
+    LayerTables sel = L.t;
+    if (deferred) {
+        TIDE_HIP(ctx, hipMemcpyAsync(L.pend_slot_of, L.t.slot_of, (size_t)ctx->cfg.n_experts * 4, hipMemcpyDeviceToDevice, stream));
+        TIDE_HIP(ctx, hipMemcpyAsync(L.pend_eis, L.t.expert_in_slot, (size_t)ctx->cfg.capacity * 4, hipMemcpyDeviceToDevice, stream));
+        sel.slot_of = L.pend_slot_of;
+        sel.expert_in_slot = L.pend_eis;
+    }
+    TIDE_HIP(ctx, launch_refresh_select(ctx->shape, sel, counts, capacity, reset_counts, L.plan, stream));
     // the plan is needed here to queue the copies; this also means every earlier step that
-    // could still read a slot about to be overwritten has finished
+    // could still read a slot (or a staging blob) about to be overwritten has finished
     TIDE_HIP(ctx, hipStreamSynchronize(stream));
     const int n = L.plan->n_copies;
-    const uint64_t bytes = tide_expert_blob_bytes(&ctx->cfg);
     TIDE_HIP(ctx, hipEventRecord(L.copies_begin, ctx->side));
     for (int i = 0; i < n; ++i) {
         const int e = L.plan->expert[i], s = L.plan->slot[i];
-        TIDE_HIP(ctx, hipMemcpyAsync(slot_ptr(ctx, L, s), L.host_blobs + (uint64_t)e * L.host_stride, bytes, hipMemcpyHostToDevice, ctx->side));
+        void* dst = deferred ? static_cast<void*>(L.staging + (uint64_t)i * bytes) : static_cast<void*>(slot_ptr(ctx, L, s));
+        TIDE_HIP(ctx, hipMemcpyAsync(dst, L.host_blobs + (uint64_t)e * L.host_stride, bytes, hipMemcpyHostToDevice, ctx->side));
         if (plan_out) {
             plan_out[i].expert = e;
             plan_out[i].slot = s;
             plan_out[i].host_offset = (uint64_t)e * L.host_stride;
             plan_out[i].bytes = bytes;
         }
+        if (deferred) L.pend_slots.push_back(s);
     }
     TIDE_HIP(ctx, hipEventRecord(L.copies_done, ctx->side));
     L.copies_recorded = true;
-    L.copies_pending = n > 0;
+    if (deferred) L.deferred_pending = true;
+    else L.copies_pending = n > 0;
     if (n_copies_out) *n_copies_out = n;
     if (resident_out) memcpy(resident_out, L.plan->expert_in_slot, ctx->cfg.capacity * sizeof(int32_t));
+    return TIDE_OK;
+}
+}  // namespace
+
+int tide_refresh(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,
+                 int32_t* resident_out, tide_copy* plan_out, int* n_copies_out, void* hip_stream) {
+    return refresh_impl(ctx, layer, counts_host, capacity, reset_counts, resident_out, plan_out, n_copies_out, hip_stream, false);
+}
+
+int tide_refresh_deferred(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,
+                          int32_t* resident_out, tide_copy* plan_out, int* n_copies_out, void* hip_stream) {
+    return refresh_impl(ctx, layer, counts_host, capacity, reset_counts, resident_out, plan_out, n_copies_out, hip_stream, true);
+}
+
+int tide_commit(tide_ctx* ctx, int layer, void* hip_stream) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    Layer& L = ctx->layers[layer];
+    if (!L.deferred_pending) return fail(ctx, TIDE_E_STATE, "layer %d: no deferred refresh to commit", layer);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const uint64_t bytes = tide_expert_blob_bytes(&ctx->cfg);
+    // after the host-link copies, and (stream order) after every step that still reads the old slots
+    TIDE_HIP(ctx, hipStreamWaitEvent(stream, L.copies_done, 0));
+    for (size_t i = 0; i < L.pend_slots.size(); ++i)
+        TIDE_HIP(ctx, hipMemcpyAsync(slot_ptr(ctx, L, L.pend_slots[i]), L.staging + (uint64_t)i * bytes, bytes, hipMemcpyDeviceToDevice, stream));
+    TIDE_HIP(ctx, hipMemcpyAsync(L.t.slot_of, L.pend_slot_of, (size_t)ctx->cfg.n_experts * 4, hipMemcpyDeviceToDevice, stream));
+    TIDE_HIP(ctx, hipMemcpyAsync(L.t.expert_in_slot, L.pend_eis, (size_t)ctx->cfg.capacity * 4, hipMemcpyDeviceToDevice, stream));
+    L.pend_slots.clear();
+    L.deferred_pending = false;
     return TIDE_OK;
 }
 

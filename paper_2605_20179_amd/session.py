@@ -111,9 +111,12 @@ class TideSession:
         return tb.tide_interval_stats(self.ctx, layer, self.E, reset, torch.cuda.current_stream())
 
     def refresh(self, layer: int, capacity: Optional[int] = None, counts: Optional[np.ndarray] = None,
-                reset_counts: bool = True):
+                reset_counts: bool = True, deferred: bool = False):
         return tb.tide_refresh(self.ctx, layer, self.C, self.C if capacity is None else capacity, counts, reset_counts,
-                               torch.cuda.current_stream())
+                               torch.cuda.current_stream(), deferred=deferred)
+
+    def commit(self, layer: int) -> None:
+        tb.tide_commit(self.ctx, layer, torch.cuda.current_stream())
 
     def table(self, layer: int) -> np.ndarray:
         return tb.tide_get_table(self.ctx, layer, self.E, torch.cuda.current_stream())

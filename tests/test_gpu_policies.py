@@ -102,3 +102,58 @@ def test_other_budgets_and_block_lengths(budget, block):
     misses, migrated = drive(sess, wl, hidden, log, wl.K, "interval", (1, 2), False)
     say("budget %d block %d: miss rate %.4f, experts migrated %d" % (budget, block, misses / (len(hidden) * wl.N * wl.k), migrated))
     sess.close()
+
+
+def test_deferred_refresh_and_commit():
+    """The overlapped variant: the refresh before step t only stages its newcomers; step t runs on the old
+    placement; tide_commit installs the new one before step t+1.  Counter, tables, plans, miss lists and the
+    bytes of every cache slot are compared with the oracle's delayed placement."""
+    wl = ti.CONFIGS[1].replace(S=14)
+    hidden = list(ti.hidden_stream(wl, 0))
+    args = (hidden, ti.router_weights(wl, 0), ti.router_bias(wl, 0), wl.gating, wl.bias_mode, wl.k, wl.E, wl.C,
+            ti.initial_resident(wl))
+    sess = _session(wl)
+    load(sess, wl, 0)
+    host = sess.host_blobs[0].numpy()
+    with pytest.raises(tb.TideError) as err:
+        sess.commit(0)
+    assert err.value.code == tb.TIDE_E_STATE
+    for K in (1, 4):
+        log, _, _ = orc.run_block_policy(*args, interval=K, deferred=True)
+        tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))
+        sess.stats(0, reset=True)
+        pending = False
+        for t, rec in enumerate(log):
+            if pending:
+                sess.commit(0)
+                pending = False
+            if t > 0 and t % K == 0:
+                eis, plan = sess.refresh(0, deferred=True)
+                pending = True
+                assert eis.tolist() == rec["pending_expert_in_slot"].tolist(), "step %d: chosen set" % t
+                assert [(e, s) for e, s, _, _ in plan] == [tuple(p) for p in rec["plan"]], "step %d: plan" % t
+                for call in (lambda: sess.refresh(0), lambda: sess.refresh(0, deferred=True)):
+                    with pytest.raises(tb.TideError) as err:
+                        call()
+                    assert err.value.code == tb.TIDE_E_STATE
+            x = sess.to_device_bf16(hidden[t])
+            sess.step_routed(0, x, torch.from_numpy(rec["idx"]).to(sess.device),
+                             torch.from_numpy(rec["w"].astype(np.float32)).to(sess.device))
+            _, _, _, miss, n_miss = sess.results(wl.N)
+            check_miss(rec["miss"], miss, n_miss)
+            assert np.array_equal(sess.table(0), rec["slot_of"]), "step %d: table" % t
+            assert np.array_equal(sess.stats(0), rec["hits"].astype(np.int32)), "step %d: counter" % t
+        if pending:
+            sess.commit(0)
+        torch.cuda.synchronize()
+        final = log[-1].get("pending_expert_in_slot", log[-1]["expert_in_slot"])
+        assert np.array_equal(sess.table(0), orc.slot_table(final, wl.E))
+        for s in (0, 1, wl.C // 2, wl.C - 1):                 # the slots hold their experts' bytes
+            assert np.array_equal(sess.read_slot(0, s), host[final[s]]), "slot %d" % s
+        say("deferred refresh K=%d: %d steps exact" % (K, len(log)))
+    # a placement set by hand cancels a pending refresh
+    sess.refresh(0, deferred=True)
+    tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))
+    with pytest.raises(tb.TideError):
+        sess.commit(0)
+    sess.close()

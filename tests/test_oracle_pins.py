@@ -475,3 +475,23 @@ def test_policy_warm_start_and_carry_over():
     for a, b in zip(second[1:], long_log[len(hidden) + 1:]):
         assert np.array_equal(a["hits"], b["hits"])
     assert np.array_equal(second[0]["hits"], long_log[len(hidden)]["hits"])
+
+
+def test_policy_deferred_refresh_is_the_same_choice_one_step_late():
+    wl, hidden, args = _policy_inputs()
+    for K in (1, 2, 4):
+        now, _, _ = orc.run_block_policy(*args, interval=K)
+        late, _, _ = orc.run_block_policy(*args, interval=K, deferred=True)
+        for t, (a, b) in enumerate(zip(now, late)):
+            assert a["plan"] == b["plan"] and np.array_equal(a["hits"], b["hits"])
+            if t > 0 and t % K == 0:
+                assert b["expert_in_slot"].tolist() == now[t - 1]["expert_in_slot"].tolist()
+                assert b["pending_expert_in_slot"].tolist() == a["expert_in_slot"].tolist()
+            else:
+                assert b["expert_in_slot"].tolist() == a["expert_in_slot"].tolist()
+            # the miss list is the split against the placement in force, stated directly
+            live = set(int(e) for e in b["expert_in_slot"] if e >= 0)
+            assert b["miss"] == [(n, int(b["idx"][n, i]), float(b["w"][n, i])) for n in range(b["idx"].shape[0])
+                                 for i in range(wl.k) if int(b["idx"][n, i]) not in live]
+    with pytest.raises(ValueError):
+        orc.run_block_policy(*args, interval=4, warm_start=True, deferred=True)
