@@ -28,7 +28,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
-def cpu_baseline(wl, ti, sample_steps=64):
+def cpu_baseline(wl, ti, sample_steps=128):
     """The oracle as it stands, on `sample_steps` consecutive denoise steps (all tokens,
     cold-start placement) of the benchmark workload."""
     import numpy as np
