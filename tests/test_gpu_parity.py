@@ -162,6 +162,12 @@ RAGGED = [
     (192, 12, 4, 128, 1, 150, 6, ti.GATING_SIGMOID, ti.BIAS_SELECT),
     (128, 9, 9, 64, 0, 70, 9, ti.GATING_SOFTMAX, ti.BIAS_LOGIT),
     (256, 300, 6, 128, 1, 33, 40, ti.GATING_SIGMOID, ti.BIAS_NONE),
+    # steps of >= 256 tokens: the 64-expert x 128-token router kernel with a partial expert group (70 = 64 + 6) and a
+    # partial gate/up group (12 column blocks = 8 + 4); its fallback when d is not a multiple of 128; slots with
+    # hundreds of rows (large work items of 9..16 token tiles) and a partial down group (20 stripes = 16 + 4)
+    (384, 70, 4, 192, 1, 257, 30, ti.GATING_SOFTMAX, ti.BIAS_LOGIT),
+    (192, 100, 5, 320, 0, 300, 20, ti.GATING_SIGMOID, ti.BIAS_SELECT),
+    (320, 8, 2, 192, 1, 700, 4, ti.GATING_SIGMOID, ti.BIAS_NONE),
 ]
 
 
