@@ -291,7 +291,7 @@ template <int V, bool SMALL, int NG>
 __device__ inline void select16(int n_base, float (&z)[NG][V], const float* __restrict__ bias, int n_tokens,
                                 int n_experts, int k, int gating, int bias_mode, int32_t* __restrict__ topk_idx,
                                 float* __restrict__ topk_w, int32_t* __restrict__ hist_step,
-                                int32_t* __restrict__ hits, int32_t* __restrict__ idx_copy,
+                                int32_t* __restrict__ idx_copy,
                                 float* __restrict__ w_copy, unsigned* s_mask, int* s_idx, float* s_w) {
     // NG groups of 16 tokens are worked on side by side: their dependency chains are independent,
     // so the single wave per SIMD always has an instruction ready to issue
@@ -409,12 +409,12 @@ __global__ __launch_bounds__(256) void topk_gate_kernel(const float* __restrict_
                                                         const float* __restrict__ bias, int n_tokens, int n_experts,
                                                         int k, int gating, int bias_mode,
                                                         int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-                                                        int32_t* __restrict__ hist_step, int32_t* __restrict__ hits,
+                                                        int32_t* __restrict__ hist_step,
                                                         int32_t* __restrict__ idx_copy, float* __restrict__ w_copy) {
     float z[1][V];
     load_logits16_any<V>(k_splits, blockIdx.x * 16, z_part, e_pad, bias, bias_mode, n_tokens, n_experts, z[0]);
     select16<V, false, 1>(blockIdx.x * 16, z, bias, n_tokens, n_experts, k, gating, bias_mode, topk_idx, topk_w,
-                          hist_step, hits, idx_copy, w_copy, nullptr, nullptr, nullptr);
+                          hist_step, idx_copy, w_copy, nullptr, nullptr, nullptr);
 }
 
 // A step of at most 32 tokens is routed by ONE workgroup: top-k of every token, the step's
@@ -454,7 +454,7 @@ __global__ __launch_bounds__(256) void route_small_kernel(const float* __restric
         s_eis[e] = t_eis[q];
     }
     __syncthreads();
-    select16<V, true, 2>(0, z, bias, da.n_tokens, n_experts, da.k, gating, bias_mode, topk_idx, topk_w, nullptr, hits,
+    select16<V, true, 2>(0, z, bias, da.n_tokens, n_experts, da.k, gating, bias_mode, topk_idx, topk_w, nullptr,
                          idx_copy, w_copy, s_mask, s_idx, s_w);
     __syncthreads();
     for (int e = threadIdx.x; e < n_experts; e += 256) {
@@ -472,7 +472,7 @@ __global__ void clear_i32_kernel(int32_t* p, int n) {
 }
 
 __global__ void count_pairs_kernel(const int32_t* __restrict__ topk_idx, int n_pairs, int n_experts,
-                                   int32_t* hist_step, int32_t* hits) {
+                                   int32_t* hist_step) {
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p < n_pairs) {
         const int e = topk_idx[p];
@@ -521,17 +521,17 @@ hipError_t launch_router_logits(const Shape& s, const uint16_t* x, int n_tokens,
 }
 
 hipError_t launch_topk_gate(const Shape& s, const float* z_part, const float* bias, int n_tokens,
-                            int32_t* topk_idx, float* topk_w, int32_t* hist_step, int32_t* hits,
+                            int32_t* topk_idx, float* topk_w, int32_t* hist_step,
                             int32_t* idx_copy, float* w_copy, hipStream_t stream, LaunchEvents ev) {
     const int ks = router_k_splits(s, n_tokens);
     const int e_pad = (s.E + 15) / 16 * 16;
     dim3 grid((n_tokens + 15) / 16);
     if (s.E <= 256) {
         TIDE_LAUNCH(topk_gate_kernel<16>, grid, dim3(256), stream, ev, z_part, ks, e_pad, bias, n_tokens, s.E, s.k,
-                           s.gating, s.bias_mode, topk_idx, topk_w, hist_step, hits, idx_copy, w_copy);
+                           s.gating, s.bias_mode, topk_idx, topk_w, hist_step, idx_copy, w_copy);
     } else {
         TIDE_LAUNCH(topk_gate_kernel<32>, grid, dim3(256), stream, ev, z_part, ks, e_pad, bias, n_tokens, s.E, s.k,
-                           s.gating, s.bias_mode, topk_idx, topk_w, hist_step, hits, idx_copy, w_copy);
+                           s.gating, s.bias_mode, topk_idx, topk_w, hist_step, idx_copy, w_copy);
     }
     return hipGetLastError();
 }
@@ -565,11 +565,11 @@ hipError_t launch_clear_i32(int32_t* p, int n, hipStream_t stream) {
 }
 
 hipError_t launch_count_pairs(const Shape& s, const int32_t* topk_idx, int n_tokens, int32_t* hist_step,
-                              int32_t* hits, hipStream_t stream) {
+                              hipStream_t stream) {
     hipLaunchKernelGGL(clear_i32_kernel, dim3((s.E + 255) / 256), dim3(256), 0, stream, hist_step, s.E);
     const int n_pairs = n_tokens * s.k;
     hipLaunchKernelGGL(count_pairs_kernel, dim3((n_pairs + 255) / 256), dim3(256), 0, stream, topk_idx, n_pairs,
-                       s.E, hist_step, hits);
+                       s.E, hist_step);
     return hipGetLastError();
 }
 

@@ -414,7 +414,7 @@ int tide_moe_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens
     } else {
         TIDE_HIP(ctx, timed(ctx, TIDE_K_TOPK, [&](LaunchEvents ev) {
             return launch_topk_gate(ctx->shape, ctx->ws.logits, router_bias_dev, n_tokens, ctx->ws.topk_idx, ctx->ws.topk_w,
-                                    ctx->ws.hist_step, L.t.hits, topk_idx_dev, topk_w_dev, stream, ev); }));
+                                    ctx->ws.hist_step, topk_idx_dev, topk_w_dev, stream, ev); }));
     }
     return common_step(ctx, layer, hidden_dev, n_tokens, ctx->ws.topk_idx, ctx->ws.topk_w, out_dev, miss_dev, miss_cap,
                        n_miss_dev, stream, one_wg);
@@ -432,8 +432,7 @@ int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n
     }
     if (!topk_idx_dev || !topk_w_dev) return fail(ctx, TIDE_E_INVAL, "topk_idx_dev / topk_w_dev is null");
     if ((uintptr_t)topk_idx_dev & 15) return fail(ctx, TIDE_E_INVAL, "topk_idx_dev must be 16-byte aligned");
-    Layer& L = ctx->layers[layer];
-    TIDE_HIP(ctx, launch_count_pairs(ctx->shape, topk_idx_dev, n_tokens, ctx->ws.hist_step, L.t.hits, stream));
+    TIDE_HIP(ctx, launch_count_pairs(ctx->shape, topk_idx_dev, n_tokens, ctx->ws.hist_step, stream));
     return common_step(ctx, layer, hidden_dev, n_tokens, topk_idx_dev, topk_w_dev, out_dev, miss_dev, miss_cap,
                        n_miss_dev, stream, false);
 }

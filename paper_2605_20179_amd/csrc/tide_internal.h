@@ -82,21 +82,21 @@ struct Shape {
 // a1: z[n][e] = <x_n, W_r[e]>  (fp32)
 hipError_t launch_router_logits(const Shape& s, const uint16_t* x, int n_tokens, const float* w_r,
                                 float* logits, int32_t* hist_step_to_clear, hipStream_t stream, LaunchEvents ev = {});
-// a2 + a3: gate, top-k, weights; hist_step[e] += 1 and hits[e] += 1 per selected pair
+// a2 + a3: gate, top-k, weights; hist_step[e] += 1 per selected pair (H += hist_step is launch_dispatch's)
 hipError_t launch_topk_gate(const Shape& s, const float* logits, const float* bias, int n_tokens,
-                            int32_t* topk_idx, float* topk_w, int32_t* hist_step, int32_t* hits,
+                            int32_t* topk_idx, float* topk_w, int32_t* hist_step,
                             int32_t* idx_copy, float* w_copy, hipStream_t stream, LaunchEvents ev = {});
 // a2..a5 for a step of at most 32 tokens, in one workgroup: top-k, weights, counts, hit/miss split
 bool routes_in_one_workgroup(const Shape& s, int n_tokens);
 hipError_t launch_route_small(const Shape& s, const LayerTables& t, const Workspace& w, const float* bias, int n_tokens,
                               int32_t* idx_copy, float* w_copy, tide_miss* miss, int miss_cap, int32_t* n_miss,
                               hipStream_t stream, LaunchEvents ev = {});
-// a3 for token states that arrive routed: clear + count
+// a3 for token states that arrive routed: clear + count into hist_step (H += hist_step is launch_dispatch's)
 hipError_t launch_count_pairs(const Shape& s, const int32_t* topk_idx, int n_tokens, int32_t* hist_step,
-                              int32_t* hits, hipStream_t stream);
+                              hipStream_t stream);
 // p[0..n) = 0 by a fill kernel (safe inside a captured graph, unlike a memset node)
 hipError_t launch_clear_i32(int32_t* p, int n, hipStream_t stream);
-// a4 + a5: hit/miss split, canonical miss list, slot-sorted rows, work items
+// a4 + a5: H += hist_step; hit/miss split, canonical miss list, slot-sorted rows, work items
 hipError_t launch_dispatch(const Shape& s, const LayerTables& t, const Workspace& w, const int32_t* topk_idx,
                            const float* topk_w, int n_tokens, tide_miss* miss, int miss_cap, int32_t* n_miss,
                            hipStream_t stream, LaunchEvents ev = {});
