@@ -163,6 +163,26 @@ def main():
     torch.cuda.synchronize()
     step_only_s = (time.perf_counter() - s0) / args.steps
 
+    # detail only: the same frozen-placement step recorded once into a HIP graph and replayed
+    graph_us = None
+    try:
+        static_in = hidden[0].clone()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            sess.step(0, static_in, want_topk=False)
+        for _ in range(8):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for i in range(args.steps):
+            static_in.copy_(hidden[i % wl.S])         # the same inputs as the eager loop above (one small device copy more)
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - g0) / args.steps * 1e6
+        del graph
+    except Exception as e:                            # reported, never fatal: the figure is a detail
+        print("bench.py: graph replay skipped: %s" % e, file=sys.stderr)
+
     # measured separately (outside the timed region): one more block with every refresh's copies timed by their own
     # events (this synchronises after each refresh, which the timed region must not do)
     tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))
@@ -252,6 +272,7 @@ def main():
             "refreshes": state["refreshes"], "experts_copied": state["copies"],
             "refresh_host_s": state["refresh_s"],
             "frozen_placement_us_per_step": step_only_s * 1e6,
+            "frozen_placement_graph_replay_us_per_step": graph_us,
             "exposed_refresh_us_per_interval": (dt / args.steps - step_only_s) * 1e6 * wl.K,
             "refresh_copies": refresh_stats,
             "frozen_placement_tokens_per_s": wl.N / step_only_s,

@@ -1,0 +1,65 @@
+"""A step (placement frozen) recorded into a HIP graph and replayed: every replay must give what the eager
+call gives -- outputs, routing, miss count and the counter -- with eager work and synchronisations between
+the replays.  Covers both the five-launch small step and a large step whose GEMMs fork onto the library's
+second stream and join back (the fork/join events are captured with the graph).  The library clears its
+counters and flags with fill kernels, never with memset nodes."""
+import numpy as np
+import pytest
+import torch
+
+import tide_inputs as ti
+from test_gpu_parity import _session, load, say
+
+pytestmark = pytest.mark.gpu
+
+LARGE = ti.TideWorkload("graph-large", d=320, E=8, k=2, I=192, n_shared=1, N=700, S=4, K=2, C=4, L=1,
+                        gating=ti.GATING_SIGMOID, bias_mode=ti.BIAS_NONE, seed=5)
+
+
+@pytest.mark.parametrize("wl", [ti.CONFIGS[1].replace(S=4), LARGE], ids=["small-step", "large-step"])
+def test_step_replayed_from_a_graph(wl):
+    sess = _session(wl)
+    load(sess, wl, 0)
+    hidden = [sess.to_device_bf16(h) for h in ti.hidden_stream(wl, 0, 4)]
+    eager = []
+    for h in hidden:
+        sess.step(0, h)
+        torch.cuda.synchronize()
+        eager.append((sess.out[:wl.N].clone(), sess.topk_idx[:wl.N].clone(), sess.topk_w[:wl.N].clone(),
+                      sess.miss[:int(sess.n_miss.item())].clone(), int(sess.n_miss.item())))
+    per_block = sess.stats(0, reset=True).copy()
+    static_in = hidden[0].clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sess.step(0, static_in)                       # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    sess.stats(0, reset=True)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sess.step(0, static_in)
+    for rep in range(3):
+        for i, h in enumerate(hidden):
+            static_in.copy_(h)
+            graph.replay()
+            torch.cuda.synchronize()
+            out, idx, w, miss, n_miss = eager[i]
+            assert int(sess.n_miss.item()) == n_miss, "replay %d step %d: miss count" % (rep, i)
+            assert torch.equal(sess.topk_idx[:wl.N], idx) and torch.equal(sess.topk_w[:wl.N], w)
+            assert torch.equal(sess.miss[:n_miss], miss)
+            assert torch.equal(sess.out[:wl.N], out), "replay %d step %d: output" % (rep, i)
+        # eager work between the rounds of replays
+        sess.step(0, hidden[rep % 4])
+        torch.cuda.synchronize()
+        assert torch.equal(sess.out[:wl.N], eager[rep % 4][0])
+    # every replay and every eager call counted its step: 3 rounds x 4 steps, plus steps 0, 1, 2 once more
+    fresh = _session(wl)
+    load(fresh, wl, 0)
+    for i in range(3):
+        fresh.step(0, hidden[i])
+    want = 3 * per_block.astype(np.int64) + fresh.stats(0).astype(np.int64)
+    assert np.array_equal(sess.stats(0).astype(np.int64), want)
+    fresh.close()
+    say("%s: 12 graph replays identical to the eager calls" % wl.name)
+    sess.close()
