@@ -29,7 +29,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 
 
-def cpu_baseline(wl, ti, sample_steps=256):
+def cpu_baseline(wl, ti, sample_steps=512):
     """The oracle as it stands, on `sample_steps` consecutive denoise steps (all tokens,
     cold-start placement) of the benchmark workload."""
     import numpy as np
