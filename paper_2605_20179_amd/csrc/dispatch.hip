@@ -57,10 +57,22 @@ __device__ inline int block_scan_excl(int v, int& total, int* lds4) {
     return base + inc - v;
 }
 
+// A group (cache slot, or expert in a miss pass) with more than kBigMinRows rows is cut into large work
+// items of up to kRowsPerBigTask rows -- when the step has enough of them: the large kernels run one
+// workgroup per compute unit, so with fewer units than compute units most of the chip would idle and the
+// small kernels (several workgroups per compute unit, the second reader of a weight tile served by L2)
+// are the faster way.  use_big is the same in every block of a launch.
+__device__ inline int n_small_items(int m, bool use_big) {
+    return (m <= kBigMinRows || !use_big) ? (m + kRowsPerTask - 1) / kRowsPerTask : 0;
+}
+__device__ inline int n_big_items(int m, bool use_big) {
+    return (m > kBigMinRows && use_big) ? (m + kRowsPerBigTask - 1) / kRowsPerBigTask : 0;
+}
+
 // Work items of one slot whose m rows start at row0.
-__device__ inline void emit_tasks(int slot, int row0, int m, Task* small_out, Task* big_out, int big_room) {
+__device__ inline void emit_tasks(int slot, int row0, int m, bool use_big, Task* small_out, Task* big_out, int big_room) {
     if (m <= 0) return;
-    if (m <= kBigMinRows) {
+    if (m <= kBigMinRows || !use_big) {
         const int ns = (m + kRowsPerTask - 1) / kRowsPerTask;
         for (int c = threadIdx.x; c < ns; c += kThreads) {
             Task t;
@@ -133,7 +145,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     int32_t* __restrict__ pair_row, int32_t* __restrict__ slot_off, Task* __restrict__ tasks, Task* __restrict__ big_tasks,
     int32_t* __restrict__ n_tasks,
     tide_miss* __restrict__ miss, int miss_cap, int32_t* __restrict__ n_miss, int64_t* __restrict__ counters,
-    int max_big) {
+    int max_big, int big_ftiles) {
     __shared__ int lds4[kThreads / 64];
     const int s = blockIdx.x;
     const int tid = threadIdx.x;
@@ -180,16 +192,24 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
         return;
     }
 
+    // large work items of the whole step (every block computes the same figure)
+    int all_big = 0;
+    for (int q = tid; q < capacity; q += kThreads) {
+        const int e = expert_in_slot[q];
+        all_big += n_big_items(e >= 0 ? hist_step[e] : 0, true);
+    }
+    all_big = block_sum(all_big, lds4) + n_big_items(n_shared ? n_tokens : 0, true);
+    const bool use_big = all_big * big_ftiles >= kMinBigUnits;
+
     // rows and work items that precede this slot
     const int upto = s < capacity ? s : capacity;
-    // a slot with up to kBigMinRows rows is cut into small work items of 32 rows, a fuller one into large ones of up to 256
     int rows_before = 0, tasks_before = 0, big_before = 0, active_before = 0;
     for (int q = tid; q < upto; q += kThreads) {
         const int e = expert_in_slot[q];
         const int m = e >= 0 ? hist_step[e] : 0;
         rows_before += m;
-        tasks_before += m <= kBigMinRows ? (m + kRowsPerTask - 1) / kRowsPerTask : 0;
-        big_before += m > kBigMinRows ? (m + kRowsPerBigTask - 1) / kRowsPerBigTask : 0;
+        tasks_before += n_small_items(m, use_big);
+        big_before += n_big_items(m, use_big);
         active_before += m > 0 ? 1 : 0;
     }
     rows_before = block_sum(rows_before, lds4);
@@ -203,9 +223,9 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
         // shared expert: every token, in token order
         const int m = n_shared ? n_tokens : 0;
         for (int n = tid; n < m; n += kThreads) row_token[rows_before + n] = n;
-        const int n_small = m <= kBigMinRows ? (m + kRowsPerTask - 1) / kRowsPerTask : 0;
-        const int n_big = m > kBigMinRows ? (m + kRowsPerBigTask - 1) / kRowsPerBigTask : 0;
-        emit_tasks(capacity, rows_before, m, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
+        const int n_small = n_small_items(m, use_big);
+        const int n_big = n_big_items(m, use_big);
+        emit_tasks(capacity, rows_before, m, use_big, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
         if (tid == 0) {
             slot_off[capacity] = rows_before;
             slot_off[capacity + 1] = rows_before + m;
@@ -226,7 +246,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     const int m = e >= 0 ? hist_step[e] : 0;
     if (tid == 0) slot_off[s] = rows_before;
     if (m == 0) return;
-    emit_tasks(s, rows_before, m, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
+    emit_tasks(s, rows_before, m, use_big, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
     collect_rows<false>(topk_idx, nullptr, n_pairs, k, e, rows_before, row_token, pair_row, lds4);
 }
 
@@ -259,16 +279,19 @@ __global__ __launch_bounds__(kThreads) void miss_group_kernel(const int32_t* __r
                                                              int32_t* __restrict__ row_token,
                                                              int32_t* __restrict__ pair_row, Task* __restrict__ tasks,
                                                              Task* __restrict__ big_tasks, int32_t* __restrict__ n_tasks,
-                                                             int max_big) {
+                                                             int max_big, int big_ftiles) {
     __shared__ int lds4[kThreads / 64];
     const int e = blockIdx.x, tid = threadIdx.x;
+    int all_big = 0;
+    for (int q = tid; q < n_experts; q += kThreads) all_big += n_big_items(miss_hist[q], true);
+    const bool use_big = block_sum(all_big, lds4) * big_ftiles >= kMinBigUnits;
     const int upto = e < n_experts ? e : n_experts;
     int rows_before = 0, tasks_before = 0, big_before = 0;
     for (int q = tid; q < upto; q += kThreads) {
         const int m = miss_hist[q];
         rows_before += m;
-        tasks_before += m <= kBigMinRows ? (m + kRowsPerTask - 1) / kRowsPerTask : 0;
-        big_before += m > kBigMinRows ? (m + kRowsPerBigTask - 1) / kRowsPerBigTask : 0;
+        tasks_before += n_small_items(m, use_big);
+        big_before += n_big_items(m, use_big);
     }
     rows_before = block_sum(rows_before, lds4);
     tasks_before = block_sum(tasks_before, lds4);
@@ -282,7 +305,7 @@ __global__ __launch_bounds__(kThreads) void miss_group_kernel(const int32_t* __r
     }
     const int m = miss_hist[e];
     if (m == 0) return;
-    emit_tasks(e, rows_before, m, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
+    emit_tasks(e, rows_before, m, use_big, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
     collect_rows<true>(m_idx, m_tok, *m_count, 1, e, rows_before, row_token, pair_row, lds4);
 }
 
@@ -326,7 +349,7 @@ hipError_t launch_miss_group(const Shape& s, const Workspace& w, const tide_miss
     hipLaunchKernelGGL(miss_prepare_kernel, dim3((miss_cap + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, miss,
                        miss_cap, n_miss, s.E, w.m_idx, w.m_tok, w.m_w, w.miss_hist, w.m_count);
     hipLaunchKernelGGL(miss_group_kernel, dim3(s.E + 1), dim3(kThreads), 0, stream, w.m_idx, w.m_tok, w.m_count, s.E,
-                       w.miss_hist, w.row_token, w.pair_row, w.tasks, w.big_tasks, w.n_tasks, max_big);
+                       w.miss_hist, w.row_token, w.pair_row, w.tasks, w.big_tasks, w.n_tasks, max_big, (s.I + 127) / 128);
     return hipGetLastError();
 }
 
@@ -342,7 +365,7 @@ hipError_t launch_dispatch(const Shape& s, const LayerTables& t, const Workspace
     TIDE_LAUNCH(dispatch_kernel, dim3(s.capacity + 2), dim3(kThreads), stream, ev, topk_idx, topk_w,
                        n_tokens, s.k, s.capacity, s.n_shared, s.E, t.slot_of, t.expert_in_slot, w.hist_step, t.hits,
                        w.row_token, w.pair_row, w.slot_off, w.tasks, w.big_tasks, w.n_tasks, miss, miss_cap, n_miss, w.counters,
-                max_big_tasks_for(s, n_tokens));
+                max_big_tasks_for(s, n_tokens), (s.I + 127) / 128);
     return hipGetLastError();
 }
 

@@ -186,9 +186,9 @@ int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, 
     // Small and large work items touch disjoint rows: the large ones run on a second stream so that
     // the two kinds of kernels overlap on the chip (fork after the split, join before the combine).
     if (max_big > 0) {
-        TIDE_HIP(ctx, launch_plan_big(ctx->ws, max_big, stream));
         TIDE_HIP(ctx, hipEventRecord(ctx->fork_ev, stream));
         TIDE_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_ev, 0));
+        TIDE_HIP(ctx, launch_plan_big(ctx->ws, max_big, ctx->aux));
         TIDE_HIP(ctx, timed(ctx, TIDE_K_GATE_UP_BIG, [&](LaunchEvents ev) {
             return launch_expert_gemm_big(0, ctx->shape, L.t, ctx->ws, x, max_big, ctx->aux, ev); }));
         TIDE_HIP(ctx, timed(ctx, TIDE_K_DOWN_BIG, [&](LaunchEvents ev) {

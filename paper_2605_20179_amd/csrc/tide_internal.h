@@ -17,6 +17,7 @@ constexpr int kRowsPerBigTask = 256;    // rows of a large work item
 #ifndef TIDE_BIG_MIN_ROWS
 #define TIDE_BIG_MIN_ROWS 32
 #endif
+constexpr int kMinBigUnits = 128;       // a step uses large work items only if they make at least this many gate/up workgroups (half the compute units)
 constexpr int kBigMinRows = TIDE_BIG_MIN_ROWS;   // a slot with more rows than this is cut into large work items, else into small ones
 
 // One grouped-GEMM work item: rows [row0, row0+nrows) of the slot-sorted row space
