@@ -94,8 +94,9 @@ int tide_pack_expert(const tide_config* cfg, const uint16_t* wg_host, const uint
 
 /* Registers the host master copy of a layer's E packed blobs: expert e starts at
  * host_blobs + e * blob_stride.  The memory must be pinned (hipHostMalloc / torch
- * pin_memory) and stay valid and unchanged until tide_destroy: refresh copies read it
- * asynchronously.  Borrowed, never written, never freed. */
+ * pin_memory) and stay valid and unchanged until tide_destroy: the refresh's copy kernel
+ * and the miss pass read it in place from the GPU, asynchronously.  Pageable memory is
+ * refused with TIDE_E_INVAL.  Borrowed, never written, never freed. */
 int tide_register_experts(tide_ctx* ctx, int layer, const void* host_blobs, uint64_t blob_stride);
 
 /* Copies one packed blob (host) into the layer's always-resident shared-expert slot.
@@ -172,8 +173,8 @@ int tide_interval_stats(tide_ctx* ctx, int layer, int32_t* counts_host, int rese
  * the first `capacity` form the new resident set.  Leaving experts, ordered by
  * (hits ascending, id), free their slots; entering experts, ordered by (hits descending,
  * id), take the freed slots in that order and then empty slots in ascending order.
- * One copy per entering expert is queued on the context's side stream from the
- * registered host blobs; eviction moves no bytes.  The tables change at once; the next
+ * The entering experts' blobs are copied from the registered host blobs by one kernel on
+ * the context's side stream (it reads pinned host memory in place); eviction moves no bytes.  The tables change at once; the next
  * step's expert GEMMs wait for the copies.
  *   counts_host     int32 [E] to rank by, or NULL = the layer's own H               (in)
  *   capacity        size of the new resident set, 0..ctx capacity                   (in)

@@ -116,11 +116,45 @@ hipError_t launch_refresh_select(const Shape& s, const LayerTables& t, const int
 }
 
 namespace {
+// The refresh's host-to-device copies as one kernel: the newcomers' blobs are read in place from pinned
+// host memory (the plan itself is read from the pinned block the selection kernel wrote) and stored to
+// their cache slots -- or, for a deferred refresh, to staging blob i.  A few dozen workgroups keep the host
+// link busy (57 GB/s against 52.7 GB/s for one DMA per 6 MiB blob) and leave the compute units to the
+// step kernels.  Each thread keeps four 16-byte reads in flight.
+constexpr int kCopyBlocks = 64, kCopyThreads = 256;
+__global__ __launch_bounds__(kCopyThreads) void refresh_copy_kernel(const uint8_t* __restrict__ host_blobs, uint64_t host_stride,
+                                                                   uint64_t blob_bytes, uint8_t* __restrict__ dst_base,
+                                                                   const RefreshOut* __restrict__ plan, int n, int dst_by_rank) {
+    const uint64_t per_blob = blob_bytes / 16;
+    const uint64_t stride = (uint64_t)gridDim.x * kCopyThreads;
+    for (int i = 0; i < n; ++i) {
+        const uint4* src = reinterpret_cast<const uint4*>(host_blobs + (uint64_t)plan->expert[i] * host_stride);
+        uint4* dst = reinterpret_cast<uint4*>(dst_base + (uint64_t)(dst_by_rank ? i : plan->slot[i]) * blob_bytes);
+        uint64_t q = (uint64_t)blockIdx.x * kCopyThreads + threadIdx.x;
+        for (; q + 3 * stride < per_blob; q += 4 * stride) {
+            const uint4 a = src[q], b = src[q + stride], c = src[q + 2 * stride], d = src[q + 3 * stride];
+            dst[q] = a;
+            dst[q + stride] = b;
+            dst[q + 2 * stride] = c;
+            dst[q + 3 * stride] = d;
+        }
+        for (; q < per_blob; q += stride) dst[q] = src[q];
+    }
+}
+
 __global__ void scale_counts_kernel(int32_t* hits, int n, int num, int den) {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e < n) hits[e] = (int32_t)(((int64_t)hits[e] * num) / den);
 }
 }  // namespace
+
+hipError_t launch_refresh_copies(const uint8_t* host_blobs, uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base,
+                                 const RefreshOut* plan, int n, bool dst_by_rank, hipStream_t stream) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(refresh_copy_kernel, dim3(kCopyBlocks), dim3(kCopyThreads), 0, stream, host_blobs, host_stride,
+                       blob_bytes, dst_base, plan, n, dst_by_rank ? 1 : 0);
+    return hipGetLastError();
+}
 
 hipError_t launch_scale_counts(int32_t* hits, int n_experts, int num, int den, hipStream_t stream) {
     hipLaunchKernelGGL(scale_counts_kernel, dim3((n_experts + 255) / 256), dim3(256), 0, stream, hits, n_experts, num, den);

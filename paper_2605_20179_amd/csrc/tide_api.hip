@@ -341,6 +341,13 @@ int tide_register_experts(tide_ctx* ctx, int layer, const void* host_blobs, uint
     if (!host_blobs) return fail(ctx, TIDE_E_INVAL, "host_blobs is null");
     if (blob_stride < tide_expert_blob_bytes(&ctx->cfg) || (blob_stride & 15) || ((uintptr_t)host_blobs & 15))
         return fail(ctx, TIDE_E_INVAL, "blob_stride must be >= blob bytes; base and stride 16-byte aligned");
+    // the refresh's copy kernel and the miss pass read the blobs in place: the memory must be pinned and
+    // mapped into the device's address space (pageable memory would fault a kernel)
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, host_blobs) != hipSuccess || attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) {
+        (void)hipGetLastError();
+        return fail(ctx, TIDE_E_INVAL, "host_blobs must be pinned host memory (hipHostMalloc, or a tensor made with pin_memory=True)");
+    }
     ctx->layers[layer].host_blobs = static_cast<const uint8_t*>(host_blobs);
     ctx->layers[layer].host_stride = blob_stride;
     return TIDE_OK;
@@ -530,10 +537,10 @@ int refresh_impl(tide_ctx* ctx, int layer, const int32_t* counts_host, int capac
     TIDE_HIP(ctx, hipStreamSynchronize(stream));
     const int n = L.plan->n_copies;
     TIDE_HIP(ctx, hipEventRecord(L.copies_begin, ctx->side));
+    TIDE_HIP(ctx, launch_refresh_copies(L.host_blobs, L.host_stride, bytes,
+                                        deferred ? L.staging : reinterpret_cast<uint8_t*>(L.slots_owned), L.plan, n, deferred, ctx->side));
     for (int i = 0; i < n; ++i) {
         const int e = L.plan->expert[i], s = L.plan->slot[i];
-        void* dst = deferred ? static_cast<void*>(L.staging + (uint64_t)i * bytes) : static_cast<void*>(slot_ptr(ctx, L, s));
-        TIDE_HIP(ctx, hipMemcpyAsync(dst, L.host_blobs + (uint64_t)e * L.host_stride, bytes, hipMemcpyHostToDevice, ctx->side));
         if (plan_out) {
             plan_out[i].expert = e;
             plan_out[i].slot = s;

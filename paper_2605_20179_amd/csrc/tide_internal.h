@@ -150,6 +150,9 @@ struct RefreshOut {           // lives in pinned host memory the kernel writes d
 hipError_t launch_refresh_select(const Shape& s, const LayerTables& t, const int32_t* counts, int capacity,
                                  int reset_counts, RefreshOut* out_hostmapped, hipStream_t stream);
 
+// a12: the plan's blobs from pinned host memory to their slots (or to staging blob i), one kernel
+hipError_t launch_refresh_copies(const uint8_t* host_blobs, uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base,
+                                 const RefreshOut* plan, int n, bool dst_by_rank, hipStream_t stream);
 // H[e] <- floor(H[e] * num / den)
 hipError_t launch_scale_counts(int32_t* hits, int n_experts, int num, int den, hipStream_t stream);
 // interval analysis (Sec. 3.2, Eq. 4-7): similarity / distinct experts / drift on the device, cost model on the host
