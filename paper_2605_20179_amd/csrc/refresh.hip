@@ -118,10 +118,11 @@ hipError_t launch_refresh_select(const Shape& s, const LayerTables& t, const int
 namespace {
 // The refresh's host-to-device copies as one kernel: the newcomers' blobs are read in place from pinned
 // host memory (the plan itself is read from the pinned block the selection kernel wrote) and stored to
-// their cache slots -- or, for a deferred refresh, to staging blob i.  A few dozen workgroups keep the host
-// link busy (57 GB/s against 52.7 GB/s for one DMA per 6 MiB blob) and leave the compute units to the
-// step kernels.  Each thread keeps four 16-byte reads in flight.
-constexpr int kCopyBlocks = 64, kCopyThreads = 256;
+// their cache slots -- or, for a deferred refresh, to staging blob i.  Sixteen workgroups keep the host link
+// busy (56.9 GB/s against 52.7 GB/s for one DMA per 6 MiB blob); more would not copy faster, and every compute
+// unit that hosts one serves the step kernels' own loads slowly while the copy lasts (its vector memory
+// pipeline is full of host-link reads).  Each thread keeps four 16-byte reads in flight.
+constexpr int kCopyBlocks = 16, kCopyThreads = 256;
 __global__ __launch_bounds__(kCopyThreads) void refresh_copy_kernel(const uint8_t* __restrict__ host_blobs, uint64_t host_stride,
                                                                    uint64_t blob_bytes, uint8_t* __restrict__ dst_base,
                                                                    const RefreshOut* __restrict__ plan, int n, int dst_by_rank) {
