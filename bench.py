@@ -77,6 +77,8 @@ def main():
     ap.add_argument("--refresh-mode", choices=("immediate", "deferred"), default="immediate",
                     help="immediate: Alg. 1 as written, the refresh step's GEMMs wait for the copies (default, the headline figure); "
                          "deferred: the refresh step runs on the old placement while the copies land, the new one serves from the next step")
+    ap.add_argument("--commit-after", type=int, default=1,
+                    help="deferred mode: steps that still run on the old placement before the new one is committed (1..refresh interval)")
     ap.add_argument("--capacity", type=int, default=0, help="cache slots (0 = the workload's own budget); 256 = every expert resident")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
@@ -118,13 +120,14 @@ def main():
 
     def one_step(timed):
         t = state["t"] % wl.S
-        if state.get("uncommitted"):
+        if state.get("uncommitted") and state["t"] >= state["commit_at"]:
             sess.commit(0)
             state["uncommitted"] = False
         if t > 0 and t % wl.K == 0:
             r0 = time.perf_counter()
             _, plan = sess.refresh(0, deferred=args.refresh_mode == "deferred")
             state["uncommitted"] = args.refresh_mode == "deferred"
+            state["commit_at"] = state["t"] + args.commit_after
             if timed:
                 state["refresh_s"] += time.perf_counter() - r0
                 state["copies"] += len(plan)
@@ -263,7 +266,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "d": wl.d, "experts": wl.E, "top_k": wl.k, "d_ff": wl.I, "shared_experts": wl.n_shared,
                    "tokens_per_step": wl.N, "capacity": wl.C, "refresh_interval": wl.K, "steps_per_block": wl.S, "layers": 1,
-                   "refresh_mode": args.refresh_mode},
+                   "refresh_mode": args.refresh_mode if args.refresh_mode == "immediate" else "deferred by %d step(s)" % args.commit_after},
         "roofline": roofline,
         "detail": {
             "kernels": kernels,

@@ -293,7 +293,7 @@ def run_block(hidden_steps, w_r, bias, gating: int, bias_mode: int, k: int, n_ex
 def run_block_policy(hidden_steps, w_r, bias, gating: int, bias_mode: int, k: int, n_experts: int,
                      capacity: int, initial_expert_in_slot: np.ndarray, interval: Optional[int],
                      counter: str = "interval", decay: Tuple[int, int] = (1, 2), warm_start: bool = False,
-                     initial_hits: Optional[np.ndarray] = None, deferred: bool = False):
+                     initial_hits: Optional[np.ndarray] = None, deferred: int = 0):
     """Routing, counter, placement and miss lists of one block under a placement policy.
 
     interval = None: static placement, never refreshed (the Fiddler-like baseline); interval = 1:
@@ -306,9 +306,10 @@ def run_block_policy(hidden_steps, w_r, bias, gating: int, bias_mode: int, k: in
     refreshed from them and the counter cleared (only with counter = "interval"), and step 0 is run again
     on the new placement, which counts it into the interval that starts there.
     initial_hits: H carried over from an earlier block (with initial_expert_in_slot its last placement).
-    deferred: the placement chosen by the refresh before step t (its copies overlap step t) serves from
-    step t+1 on; step t itself still runs on the old placement (R5's overlapped variant).  The choice, the
-    plan and the counter are what they are without the delay.
+    deferred = j > 0: the placement chosen by the refresh before step t (its copies overlap steps t..t+j-1)
+    serves from step t+j on; until then the old placement does (R5's overlapped variant; True means j = 1).
+    The counter is what it is without the delay; the choice is made against the placement in force, so with
+    j <= interval the plans are those of the undelayed run too.  j must not exceed the interval.
     Returns (log, final expert_in_slot, final hits); log[t] has idx, w, hist, hits, expert_in_slot,
     slot_of, plan, miss like run_block's."""
     if warm_start and counter != "interval":
@@ -324,13 +325,16 @@ def run_block_policy(hidden_steps, w_r, bias, gating: int, bias_mode: int, k: in
         elif counter != "cumulative":
             raise ValueError(counter)
 
+    deferred = int(deferred)
     if deferred and warm_start:
         raise ValueError("a warm start is a blocking refresh")
+    if deferred and (interval is None or deferred > interval):
+        raise ValueError("the delay must not exceed the refresh interval")
     log = []
-    pending = None
+    pending, due = None, -1
     for t, x_bits in enumerate(hidden_steps):
         rec: Dict = {"t": t, "plan": None}
-        if pending is not None:
+        if pending is not None and t == due:
             eis, pending = pending, None
         idx, w, amb, key = route(x_bits, w_r, bias, gating, bias_mode, k)
         hist = step_histogram(idx, n_experts)
@@ -342,7 +346,7 @@ def run_block_policy(hidden_steps, w_r, bias, gating: int, bias_mode: int, k: in
             new_eis, rec["plan"] = refresh(hits, eis, capacity)
             after_refresh(hits)
             if deferred:
-                pending = new_eis
+                pending, due = new_eis, t + deferred
                 rec["pending_expert_in_slot"] = new_eis.copy()
             else:
                 eis = new_eis

@@ -106,7 +106,7 @@ def test_other_budgets_and_block_lengths(budget, block):
 
 def test_deferred_refresh_and_commit():
     """The overlapped variant: the refresh before step t only stages its newcomers; step t runs on the old
-    placement; tide_commit installs the new one before step t+1.  Counter, tables, plans, miss lists and the
+    placement; tide_commit installs the new one before step t+1 (or, called later, before step t+j).  Counter, tables, plans, miss lists and the
     bytes of every cache slot are compared with the oracle's delayed placement."""
     wl = ti.CONFIGS[1].replace(S=14)
     hidden = list(ti.hidden_stream(wl, 0))
@@ -118,18 +118,18 @@ def test_deferred_refresh_and_commit():
     with pytest.raises(tb.TideError) as err:
         sess.commit(0)
     assert err.value.code == tb.TIDE_E_STATE
-    for K in (1, 4):
-        log, _, _ = orc.run_block_policy(*args, interval=K, deferred=True)
+    for K, delay in ((1, 1), (4, 1), (4, 3)):
+        log, _, _ = orc.run_block_policy(*args, interval=K, deferred=delay)
         tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))
         sess.stats(0, reset=True)
-        pending = False
+        pending, due = False, -1
         for t, rec in enumerate(log):
-            if pending:
+            if pending and t == due:
                 sess.commit(0)
                 pending = False
             if t > 0 and t % K == 0:
                 eis, plan = sess.refresh(0, deferred=True)
-                pending = True
+                pending, due, chosen = True, t + delay, rec["pending_expert_in_slot"]
                 assert eis.tolist() == rec["pending_expert_in_slot"].tolist(), "step %d: chosen set" % t
                 assert [(e, s) for e, s, _, _ in plan] == [tuple(p) for p in rec["plan"]], "step %d: plan" % t
                 for call in (lambda: sess.refresh(0), lambda: sess.refresh(0, deferred=True)):
@@ -146,11 +146,12 @@ def test_deferred_refresh_and_commit():
         if pending:
             sess.commit(0)
         torch.cuda.synchronize()
-        final = log[-1].get("pending_expert_in_slot", log[-1]["expert_in_slot"])
+        final = chosen                                  # the last refresh's choice is in force once committed
         assert np.array_equal(sess.table(0), orc.slot_table(final, wl.E))
         for s in (0, 1, wl.C // 2, wl.C - 1):                 # the slots hold their experts' bytes
             assert np.array_equal(sess.read_slot(0, s), host[final[s]]), "slot %d" % s
-        say("deferred refresh K=%d: %d steps exact" % (K, len(log)))
+        say("deferred refresh K=%d, serving %d step(s) late: %d steps exact, miss rate %.4f"
+            % (K, delay, len(log), sum(len(r["miss"]) for r in log) / (len(log) * wl.N * wl.k)))
     # a placement set by hand cancels a pending refresh
     sess.refresh(0, deferred=True)
     tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))

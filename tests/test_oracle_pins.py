@@ -493,5 +493,14 @@ def test_policy_deferred_refresh_is_the_same_choice_one_step_late():
             live = set(int(e) for e in b["expert_in_slot"] if e >= 0)
             assert b["miss"] == [(n, int(b["idx"][n, i]), float(b["w"][n, i])) for n in range(b["idx"].shape[0])
                                  for i in range(wl.k) if int(b["idx"][n, i]) not in live]
+    # a longer delay: the same choices, each serving j steps late
+    now, _, _ = orc.run_block_policy(*args, interval=4)
+    late, _, _ = orc.run_block_policy(*args, interval=4, deferred=3)
+    for t, (a, b) in enumerate(zip(now, late)):
+        assert a["plan"] == b["plan"] and np.array_equal(a["hits"], b["hits"])
+        src = t if (t < 4 or t % 4 == 3) else (t // 4) * 4 - 1       # steps 4k..4k+2 still run on the placement of step 4k-1
+        assert b["expert_in_slot"].tolist() == now[src]["expert_in_slot"].tolist(), t
     with pytest.raises(ValueError):
         orc.run_block_policy(*args, interval=4, warm_start=True, deferred=True)
+    with pytest.raises(ValueError):
+        orc.run_block_policy(*args, interval=4, deferred=5)
