@@ -43,7 +43,7 @@ __device__ inline bf16x8 load_weights(const uint16_t* p) {
 
 __device__ inline float silu(float g) { return g / (1.f + __expf(-g)); }
 
-// Shared skeleton of the small (<= 32 rows) and large (<= 128 rows) work-item kernels.
+// Shared skeleton of the small (<= 32 rows) and large (<= 256 rows) work-item kernels.
 //
 //   PASS 0: a wave owns G gate stripes and the G matching up stripes (RT = 2G weight stripes of
 //           16 rows), i.e. SwiGLU columns wtile*16G .. +16G-1; K = d; activations are gathered
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
 // weight rows x up to 256 tokens: what bounds these kernels is the rate at which a compute unit's
 // vector cache can be filled, so the tile is as large as the accumulators allow (256 of a wave's 512
 // registers).  Up to 128 rows: eight token tiles, 256-column stages, ring depth 8.  Above: up to 16
-// token tiles in two half sets, 64-column stages, ring depth 4 (the same lead in MFMA time).
+// token tiles in two half sets, 128-column stages, ring depth 4 (the same lead in MFMA time).
 constexpr int kBigPC = 8, kBigD = 8;       // <= 8 token tiles
 constexpr int kWidePC = 4, kWideD = 4;     // 9..16 token tiles
 constexpr int kBigLdsElems = 2 * 128 * (kBigPC * 32 + 8) > 2 * 256 * (kWidePC * 32 + 8) ? 2 * 128 * (kBigPC * 32 + 8)
