@@ -79,6 +79,7 @@ def main():
                          "deferred: the refresh step runs on the old placement while the copies land, the new one serves from the next step")
     ap.add_argument("--commit-after", type=int, default=1,
                     help="deferred mode: steps that still run on the old placement before the new one is committed (1..refresh interval)")
+    ap.add_argument("--tokens", type=int, default=0, help="tokens per step (0 = the workload's own; e.g. 4096 = batch 128 of block 32)")
     ap.add_argument("--capacity", type=int, default=0, help="cache slots (0 = the workload's own budget); 256 = every expert resident")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
@@ -110,6 +111,8 @@ def main():
     wl = ti.CONFIGS[args.config]
     if args.capacity:
         wl = wl.replace(C=args.capacity)
+    if args.tokens:
+        wl = wl.replace(N=args.tokens)
     sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode)
     sess.load_layer(0, lambda e: ti.expert_weights(wl, 0, e), ti.router_weights(wl, 0), ti.router_bias(wl, 0),
                     ti.initial_resident(wl), workers=16)
