@@ -168,6 +168,10 @@ RAGGED = [
     (384, 70, 4, 192, 1, 257, 30, ti.GATING_SOFTMAX, ti.BIAS_LOGIT),
     (192, 100, 5, 320, 0, 300, 20, ti.GATING_SIGMOID, ti.BIAS_SELECT),
     (320, 8, 2, 192, 1, 700, 4, ti.GATING_SIGMOID, ti.BIAS_NONE),
+    # the largest expert count and top-k the library takes, on the one-workgroup path and on the many-workgroup
+    # path, the second with every expert resident
+    (128, 512, 16, 64, 1, 20, 100, ti.GATING_SIGMOID, ti.BIAS_LOGIT),
+    (128, 512, 16, 64, 0, 90, 512, ti.GATING_SOFTMAX, ti.BIAS_NONE),
 ]
 
 
