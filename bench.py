@@ -52,6 +52,60 @@ def cpu_baseline(wl, ti, sample_steps=512):
                       "%.1f s (includes bf16->fp64 weight conversion on first use)" % (sample_steps, wl.N, dt)}
 
 
+def run_stack(args, wl, ti, tb, TideSession, torch):
+    """A stack of L independent MoE layers per denoise step (the stack workloads' metric: N / sum over the
+    layers).  Detail measurement, not the headline: prints its own JSON line."""
+    L = args.stack
+    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, n_layers=L)
+    packed = sess.pack_layer(lambda e: ti.expert_weights(wl, 0, e), workers=16)
+    hidden = []
+    for l in range(L):
+        sess.load_layer(l, None, ti.router_weights(wl, l), ti.router_bias(wl, l), ti.initial_resident(wl), packed=packed)
+        hidden.append([sess.to_device_bf16(h) for h in ti.hidden_stream(wl, l)])
+    torch.cuda.synchronize()
+    state = {"t": 0, "copies": 0}
+
+    def one_step():
+        t = state["t"] % wl.S
+        due = t > 0 and t % wl.K == 0
+        if due and args.refresh_order == "all-first":
+            for l in range(L):
+                state["copies"] += len(sess.refresh(l)[1])
+        for l in range(L):
+            if due and args.refresh_order == "per-layer":
+                state["copies"] += len(sess.refresh(l)[1])
+            sess.step(l, hidden[l][t], want_topk=False)
+        state["t"] += 1
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    state["copies"] = 0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    s0 = time.perf_counter()
+    for i in range(args.steps):
+        for l in range(L):
+            sess.step(l, hidden[l][i % wl.S], want_topk=False)
+    torch.cuda.synchronize()
+    frozen = (time.perf_counter() - s0) / args.steps
+    print(json.dumps({
+        "metric": "MoE-layer tokens/s per denoise step", "value": wl.N * args.steps / dt, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "d": wl.d, "experts": wl.E, "top_k": wl.k, "d_ff": wl.I, "shared_experts": wl.n_shared,
+                   "tokens_per_step": wl.N, "capacity": wl.C, "refresh_interval": wl.K, "steps_per_block": wl.S, "layers": L,
+                   "refresh_order": args.refresh_order, "note": "layers share layer 0's expert values; routers, streams, caches differ"},
+        "detail": {"experts_copied": state["copies"], "blob_MiB": sess.blob_bytes / 2 ** 20,
+                   "frozen_placement_us_per_step": frozen * 1e6, "frozen_placement_us_per_layer": frozen * 1e6 / L,
+                   "us_per_layer": 1e6 * dt / args.steps / L}}))
+    sess.close()
+
+
 TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "cfg1_mini_layer_hbm_traffic.md")
 
 
@@ -80,6 +134,12 @@ def main():
     ap.add_argument("--commit-after", type=int, default=1,
                     help="deferred mode: steps that still run on the old placement before the new one is committed (1..refresh interval)")
     ap.add_argument("--tokens", type=int, default=0, help="tokens per step (0 = the workload's own; e.g. 4096 = batch 128 of block 32)")
+    ap.add_argument("--stack", type=int, default=0,
+                    help="run L layers of the workload per denoise step (own router, hidden stream, cache, counter and refresh "
+                         "per layer; the layers share layer 0's expert values) and report N / sum of the layers' times")
+    ap.add_argument("--refresh-order", choices=("per-layer", "all-first"), default="all-first",
+                    help="--stack: at a refresh step, refresh each layer right before its own step, or all layers first so "
+                         "that later layers' copies overlap earlier layers' compute")
     ap.add_argument("--capacity", type=int, default=0, help="cache slots (0 = the workload's own budget); 256 = every expert resident")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
@@ -113,6 +173,9 @@ def main():
         wl = wl.replace(C=args.capacity)
     if args.tokens:
         wl = wl.replace(N=args.tokens)
+    if args.stack:
+        run_stack(args, wl, ti, tb, TideSession, torch)
+        return
     sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode)
     sess.load_layer(0, lambda e: ti.expert_weights(wl, 0, e), ti.router_weights(wl, 0), ti.router_bias(wl, 0),
                     ti.initial_resident(wl), workers=16)
