@@ -122,6 +122,49 @@ def read_traffic_summary():
     return None, None
 
 
+def run_lossless(args, sess, wl, hidden, tb, ti, torch, mode):
+    """The layer with its misses evaluated too (full MoE output at every step), refresh every K steps as in the timed
+    region.  mode 'device': tide_moe_apply_misses; mode 'host': tide_moe_apply_misses_host, whose workers run while the
+    GPU is on the step's hits (Sec. 3.3: layer time = the longer of the two)."""
+    if mode == "host":
+        sess.host_experts(args.host_threads)
+    tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))
+    sess.stats(0, reset=True)
+    tb.tide_counters(sess.ctx, reset=True)
+    steps = min(args.steps, 4 * wl.S)
+    acc = [0.0, 0.0, 0.0]
+
+    def one(t, timed):
+        if t > 0 and t % wl.K == 0:
+            sess.refresh(0)
+        sess.step(0, hidden[t], want_topk=False)
+        if mode == "host":
+            sess.apply_misses_host(0, hidden[t])
+            if timed:
+                for i, v in enumerate(tb.tide_host_miss_ms(sess.ctx)):
+                    acc[i] += v
+        else:
+            sess.apply_misses(0, hidden[t])
+
+    for i in range(wl.K * 2):
+        one(i % wl.S, False)
+    torch.cuda.synchronize()
+    tb.tide_counters(sess.ctx, reset=True)
+    t0 = time.perf_counter()
+    for i in range(steps):
+        one((wl.K * 2 + i) % wl.S, True)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    cnt = tb.tide_counters(sess.ctx)
+    res = {"us_per_step": dt * 1e6, "tokens_per_s": wl.N / dt, "steps": steps,
+           "missed_pairs_per_step": cnt["misses"] / max(cnt["steps"], 1)}
+    if mode == "host":
+        res.update({"host_threads": args.host_threads, "wait_for_list_us": acc[0] / steps * 1e3,
+                    "host_experts_us": acc[1] / steps * 1e3, "call_us": acc[2] / steps * 1e3})
+        sess.host_experts(0)
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,6 +184,10 @@ def main():
                     help="--stack: at a refresh step, refresh each layer right before its own step, or all layers first so "
                          "that later layers' copies overlap earlier layers' compute")
     ap.add_argument("--capacity", type=int, default=0, help="cache slots (0 = the workload's own budget); 256 = every expert resident")
+    ap.add_argument("--miss-mode", choices=("none", "device", "host", "both"), default="none",
+                    help="detail only: also time the lossless layer (step + evaluation of its misses): 'device' = the GPU reads the "
+                         "missed experts in place from pinned host memory; 'host' = host worker threads evaluate them while the GPU runs the hits")
+    ap.add_argument("--host-threads", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -283,6 +330,11 @@ def main():
         h2d = {"GB/s": len(plan) * sess.blob_bytes / ms / 1e6, "copies": len(plan), "MiB_each": sess.blob_bytes / 2 ** 20}
     probe.close()
 
+    lossless = None
+    if args.miss_mode != "none":
+        lossless = {m: run_lossless(args, sess, wl, hidden, tb, ti, torch, m)
+                    for m in (("device", "host") if args.miss_mode == "both" else (args.miss_mode,))}
+
     tokens = wl.N * args.steps
     value = tokens / dt
     blob = sess.blob_bytes
@@ -346,6 +398,7 @@ def main():
             "refresh_copies": refresh_stats,
             "frozen_placement_tokens_per_s": wl.N / step_only_s,
             "h2d_probe": h2d,
+            "lossless_layer": lossless,
         },
     }
     if not args.no_cpu_baseline:

@@ -60,7 +60,7 @@ typedef struct {
     int32_t n_shared;    /* 0 or 1 always-resident shared expert (weight 1, not counted) */
     int32_t n_layers;    /* independent MoE layers, each with its own cache and counter  */
     int32_t capacity;    /* cache slots per layer (the paper's B), 1..E                  */
-    int32_t max_tokens;  /* largest n_tokens a step may carry                            */
+    int32_t max_tokens;  /* largest n_tokens a step may carry, 1..65535                  */
     int32_t gating;      /* TIDE_GATING_*                                                */
     int32_t bias_mode;   /* TIDE_BIAS_*                                                  */
 } tide_config;
@@ -160,6 +160,40 @@ int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n
 int tide_moe_apply_misses(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens,
                           const tide_miss* miss_dev, int miss_cap, const int32_t* n_miss_dev,
                           float* out_dev, void* hip_stream);
+
+/* Host-core execution of misses (Sec. 3.3, Alg. 1: a token whose expert is not in the GPU set is
+ * evaluated by the CPU copy of that expert while the GPU evaluates the hits; the partial results
+ * are brought together at the end of the layer).
+ *
+ * tide_host_experts starts n_threads worker threads (the calling thread of a later
+ * tide_moe_apply_misses_host counts as one of them) and allocates the pinned exchange buffers
+ * (miss list, token states, result rows, sized by max_tokens); n_threads == 0 stops the workers.
+ * Synchronises the device.  While workers exist, every step records one more event. */
+int tide_host_experts(tide_ctx* ctx, int n_threads);
+
+/* Same contract and arguments as tide_moe_apply_misses, but the listed misses are evaluated by the
+ * host workers from the registered host blobs (fp32 arithmetic on the bf16 weights and token
+ * states), and the per-token sums are added to out_dev by a kernel queued on hip_stream.
+ * The call blocks the calling thread until the host work is done; it does NOT wait for the GPU
+ * work queued on hip_stream: when hidden_dev / miss_dev / hip_stream are those of the last step
+ * issued, the list and the token states are fetched as soon as that step's hit/miss split has run,
+ * so the host cores work while the GPU runs the step's expert GEMMs (layer time = the longer of
+ * the two, Sec. 3.3); with other buffers the fetch waits for everything queued on hip_stream.
+ * Errors: TIDE_E_STATE without workers or registered experts; TIDE_E_INVAL for a list entry
+ * that names a token or an expert out of range (nothing is added then). */
+int tide_moe_apply_misses_host(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens,
+                               const tide_miss* miss_dev, int miss_cap, const int32_t* n_miss_dev,
+                               float* out_dev, void* hip_stream);
+
+/* Host wall-clock milliseconds of the last tide_moe_apply_misses_host: ms3_host[0] waiting for the
+ * list and the token states, [1] the host experts, [2] the whole call. */
+int tide_host_miss_ms(tide_ctx* ctx, float* ms3_host);
+
+/* One expert on the calling host thread, no GPU involved: y_host[t][:] = e(x_t) for m token
+ * states x_host (bf16 [m][d], host) through one packed blob (host); y_host fp32 [m][d].
+ * The arithmetic of the host workers, exposed for checking it without a device. */
+int tide_host_expert(const tide_config* cfg, const void* blob_host, const uint16_t* x_host, int m,
+                     float* y_host);
 
 /* ---- interval statistics and refresh ---------------------------------------------- */
 

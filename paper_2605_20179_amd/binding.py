@@ -24,6 +24,7 @@ EXPORTS = [
     "tide_interval_stats", "tide_refresh", "tide_wait_refresh", "tide_get_table", "tide_read_slot",
     "tide_refresh_copy_ms", "tide_profile", "tide_profile_read", "tide_counters", "tide_moe_apply_misses",
     "tide_step_histogram", "tide_routing_stability", "tide_interval_costs", "tide_optimal_interval", "tide_fit_drift", "tide_scale_counts", "tide_refresh_deferred", "tide_commit",
+    "tide_host_experts", "tide_moe_apply_misses_host", "tide_host_miss_ms", "tide_host_expert",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -70,6 +71,10 @@ def _load() -> C.CDLL:
     lib.tide_moe_step.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp, vp, vp]
     lib.tide_moe_step_routed.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp]
     lib.tide_moe_apply_misses.argtypes = [vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, vp, vp]
+    lib.tide_moe_apply_misses_host.argtypes = lib.tide_moe_apply_misses.argtypes
+    lib.tide_host_experts.argtypes = [vp, C.c_int]
+    lib.tide_host_miss_ms.argtypes = [vp, vp]
+    lib.tide_host_expert.argtypes = [cfgp, vp, vp, C.c_int, vp]
     lib.tide_interval_stats.argtypes = [vp, C.c_int, vp, C.c_int, vp]
     lib.tide_refresh.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, vp, vp, C.POINTER(C.c_int), vp]
     lib.tide_refresh_deferred.argtypes = lib.tide_refresh.argtypes
@@ -174,6 +179,31 @@ def tide_moe_step_routed(ctx, layer: int, hidden, n_tokens: int, topk_idx, topk_
 def tide_moe_apply_misses(ctx, layer: int, hidden, n_tokens: int, miss, miss_cap: int, n_miss, out, stream=None) -> None:
     _check(lib.tide_moe_apply_misses(ctx, layer, _ptr(hidden), n_tokens, _ptr(miss), miss_cap, _ptr(n_miss), _ptr(out),
                                      _stream_ptr(stream)), ctx)
+
+
+def tide_host_experts(ctx, n_threads: int) -> None:
+    _check(lib.tide_host_experts(ctx, n_threads), ctx)
+
+
+def tide_moe_apply_misses_host(ctx, layer: int, hidden, n_tokens: int, miss, miss_cap: int, n_miss, out, stream=None) -> None:
+    _check(lib.tide_moe_apply_misses_host(ctx, layer, _ptr(hidden), n_tokens, _ptr(miss), miss_cap, _ptr(n_miss),
+                                          _ptr(out), _stream_ptr(stream)), ctx)
+
+
+def tide_host_miss_ms(ctx):
+    """(ms waiting for the list, ms of host experts, ms of the whole call) of the last host miss pass."""
+    ms = np.zeros(3, dtype=np.float32)
+    _check(lib.tide_host_miss_ms(ctx, _ptr(ms)), ctx)
+    return float(ms[0]), float(ms[1]), float(ms[2])
+
+
+def tide_host_expert(cfg: tide_config, blob, x_bits: np.ndarray) -> np.ndarray:
+    """e(x) of m token states (uint16 bf16 bits [m, d]) through one packed blob, on the calling host thread."""
+    x = np.ascontiguousarray(x_bits, dtype=np.uint16)
+    assert x.ndim == 2 and x.shape[1] == cfg.d
+    y = np.zeros((x.shape[0], cfg.d), dtype=np.float32)
+    _check(lib.tide_host_expert(C.byref(cfg), _ptr(blob), _ptr(x), x.shape[0], _ptr(y)), None)
+    return y
 
 
 def tide_interval_stats(ctx, layer: int, n_experts: int, reset: bool, stream=None) -> np.ndarray:

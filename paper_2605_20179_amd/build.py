@@ -13,6 +13,8 @@ BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtide.so")
 
 SOURCES = ["router.hip", "dispatch.hip", "expert_gemm.hip", "combine.hip", "refresh.hip", "analysis.hip", "tide_api.hip"]
+HOST_SOURCES = ["host_experts.cpp"]      # plain C++ (the host cores' expert path), compiled by the host compiler
+HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-pthread", "-Wall", "-Wno-psabi", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          # keep the compiler from forming packed-fp32 instructions
@@ -42,9 +44,12 @@ def build(verbose: bool = False) -> str:
     hipcc = _hipcc()
     objs = [os.path.join(BUILD, s.replace(".hip", ".o")) for s in SOURCES]
     cmds = [[hipcc, *FLAGS, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    for s in HOST_SOURCES:
+        objs.append(os.path.join(BUILD, s.replace(".cpp", ".o")))
+        cmds.append([os.environ.get("CXX", "g++"), *HOST_FLAGS, "-c", os.path.join(CSRC, s), "-o", objs[-1]])
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(cmds))) as ex:
         list(ex.map(_run, cmds))
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", LIB, *objs])
     if verbose:
         print("built", LIB)
     return LIB

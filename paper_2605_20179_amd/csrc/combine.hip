@@ -34,7 +34,27 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
     *reinterpret_cast<float4*>(out + (int64_t)n * d + c) = acc;
 }
 
+// out[tokens[r]][:] += rows[r][:].  grid = (n_rows, ceil(d / 1024)).  `rows` and `tokens` may lie in pinned host
+// memory: each element is read once.
+__global__ __launch_bounds__(256) void add_rows_kernel(const float* __restrict__ rows, const int32_t* __restrict__ tokens,
+                                                       int d, float* __restrict__ out) {
+    const int r = blockIdx.x;
+    const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
+    if (c >= d) return;
+    const float4 v = *reinterpret_cast<const float4*>(rows + (int64_t)r * d + c);
+    float4* o = reinterpret_cast<float4*>(out + (int64_t)tokens[r] * d + c);
+    float4 a = *o;
+    a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+    *o = a;
+}
+
 }  // namespace
+
+hipError_t launch_add_rows(const float* rows, const int32_t* tokens, int n_rows, int d, float* out, hipStream_t stream) {
+    if (n_rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(add_rows_kernel, dim3(n_rows, (d + 1023) / 1024), dim3(256), 0, stream, rows, tokens, d, out);
+    return hipGetLastError();
+}
 
 hipError_t launch_combine(const Shape& s, const Workspace& w, const float* topk_w, int n_tokens, float* out,
                           hipStream_t stream, LaunchEvents ev) {

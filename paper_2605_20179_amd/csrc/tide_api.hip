@@ -10,9 +10,15 @@
 #include <string>
 #include <vector>
 
+#include <chrono>
+
+#include "host_experts.h"
 #include "tide_internal.h"
 
 using namespace tide;
+
+static_assert(kHostGateUpGroup == kGateUpGroup && kHostDownGroup == kDownGroup,
+              "the host experts and the GEMM kernels read the same packed layout");
 
 namespace {
 
@@ -58,6 +64,20 @@ struct tide_ctx {
     size_t prof_used = 0;
     std::vector<std::pair<int, std::pair<hipEvent_t, hipEvent_t>>> prof_spans;   // (kernel id, begin, end)
     int64_t steps_issued = 0;
+    // host-core execution of misses (tide_host_experts / tide_moe_apply_misses_host)
+    HostPool* pool = nullptr;
+    hipStream_t xfer = nullptr;             // device-to-host copies of the miss list and the token states
+    hipEvent_t split_ev = nullptr;          // the last step's miss list is final
+    bool split_valid = false;
+    const void* split_miss = nullptr;       // the buffers that event speaks for
+    const void* split_hidden = nullptr;
+    hipStream_t split_stream = nullptr;
+    tide_miss* h_miss = nullptr;            // pinned: [max_tokens * k]
+    int32_t* h_n_miss = nullptr;            // pinned: [1]
+    uint16_t* h_hidden = nullptr;           // pinned: [max_tokens][d]
+    float* h_rows = nullptr;                // pinned, read by the device in place: [max_tokens][d]
+    int32_t* h_tokens = nullptr;            // pinned, read by the device in place: [max_tokens]
+    float host_ms[3] = {0.f, 0.f, 0.f};     // last call: wait for the list, host compute, whole call
 };
 
 namespace {
@@ -110,7 +130,7 @@ int check_cfg(const tide_config* c) {
     if (c->n_shared < 0 || c->n_shared > 1) return fail(nullptr, TIDE_E_INVAL, "n_shared must be 0 or 1");
     if (c->n_layers < 1) return fail(nullptr, TIDE_E_INVAL, "n_layers must be >= 1");
     if (c->capacity < 1 || c->capacity > c->n_experts) return fail(nullptr, TIDE_E_RANGE, "capacity must be 1..E");
-    if (c->max_tokens < 1 || (int64_t)c->max_tokens * c->top_k > (1 << 26)) return fail(nullptr, TIDE_E_RANGE, "max_tokens out of range");
+    if (c->max_tokens < 1 || c->max_tokens > kMaxTokens) return fail(nullptr, TIDE_E_RANGE, "max_tokens must be 1..%d", kMaxTokens);
     if (c->gating != TIDE_GATING_SOFTMAX && c->gating != TIDE_GATING_SIGMOID) return fail(nullptr, TIDE_E_INVAL, "bad gating");
     if (c->bias_mode < TIDE_BIAS_NONE || c->bias_mode > TIDE_BIAS_SELECT) return fail(nullptr, TIDE_E_INVAL, "bad bias_mode");
     return TIDE_OK;
@@ -176,6 +196,14 @@ int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, 
     if (!split_done)
         TIDE_HIP(ctx, timed(ctx, TIDE_K_DISPATCH, [&](LaunchEvents ev) {
             return launch_dispatch(ctx->shape, L.t, ctx->ws, idx, w, n_tokens, miss_dev, miss_cap, n_miss_dev, stream, ev); }));
+    if (ctx->pool) {
+        // the miss list is final here, long before the step's GEMMs end: the host cores can start on it
+        TIDE_HIP(ctx, hipEventRecord(ctx->split_ev, stream));
+        ctx->split_valid = true;
+        ctx->split_miss = miss_dev;
+        ctx->split_hidden = hidden_dev;
+        ctx->split_stream = stream;
+    }
     if (L.copies_pending) {
         TIDE_HIP(ctx, hipStreamWaitEvent(stream, L.copies_done, 0));
         L.copies_pending = false;
@@ -324,6 +352,11 @@ int tide_destroy(tide_ctx* ctx) {
         if (L.staging) (void)hipFree(L.staging);
         if (L.pend_slot_of) (void)hipFree(L.pend_slot_of);
     }
+    host_pool_destroy(ctx->pool);
+    if (ctx->split_ev) (void)hipEventDestroy(ctx->split_ev);
+    if (ctx->xfer) (void)hipStreamDestroy(ctx->xfer);
+    for (void* q : {(void*)ctx->h_miss, (void*)ctx->h_n_miss, (void*)ctx->h_hidden, (void*)ctx->h_rows, (void*)ctx->h_tokens})
+        if (q) (void)hipHostFree(q);
     for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
     if (ctx->compute_mark) (void)hipEventDestroy(ctx->compute_mark);
     if (ctx->fork_ev) (void)hipEventDestroy(ctx->fork_ev);
@@ -473,6 +506,96 @@ int tide_moe_apply_misses(tide_ctx* ctx, int layer, const void* hidden_dev, int 
     TIDE_HIP(ctx, launch_expert_gemm(1, shape, host_view, ctx->ws, x, max_small, stream));
     if (max_big > 0) TIDE_HIP(ctx, launch_expert_gemm_big(1, shape, host_view, ctx->ws, x, max_big, stream));
     TIDE_HIP(ctx, launch_miss_combine(ctx->shape, ctx->ws, n_tokens, out_dev, stream));
+    return TIDE_OK;
+}
+
+int tide_host_experts(tide_ctx* ctx, int n_threads) {
+    if (!ctx) return TIDE_E_INVAL;
+    if (n_threads < 0 || n_threads > 1024) return fail(ctx, TIDE_E_RANGE, "n_threads must be 0..1024");
+    TIDE_HIP(ctx, hipDeviceSynchronize());
+    host_pool_destroy(ctx->pool);
+    ctx->pool = nullptr;
+    ctx->split_valid = false;
+    if (n_threads == 0) return TIDE_OK;
+    if (!ctx->h_tokens) {
+        const size_t N = ctx->cfg.max_tokens, P = N * ctx->cfg.top_k, d = ctx->cfg.d;
+        if (!ctx->xfer) TIDE_HIP(ctx, hipStreamCreateWithFlags(&ctx->xfer, hipStreamNonBlocking));
+        if (!ctx->split_ev) TIDE_HIP(ctx, hipEventCreateWithFlags(&ctx->split_ev, hipEventDisableTiming));
+        for (void* old : {(void*)ctx->h_miss, (void*)ctx->h_n_miss, (void*)ctx->h_hidden, (void*)ctx->h_rows})
+            if (old) (void)hipHostFree(old);
+        ctx->h_miss = nullptr; ctx->h_n_miss = nullptr; ctx->h_hidden = nullptr; ctx->h_rows = nullptr;
+        void* q = nullptr;
+        if (hipHostMalloc(&q, P * sizeof(tide_miss), hipHostMallocDefault) != hipSuccess) return fail(ctx, TIDE_E_NOMEM, "pinned miss list");
+        ctx->h_miss = static_cast<tide_miss*>(q);
+        if (hipHostMalloc(&q, 64, hipHostMallocDefault) != hipSuccess) return fail(ctx, TIDE_E_NOMEM, "pinned counter");
+        ctx->h_n_miss = static_cast<int32_t*>(q);
+        if (hipHostMalloc(&q, N * d * 2, hipHostMallocDefault) != hipSuccess) return fail(ctx, TIDE_E_NOMEM, "pinned token states");
+        ctx->h_hidden = static_cast<uint16_t*>(q);
+        if (hipHostMalloc(&q, N * d * 4, hipHostMallocDefault) != hipSuccess) return fail(ctx, TIDE_E_NOMEM, "pinned result rows");
+        ctx->h_rows = static_cast<float*>(q);
+        if (hipHostMalloc(&q, N * 4, hipHostMallocDefault) != hipSuccess) return fail(ctx, TIDE_E_NOMEM, "pinned row tokens");
+        ctx->h_tokens = static_cast<int32_t*>(q);
+    }
+    ctx->pool = host_pool_create(n_threads);
+    return TIDE_OK;
+}
+
+int tide_moe_apply_misses_host(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const tide_miss* miss_dev,
+                               int miss_cap, const int32_t* n_miss_dev, float* out_dev, void* hip_stream) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    if (!ctx->pool) return fail(ctx, TIDE_E_STATE, "no host workers: call tide_host_experts first");
+    if (n_tokens < 0 || n_tokens > ctx->cfg.max_tokens) return fail(ctx, TIDE_E_RANGE, "n_tokens %d outside 0..max_tokens=%d", n_tokens, ctx->cfg.max_tokens);
+    if (n_tokens == 0 || miss_cap == 0) return TIDE_OK;
+    if (!hidden_dev || !out_dev || !miss_dev || !n_miss_dev) return fail(ctx, TIDE_E_INVAL, "null argument");
+    if (miss_cap < 0 || (int64_t)miss_cap > (int64_t)ctx->cfg.max_tokens * ctx->cfg.top_k) return fail(ctx, TIDE_E_RANGE, "miss_cap outside 0..max_tokens*k");
+    if (((uintptr_t)hidden_dev & 15) || ((uintptr_t)out_dev & 15)) return fail(ctx, TIDE_E_INVAL, "hidden_dev / out_dev must be 16-byte aligned");
+    Layer& L = ctx->layers[layer];
+    if (!L.host_blobs) return fail(ctx, TIDE_E_STATE, "layer %d: experts not registered", layer);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const auto t0 = std::chrono::steady_clock::now();
+    // The list and the token states come to the host on a stream of their own.  If they are the buffers of
+    // the last step issued on this stream, that stream waits only for the step's split, so the host cores
+    // work while the GPU is still on the step's expert GEMMs; otherwise it waits for all work queued so far.
+    if (!(ctx->split_valid && ctx->split_miss == miss_dev && ctx->split_hidden == hidden_dev && ctx->split_stream == stream))
+        TIDE_HIP(ctx, hipEventRecord(ctx->split_ev, stream));
+    ctx->split_valid = false;
+    TIDE_HIP(ctx, hipStreamWaitEvent(ctx->xfer, ctx->split_ev, 0));
+    const int cap = std::min(miss_cap, n_tokens * ctx->cfg.top_k);
+    TIDE_HIP(ctx, hipMemcpyAsync(ctx->h_n_miss, n_miss_dev, 4, hipMemcpyDeviceToHost, ctx->xfer));
+    TIDE_HIP(ctx, hipMemcpyAsync(ctx->h_miss, miss_dev, (size_t)cap * sizeof(tide_miss), hipMemcpyDeviceToHost, ctx->xfer));
+    TIDE_HIP(ctx, hipMemcpyAsync(ctx->h_hidden, hidden_dev, (size_t)n_tokens * ctx->cfg.d * 2, hipMemcpyDeviceToHost, ctx->xfer));
+    TIDE_HIP(ctx, hipStreamSynchronize(ctx->xfer));
+    const auto t1 = std::chrono::steady_clock::now();
+    const int n = std::max(0, std::min(*ctx->h_n_miss, cap));
+    const int rows = host_apply_misses(ctx->pool, L.host_blobs, L.host_stride, ctx->cfg.d, ctx->cfg.d_ff, ctx->cfg.n_experts,
+                                       ctx->h_hidden, n_tokens, ctx->h_miss, n, ctx->h_rows, ctx->h_tokens);
+    const auto t2 = std::chrono::steady_clock::now();
+    if (rows < 0) return fail(ctx, TIDE_E_INVAL, "the miss list names a token or an expert out of range");
+    // the rows are added by a kernel that reads them in place from pinned host memory, after the step's own combine
+    TIDE_HIP(ctx, launch_add_rows(ctx->h_rows, ctx->h_tokens, rows, ctx->cfg.d, out_dev, stream));
+    const auto t3 = std::chrono::steady_clock::now();
+    auto ms = [](auto a, auto b) { return std::chrono::duration<float, std::milli>(b - a).count(); };
+    ctx->host_ms[0] = ms(t0, t1);
+    ctx->host_ms[1] = ms(t1, t2);
+    ctx->host_ms[2] = ms(t0, t3);
+    return TIDE_OK;
+}
+
+int tide_host_miss_ms(tide_ctx* ctx, float* ms3_host) {
+    if (!ctx) return TIDE_E_INVAL;
+    if (!ms3_host) return fail(ctx, TIDE_E_INVAL, "ms3_host is null");
+    memcpy(ms3_host, ctx->host_ms, sizeof ctx->host_ms);
+    return TIDE_OK;
+}
+
+int tide_host_expert(const tide_config* cfg, const void* blob_host, const uint16_t* x_host, int m, float* y_host) {
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    if (m < 0) return fail(nullptr, TIDE_E_RANGE, "m is negative");
+    if (m == 0) return TIDE_OK;
+    if (!blob_host || !x_host || !y_host) return fail(nullptr, TIDE_E_INVAL, "null argument");
+    host_expert_forward(blob_host, cfg->d, cfg->d_ff, x_host, m, y_host);
     return TIDE_OK;
 }
 

@@ -10,6 +10,7 @@
 namespace tide {
 
 constexpr int kMaxExperts = 512;        // E limit: 8 router scores per lane of a 64-wide wave
+constexpr int kMaxTokens = 65535;       // tokens per step: the per-token kernels put the token on a 16-bit grid axis
 constexpr int kMaxTopK = 16;             // one selection per lane of a 16-lane group
 constexpr int kMaxRouterSplits = 8;      // slices of the hidden dimension the router logits are computed in
 constexpr int kRowsPerTask = 32;        // rows of a small work item
@@ -139,6 +140,8 @@ hipError_t launch_miss_combine(const Shape& s, const Workspace& w, int n_tokens,
 // a9: out[n] = shared row + sum over hit pairs in rank order of w * y[row]
 hipError_t launch_combine(const Shape& s, const Workspace& w, const float* topk_w, int n_tokens, float* out,
                           hipStream_t stream, LaunchEvents ev = {});
+// out[tokens[r]] += rows[r] for n_rows rows of d floats (rows / tokens: device or pinned host memory)
+hipError_t launch_add_rows(const float* rows, const int32_t* tokens, int n_rows, int d, float* out, hipStream_t stream);
 // a11: top-capacity selection + slot plan, tables updated in place
 struct RefreshOut {           // lives in pinned host memory the kernel writes directly
     int32_t n_copies;

@@ -95,6 +95,16 @@ class TideSession:
         tb.tide_moe_apply_misses(self.ctx, layer, hidden_dev, n, self.miss, cap, self.n_miss, self.out,
                                  torch.cuda.current_stream())
 
+    def host_experts(self, n_threads: int) -> None:
+        tb.tide_host_experts(self.ctx, n_threads)
+
+    def apply_misses_host(self, layer: int, hidden_dev: torch.Tensor, miss_cap: Optional[int] = None) -> None:
+        """Adds the last step's misses, evaluated by the host workers, to self.out."""
+        n = hidden_dev.shape[0]
+        cap = n * self.k if miss_cap is None else miss_cap
+        tb.tide_moe_apply_misses_host(self.ctx, layer, hidden_dev, n, self.miss, cap, self.n_miss, self.out,
+                                      torch.cuda.current_stream())
+
     def results(self, n_tokens: int):
         """(out[n,d] fp32, idx[n,k], w[n,k], miss list of (token, expert, weight)) on the host."""
         torch.cuda.synchronize()

@@ -1,0 +1,101 @@
+"""GPU parity of the host-core miss path (Sec. 3.3: tokens whose expert is not resident run on CPU
+experts while the GPU runs the hits): tide_moe_step + tide_moe_apply_misses_host must give the
+oracle's full MoE output, whatever the placement, and must agree with the device miss pass."""
+import numpy as np
+import pytest
+import torch
+
+import tide_inputs as ti
+import test_gpu_parity as tp
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # workload, steps whose outputs are compared, host threads
+    ("cfg0", [0, 1, 2, 3], 3),
+    ("cfg1", [0, 4, 5], 16),
+    # partial gate/up group (12 column blocks) and partial down group (20 stripes); hundreds of misses per expert
+    ((320, 8, 2, 192, 1, 700, 4, ti.GATING_SIGMOID, ti.BIAS_NONE), [0, 2], 4),
+    ((384, 70, 4, 192, 1, 257, 30, ti.GATING_SOFTMAX, ti.BIAS_LOGIT), [0, 3], 1),
+    # more missed experts than 4 x threads: one work item per expert
+    ((128, 300, 6, 128, 1, 33, 40, ti.GATING_SIGMOID, ti.BIAS_NONE), [1], 2),
+]
+
+
+def _workload(spec):
+    if spec == "cfg0":
+        return ti.CONFIGS[0]
+    if spec == "cfg1":
+        return ti.CONFIGS[1]
+    d, E, k, I, sh, N, C, gating, bias_mode = spec
+    return ti.TideWorkload("ragged", d=d, E=E, k=k, I=I, n_shared=sh, N=N, S=5, K=2, C=C, L=1, gating=gating,
+                           bias_mode=bias_mode, seed=177 + N)
+
+
+@pytest.mark.parametrize("spec,out_steps,threads", CASES)
+def test_host_miss_path_completes_the_output(spec, out_steps, threads):
+    from paper_2605_20179_amd import binding as tb
+    wl = _workload(spec)
+    tp.say("host miss path %s, %d threads" % (wl.name if isinstance(spec, str) else spec, threads))
+    log, hidden = tp.oracle_block(wl, 0, out_steps)
+    sess = tp._session(wl)
+    tp.load(sess, wl, 0)
+    with pytest.raises(tb.TideError) as ei:                      # no workers yet
+        sess.apply_misses_host(0, sess.to_device_bf16(hidden[0]))
+    assert ei.value.code == tb.TIDE_E_STATE
+    sess.host_experts(threads)
+    worst = 0.0
+    for t, rec in enumerate(log):
+        if t > 0 and t % wl.K == 0:
+            sess.refresh(0)
+        x = sess.to_device_bf16(hidden[t])
+        idx_d = torch.from_numpy(rec["idx"]).to(sess.device)
+        w_d = torch.from_numpy(rec["w"].astype(np.float32)).to(sess.device)
+        torch.cuda.synchronize()
+        sess.step_routed(0, x, idx_d, w_d)
+        if t not in out_steps:
+            continue
+        # no synchronisation in between: the host workers start from the step's split while the GPU is still
+        # in the step's GEMMs, and the rows are added after the step's own combine
+        sess.apply_misses_host(0, x)
+        torch.cuda.synchronize()
+        full = sess.out[:wl.N].cpu().numpy()
+        worst = max(worst, tp.check_out(full, rec["y_full"]))
+        assert np.array_equal(sess.stats(0), rec["hits"].astype(np.int32)), "the miss path must not count"
+        assert np.array_equal(sess.table(0), rec["slot_of"]), "the miss path must not move experts"
+        # the same list handed over in other buffers (no shortcut through the step's split event), added to zeros:
+        # the misses' own sum = full - resident part
+        miss2, n2, zeros = sess.miss.clone(), sess.n_miss.clone(), torch.zeros_like(sess.out)
+        tb.tide_moe_apply_misses_host(sess.ctx, 0, x.clone(), wl.N, miss2, wl.N * wl.k, n2, zeros, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        want = rec["y_full"] - rec["y_res"]
+        rms = float(np.sqrt(np.mean(rec["y_full"] ** 2)))
+        assert np.abs(zeros[:wl.N].cpu().numpy() - want).max() <= tp.OUT_TOL * rms
+        ms = tb.tide_host_miss_ms(sess.ctx)
+        assert ms[2] >= ms[1] >= 0.0
+    tp.say("host miss path worst err %.2e x RMS" % worst)
+    sess.host_experts(0)                                         # workers stopped: the call is refused again
+    with pytest.raises(tb.TideError):
+        sess.apply_misses_host(0, sess.to_device_bf16(hidden[0]))
+    sess.close()
+
+
+def test_host_miss_path_rejects_a_bad_list():
+    from paper_2605_20179_amd import binding as tb
+    wl = ti.CONFIGS[0]
+    sess = tp._session(wl)
+    tp.load(sess, wl, 0)
+    sess.host_experts(2)
+    x = sess.to_device_bf16(next(iter(ti.hidden_stream(wl, 0))))
+    out = torch.zeros_like(sess.out)
+    for token, expert in ((wl.N, 0), (-1, 0), (0, wl.E), (0, -1)):
+        bad = np.zeros(wl.N * wl.k, dtype=tb.MISS_DTYPE)
+        bad[0] = (token, expert, 1.0)
+        miss = torch.from_numpy(bad.view(np.int32).reshape(-1, 3)).to(sess.device)
+        n = torch.ones(1, dtype=torch.int32, device=sess.device)
+        with pytest.raises(tb.TideError) as ei:
+            tb.tide_moe_apply_misses_host(sess.ctx, 0, x, wl.N, miss, wl.N * wl.k, n, out, torch.cuda.current_stream())
+        assert ei.value.code == tb.TIDE_E_INVAL
+    torch.cuda.synchronize()
+    assert float(out.abs().max()) == 0.0
+    sess.close()

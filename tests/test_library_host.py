@@ -73,6 +73,28 @@ def test_pack_layout(tb):
     assert np.array_equal(np.sort(b), np.sort(np.concatenate([wg.ravel(), wu.ravel(), wd.ravel()])))
 
 
+@pytest.mark.parametrize("d,d_ff,m", [(256, 128, 1), (320, 192, 3), (320, 192, 6), (512, 256, 9)])
+def test_host_expert_matches_the_oracle(tb, d, d_ff, m):
+    """The host cores' expert path (Sec. 3.3: misses run on CPU experts) reads the packed blob in place;
+    checked here against the oracle's e(x), full and ragged stripe groups, one to three token blocks."""
+    import sys
+    sys.path.insert(0, ROOT)
+    from oracle import tide_oracle as orc
+    cfg = tb.make_config(d, 8, 2, d_ff, 0, 1, 4, 16, 0, 0)
+    rng = np.random.default_rng(d + m)
+    def bits(shape, scale):          # any bf16 bit patterns will do: fp32 draws cut to their upper halves
+        return (np.ascontiguousarray(rng.normal(0, scale, size=shape), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    wg, wu, wd, x = bits((d_ff, d), 0.05), bits((d_ff, d), 0.05), bits((d, d_ff), 0.05), bits((m, d), 1.0)
+    blob = np.zeros(tb.tide_expert_blob_bytes(cfg), dtype=np.uint8)
+    tb.tide_pack_expert(cfg, wg, wu, wd, blob)
+    got = tb.tide_host_expert(cfg, blob, x)
+    W = [orc.bf16_to_f64(w) for w in (wg, wu, wd)]
+    want = np.stack([orc.expert_ffn(orc.bf16_to_f64(x[t]), *W) for t in range(m)])
+    rms = float(np.sqrt(np.mean(want ** 2)))
+    assert rms > 0
+    assert np.max(np.abs(got - want)) <= 2e-3 * rms, np.max(np.abs(got - want)) / rms
+
+
 def test_config_validation_and_no_device(tb):
     ok = dict(d=256, n_experts=16, top_k=2, d_ff=128, n_shared=0, n_layers=1, capacity=8, max_tokens=8, gating=0, bias_mode=0)
     blob = np.zeros(3 * 256 * 128 * 2, dtype=np.uint8)
