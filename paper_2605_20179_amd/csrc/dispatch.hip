@@ -341,7 +341,39 @@ __global__ __launch_bounds__(256) void miss_combine_kernel(const float* __restri
     if (any) *reinterpret_cast<float4*>(out + (int64_t)n * d + c) = acc;
 }
 
+// Hands a step's miss list to the host: the first min(*n_miss, cap) entries, their number, and the token states
+// (bf16 rows of d elements) of the tokens that appear in them, written straight into pinned host memory.  Four list
+// entries per block; a token's row is copied by the block that holds the first entry of the token's run (the list is
+// ordered by token; a row copied twice because of an unordered list is the same row).
+__global__ __launch_bounds__(256) void miss_export_kernel(const tide_miss* __restrict__ miss, int cap,
+                                                          const int32_t* __restrict__ n_miss,
+                                                          const uint16_t* __restrict__ x, int n_tokens, int d,
+                                                          tide_miss* __restrict__ miss_host, int32_t* __restrict__ n_host,
+                                                          uint16_t* __restrict__ x_host) {
+    const int n = min(max(*n_miss, 0), cap);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *n_host = n;
+    const int i0 = blockIdx.x * 4;
+    for (int j = 0; j < 4; ++j) {
+        const int i = i0 + j;
+        if (i >= n) return;
+        const tide_miss m = miss[i];
+        if (threadIdx.x == 0) miss_host[i] = m;
+        if (m.token < 0 || m.token >= n_tokens) continue;                 // the host refuses such a list
+        if (i > 0 && miss[i - 1].token == m.token) continue;
+        const uint4* src = reinterpret_cast<const uint4*>(x + (int64_t)m.token * d);
+        uint4* dst = reinterpret_cast<uint4*>(x_host + (int64_t)m.token * d);
+        for (int c = threadIdx.x; c < d / 8; c += 256) dst[c] = src[c];
+    }
+}
+
 }  // namespace
+
+hipError_t launch_miss_export(const tide_miss* miss, int cap, const int32_t* n_miss, const uint16_t* x, int n_tokens,
+                              int d, tide_miss* miss_host, int32_t* n_host, uint16_t* x_host, hipStream_t stream) {
+    hipLaunchKernelGGL(miss_export_kernel, dim3(cap > 0 ? (cap + 3) / 4 : 1), dim3(256), 0, stream, miss, cap, n_miss, x,
+                       n_tokens, d, miss_host, n_host, x_host);
+    return hipGetLastError();
+}
 
 hipError_t launch_miss_group(const Shape& s, const Workspace& w, const tide_miss* miss, int miss_cap,
                              const int32_t* n_miss, int max_big, hipStream_t stream) {

@@ -7,7 +7,12 @@
 // the 8 matching elements of a token row and added into an 8-wide accumulator per (token, weight
 // row); the accumulators of one stripe group live in the core's L1 while the group's region of the
 // blob is streamed front to back once, and are summed across their 8 lanes at the end.
+// On cores with AVX-512 BF16 the same walk uses the bf16 dot-product instruction instead: a 64-byte line of
+// a tile is four rows x 8 K elements, one instruction multiplies it with a token's 8 bf16 elements (no
+// conversion of either operand) and adds the products pairwise into 16 fp32 lanes, four per row.
 #include "host_experts.h"
+
+#include <immintrin.h>
 
 #include <algorithm>
 #include <atomic>
@@ -62,10 +67,11 @@ struct PartArgs {
     int d, d_ff;
     int g0, g1;               // gate/up groups [g0, g1) of the expert: columns g*128.. of the intermediate
     int m;                    // tokens
-    const float* const* x;    // m pointers to fp32 token rows [d]
+    const float* const* x;    // m pointers to fp32 token rows [d] (vector path)
+    const uint16_t* const* xb;  // m pointers to bf16 token rows [d] (bf16 dot-product path)
     float* y;                 // [m][d], overwritten: the part of e(x) that comes from those columns
-    f8* acc;                  // [kTokBlock][kAccRows] scratch, 32-byte aligned
-    float* h;                 // [kTokBlock][128] scratch
+    f8* acc;                  // [kTokBlock][kAccRows] scratch, 64-byte aligned
+    float* h;                 // [kTokBlock][128] scratch (the bf16 path keeps bf16 bits in its first half)
 };
 
 // acc[t][j*16 + r] += tile piece (q, r) * operand piece q of token t, over `ntiles` consecutive tiles
@@ -85,12 +91,12 @@ TIDE_INLINE void tiles_fma(const uint16_t* tiles, int ntiles, const f8 (&xq)[4][
     }
 }
 
+// one gate/up group g (128 columns of the intermediate) for TB tokens: y[t0..][:] += their part of e(x)
 template <int TB>
-TIDE_INLINE void part_block(const PartArgs& a, int t0) {
+TIDE_INLINE void part_block(const PartArgs& a, int g, int t0) {
     const int d = a.d, I = a.d_ff, kcd = d / 32, kci = I / 32, blocks = I / 16, stripes = d / 16;
     const uint16_t* down = a.blob + 2ll * d * I;
-    for (int t = 0; t < TB; ++t) memset(a.y + (int64_t)(t0 + t) * d, 0, sizeof(float) * d);
-    for (int g = a.g0; g < a.g1; ++g) {
+    {
         const int ng = std::min(kHostGateUpGroup, blocks - g * kHostGateUpGroup);
         const int rows = 2 * ng * 16;
         for (int i = 0; i < TB * rows; ++i) a.acc[i] = f8{0, 0, 0, 0, 0, 0, 0, 0};
@@ -130,23 +136,138 @@ TIDE_INLINE void part_block(const PartArgs& a, int t0) {
     }
 }
 
+// Group by group, every token block inside: a group's region of the blob (gate/up stripes and the matching K
+// chunks of the down stripes) comes from memory once and from the core's caches for the later token blocks.
 TIDE_INLINE void part_body(const PartArgs& a) {
-    for (int t0 = 0; t0 < a.m; t0 += kTokBlock) {
-        switch (std::min(kTokBlock, a.m - t0)) {
-            case 1: part_block<1>(a, t0); break;
-            case 2: part_block<2>(a, t0); break;
-            case 3: part_block<3>(a, t0); break;
-            default: part_block<4>(a, t0); break;
+    memset(a.y, 0, sizeof(float) * (size_t)a.m * a.d);
+    for (int g = a.g0; g < a.g1; ++g)
+        for (int t0 = 0; t0 < a.m; t0 += kTokBlock) {
+            switch (std::min(kTokBlock, a.m - t0)) {
+                case 1: part_block<1>(a, g, t0); break;
+                case 2: part_block<2>(a, g, t0); break;
+                case 3: part_block<3>(a, g, t0); break;
+                default: part_block<4>(a, g, t0); break;
+            }
         }
-    }
 }
 
 __attribute__((target("avx2,fma"))) void part_avx2(const PartArgs& a) { part_body(a); }
 void part_generic(const PartArgs& a) { part_body(a); }
 
+// ---- AVX-512 BF16 ------------------------------------------------------------------------------------
+#define TIDE_BF16 __attribute__((target("avx512f,avx512bw,avx512vl,avx512bf16")))
+#define TIDE_BF16_INLINE TIDE_BF16 inline __attribute__((always_inline))
+
+TIDE_BF16_INLINE uint16_t bf16_bits(float v) {
+    uint32_t u;
+    memcpy(&u, &v, 4);
+    if ((u & 0x7f800000u) != 0x7f800000u) u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// acc[t][j*4 + rr] (16 lanes: rows rr*4 .. +3 of tile j, four partial sums each) += line (q, rr) of the tile
+// dotted pairwise with the 8 bf16 operand elements of token t at K offset q*8
+template <int TB>
+TIDE_BF16_INLINE void tiles_dp(const uint16_t* tiles, int ntiles, const uint16_t* const (&xk)[kTokBlock], __m512* acc,
+                               int acc_stride) {
+    for (int j = 0; j < ntiles; ++j) {
+        const char* tp = reinterpret_cast<const char*>(tiles + j * 512);
+        __m512 a[TB][4];
+        for (int t = 0; t < TB; ++t)
+            for (int rr = 0; rr < 4; ++rr) a[t][rr] = acc[t * acc_stride + j * 4 + rr];
+        for (int q = 0; q < 4; ++q) {
+            __m512bh xq[TB];
+            for (int t = 0; t < TB; ++t)
+                xq[t] = (__m512bh)_mm512_broadcast_i32x4(_mm_loadu_si128(reinterpret_cast<const __m128i*>(xk[t] + q * 8)));
+            for (int rr = 0; rr < 4; ++rr) {
+                const __m512bh w = (__m512bh)_mm512_loadu_si512(tp + (q * 4 + rr) * 64);
+                for (int t = 0; t < TB; ++t) a[t][rr] = _mm512_dpbf16_ps(a[t][rr], w, xq[t]);
+            }
+        }
+        for (int t = 0; t < TB; ++t)
+            for (int rr = 0; rr < 4; ++rr) acc[t * acc_stride + j * 4 + rr] = a[t][rr];
+    }
+}
+
+// sum of the four partial lanes of row c (lanes 4*(c%4) .. +3 of accumulator c/4)
+TIDE_BF16_INLINE float row_sum(const float* acc_f, int c) {
+    const float* p = acc_f + (c >> 2) * 16 + (c & 3) * 4;
+    return (p[0] + p[2]) + (p[1] + p[3]);
+}
+
+template <int TB>
+TIDE_BF16_INLINE void part_block_bf16(const PartArgs& a, int g, int t0) {
+    const int d = a.d, I = a.d_ff, kcd = d / 32, kci = I / 32, blocks = I / 16, stripes = d / 16;
+    const uint16_t* down = a.blob + 2ll * d * I;
+    __m512* acc = reinterpret_cast<__m512*>(a.acc);
+    const float* acc_f = reinterpret_cast<const float*>(a.acc);
+    uint16_t* h16 = reinterpret_cast<uint16_t*>(a.h);                 // [TB][128] bf16 bits
+    {
+        const int ng = std::min(kHostGateUpGroup, blocks - g * kHostGateUpGroup);
+        const int rows = 2 * ng * 16, stride = rows / 4;
+        for (int i = 0; i < TB * stride; ++i) acc[i] = _mm512_setzero_ps();
+        const uint16_t* base = a.blob + (int64_t)g * 2 * kHostGateUpGroup * kcd * 512;
+        for (int kc = 0; kc < kcd; ++kc) {
+            const uint16_t* xk[kTokBlock];
+            for (int t = 0; t < TB; ++t) xk[t] = a.xb[t0 + t] + kc * 32;
+            tiles_dp<TB>(base + (int64_t)kc * 2 * ng * 512, 2 * ng, xk, acc, stride);
+        }
+        const int ncol = ng * 16;
+        for (int t = 0; t < TB; ++t)
+            for (int c = 0; c < ncol; ++c) {
+                const float gate = row_sum(acc_f + t * rows * 4, c), up = row_sum(acc_f + t * rows * 4, ncol + c);
+                h16[t * 128 + c] = bf16_bits(gate / (1.0f + expf(-gate)) * up);
+            }
+        const int nkc = ncol / 32;
+        for (int G = 0; G * kHostDownGroup < stripes; ++G) {
+            const int ngd = std::min(kHostDownGroup, stripes - G * kHostDownGroup);
+            const int drows = ngd * 16, dstride = drows / 4;
+            for (int i = 0; i < TB * dstride; ++i) acc[i] = _mm512_setzero_ps();
+            const uint16_t* gbase = down + (int64_t)G * kHostDownGroup * kci * 512;
+            for (int kk = 0; kk < nkc; ++kk) {
+                const int kc = g * (kHostGateUpGroup / 2) + kk;
+                const uint16_t* hk[kTokBlock];
+                for (int t = 0; t < TB; ++t) hk[t] = h16 + t * 128 + kk * 32;
+                tiles_dp<TB>(gbase + (int64_t)kc * ngd * 512, ngd, hk, acc, dstride);
+            }
+            for (int t = 0; t < TB; ++t) {
+                float* yr = a.y + (int64_t)(t0 + t) * d + G * kHostDownGroup * 16;
+                for (int c = 0; c < drows; ++c) yr[c] += row_sum(acc_f + t * drows * 4, c);
+            }
+        }
+    }
+}
+
+TIDE_BF16 void part_bf16(const PartArgs& a) {
+    memset(a.y, 0, sizeof(float) * (size_t)a.m * a.d);
+    for (int g = a.g0; g < a.g1; ++g)
+        for (int t0 = 0; t0 < a.m; t0 += kTokBlock) {
+            switch (std::min(kTokBlock, a.m - t0)) {
+                case 1: part_block_bf16<1>(a, g, t0); break;
+                case 2: part_block_bf16<2>(a, g, t0); break;
+                case 3: part_block_bf16<3>(a, g, t0); break;
+                default: part_block_bf16<4>(a, g, t0); break;
+            }
+        }
+}
+
+enum Isa { kGeneric = 0, kAvx2 = 1, kAvx512Bf16 = 2 };
+Isa detect_isa() {
+    const char* force = getenv("TIDE_HOST_ISA");              // "generic" | "avx2": for checking the other paths
+    __builtin_cpu_init();
+    const bool avx2 = __builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma");
+    const bool bf16 = __builtin_cpu_supports("avx512f") && __builtin_cpu_supports("avx512bw") &&
+                      __builtin_cpu_supports("avx512vl") && __builtin_cpu_supports("avx512bf16");
+    if (force && !strcmp(force, "generic")) return kGeneric;
+    if (force && !strcmp(force, "avx2")) return avx2 ? kAvx2 : kGeneric;
+    return bf16 ? kAvx512Bf16 : avx2 ? kAvx2 : kGeneric;
+}
+
 void run_part(const PartArgs& a) {
-    static const bool avx2 = __builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma");
-    if (avx2) part_avx2(a); else part_generic(a);
+    static const Isa isa = detect_isa();
+    if (isa == kAvx512Bf16) part_bf16(a);
+    else if (isa == kAvx2) part_avx2(a);
+    else part_generic(a);
 }
 
 struct Scratch {
@@ -185,6 +306,7 @@ struct HostPool {
     // buffers reused from call to call
     std::vector<float> xf, ypart;
     std::vector<const float*> xptr;
+    std::vector<const uint16_t*> xbptr;
     std::vector<int32_t> by_expert, pos_of, exp_off, tok_off, by_token, tok_row;
 
     explicit HostPool(int threads) : n(threads), scratch(threads) {}
@@ -251,12 +373,14 @@ void host_expert_forward(const void* blob, int d, int d_ff, const uint16_t* x, i
     Scratch s;
     std::vector<float> xf((size_t)m * d);
     std::vector<const float*> xp(m);
+    std::vector<const uint16_t*> xbp(m);
     for (int t = 0; t < m; ++t) {
         bf16_row_to_f32(x + (int64_t)t * d, xf.data() + (int64_t)t * d, d);
         xp[t] = xf.data() + (int64_t)t * d;
+        xbp[t] = x + (int64_t)t * d;
     }
     const int groups = (d_ff / 16 + kHostGateUpGroup - 1) / kHostGateUpGroup;
-    PartArgs a{static_cast<const uint16_t*>(blob), d, d_ff, 0, groups, m, xp.data(), y, s.acc, s.h};
+    PartArgs a{static_cast<const uint16_t*>(blob), d, d_ff, 0, groups, m, xp.data(), xbp.data(), y, s.acc, s.h};
     run_part(a);
 }
 
@@ -299,7 +423,12 @@ int host_apply_misses(HostPool* p, const uint8_t* blobs, uint64_t stride, int d,
     float* xf = p->xf.data();
     p->run(n_rows, [&](int r, int) { bf16_row_to_f32(x + (int64_t)tokens_out[r] * d, xf + (int64_t)r * d, d); });
     p->xptr.resize(n);
-    for (int j = 0; j < n; ++j) p->xptr[j] = xf + (int64_t)p->tok_row[miss[p->by_expert[j]].token] * d;
+    p->xbptr.resize(n);
+    for (int j = 0; j < n; ++j) {
+        const int tok = miss[p->by_expert[j]].token;
+        p->xptr[j] = xf + (int64_t)p->tok_row[tok] * d;
+        p->xbptr[j] = x + (int64_t)tok * d;
+    }
 
     // work items: (expert with misses, part of its intermediate columns).  With few missed experts each is
     // cut into its gate/up groups so that every core has work; otherwise one item per expert.
@@ -318,7 +447,7 @@ int host_apply_misses(HostPool* p, const uint8_t* blobs, uint64_t stride, int d,
         const int e = experts[item / parts], part = item % parts;
         const int j0 = p->exp_off[e], m = p->exp_off[e + 1] - j0;
         PartArgs a{reinterpret_cast<const uint16_t*>(blobs + (uint64_t)e * stride), d, d_ff, part * per_part,
-                   std::min(groups, (part + 1) * per_part), m, p->xptr.data() + j0,
+                   std::min(groups, (part + 1) * per_part), m, p->xptr.data() + j0, p->xbptr.data() + j0,
                    ypart + ((int64_t)part * n + j0) * d, p->scratch[worker].acc, p->scratch[worker].h};
         run_part(a);
     });

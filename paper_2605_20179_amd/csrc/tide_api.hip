@@ -562,9 +562,8 @@ int tide_moe_apply_misses_host(tide_ctx* ctx, int layer, const void* hidden_dev,
     ctx->split_valid = false;
     TIDE_HIP(ctx, hipStreamWaitEvent(ctx->xfer, ctx->split_ev, 0));
     const int cap = std::min(miss_cap, n_tokens * ctx->cfg.top_k);
-    TIDE_HIP(ctx, hipMemcpyAsync(ctx->h_n_miss, n_miss_dev, 4, hipMemcpyDeviceToHost, ctx->xfer));
-    TIDE_HIP(ctx, hipMemcpyAsync(ctx->h_miss, miss_dev, (size_t)cap * sizeof(tide_miss), hipMemcpyDeviceToHost, ctx->xfer));
-    TIDE_HIP(ctx, hipMemcpyAsync(ctx->h_hidden, hidden_dev, (size_t)n_tokens * ctx->cfg.d * 2, hipMemcpyDeviceToHost, ctx->xfer));
+    TIDE_HIP(ctx, launch_miss_export(miss_dev, cap, n_miss_dev, static_cast<const uint16_t*>(hidden_dev), n_tokens, ctx->cfg.d,
+                                     ctx->h_miss, ctx->h_n_miss, ctx->h_hidden, ctx->xfer));
     TIDE_HIP(ctx, hipStreamSynchronize(ctx->xfer));
     const auto t1 = std::chrono::steady_clock::now();
     const int n = std::max(0, std::min(*ctx->h_n_miss, cap));

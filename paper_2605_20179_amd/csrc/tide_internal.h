@@ -140,6 +140,9 @@ hipError_t launch_miss_combine(const Shape& s, const Workspace& w, int n_tokens,
 // a9: out[n] = shared row + sum over hit pairs in rank order of w * y[row]
 hipError_t launch_combine(const Shape& s, const Workspace& w, const float* topk_w, int n_tokens, float* out,
                           hipStream_t stream, LaunchEvents ev = {});
+// the first min(*n_miss, cap) list entries, their number and the token states they name -> pinned host memory
+hipError_t launch_miss_export(const tide_miss* miss, int cap, const int32_t* n_miss, const uint16_t* x, int n_tokens,
+                              int d, tide_miss* miss_host, int32_t* n_host, uint16_t* x_host, hipStream_t stream);
 // out[tokens[r]] += rows[r] for n_rows rows of d floats (rows / tokens: device or pinned host memory)
 hipError_t launch_add_rows(const float* rows, const int32_t* tokens, int n_rows, int d, float* out, hipStream_t stream);
 // a11: top-capacity selection + slot plan, tables updated in place

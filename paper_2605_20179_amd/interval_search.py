@@ -5,7 +5,9 @@ measurements on this machine:
 
 For every candidate interval the block of the chosen workload is run on the GPU with a refresh every
 tau steps; the run logs the experts migrated per refresh, the miss rate, the time of the refresh
-copies (host link) and the time of the miss pass (the library's stand-in for the paper's CPU experts).
+copies (host link) and the time of the miss path: --miss-path host = the paper's CPU experts (host worker
+threads, tide_moe_apply_misses_host), --miss-path device = the GPU reading the missed experts in place
+across the host link (tide_moe_apply_misses).
 From these the constants of the model are taken -- C_io = seconds per migrated expert, C_cpu = seconds
 per unit of f, f(tau) = measured miss rate made monotone and interpolated, d = Eq. 4 on the logged
 activation vectors and, beside it, the d that Eq. 5 needs to reproduce each measured migration count --
@@ -21,7 +23,7 @@ import time
 import numpy as np
 
 
-def run_block(sess, tb, torch, wl, hidden, tau):
+def run_block(sess, tb, torch, wl, hidden, tau, miss_path):
     sess_layer = 0
     import tide_inputs as ti
     tb.tide_set_resident(sess.ctx, sess_layer, ti.initial_resident(wl))
@@ -36,11 +38,16 @@ def run_block(sess, tb, torch, wl, hidden, tau):
             if plan:
                 copy_ms += tb.tide_refresh_copy_ms(sess.ctx, sess_layer)
         sess.step(sess_layer, h, want_topk=False)
-        ev0.record()
-        sess.apply_misses(sess_layer, h)
-        ev1.record()
-        torch.cuda.synchronize()
-        miss_ms += ev0.elapsed_time(ev1)
+        if miss_path == "host":
+            sess.apply_misses_host(sess_layer, h)             # blocks this thread while the workers run
+            torch.cuda.synchronize()
+            miss_ms += tb.tide_host_miss_ms(sess.ctx)[2]
+        else:
+            ev0.record()
+            sess.apply_misses(sess_layer, h)
+            ev1.record()
+            torch.cuda.synchronize()
+            miss_ms += ev0.elapsed_time(ev1)
         misses += int(sess.n_miss.item())
     return dict(tau=tau, refreshes=refreshes, migrated=migrated, copy_ms=copy_ms, misses=misses, miss_ms=miss_ms)
 
@@ -50,6 +57,8 @@ def main():
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--taus", default="1,2,4,8,16")
+    ap.add_argument("--miss-path", choices=("device", "host"), default="host")
+    ap.add_argument("--host-threads", type=int, default=16)
     args = ap.parse_args()
     import torch
     import tide_inputs as ti
@@ -81,7 +90,9 @@ def main():
     sim_h, d_steps = sim.cpu().numpy(), drift.cpu().numpy()
     d_eq4 = float(d_steps[1:].mean())
 
-    rows = [run_block(sess, tb, torch, wl, hidden, tau) for tau in taus]
+    if args.miss_path == "host":
+        sess.host_experts(args.host_threads)
+    rows = [run_block(sess, tb, torch, wl, hidden, tau, args.miss_path) for tau in taus]
     for r in rows:
         r["miss_rate"] = r["misses"] / float(T * pairs)
         r["d_fit"] = tb.tide_fit_drift(float(r["migrated"]), B, T, r["tau"])
@@ -100,7 +111,7 @@ def main():
     for r in rows:
         r["model_io_ms"] = io[r["tau"] - 1] * 1e3
         r["model_cpu_ms"] = cpu[r["tau"] - 1] * 1e3
-    out = dict(workload=wl.name, steps=T, budget=B, adjacent_similarity=float(np.mean([sim_h[t, t + 1] for t in range(T - 1)])),
+    out = dict(workload=wl.name, miss_path=args.miss_path, steps=T, budget=B, adjacent_similarity=float(np.mean([sim_h[t, t + 1] for t in range(T - 1)])),
                similarity_5_apart=float(np.mean([sim_h[t, t + 5] for t in range(T - 5)])),
                distinct_experts=[int(uniq.min().item()), int(uniq.max().item())], drift_eq4=d_eq4, drift_model=d_model,
                c_io_s_per_expert=c_io, c_cpu=c_cpu, optimal_tau=tau_opt, optimal_cost_ms=cost * 1e3, sweep=rows)
