@@ -184,7 +184,7 @@ def main():
                     help="--stack: at a refresh step, refresh each layer right before its own step, or all layers first so "
                          "that later layers' copies overlap earlier layers' compute")
     ap.add_argument("--capacity", type=int, default=0, help="cache slots (0 = the workload's own budget); 256 = every expert resident")
-    ap.add_argument("--miss-mode", choices=("none", "device", "host", "both"), default="none",
+    ap.add_argument("--miss-mode", choices=("none", "device", "host", "both"), default="both",
                     help="detail only: also time the lossless layer (step + evaluation of its misses): 'device' = the GPU reads the "
                          "missed experts in place from pinned host memory; 'host' = host worker threads evaluate them while the GPU runs the hits")
     ap.add_argument("--host-threads", type=int, default=16)
