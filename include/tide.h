@@ -168,17 +168,20 @@ int tide_moe_apply_misses(tide_ctx* ctx, int layer, const void* hidden_dev, int 
  * tide_host_experts starts n_threads worker threads (the calling thread of a later
  * tide_moe_apply_misses_host counts as one of them) and allocates the pinned exchange buffers
  * (miss list, token states, result rows, sized by max_tokens); n_threads == 0 stops the workers.
- * Synchronises the device.  While workers exist, every step records one more event. */
+ * Synchronises the device.  While workers exist, every step also queues, on its second stream and
+ * right behind its hit/miss split, a small kernel that writes the miss list and the token states it
+ * names to those pinned buffers. */
 int tide_host_experts(tide_ctx* ctx, int n_threads);
 
 /* Same contract and arguments as tide_moe_apply_misses, but the listed misses are evaluated by the
  * host workers from the registered host blobs (fp32 arithmetic on the bf16 weights and token
  * states), and the per-token sums are added to out_dev by a kernel queued on hip_stream.
  * The call blocks the calling thread until the host work is done; it does NOT wait for the GPU
- * work queued on hip_stream: when hidden_dev / miss_dev / hip_stream are those of the last step
- * issued, the list and the token states are fetched as soon as that step's hit/miss split has run,
- * so the host cores work while the GPU runs the step's expert GEMMs (layer time = the longer of
- * the two, Sec. 3.3); with other buffers the fetch waits for everything queued on hip_stream.
+ * work queued on hip_stream: when hidden_dev / n_tokens / miss_dev / miss_cap / hip_stream are those
+ * of the last step issued (and the buffers are untouched since), the list and the token states are
+ * the ones that step handed over right after its hit/miss split, so the host cores work while the
+ * GPU runs the step's expert GEMMs (layer time = the longer of the two, Sec. 3.3); with other
+ * buffers the hand-over is queued now and waits for everything queued on hip_stream.
  * Errors: TIDE_E_STATE without workers or registered experts; TIDE_E_INVAL for a list entry
  * that names a token or an expert out of range (nothing is added then). */
 int tide_moe_apply_misses_host(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens,

@@ -66,12 +66,12 @@ struct tide_ctx {
     int64_t steps_issued = 0;
     // host-core execution of misses (tide_host_experts / tide_moe_apply_misses_host)
     HostPool* pool = nullptr;
-    hipStream_t xfer = nullptr;             // device-to-host copies of the miss list and the token states
-    hipEvent_t split_ev = nullptr;          // the last step's miss list is final
-    bool split_valid = false;
-    const void* split_miss = nullptr;       // the buffers that event speaks for
-    const void* split_hidden = nullptr;
-    hipStream_t split_stream = nullptr;
+    hipEvent_t listed_ev = nullptr;         // the last exported miss list and its token states are in host memory
+    bool listed_valid = false;
+    const void* listed_miss = nullptr;      // the buffers, the size and the stream of the step that export speaks for
+    const void* listed_hidden = nullptr;
+    hipStream_t listed_stream = nullptr;
+    int listed_cap = 0, listed_tokens = 0;
     tide_miss* h_miss = nullptr;            // pinned: [max_tokens * k]
     int32_t* h_n_miss = nullptr;            // pinned: [1]
     uint16_t* h_hidden = nullptr;           // pinned: [max_tokens][d]
@@ -196,26 +196,36 @@ int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, 
     if (!split_done)
         TIDE_HIP(ctx, timed(ctx, TIDE_K_DISPATCH, [&](LaunchEvents ev) {
             return launch_dispatch(ctx->shape, L.t, ctx->ws, idx, w, n_tokens, miss_dev, miss_cap, n_miss_dev, stream, ev); }));
-    if (ctx->pool) {
-        // the miss list is final here, long before the step's GEMMs end: the host cores can start on it
-        TIDE_HIP(ctx, hipEventRecord(ctx->split_ev, stream));
-        ctx->split_valid = true;
-        ctx->split_miss = miss_dev;
-        ctx->split_hidden = hidden_dev;
-        ctx->split_stream = stream;
-    }
-    if (L.copies_pending) {
-        TIDE_HIP(ctx, hipStreamWaitEvent(stream, L.copies_done, 0));
-        L.copies_pending = false;
-    }
     const int max_tasks = max_small_tasks_for(ctx->shape, n_tokens);
     const int max_big = max_big_tasks_for(ctx->shape, n_tokens);
     const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
-    // Small and large work items touch disjoint rows: the large ones run on a second stream so that
-    // the two kinds of kernels overlap on the chip (fork after the split, join before the combine).
-    if (max_big > 0) {
+    // The second stream forks here, after the split.  With host workers its first kernel hands the miss list
+    // and the token states it names to pinned host memory: the list is final long before the step's GEMMs
+    // end, and the host cores can start on it at once.
+    if (ctx->pool || max_big > 0) {
         TIDE_HIP(ctx, hipEventRecord(ctx->fork_ev, stream));
         TIDE_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_ev, 0));
+    }
+    if (ctx->pool) {
+        const int cap = std::min(miss_cap, n_tokens * ctx->cfg.top_k);
+        TIDE_HIP(ctx, launch_miss_export(miss_dev, cap, n_miss_dev, x, n_tokens, ctx->cfg.d, ctx->h_miss, ctx->h_n_miss,
+                                         ctx->h_hidden, ctx->aux));
+        TIDE_HIP(ctx, hipEventRecord(ctx->listed_ev, ctx->aux));
+        ctx->listed_valid = true;
+        ctx->listed_miss = miss_dev;
+        ctx->listed_hidden = hidden_dev;
+        ctx->listed_stream = stream;
+        ctx->listed_cap = cap;
+        ctx->listed_tokens = n_tokens;
+    }
+    if (L.copies_pending) {                  // the GEMMs of both streams wait for a refresh's copies; nothing before them does
+        TIDE_HIP(ctx, hipStreamWaitEvent(stream, L.copies_done, 0));
+        if (max_big > 0) TIDE_HIP(ctx, hipStreamWaitEvent(ctx->aux, L.copies_done, 0));
+        L.copies_pending = false;
+    }
+    // Small and large work items touch disjoint rows: the large ones run on the second stream so that
+    // the two kinds of kernels overlap on the chip (join before the combine).
+    if (max_big > 0) {
         TIDE_HIP(ctx, launch_plan_big(ctx->ws, max_big, ctx->aux));
         TIDE_HIP(ctx, timed(ctx, TIDE_K_GATE_UP_BIG, [&](LaunchEvents ev) {
             return launch_expert_gemm_big(0, ctx->shape, L.t, ctx->ws, x, max_big, ctx->aux, ev); }));
@@ -228,6 +238,7 @@ int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, 
     TIDE_HIP(ctx, timed(ctx, TIDE_K_DOWN, [&](LaunchEvents ev) {
         return launch_expert_gemm(1, ctx->shape, L.t, ctx->ws, x, max_tasks, stream, ev); }));
     if (max_big > 0) TIDE_HIP(ctx, hipStreamWaitEvent(stream, ctx->join_ev, 0));
+    else if (ctx->pool) TIDE_HIP(ctx, hipStreamWaitEvent(stream, ctx->listed_ev, 0));    // the export read hidden_dev
     TIDE_HIP(ctx, timed(ctx, TIDE_K_COMBINE, [&](LaunchEvents ev) {
         return launch_combine(ctx->shape, ctx->ws, w, n_tokens, out_dev, stream, ev); }));
     ctx->steps_issued++;
@@ -353,8 +364,7 @@ int tide_destroy(tide_ctx* ctx) {
         if (L.pend_slot_of) (void)hipFree(L.pend_slot_of);
     }
     host_pool_destroy(ctx->pool);
-    if (ctx->split_ev) (void)hipEventDestroy(ctx->split_ev);
-    if (ctx->xfer) (void)hipStreamDestroy(ctx->xfer);
+    if (ctx->listed_ev) (void)hipEventDestroy(ctx->listed_ev);
     for (void* q : {(void*)ctx->h_miss, (void*)ctx->h_n_miss, (void*)ctx->h_hidden, (void*)ctx->h_rows, (void*)ctx->h_tokens})
         if (q) (void)hipHostFree(q);
     for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
@@ -515,12 +525,11 @@ int tide_host_experts(tide_ctx* ctx, int n_threads) {
     TIDE_HIP(ctx, hipDeviceSynchronize());
     host_pool_destroy(ctx->pool);
     ctx->pool = nullptr;
-    ctx->split_valid = false;
+    ctx->listed_valid = false;
     if (n_threads == 0) return TIDE_OK;
     if (!ctx->h_tokens) {
         const size_t N = ctx->cfg.max_tokens, P = N * ctx->cfg.top_k, d = ctx->cfg.d;
-        if (!ctx->xfer) TIDE_HIP(ctx, hipStreamCreateWithFlags(&ctx->xfer, hipStreamNonBlocking));
-        if (!ctx->split_ev) TIDE_HIP(ctx, hipEventCreateWithFlags(&ctx->split_ev, hipEventDisableTiming));
+        if (!ctx->listed_ev) TIDE_HIP(ctx, hipEventCreateWithFlags(&ctx->listed_ev, hipEventDisableTiming));
         for (void* old : {(void*)ctx->h_miss, (void*)ctx->h_n_miss, (void*)ctx->h_hidden, (void*)ctx->h_rows})
             if (old) (void)hipHostFree(old);
         ctx->h_miss = nullptr; ctx->h_n_miss = nullptr; ctx->h_hidden = nullptr; ctx->h_rows = nullptr;
@@ -554,17 +563,21 @@ int tide_moe_apply_misses_host(tide_ctx* ctx, int layer, const void* hidden_dev,
     if (!L.host_blobs) return fail(ctx, TIDE_E_STATE, "layer %d: experts not registered", layer);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const auto t0 = std::chrono::steady_clock::now();
-    // The list and the token states come to the host on a stream of their own.  If they are the buffers of
-    // the last step issued on this stream, that stream waits only for the step's split, so the host cores
-    // work while the GPU is still on the step's expert GEMMs; otherwise it waits for all work queued so far.
-    if (!(ctx->split_valid && ctx->split_miss == miss_dev && ctx->split_hidden == hidden_dev && ctx->split_stream == stream))
-        TIDE_HIP(ctx, hipEventRecord(ctx->split_ev, stream));
-    ctx->split_valid = false;
-    TIDE_HIP(ctx, hipStreamWaitEvent(ctx->xfer, ctx->split_ev, 0));
+    // The list and the token states reach the host through a kernel on the second stream.  If they are the buffers
+    // of the last step issued on this stream, that step has queued the export right behind its split, so the host
+    // cores work while the GPU is still on the step's expert GEMMs; otherwise the export is queued now, behind all
+    // work on hip_stream.
     const int cap = std::min(miss_cap, n_tokens * ctx->cfg.top_k);
-    TIDE_HIP(ctx, launch_miss_export(miss_dev, cap, n_miss_dev, static_cast<const uint16_t*>(hidden_dev), n_tokens, ctx->cfg.d,
-                                     ctx->h_miss, ctx->h_n_miss, ctx->h_hidden, ctx->xfer));
-    TIDE_HIP(ctx, hipStreamSynchronize(ctx->xfer));
+    if (!(ctx->listed_valid && ctx->listed_miss == miss_dev && ctx->listed_hidden == hidden_dev && ctx->listed_stream == stream &&
+          ctx->listed_cap == cap && ctx->listed_tokens == n_tokens)) {
+        TIDE_HIP(ctx, hipEventRecord(ctx->fork_ev, stream));
+        TIDE_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_ev, 0));
+        TIDE_HIP(ctx, launch_miss_export(miss_dev, cap, n_miss_dev, static_cast<const uint16_t*>(hidden_dev), n_tokens, ctx->cfg.d,
+                                         ctx->h_miss, ctx->h_n_miss, ctx->h_hidden, ctx->aux));
+        TIDE_HIP(ctx, hipEventRecord(ctx->listed_ev, ctx->aux));
+    }
+    ctx->listed_valid = false;
+    TIDE_HIP(ctx, hipEventSynchronize(ctx->listed_ev));
     const auto t1 = std::chrono::steady_clock::now();
     const int n = std::max(0, std::min(*ctx->h_n_miss, cap));
     const int rows = host_apply_misses(ctx->pool, L.host_blobs, L.host_stride, ctx->cfg.d, ctx->cfg.d_ff, ctx->cfg.n_experts,

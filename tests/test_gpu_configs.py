@@ -81,6 +81,18 @@ def test_config3_flash_layer():
         sess.stats(0, reset=True)
         flips, worst = run_block_on_gpu(wl, 0, sess, log, hidden, forced, out_steps, tokens=toks)
         say("cfg3 forced=%s flips=%d worst=%.2e" % (forced, flips, worst))
+    # the host-core miss path at this size (hundreds of missed pairs over most of the 192 non-resident experts):
+    # step 0 from the initial placement, with the oracle's routing
+    load_packed(sess, wl, 0)
+    sess.stats(0, reset=True)
+    sess.host_experts(16)
+    x = sess.to_device_bf16(hidden[0])
+    sess.step_routed(0, x, torch.from_numpy(log[0]["idx"]).to(sess.device),
+                     torch.from_numpy(log[0]["w"].astype(np.float32)).to(sess.device))
+    sess.apply_misses_host(0, x)
+    torch.cuda.synchronize()
+    err = check_out(sess.out[:wl.N].cpu().numpy(), log[0]["y_full"], rows=toks)
+    say("cfg3 host miss path: %d misses, worst=%.2e" % (len(log[0]["miss"]), err))
     sess.close()
 
 

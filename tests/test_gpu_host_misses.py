@@ -80,6 +80,29 @@ def test_host_miss_path_completes_the_output(spec, out_steps, threads):
     sess.close()
 
 
+def test_host_miss_path_is_deterministic_and_thread_count_changes_only_rounding():
+    """Same thread count: bit-identical rows (fixed work decomposition, fixed summation order).  Another thread
+    count may cut experts into column groups differently: the sums differ by fp32 rounding only."""
+    from paper_2605_20179_amd import binding as tb
+    wl = ti.CONFIGS[1]
+    sess = tp._session(wl)
+    tp.load(sess, wl, 0)
+    x = sess.to_device_bf16(next(iter(ti.hidden_stream(wl, 0))))
+    outs = []
+    for threads in (16, 16, 1):
+        sess.host_experts(threads)
+        sess.stats(0, reset=True)
+        sess.step(0, x)
+        sess.apply_misses_host(0, x)
+        torch.cuda.synchronize()
+        outs.append(sess.out[:wl.N].cpu().numpy().copy())
+    assert int(sess.n_miss.item()) > 0
+    assert np.array_equal(outs[0], outs[1])
+    rms = float(np.sqrt(np.mean(outs[0] ** 2)))
+    assert np.abs(outs[0] - outs[2]).max() <= 1e-5 * rms
+    sess.close()
+
+
 def test_host_miss_path_rejects_a_bad_list():
     from paper_2605_20179_amd import binding as tb
     wl = ti.CONFIGS[0]
