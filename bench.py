@@ -122,12 +122,13 @@ def read_traffic_summary():
     return None, None
 
 
-def run_lossless(args, sess, wl, hidden, tb, ti, torch, mode):
+def run_lossless(args, sess, wl, hidden, tb, ti, torch, mode, share):
     """The layer with its misses evaluated too (full MoE output at every step), refresh every K steps as in the timed
     region.  mode 'device': tide_moe_apply_misses; mode 'host': tide_moe_apply_misses_host, whose workers run while the
     GPU is on the step's hits (Sec. 3.3: layer time = the longer of the two)."""
     if mode == "host":
         sess.host_experts(args.host_threads)
+        tb.tide_host_link_share(sess.ctx, share)
     tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))
     sess.stats(0, reset=True)
     tb.tide_counters(sess.ctx, reset=True)
@@ -159,7 +160,7 @@ def run_lossless(args, sess, wl, hidden, tb, ti, torch, mode):
     res = {"us_per_step": dt * 1e6, "tokens_per_s": wl.N / dt, "steps": steps,
            "missed_pairs_per_step": cnt["misses"] / max(cnt["steps"], 1)}
     if mode == "host":
-        res.update({"host_threads": args.host_threads, "wait_for_list_us": acc[0] / steps * 1e3,
+        res.update({"host_threads": args.host_threads, "link_share_percent": share, "wait_for_list_us": acc[0] / steps * 1e3,
                     "host_experts_us": acc[1] / steps * 1e3, "call_us": acc[2] / steps * 1e3})
         sess.host_experts(0)
     return res
@@ -188,6 +189,9 @@ def main():
                     help="detail only: also time the lossless layer (step + evaluation of its misses): 'device' = the GPU reads the "
                          "missed experts in place from pinned host memory; 'host' = host worker threads evaluate them while the GPU runs the hits")
     ap.add_argument("--host-threads", type=int, default=16)
+    ap.add_argument("--link-share", default="0",
+                    help="comma list of percents: share of a step's missed experts the GPU evaluates over the host link while the host "
+                         "workers do the rest (0 = all on the host cores, the paper's design); one 'host' measurement per value")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -332,8 +336,13 @@ def main():
 
     lossless = None
     if args.miss_mode != "none":
-        lossless = {m: run_lossless(args, sess, wl, hidden, tb, ti, torch, m)
-                    for m in (("device", "host") if args.miss_mode == "both" else (args.miss_mode,))}
+        lossless = {}
+        for m in (("device", "host") if args.miss_mode == "both" else (args.miss_mode,)):
+            if m == "device":
+                lossless[m] = run_lossless(args, sess, wl, hidden, tb, ti, torch, m, 0)
+            else:
+                for share in [int(v) for v in args.link_share.split(",")]:
+                    lossless["host" if share == 0 else "host+link%d" % share] = run_lossless(args, sess, wl, hidden, tb, ti, torch, m, share)
 
     tokens = wl.N * args.steps
     value = tokens / dt

@@ -188,6 +188,13 @@ int tide_moe_apply_misses_host(tide_ctx* ctx, int layer, const void* hidden_dev,
                                const tide_miss* miss_dev, int miss_cap, const int32_t* n_miss_dev,
                                float* out_dev, void* hip_stream);
 
+/* Splits the work of tide_moe_apply_misses_host between the two places a missed expert's weights can be
+ * read from: `percent` (0..100, default 0 = Sec. 3.3's design, everything on the host cores) of the
+ * step's distinct missed experts, those with the most tokens first, are evaluated by the GPU, which
+ * reads their blobs in place over the host link (as tide_moe_apply_misses does) behind the step on
+ * hip_stream, while the host workers evaluate the others from host memory.  The sum is the same. */
+int tide_host_link_share(tide_ctx* ctx, int percent);
+
 /* Host wall-clock milliseconds of the last tide_moe_apply_misses_host: ms3_host[0] waiting for the
  * list and the token states, [1] the host experts, [2] the whole call. */
 int tide_host_miss_ms(tide_ctx* ctx, float* ms3_host);

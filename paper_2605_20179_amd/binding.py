@@ -24,7 +24,7 @@ EXPORTS = [
     "tide_interval_stats", "tide_refresh", "tide_wait_refresh", "tide_get_table", "tide_read_slot",
     "tide_refresh_copy_ms", "tide_profile", "tide_profile_read", "tide_counters", "tide_moe_apply_misses",
     "tide_step_histogram", "tide_routing_stability", "tide_interval_costs", "tide_optimal_interval", "tide_fit_drift", "tide_scale_counts", "tide_refresh_deferred", "tide_commit",
-    "tide_host_experts", "tide_moe_apply_misses_host", "tide_host_miss_ms", "tide_host_expert",
+    "tide_host_experts", "tide_moe_apply_misses_host", "tide_host_miss_ms", "tide_host_expert", "tide_host_link_share",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -74,6 +74,7 @@ def _load() -> C.CDLL:
     lib.tide_moe_apply_misses_host.argtypes = lib.tide_moe_apply_misses.argtypes
     lib.tide_host_experts.argtypes = [vp, C.c_int]
     lib.tide_host_miss_ms.argtypes = [vp, vp]
+    lib.tide_host_link_share.argtypes = [vp, C.c_int]
     lib.tide_host_expert.argtypes = [cfgp, vp, vp, C.c_int, vp]
     lib.tide_interval_stats.argtypes = [vp, C.c_int, vp, C.c_int, vp]
     lib.tide_refresh.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, vp, vp, C.POINTER(C.c_int), vp]
@@ -188,6 +189,10 @@ def tide_host_experts(ctx, n_threads: int) -> None:
 def tide_moe_apply_misses_host(ctx, layer: int, hidden, n_tokens: int, miss, miss_cap: int, n_miss, out, stream=None) -> None:
     _check(lib.tide_moe_apply_misses_host(ctx, layer, _ptr(hidden), n_tokens, _ptr(miss), miss_cap, _ptr(n_miss),
                                           _ptr(out), _stream_ptr(stream)), ctx)
+
+
+def tide_host_link_share(ctx, percent: int) -> None:
+    _check(lib.tide_host_link_share(ctx, percent), ctx)
 
 
 def tide_host_miss_ms(ctx):

@@ -308,6 +308,7 @@ struct HostPool {
     std::vector<const float*> xptr;
     std::vector<const uint16_t*> xbptr;
     std::vector<int32_t> by_expert, pos_of, exp_off, tok_off, by_token, tok_row;
+    std::vector<tide_miss> kept;
 
     explicit HostPool(int threads) : n(threads), scratch(threads) {}
 
@@ -385,11 +386,23 @@ void host_expert_forward(const void* blob, int d, int d_ff, const uint16_t* x, i
 }
 
 int host_apply_misses(HostPool* p, const uint8_t* blobs, uint64_t stride, int d, int d_ff, int n_experts,
-                      const uint16_t* x, int n_tokens, const tide_miss* miss, int n, float* y_rows,
-                      int32_t* tokens_out) {
-    if (n <= 0) return 0;
-    for (int i = 0; i < n; ++i)
-        if (miss[i].token < 0 || miss[i].token >= n_tokens || miss[i].expert < 0 || miss[i].expert >= n_experts) return -1;
+                      const uint16_t* x, int n_tokens, const tide_miss* miss_all, int n_all, float* y_rows,
+                      int32_t* tokens_out, const uint8_t* skip_expert) {
+    if (n_all <= 0) return 0;
+    for (int i = 0; i < n_all; ++i)
+        if (miss_all[i].token < 0 || miss_all[i].token >= n_tokens || miss_all[i].expert < 0 || miss_all[i].expert >= n_experts)
+            return -1;
+    // the entries this call evaluates, in list order
+    const tide_miss* miss = miss_all;
+    int n = n_all;
+    if (skip_expert) {
+        p->kept.clear();
+        for (int i = 0; i < n_all; ++i)
+            if (!skip_expert[miss_all[i].expert]) p->kept.push_back(miss_all[i]);
+        miss = p->kept.data();
+        n = (int)p->kept.size();
+        if (n == 0) return 0;
+    }
     // the list grouped by expert (stable) and by token (stable: list order inside a token)
     p->exp_off.assign(n_experts + 1, 0);
     p->tok_off.assign(n_tokens + 1, 0);

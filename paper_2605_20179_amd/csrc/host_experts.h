@@ -28,8 +28,10 @@ void host_expert_forward(const void* blob, int d, int d_ff, const uint16_t* x, i
 //   blobs + e * stride  packed blob of expert e (host memory)
 //   x                   bf16 [n_tokens][d] (host)
 //   y_rows              fp32 [min(n, n_tokens)][d] at least; tokens_out int32 [same]
+//   skip_expert         [n_experts] bytes or null: entries of experts with a non-zero byte are left out (someone
+//                       else evaluates them)
 int host_apply_misses(HostPool* pool, const uint8_t* blobs, uint64_t stride, int d, int d_ff, int n_experts,
                       const uint16_t* x, int n_tokens, const tide_miss* miss, int n, float* y_rows,
-                      int32_t* tokens_out);
+                      int32_t* tokens_out, const uint8_t* skip_expert = nullptr);
 
 }  // namespace tide

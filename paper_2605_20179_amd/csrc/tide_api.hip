@@ -77,6 +77,8 @@ struct tide_ctx {
     uint16_t* h_hidden = nullptr;           // pinned: [max_tokens][d]
     float* h_rows = nullptr;                // pinned, read by the device in place: [max_tokens][d]
     int32_t* h_tokens = nullptr;            // pinned, read by the device in place: [max_tokens]
+    uint8_t* h_mask = nullptr;              // pinned, read by the device in place: [E] experts the GPU takes over the link
+    int link_share = 0;                     // percent of a step's missed experts evaluated by the GPU over the host link
     float host_ms[3] = {0.f, 0.f, 0.f};     // last call: wait for the list, host compute, whole call
 };
 
@@ -260,6 +262,29 @@ int step_args_ok(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens,
     return TIDE_OK;
 }
 
+// The listed misses (of the experts the mask keeps) evaluated on the GPU and added to out_dev: the work items'
+// "slots" are expert ids and their weights the experts' pinned host blobs, which the GEMM kernels read in
+// place across the host link.
+int device_miss_pass(tide_ctx* ctx, Layer& L, const void* hidden_dev, int n_tokens, const tide_miss* miss_dev, int miss_cap,
+                     const int32_t* n_miss_dev, float* out_dev, hipStream_t stream, const uint8_t* expert_mask) {
+    const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
+    LayerTables host_view = L.t;
+    host_view.slots = reinterpret_cast<const uint16_t*>(L.host_blobs);
+    Shape shape = ctx->shape;
+    shape.blob_elems = (int64_t)(L.host_stride / 2);
+    const int max_small = max_miss_small_tasks_for(ctx->shape, n_tokens);
+    const int max_big = max_miss_big_tasks_for(ctx->shape, n_tokens);
+    TIDE_HIP(ctx, launch_clear_i32(ctx->ws.miss_hist, ctx->cfg.n_experts, stream));
+    TIDE_HIP(ctx, launch_miss_group(ctx->shape, ctx->ws, miss_dev, miss_cap, n_miss_dev, max_big, stream, expert_mask));
+    TIDE_HIP(ctx, launch_expert_gemm(0, shape, host_view, ctx->ws, x, max_small, stream));
+    if (max_big > 0) TIDE_HIP(ctx, launch_plan_big(ctx->ws, max_big, stream));
+    if (max_big > 0) TIDE_HIP(ctx, launch_expert_gemm_big(0, shape, host_view, ctx->ws, x, max_big, stream));
+    TIDE_HIP(ctx, launch_expert_gemm(1, shape, host_view, ctx->ws, x, max_small, stream));
+    if (max_big > 0) TIDE_HIP(ctx, launch_expert_gemm_big(1, shape, host_view, ctx->ws, x, max_big, stream));
+    TIDE_HIP(ctx, launch_miss_combine(ctx->shape, ctx->ws, n_tokens, out_dev, stream));
+    return TIDE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -365,7 +390,7 @@ int tide_destroy(tide_ctx* ctx) {
     }
     host_pool_destroy(ctx->pool);
     if (ctx->listed_ev) (void)hipEventDestroy(ctx->listed_ev);
-    for (void* q : {(void*)ctx->h_miss, (void*)ctx->h_n_miss, (void*)ctx->h_hidden, (void*)ctx->h_rows, (void*)ctx->h_tokens})
+    for (void* q : {(void*)ctx->h_miss, (void*)ctx->h_n_miss, (void*)ctx->h_hidden, (void*)ctx->h_rows, (void*)ctx->h_tokens, (void*)ctx->h_mask})
         if (q) (void)hipHostFree(q);
     for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
     if (ctx->compute_mark) (void)hipEventDestroy(ctx->compute_mark);
@@ -498,25 +523,8 @@ int tide_moe_apply_misses(tide_ctx* ctx, int layer, const void* hidden_dev, int 
     if (((uintptr_t)hidden_dev & 15) || ((uintptr_t)out_dev & 15)) return fail(ctx, TIDE_E_INVAL, "hidden_dev / out_dev must be 16-byte aligned");
     Layer& L = ctx->layers[layer];
     if (!L.host_blobs) return fail(ctx, TIDE_E_STATE, "layer %d: experts not registered", layer);
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
-    // the work items' "slots" are expert ids and their weights the experts' pinned host blobs, which the
-    // GEMM kernels read in place across the host link
-    LayerTables host_view = L.t;
-    host_view.slots = reinterpret_cast<const uint16_t*>(L.host_blobs);
-    Shape shape = ctx->shape;
-    shape.blob_elems = (int64_t)(L.host_stride / 2);
-    const int max_small = max_miss_small_tasks_for(ctx->shape, n_tokens);
-    const int max_big = max_miss_big_tasks_for(ctx->shape, n_tokens);
-    TIDE_HIP(ctx, launch_clear_i32(ctx->ws.miss_hist, ctx->cfg.n_experts, stream));
-    TIDE_HIP(ctx, launch_miss_group(ctx->shape, ctx->ws, miss_dev, miss_cap, n_miss_dev, max_big, stream));
-    TIDE_HIP(ctx, launch_expert_gemm(0, shape, host_view, ctx->ws, x, max_small, stream));
-    if (max_big > 0) TIDE_HIP(ctx, launch_plan_big(ctx->ws, max_big, stream));
-    if (max_big > 0) TIDE_HIP(ctx, launch_expert_gemm_big(0, shape, host_view, ctx->ws, x, max_big, stream));
-    TIDE_HIP(ctx, launch_expert_gemm(1, shape, host_view, ctx->ws, x, max_small, stream));
-    if (max_big > 0) TIDE_HIP(ctx, launch_expert_gemm_big(1, shape, host_view, ctx->ws, x, max_big, stream));
-    TIDE_HIP(ctx, launch_miss_combine(ctx->shape, ctx->ws, n_tokens, out_dev, stream));
-    return TIDE_OK;
+    return device_miss_pass(ctx, L, hidden_dev, n_tokens, miss_dev, miss_cap, n_miss_dev, out_dev,
+                            static_cast<hipStream_t>(hip_stream), nullptr);
 }
 
 int tide_host_experts(tide_ctx* ctx, int n_threads) {
@@ -530,9 +538,9 @@ int tide_host_experts(tide_ctx* ctx, int n_threads) {
     if (!ctx->h_tokens) {
         const size_t N = ctx->cfg.max_tokens, P = N * ctx->cfg.top_k, d = ctx->cfg.d;
         if (!ctx->listed_ev) TIDE_HIP(ctx, hipEventCreateWithFlags(&ctx->listed_ev, hipEventDisableTiming));
-        for (void* old : {(void*)ctx->h_miss, (void*)ctx->h_n_miss, (void*)ctx->h_hidden, (void*)ctx->h_rows})
+        for (void* old : {(void*)ctx->h_miss, (void*)ctx->h_n_miss, (void*)ctx->h_hidden, (void*)ctx->h_rows, (void*)ctx->h_mask})
             if (old) (void)hipHostFree(old);
-        ctx->h_miss = nullptr; ctx->h_n_miss = nullptr; ctx->h_hidden = nullptr; ctx->h_rows = nullptr;
+        ctx->h_miss = nullptr; ctx->h_n_miss = nullptr; ctx->h_hidden = nullptr; ctx->h_rows = nullptr; ctx->h_mask = nullptr;
         void* q = nullptr;
         if (hipHostMalloc(&q, P * sizeof(tide_miss), hipHostMallocDefault) != hipSuccess) return fail(ctx, TIDE_E_NOMEM, "pinned miss list");
         ctx->h_miss = static_cast<tide_miss*>(q);
@@ -542,6 +550,8 @@ int tide_host_experts(tide_ctx* ctx, int n_threads) {
         ctx->h_hidden = static_cast<uint16_t*>(q);
         if (hipHostMalloc(&q, N * d * 4, hipHostMallocDefault) != hipSuccess) return fail(ctx, TIDE_E_NOMEM, "pinned result rows");
         ctx->h_rows = static_cast<float*>(q);
+        if (hipHostMalloc(&q, (size_t)ctx->cfg.n_experts + 64, hipHostMallocDefault) != hipSuccess) return fail(ctx, TIDE_E_NOMEM, "pinned expert mask");
+        ctx->h_mask = static_cast<uint8_t*>(q);
         if (hipHostMalloc(&q, N * 4, hipHostMallocDefault) != hipSuccess) return fail(ctx, TIDE_E_NOMEM, "pinned row tokens");
         ctx->h_tokens = static_cast<int32_t*>(q);
     }
@@ -580,8 +590,30 @@ int tide_moe_apply_misses_host(tide_ctx* ctx, int layer, const void* hidden_dev,
     TIDE_HIP(ctx, hipEventSynchronize(ctx->listed_ev));
     const auto t1 = std::chrono::steady_clock::now();
     const int n = std::max(0, std::min(*ctx->h_n_miss, cap));
-    const int rows = host_apply_misses(ctx->pool, L.host_blobs, L.host_stride, ctx->cfg.d, ctx->cfg.d_ff, ctx->cfg.n_experts,
-                                       ctx->h_hidden, n_tokens, ctx->h_miss, n, ctx->h_rows, ctx->h_tokens);
+    const int E = ctx->cfg.n_experts;
+    for (int i = 0; i < n; ++i)
+        if (ctx->h_miss[i].token < 0 || ctx->h_miss[i].token >= n_tokens || ctx->h_miss[i].expert < 0 || ctx->h_miss[i].expert >= E)
+            return fail(ctx, TIDE_E_INVAL, "the miss list names a token or an expert out of range");
+    // Optionally the GPU takes a share of the missed experts -- those with the most tokens -- and evaluates them
+    // over the host link, queued behind the step on hip_stream, while the host workers do the rest.
+    const uint8_t* skip = nullptr;
+    if (ctx->link_share > 0 && n > 0) {
+        std::vector<int32_t> cnt(E, 0), order;
+        for (int i = 0; i < n; ++i) cnt[ctx->h_miss[i].expert]++;
+        for (int e = 0; e < E; ++e)
+            if (cnt[e]) order.push_back(e);
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cnt[a] > cnt[b]; });
+        const int take = (int)((int64_t)order.size() * ctx->link_share / 100);
+        if (take > 0) {
+            memset(ctx->h_mask, 0, E);
+            for (int j = 0; j < take; ++j) ctx->h_mask[order[j]] = 1;
+            skip = ctx->h_mask;
+            rc = device_miss_pass(ctx, L, hidden_dev, n_tokens, miss_dev, cap, n_miss_dev, out_dev, stream, ctx->h_mask);
+            if (rc) return rc;
+        }
+    }
+    const int rows = host_apply_misses(ctx->pool, L.host_blobs, L.host_stride, ctx->cfg.d, ctx->cfg.d_ff, E,
+                                       ctx->h_hidden, n_tokens, ctx->h_miss, n, ctx->h_rows, ctx->h_tokens, skip);
     const auto t2 = std::chrono::steady_clock::now();
     if (rows < 0) return fail(ctx, TIDE_E_INVAL, "the miss list names a token or an expert out of range");
     // the rows are added by a kernel that reads them in place from pinned host memory, after the step's own combine
@@ -591,6 +623,13 @@ int tide_moe_apply_misses_host(tide_ctx* ctx, int layer, const void* hidden_dev,
     ctx->host_ms[0] = ms(t0, t1);
     ctx->host_ms[1] = ms(t1, t2);
     ctx->host_ms[2] = ms(t0, t3);
+    return TIDE_OK;
+}
+
+int tide_host_link_share(tide_ctx* ctx, int percent) {
+    if (!ctx) return TIDE_E_INVAL;
+    if (percent < 0 || percent > 100) return fail(ctx, TIDE_E_RANGE, "percent must be 0..100");
+    ctx->link_share = percent;
     return TIDE_OK;
 }
 

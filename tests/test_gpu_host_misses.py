@@ -11,14 +11,18 @@ import test_gpu_parity as tp
 pytestmark = pytest.mark.gpu
 
 CASES = [
-    # workload, steps whose outputs are compared, host threads
-    ("cfg0", [0, 1, 2, 3], 3),
-    ("cfg1", [0, 4, 5], 16),
+    # workload, steps whose outputs are compared, host threads, percent of the missed experts the GPU takes over the link
+    ("cfg0", [0, 1, 2, 3], 3, 0),
+    ("cfg1", [0, 4, 5], 16, 0),
+    ("cfg1", [0, 4], 16, 25),
+    ("cfg0", [0, 1, 2, 3], 2, 50),
+    ("cfg0", [1, 2], 2, 100),
     # partial gate/up group (12 column blocks) and partial down group (20 stripes); hundreds of misses per expert
-    ((320, 8, 2, 192, 1, 700, 4, ti.GATING_SIGMOID, ti.BIAS_NONE), [0, 2], 4),
-    ((384, 70, 4, 192, 1, 257, 30, ti.GATING_SOFTMAX, ti.BIAS_LOGIT), [0, 3], 1),
+    ((320, 8, 2, 192, 1, 700, 4, ti.GATING_SIGMOID, ti.BIAS_NONE), [0, 2], 4, 0),
+    ((384, 70, 4, 192, 1, 257, 30, ti.GATING_SOFTMAX, ti.BIAS_LOGIT), [0, 3], 1, 0),
+    ((384, 70, 4, 192, 1, 257, 30, ti.GATING_SOFTMAX, ti.BIAS_LOGIT), [0, 3], 4, 30),
     # more missed experts than 4 x threads: one work item per expert
-    ((128, 300, 6, 128, 1, 33, 40, ti.GATING_SIGMOID, ti.BIAS_NONE), [1], 2),
+    ((128, 300, 6, 128, 1, 33, 40, ti.GATING_SIGMOID, ti.BIAS_NONE), [1], 2, 0),
 ]
 
 
@@ -32,11 +36,11 @@ def _workload(spec):
                            bias_mode=bias_mode, seed=177 + N)
 
 
-@pytest.mark.parametrize("spec,out_steps,threads", CASES)
-def test_host_miss_path_completes_the_output(spec, out_steps, threads):
+@pytest.mark.parametrize("spec,out_steps,threads,share", CASES)
+def test_host_miss_path_completes_the_output(spec, out_steps, threads, share):
     from paper_2605_20179_amd import binding as tb
     wl = _workload(spec)
-    tp.say("host miss path %s, %d threads" % (wl.name if isinstance(spec, str) else spec, threads))
+    tp.say("host miss path %s, %d threads, link share %d" % (wl.name if isinstance(spec, str) else spec, threads, share))
     log, hidden = tp.oracle_block(wl, 0, out_steps)
     sess = tp._session(wl)
     tp.load(sess, wl, 0)
@@ -44,6 +48,7 @@ def test_host_miss_path_completes_the_output(spec, out_steps, threads):
         sess.apply_misses_host(0, sess.to_device_bf16(hidden[0]))
     assert ei.value.code == tb.TIDE_E_STATE
     sess.host_experts(threads)
+    tb.tide_host_link_share(sess.ctx, share)
     worst = 0.0
     for t, rec in enumerate(log):
         if t > 0 and t % wl.K == 0:
