@@ -194,6 +194,8 @@ def main():
                          "workers do the rest (0 = all on the host cores, the paper's design); one 'host' measurement per value")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--gemm-calibration", action="store_true",
+                    help="print what the vendor library's bf16 GEMM sustains on this GPU at comparable shapes and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 8 plain device copies of 1 GiB (what rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled by) and exit")
     args = ap.parse_args()
@@ -218,6 +220,29 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 8}}))
+        return
+    if args.gemm_calibration:
+        # what the vendor's bf16 GEMM (torch.matmul / torch.bmm -> hipBLASLt) sustains on this machine at comparable shapes:
+        # a yardstick for the grouped expert GEMM's MFMA fraction, not part of the path
+        def rate(fn, flop, n=20):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            return flop / ((time.perf_counter() - t0) / n) / 1e12
+        res = {}
+        for m, k, n in ((16384, 4096, 2048), (8192, 8192, 8192)):
+            a = torch.randn(m, k, device="cuda:0", dtype=torch.bfloat16)
+            b = torch.randn(k, n, device="cuda:0", dtype=torch.bfloat16)
+            res["mm_%dx%dx%d" % (m, k, n)] = rate(lambda: a @ b, 2.0 * m * k * n)
+        for g, m, k, n in ((65, 208, 4096, 2048), (65, 1024, 4096, 2048)):      # 65 slots x rows per slot, gate+up of the flash shape
+            a = torch.randn(g, m, k, device="cuda:0", dtype=torch.bfloat16)
+            b = torch.randn(g, k, n, device="cuda:0", dtype=torch.bfloat16)
+            res["bmm_%dx%dx%dx%d" % (g, m, k, n)] = rate(lambda: torch.bmm(a, b), 2.0 * g * m * k * n)
+        print(json.dumps({"gemm_calibration_TFLOP/s": res, "peak": MFMA_BF16_PEAK_TFLOPS}))
         return
     wl = ti.CONFIGS[args.config]
     if args.capacity:
