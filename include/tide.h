@@ -199,6 +199,16 @@ int tide_host_link_share(tide_ctx* ctx, int percent);
  * list and the token states, [1] the host experts, [2] the whole call. */
 int tide_host_miss_ms(tide_ctx* ctx, float* ms3_host);
 
+/* The host workers' whole miss path with host buffers only, no GPU involved: for every listed miss
+ * out_host[token][:] += weight * e_expert(x_token), evaluated by n_threads threads (started and
+ * stopped inside the call) from packed blobs at blobs_host + expert * blob_stride.
+ *   x_host bf16 [n_tokens][d]; miss_host tide_miss[n_miss] in any order; out_host fp32 [n_tokens][d]
+ * (in/out).  TIDE_E_INVAL for an entry that names a token or an expert out of range (nothing is added).
+ * What tide_moe_apply_misses_host runs between its two kernels, exposed for checking it without a device. */
+int tide_host_misses(const tide_config* cfg, const void* blobs_host, uint64_t blob_stride,
+                     const uint16_t* x_host, int n_tokens, const tide_miss* miss_host, int n_miss,
+                     int n_threads, float* out_host);
+
 /* One expert on the calling host thread, no GPU involved: y_host[t][:] = e(x_t) for m token
  * states x_host (bf16 [m][d], host) through one packed blob (host); y_host fp32 [m][d].
  * The arithmetic of the host workers, exposed for checking it without a device. */

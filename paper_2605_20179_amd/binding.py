@@ -24,7 +24,7 @@ EXPORTS = [
     "tide_interval_stats", "tide_refresh", "tide_wait_refresh", "tide_get_table", "tide_read_slot",
     "tide_refresh_copy_ms", "tide_profile", "tide_profile_read", "tide_counters", "tide_moe_apply_misses",
     "tide_step_histogram", "tide_routing_stability", "tide_interval_costs", "tide_optimal_interval", "tide_fit_drift", "tide_scale_counts", "tide_refresh_deferred", "tide_commit",
-    "tide_host_experts", "tide_moe_apply_misses_host", "tide_host_miss_ms", "tide_host_expert", "tide_host_link_share",
+    "tide_host_experts", "tide_moe_apply_misses_host", "tide_host_miss_ms", "tide_host_expert", "tide_host_link_share", "tide_host_misses",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -76,6 +76,7 @@ def _load() -> C.CDLL:
     lib.tide_host_miss_ms.argtypes = [vp, vp]
     lib.tide_host_link_share.argtypes = [vp, C.c_int]
     lib.tide_host_expert.argtypes = [cfgp, vp, vp, C.c_int, vp]
+    lib.tide_host_misses.argtypes = [cfgp, vp, C.c_uint64, vp, C.c_int, vp, C.c_int, C.c_int, vp]
     lib.tide_interval_stats.argtypes = [vp, C.c_int, vp, C.c_int, vp]
     lib.tide_refresh.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, vp, vp, C.POINTER(C.c_int), vp]
     lib.tide_refresh_deferred.argtypes = lib.tide_refresh.argtypes
@@ -200,6 +201,18 @@ def tide_host_miss_ms(ctx):
     ms = np.zeros(3, dtype=np.float32)
     _check(lib.tide_host_miss_ms(ctx, _ptr(ms)), ctx)
     return float(ms[0]), float(ms[1]), float(ms[2])
+
+
+def tide_host_misses(cfg: tide_config, blobs: np.ndarray, x_bits: np.ndarray, miss: np.ndarray, n_threads: int,
+                     out: np.ndarray) -> None:
+    """out[token] += weight * e_expert(x_token) for every entry of miss (MISS_DTYPE), on n_threads host threads.
+    blobs: uint8 [E, blob_bytes] packed blobs (host)."""
+    x = np.ascontiguousarray(x_bits, dtype=np.uint16)
+    m = np.ascontiguousarray(miss, dtype=MISS_DTYPE)
+    assert blobs.dtype == np.uint8 and blobs.ndim == 2 and blobs.flags["C_CONTIGUOUS"]
+    assert out.dtype == np.float32 and out.shape == (x.shape[0], cfg.d) and out.flags["C_CONTIGUOUS"]
+    _check(lib.tide_host_misses(C.byref(cfg), _ptr(blobs), blobs.shape[1], _ptr(x), x.shape[0], m.ctypes.data if m.size else None,
+                                m.size, n_threads, _ptr(out)), None)
 
 
 def tide_host_expert(cfg: tide_config, blob, x_bits: np.ndarray) -> np.ndarray:

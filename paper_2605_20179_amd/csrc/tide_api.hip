@@ -640,6 +640,31 @@ int tide_host_miss_ms(tide_ctx* ctx, float* ms3_host) {
     return TIDE_OK;
 }
 
+int tide_host_misses(const tide_config* cfg, const void* blobs_host, uint64_t blob_stride, const uint16_t* x_host, int n_tokens,
+                     const tide_miss* miss_host, int n_miss, int n_threads, float* out_host) {
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    if (n_tokens < 0 || n_tokens > cfg->max_tokens) return fail(nullptr, TIDE_E_RANGE, "n_tokens outside 0..max_tokens");
+    if (n_miss < 0 || (int64_t)n_miss > (int64_t)n_tokens * cfg->top_k) return fail(nullptr, TIDE_E_RANGE, "n_miss outside 0..n_tokens*k");
+    if (n_threads < 1 || n_threads > 1024) return fail(nullptr, TIDE_E_RANGE, "n_threads must be 1..1024");
+    if (n_miss == 0) return TIDE_OK;
+    if (!blobs_host || !x_host || !miss_host || !out_host) return fail(nullptr, TIDE_E_INVAL, "null argument");
+    if (blob_stride < tide_expert_blob_bytes(cfg) || (blob_stride & 15)) return fail(nullptr, TIDE_E_INVAL, "blob_stride must be >= blob bytes and 16-byte aligned");
+    std::vector<float> rows((size_t)std::min(n_miss, n_tokens) * cfg->d);
+    std::vector<int32_t> tokens(std::min(n_miss, n_tokens));
+    HostPool* pool = host_pool_create(n_threads);
+    const int n_rows = host_apply_misses(pool, static_cast<const uint8_t*>(blobs_host), blob_stride, cfg->d, cfg->d_ff, cfg->n_experts,
+                                         x_host, n_tokens, miss_host, n_miss, rows.data(), tokens.data());
+    host_pool_destroy(pool);
+    if (n_rows < 0) return fail(nullptr, TIDE_E_INVAL, "the miss list names a token or an expert out of range");
+    for (int r = 0; r < n_rows; ++r) {
+        float* o = out_host + (int64_t)tokens[r] * cfg->d;
+        const float* v = rows.data() + (int64_t)r * cfg->d;
+        for (int c = 0; c < cfg->d; ++c) o[c] += v[c];
+    }
+    return TIDE_OK;
+}
+
 int tide_host_expert(const tide_config* cfg, const void* blob_host, const uint16_t* x_host, int m, float* y_host) {
     int rc = check_cfg(cfg);
     if (rc) return rc;

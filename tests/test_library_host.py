@@ -95,6 +95,54 @@ def test_host_expert_matches_the_oracle(tb, d, d_ff, m):
     assert np.max(np.abs(got - want)) <= 2e-3 * rms, np.max(np.abs(got - want)) / rms
 
 
+@pytest.mark.parametrize("n_tokens,n_experts,k,threads,shuffle", [(5, 6, 2, 1, False), (40, 6, 3, 3, False), (9, 40, 4, 2, True)])
+def test_host_miss_path_matches_the_oracle(tb, n_tokens, n_experts, k, threads, shuffle):
+    """The host workers' grouping, threading and per-token summation against the definition: out[token] +=
+    w * e(x_token) for every listed (token, expert, w).  Few experts per thread (each expert cut into its column
+    groups) and many (one work item per expert); list in token order and shuffled; the result lands on top of
+    what out already holds."""
+    import sys
+    sys.path.insert(0, ROOT)
+    from oracle import tide_oracle as orc
+    d, d_ff = 192, 192
+    cfg = tb.make_config(d, n_experts, k, d_ff, 0, 1, 1, 64, 0, 0)
+    rng = np.random.default_rng(n_tokens * 100 + n_experts)
+    def bits(shape, scale):
+        return (np.ascontiguousarray(rng.normal(0, scale, size=shape), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    W = [(bits((d_ff, d), 0.08), bits((d_ff, d), 0.08), bits((d, d_ff), 0.08)) for _ in range(n_experts)]
+    blobs = np.zeros((n_experts, tb.tide_expert_blob_bytes(cfg)), dtype=np.uint8)
+    for e, (wg, wu, wd) in enumerate(W):
+        tb.tide_pack_expert(cfg, wg, wu, wd, blobs[e])
+    x = bits((n_tokens, d), 1.0)
+    entries = []
+    for t in range(n_tokens):
+        if t % 4 == 3:
+            continue                                             # a token without misses keeps its row
+        for e in rng.choice(n_experts, size=int(rng.integers(1, k + 1)), replace=False):
+            entries.append((t, int(e), float(rng.uniform(0.05, 0.6))))
+    if shuffle:
+        rng.shuffle(entries)
+    miss = np.array(entries, dtype=tb.MISS_DTYPE)
+    base = rng.normal(0, 1, size=(n_tokens, d)).astype(np.float32)
+    got = base.copy()
+    tb.tide_host_misses(cfg, blobs, x, miss, threads, got)
+    want = base.astype(np.float64)
+    Wf = [tuple(orc.bf16_to_f64(m) for m in w) for w in W]
+    for t, e, w in entries:
+        want[t] += np.float32(w).astype(np.float64) * orc.expert_ffn(orc.bf16_to_f64(x[t]), *Wf[e])
+    rms = float(np.sqrt(np.mean((want - base) ** 2)))
+    assert np.max(np.abs(got - want)) <= 2e-3 * rms
+    untouched = [t for t in range(n_tokens) if t % 4 == 3]
+    assert np.array_equal(got[untouched], base[untouched])
+    # a bad entry: refused, nothing added
+    bad = miss.copy()
+    bad[len(bad) // 2]["expert"] = n_experts
+    again = base.copy()
+    with pytest.raises(tb.TideError) as ei:
+        tb.tide_host_misses(cfg, blobs, x, bad, threads, again)
+    assert ei.value.code == tb.TIDE_E_INVAL and np.array_equal(again, base)
+
+
 def test_config_validation_and_no_device(tb):
     ok = dict(d=256, n_experts=16, top_k=2, d_ff=128, n_shared=0, n_layers=1, capacity=8, max_tokens=8, gating=0, bias_mode=0)
     blob = np.zeros(3 * 256 * 128 * 2, dtype=np.uint8)
