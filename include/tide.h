@@ -153,7 +153,8 @@ int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n
  * property, the cost is one pass over each missed expert's weights at host-link speed).
  *   hidden_dev  the step's input, as passed to tide_moe_step                      (in)
  *   miss_dev / miss_cap / n_miss_dev  the list that step returned; min(*n_miss_dev, miss_cap)
- *               entries are used                                                   (in)
+ *               entries are used; an entry that names an expert outside [0,E) or a token
+ *               outside [0,n_tokens) is skipped                                    (in)
  *   out_dev     fp32 [n_tokens][d], the step's resident-partial output             (in/out)
  * Asynchronous on hip_stream; must follow the step on the same stream (it reuses the context's
  * workspace).  Does not touch H or the tables. */

@@ -256,7 +256,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
 // With a mask only the entries of experts e with mask[e] != 0 are kept.
 __global__ __launch_bounds__(kThreads) void miss_prepare_kernel(const tide_miss* __restrict__ miss, int miss_cap,
                                                                const int32_t* __restrict__ n_miss, int n_experts,
-                                                               const uint8_t* __restrict__ mask,
+                                                               int n_tokens, const uint8_t* __restrict__ mask,
                                                                int32_t* __restrict__ m_idx, int32_t* __restrict__ m_tok,
                                                                float* __restrict__ m_w, int32_t* __restrict__ miss_hist,
                                                                int32_t* __restrict__ m_count) {
@@ -265,8 +265,9 @@ __global__ __launch_bounds__(kThreads) void miss_prepare_kernel(const tide_miss*
     if (p == 0) *m_count = n;
     if (p >= n) return;
     const tide_miss m = miss[p];
-    const bool ok = m.expert >= 0 && m.expert < n_experts && (mask == nullptr || mask[m.expert] != 0);
-    m_idx[p] = ok ? m.expert : -1;                           // an id outside [0,E) or masked out is skipped
+    const bool ok = m.expert >= 0 && m.expert < n_experts && m.token >= 0 && m.token < n_tokens &&
+                    (mask == nullptr || mask[m.expert] != 0);
+    m_idx[p] = ok ? m.expert : -1;                           // an entry out of range or masked out is skipped
     m_tok[p] = m.token;
     m_w[p] = m.weight;
     if (ok) atomicAdd(&miss_hist[m.expert], 1);
@@ -378,10 +379,11 @@ hipError_t launch_miss_export(const tide_miss* miss, int cap, const int32_t* n_m
 }
 
 hipError_t launch_miss_group(const Shape& s, const Workspace& w, const tide_miss* miss, int miss_cap,
-                             const int32_t* n_miss, int max_big, hipStream_t stream, const uint8_t* expert_mask) {
+                             const int32_t* n_miss, int n_tokens, int max_big, hipStream_t stream,
+                             const uint8_t* expert_mask) {
     if (miss_cap <= 0) return hipSuccess;
     hipLaunchKernelGGL(miss_prepare_kernel, dim3((miss_cap + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, miss,
-                       miss_cap, n_miss, s.E, expert_mask, w.m_idx, w.m_tok, w.m_w, w.miss_hist, w.m_count);
+                       miss_cap, n_miss, s.E, n_tokens, expert_mask, w.m_idx, w.m_tok, w.m_w, w.miss_hist, w.m_count);
     hipLaunchKernelGGL(miss_group_kernel, dim3(s.E + 1), dim3(kThreads), 0, stream, w.m_idx, w.m_tok, w.m_count, s.E,
                        w.miss_hist, w.row_token, w.pair_row, w.tasks, w.big_tasks, w.n_tasks, max_big, (s.I + 127) / 128);
     return hipGetLastError();

@@ -275,7 +275,7 @@ int device_miss_pass(tide_ctx* ctx, Layer& L, const void* hidden_dev, int n_toke
     const int max_small = max_miss_small_tasks_for(ctx->shape, n_tokens);
     const int max_big = max_miss_big_tasks_for(ctx->shape, n_tokens);
     TIDE_HIP(ctx, launch_clear_i32(ctx->ws.miss_hist, ctx->cfg.n_experts, stream));
-    TIDE_HIP(ctx, launch_miss_group(ctx->shape, ctx->ws, miss_dev, miss_cap, n_miss_dev, max_big, stream, expert_mask));
+    TIDE_HIP(ctx, launch_miss_group(ctx->shape, ctx->ws, miss_dev, miss_cap, n_miss_dev, n_tokens, max_big, stream, expert_mask));
     TIDE_HIP(ctx, launch_expert_gemm(0, shape, host_view, ctx->ws, x, max_small, stream));
     if (max_big > 0) TIDE_HIP(ctx, launch_plan_big(ctx->ws, max_big, stream));
     if (max_big > 0) TIDE_HIP(ctx, launch_expert_gemm_big(0, shape, host_view, ctx->ws, x, max_big, stream));

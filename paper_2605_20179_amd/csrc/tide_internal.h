@@ -132,11 +132,13 @@ inline int max_miss_big_tasks_for(const Shape& s, int n_tokens) {
     const int busy = rows / (kBigMinRows + 1);
     return rows / kRowsPerBigTask + (busy < s.E ? busy : s.E);
 }
-// miss pass (the step's misses evaluated from the host-resident blobs): group the list by expert into
+// miss pass (the step's misses evaluated from the host-resident blobs; entries that name an expert outside [0,E)
+// or a token outside [0,n_tokens) are skipped): group the list by expert into
 // rows and work items whose "slot" is the expert id; add the weighted results to out
 // expert_mask (device or pinned host, [E] bytes, may be null): only experts with a non-zero byte are evaluated
 hipError_t launch_miss_group(const Shape& s, const Workspace& w, const tide_miss* miss, int miss_cap,
-                             const int32_t* n_miss, int max_big, hipStream_t stream, const uint8_t* expert_mask = nullptr);
+                             const int32_t* n_miss, int n_tokens, int max_big, hipStream_t stream,
+                             const uint8_t* expert_mask = nullptr);
 hipError_t launch_miss_combine(const Shape& s, const Workspace& w, int n_tokens, float* out, hipStream_t stream);
 // a9: out[n] = shared row + sum over hit pairs in rank order of w * y[row]
 hipError_t launch_combine(const Shape& s, const Workspace& w, const float* topk_w, int n_tokens, float* out,
