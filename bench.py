@@ -62,6 +62,10 @@ def run_stack(args, wl, ti, tb, TideSession, torch):
     for l in range(L):
         sess.load_layer(l, None, ti.router_weights(wl, l), ti.router_bias(wl, l), ti.initial_resident(wl), packed=packed)
         hidden.append([sess.to_device_bf16(h) for h in ti.hidden_stream(wl, l)])
+    if args.refresh_source == "packed12":              # the layers share layer 0's blobs, so one compressed copy serves all
+        sess.compress_layer(0, workers=16)
+        for l in range(1, L):
+            tb.tide_register_compressed(sess.ctx, l, sess.comp_blobs[0], tb.tide_compressed_blob_bytes(sess.cfg))
     torch.cuda.synchronize()
     state = {"t": 0, "copies": 0}
 
@@ -99,7 +103,7 @@ def run_stack(args, wl, ti, tb, TideSession, torch):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "d": wl.d, "experts": wl.E, "top_k": wl.k, "d_ff": wl.I, "shared_experts": wl.n_shared,
                    "tokens_per_step": wl.N, "capacity": wl.C, "refresh_interval": wl.K, "steps_per_block": wl.S, "layers": L,
-                   "refresh_order": args.refresh_order, "note": "layers share layer 0's expert values; routers, streams, caches differ"},
+                   "refresh_order": args.refresh_order, "refresh_source": args.refresh_source, "note": "layers share layer 0's expert values; routers, streams, caches differ"},
         "detail": {"experts_copied": state["copies"], "blob_MiB": sess.blob_bytes / 2 ** 20,
                    "frozen_placement_us_per_step": frozen * 1e6, "frozen_placement_us_per_layer": frozen * 1e6 / L,
                    "us_per_layer": 1e6 * dt / args.steps / L}}))
@@ -185,6 +189,9 @@ def main():
                     help="--stack: at a refresh step, refresh each layer right before its own step, or all layers first so "
                          "that later layers' copies overlap earlier layers' compute")
     ap.add_argument("--capacity", type=int, default=0, help="cache slots (0 = the workload's own budget); 256 = every expert resident")
+    ap.add_argument("--refresh-source", choices=("raw", "packed12"), default="packed12",
+                    help="what the refresh copies read over the host link: the raw blobs, or their lossless 12-bit form "
+                         "(3/4 of the bytes; slots bit-identical)")
     ap.add_argument("--miss-mode", choices=("none", "device", "host", "both"), default="both",
                     help="detail only: also time the lossless layer (step + evaluation of its misses): 'device' = the GPU reads the "
                          "missed experts in place from pinned host memory; 'host' = host worker threads evaluate them while the GPU runs the hits")
@@ -194,6 +201,10 @@ def main():
                          "workers do the rest (0 = all on the host cores, the paper's design); one 'host' measurement per value")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--events", choices=("all", "gemm"), default="all",
+                    help="which launches of the timed region carry start/stop events: every kernel of a step (what a profiler does "
+                         "too), or the expert GEMMs only (less host bookkeeping; the cache maintenance between two kernels is then "
+                         "counted inside the GEMM's interval, ~1 us)")
     ap.add_argument("--gemm-calibration", action="store_true",
                     help="print what the vendor library's bf16 GEMM sustains on this GPU at comparable shapes and exit")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -255,6 +266,8 @@ def main():
     sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode)
     sess.load_layer(0, lambda e: ti.expert_weights(wl, 0, e), ti.router_weights(wl, 0), ti.router_bias(wl, 0),
                     ti.initial_resident(wl), workers=16)
+    if args.refresh_source == "packed12":
+        sess.compress_layer(0, workers=16)
     hidden = [sess.to_device_bf16(h) for h in ti.hidden_stream(wl, 0)]
     torch.cuda.synchronize()
 
@@ -283,7 +296,7 @@ def main():
     torch.cuda.synchronize()
     tb.tide_counters(sess.ctx, reset=True)
     if not args.no_kernel_events:
-        tb.tide_profile(sess.ctx, True)
+        tb.tide_profile(sess.ctx, 2 if args.events == "gemm" else 1)
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -299,6 +312,16 @@ def main():
     tb.tide_profile(sess.ctx, False)
     cnt = tb.tide_counters(sess.ctx)
     assert cnt["steps"] == args.steps
+
+    # detail only: every kernel of the step bracketed, over the same steps with the placement frozen
+    if prof:
+        tb.tide_profile(sess.ctx, 1)
+        for i in range(args.steps):
+            sess.step(0, hidden[i % wl.S], want_topk=False)
+        for name, v in tb.tide_profile_read(sess.ctx).items():
+            if name not in ("gate_up_swiglu", "down", "gate_up_swiglu_big", "down_big"):
+                prof[name] = v
+        tb.tide_profile(sess.ctx, False)
 
     # detail only: the same steps with the placement frozen (no refresh, no event brackets)
     torch.cuda.synchronize()
@@ -342,8 +365,10 @@ def main():
                 copy_ms += tb.tide_refresh_copy_ms(sess.ctx, 0)
         sess.step(0, hidden[t], want_topk=False)
     torch.cuda.synchronize()
+    link_bytes = tb.tide_compressed_blob_bytes(sess.cfg) if args.refresh_source == "packed12" else sess.blob_bytes
     refresh_stats = {"refreshes": n_ref, "experts_copied": copied, "copy_ms_total": copy_ms,
-                     "copy_GB/s": (copied * sess.blob_bytes / copy_ms / 1e6) if copy_ms > 0 else None}
+                     "copy_GB/s": (copied * sess.blob_bytes / copy_ms / 1e6) if copy_ms > 0 else None,       # expert bytes landed
+                     "link_GB/s": (copied * link_bytes / copy_ms / 1e6) if copy_ms > 0 else None}             # bytes that crossed the link
 
     # pinned-host -> HBM rate of one refresh's copies when a whole budget of experts moves
     h2d = None
@@ -357,6 +382,41 @@ def main():
     ms = tb.tide_refresh_copy_ms(probe.ctx, 0)
     if plan and ms > 0:
         h2d = {"GB/s": len(plan) * sess.blob_bytes / ms / 1e6, "copies": len(plan), "MiB_each": sess.blob_bytes / 2 ** 20}
+    # detail only: the timed loop once more without event brackets, and (if the copies read the 12-bit form) once more
+    # with the refresh copies reading the raw blobs (Alg. 1's copies as they are)
+    def plain_pass():
+        tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))
+        sess.stats(0, reset=True)
+        state.update({"t": 0, "uncommitted": False})
+        for _ in range(args.warmup):
+            one_step(False)
+        torch.cuda.synchronize()
+        r0 = time.perf_counter()
+        for _ in range(args.steps):
+            one_step(False)
+        if state.get("uncommitted"):
+            sess.commit(0)
+            state["uncommitted"] = False
+        torch.cuda.synchronize()
+        rdt = time.perf_counter() - r0
+        return {"tokens_per_s": wl.N * args.steps / rdt, "us_per_step": rdt / args.steps * 1e6}
+
+    no_events = plain_pass()
+    raw_source = None
+    if args.refresh_source == "packed12":
+        tb.tide_register_compressed(sess.ctx, 0, None, 0)
+        raw_source = plain_pass()
+        tb.tide_register_compressed(sess.ctx, 0, sess.comp_blobs[0], tb.tide_compressed_blob_bytes(sess.cfg))
+    h2d_p12 = None
+    if args.refresh_source == "packed12":
+        cbytes = tb.tide_compressed_blob_bytes(sess.cfg)
+        tb.tide_register_compressed(probe.ctx, 0, sess.comp_blobs[0], cbytes)
+        tb.tide_set_resident(probe.ctx, 0, list(range(wl.C)))
+        _, plan = probe.refresh(0, counts=counts)
+        ms = tb.tide_refresh_copy_ms(probe.ctx, 0)
+        if plan and ms > 0:
+            h2d_p12 = {"expert_GB/s": len(plan) * sess.blob_bytes / ms / 1e6, "link_GB/s": len(plan) * cbytes / ms / 1e6,
+                       "copies": len(plan), "bytes_over_link_per_expert": cbytes}
     probe.close()
 
     lossless = None
@@ -418,6 +478,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "d": wl.d, "experts": wl.E, "top_k": wl.k, "d_ff": wl.I, "shared_experts": wl.n_shared,
                    "tokens_per_step": wl.N, "capacity": wl.C, "refresh_interval": wl.K, "steps_per_block": wl.S, "layers": 1,
+                   "refresh_source": args.refresh_source,
                    "refresh_mode": args.refresh_mode if args.refresh_mode == "immediate" else "deferred by %d step(s)" % args.commit_after},
         "roofline": roofline,
         "detail": {
@@ -432,6 +493,9 @@ def main():
             "refresh_copies": refresh_stats,
             "frozen_placement_tokens_per_s": wl.N / step_only_s,
             "h2d_probe": h2d,
+            "h2d_probe_packed12": h2d_p12,
+            "without_kernel_events": no_events,
+            "without_kernel_events_raw_refresh_copies": raw_source,
             "lossless_layer": lossless,
         },
     }

@@ -99,6 +99,23 @@ int tide_pack_expert(const tide_config* cfg, const uint16_t* wg_host, const uint
  * refused with TIDE_E_INVAL.  Borrowed, never written, never freed. */
 int tide_register_experts(tide_ctx* ctx, int layer, const void* host_blobs, uint64_t blob_stride);
 
+/* Optional: a lossless 12-bit form of the packed blobs as the SOURCE OF REFRESH COPIES, so that 3/4 of the
+ * bytes cross the host link; the copy kernel rebuilds the blob bit for bit in the cache slot (or staging
+ * blob).  Everything else (tide_set_resident, the miss paths) keeps reading the raw blobs, which must stay
+ * registered.  Format: per 16 x 32 tile one exponent (the top of the 16-binade window that holds most of
+ * the tile), per element sign | 4-bit distance below it | 7-bit mantissa; elements outside the window
+ * are listed as exceptions (up to one per tile on average; an expert with more is marked "raw" and copied
+ * from its raw blob).
+ *   tide_compressed_blob_bytes  size of one compressed blob (a multiple of 64)
+ *   tide_compress_expert        host: packed blob (tide_pack_expert) -> compressed blob
+ *   tide_register_compressed    expert e at comp_host_blobs + e * comp_stride; pinned host memory, 64-byte
+ *                               aligned, valid and unchanged until tide_destroy; NULL goes back to raw copies.
+ *                               Synchronises the device.  TIDE_E_INVAL for pageable memory or a blob that is
+ *                               not of this configuration, TIDE_E_STATE before tide_register_experts. */
+uint64_t tide_compressed_blob_bytes(const tide_config* cfg);
+int tide_compress_expert(const tide_config* cfg, const void* blob_host, void* comp_host);
+int tide_register_compressed(tide_ctx* ctx, int layer, const void* comp_host_blobs, uint64_t comp_stride);
+
 /* Copies one packed blob (host) into the layer's always-resident shared-expert slot.
  * Synchronous.  Required before the first step when n_shared == 1. */
 int tide_set_shared(tide_ctx* ctx, int layer, const void* blob_host);
@@ -281,13 +298,15 @@ int tide_refresh_copy_ms(tide_ctx* ctx, int layer, float* ms_out);
 #define TIDE_K_GATE_UP  3   /* grouped gate/up GEMM + SwiGLU          */
 #define TIDE_K_DOWN     4   /* grouped down GEMM                      */
 #define TIDE_K_COMBINE  5   /* weighted combine                       */
-#define TIDE_K_GATE_UP_BIG 6 /* the same two GEMMs over work items of up to 128 rows   */
+#define TIDE_K_GATE_UP_BIG 6 /* the same two GEMMs over work items of up to 256 rows   */
 #define TIDE_K_DOWN_BIG    7 /* (slots with more than 32 rows; not launched at <= 32 tokens) */
 #define TIDE_K_COUNT    8
 
 /* enable != 0: from now on every kernel launch of a step carries a start and a stop HIP
  * event that the dispatch itself stamps when it begins and ends on its stream (no extra
- * packets between the kernels).  Synchronises the device and drops earlier samples. */
+ * packets between the kernels); enable == 2: only the expert GEMM launches (TIDE_K_GATE_UP,
+ * TIDE_K_DOWN and their _BIG forms) do, which costs the host a fifth of the bookkeeping per step.
+ * Synchronises the device and drops earlier samples. */
 int tide_profile(tide_ctx* ctx, int enable);
 /* Waits for the device, then writes per kernel id the summed start-to-stop time in
  * milliseconds (ms_sum_host[TIDE_K_COUNT]) and the number of launches

@@ -25,6 +25,7 @@ EXPORTS = [
     "tide_refresh_copy_ms", "tide_profile", "tide_profile_read", "tide_counters", "tide_moe_apply_misses",
     "tide_step_histogram", "tide_routing_stability", "tide_interval_costs", "tide_optimal_interval", "tide_fit_drift", "tide_scale_counts", "tide_refresh_deferred", "tide_commit",
     "tide_host_experts", "tide_moe_apply_misses_host", "tide_host_miss_ms", "tide_host_expert", "tide_host_link_share", "tide_host_misses",
+    "tide_compressed_blob_bytes", "tide_compress_expert", "tide_register_compressed",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -65,6 +66,10 @@ def _load() -> C.CDLL:
     lib.tide_expert_blob_bytes.argtypes = [cfgp]
     lib.tide_expert_blob_bytes.restype = C.c_uint64
     lib.tide_pack_expert.argtypes = [cfgp, vp, vp, vp, vp]
+    lib.tide_compressed_blob_bytes.argtypes = [cfgp]
+    lib.tide_compressed_blob_bytes.restype = C.c_uint64
+    lib.tide_compress_expert.argtypes = [cfgp, vp, vp]
+    lib.tide_register_compressed.argtypes = [vp, C.c_int, vp, C.c_uint64]
     lib.tide_register_experts.argtypes = [vp, C.c_int, vp, C.c_uint64]
     lib.tide_set_shared.argtypes = [vp, C.c_int, vp]
     lib.tide_set_resident.argtypes = [vp, C.c_int, vp, C.c_int]
@@ -96,7 +101,7 @@ def _load() -> C.CDLL:
     lib.tide_optimal_interval.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, vp, C.POINTER(C.c_int),
                                           C.POINTER(C.c_double)]
     for name in EXPORTS:
-        if name not in ("tide_last_error", "tide_expert_blob_bytes"):
+        if name not in ("tide_last_error", "tide_expert_blob_bytes", "tide_compressed_blob_bytes"):
             getattr(lib, name).restype = C.c_int
     return lib
 
@@ -140,6 +145,19 @@ def tide_pack_expert(cfg: tide_config, wg: np.ndarray, wu: np.ndarray, wd: np.nd
     assert wd.dtype == np.uint16 and wd.shape == (cfg.d, cfg.d_ff)
     _check(lib.tide_pack_expert(C.byref(cfg), _ptr(np.ascontiguousarray(wg)), _ptr(np.ascontiguousarray(wu)),
                                 _ptr(np.ascontiguousarray(wd)), _ptr(blob)), None)
+
+
+def tide_compressed_blob_bytes(cfg: tide_config) -> int:
+    return int(lib.tide_compressed_blob_bytes(C.byref(cfg)))
+
+
+def tide_compress_expert(cfg: tide_config, blob, comp) -> None:
+    """packed blob (host uint8 buffer) -> its 12-bit form (host uint8 buffer of tide_compressed_blob_bytes)."""
+    _check(lib.tide_compress_expert(C.byref(cfg), _ptr(blob), _ptr(comp)), None)
+
+
+def tide_register_compressed(ctx, layer: int, comp_blobs, comp_stride: int) -> None:
+    _check(lib.tide_register_compressed(ctx, layer, _ptr(comp_blobs), comp_stride), ctx)
 
 
 def tide_create(cfg: tide_config) -> int:
@@ -266,7 +284,8 @@ def tide_read_slot(ctx, layer: int, slot: int, blob_bytes: int) -> np.ndarray:
     return b
 
 
-def tide_profile(ctx, enable: bool) -> None:
+def tide_profile(ctx, enable) -> None:
+    """False/0 off, True/1 every kernel of a step, 2 the expert GEMM kernels only."""
     _check(lib.tide_profile(ctx, int(enable)), ctx)
 
 

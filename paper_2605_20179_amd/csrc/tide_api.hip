@@ -13,6 +13,7 @@
 #include <chrono>
 
 #include "host_experts.h"
+#include "packed12.h"
 #include "tide_internal.h"
 
 using namespace tide;
@@ -29,6 +30,8 @@ struct Layer {
     uint16_t* slots_owned = nullptr;     // capacity+1 blobs
     const uint8_t* host_blobs = nullptr;
     uint64_t host_stride = 0;
+    const uint8_t* comp_blobs = nullptr;  // optional 12-bit form of the same blobs: the source of refresh copies
+    uint64_t comp_stride = 0;
     bool shared_set = false;
     bool placed = false;
     hipEvent_t copies_begin = nullptr, copies_done = nullptr;
@@ -59,7 +62,7 @@ struct tide_ctx {
     int max_rows = 0, max_tasks = 0;
     std::string err;
     // optional per-kernel timing: every kernel launch of a step stamps a start and a stop event
-    bool profiling = false;
+    int profiling = 0;                      // 0 off, 1 every kernel of a step, 2 the expert GEMM kernels only
     std::vector<hipEvent_t> prof_pool;      // created on demand, reused
     size_t prof_used = 0;
     std::vector<std::pair<int, std::pair<hipEvent_t, hipEvent_t>>> prof_spans;   // (kernel id, begin, end)
@@ -114,7 +117,8 @@ hipEvent_t prof_event(tide_ctx* ctx) {
 template <typename F>
 hipError_t timed(tide_ctx* ctx, int kernel_id, F&& launch) {
     LaunchEvents ev;
-    if (!ctx->profiling) return launch(ev);
+    const bool gemm = kernel_id == TIDE_K_GATE_UP || kernel_id == TIDE_K_DOWN || kernel_id == TIDE_K_GATE_UP_BIG || kernel_id == TIDE_K_DOWN_BIG;
+    if (!ctx->profiling || (ctx->profiling == 2 && !gemm)) return launch(ev);
     ev.start = prof_event(ctx);
     ev.stop = prof_event(ctx);
     if (!ev.start || !ev.stop) return hipErrorOutOfMemory;
@@ -418,6 +422,92 @@ int tide_register_experts(tide_ctx* ctx, int layer, const void* host_blobs, uint
     }
     ctx->layers[layer].host_blobs = static_cast<const uint8_t*>(host_blobs);
     ctx->layers[layer].host_stride = blob_stride;
+    return TIDE_OK;
+}
+
+uint64_t tide_compressed_blob_bytes(const tide_config* cfg) {
+    if (!cfg) return 0;
+    return p12_layout(tide_expert_blob_bytes(cfg) / 1024).bytes;
+}
+
+int tide_compress_expert(const tide_config* cfg, const void* blob_host, void* comp_host) {
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    if (!blob_host || !comp_host) return fail(nullptr, TIDE_E_INVAL, "null matrix or blob pointer");
+    const uint32_t n_tiles = (uint32_t)(tide_expert_blob_bytes(cfg) / 1024);
+    const P12Layout lay = p12_layout(n_tiles);
+    uint8_t* out = static_cast<uint8_t*>(comp_host);
+    memset(out, 0, lay.bytes);
+    P12Header* h = reinterpret_cast<P12Header*>(out);
+    h->magic = kP12Magic;
+    h->n_tiles = n_tiles;
+    const uint16_t* src = static_cast<const uint16_t*>(blob_host);
+    uint32_t* exc_idx = reinterpret_cast<uint32_t*>(out + lay.off_exc_idx);
+    uint16_t* exc_val = reinterpret_cast<uint16_t*>(out + lay.off_exc_val);
+    uint32_t n_exc = 0;
+    for (uint32_t t = 0; t < n_tiles && !h->raw; ++t) {
+        const uint16_t* tile = src + (uint64_t)t * 512;
+        // base: the top of the 16-binade window that holds the most elements of the tile (the highest such window)
+        uint32_t hist[256 + 16] = {0};
+        for (int i = 0; i < 512; ++i) hist[(tile[i] >> 7) & 0xff]++;
+        uint32_t base = 15, in_window = 0, best = 0;
+        for (uint32_t e = 0; e < 16; ++e) in_window += hist[e];
+        best = in_window;
+        for (uint32_t top = 16; top < 256; ++top) {
+            in_window += hist[top] - hist[top - 16];
+            if (in_window >= best) { best = in_window; base = top; }
+        }
+        out[lay.off_base + t] = (uint8_t)base;
+        uint32_t* words = reinterpret_cast<uint32_t*>(out + lay.off_payload + (uint64_t)t * kP12TileBytes);
+        for (int l = 0; l < 64; ++l) {
+            uint32_t code[8];
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t v = tile[l * 8 + j], e = (v >> 7) & 0xff;
+                uint32_t delta = base - e;             // wraps for an exponent above the window
+                if (delta > 15) {                      // outside the tile's 16-binade window: listed
+                    if (n_exc == n_tiles) { h->raw = 1; break; }
+                    exc_idx[n_exc] = t * 512 + l * 8 + j;
+                    exc_val[n_exc++] = (uint16_t)v;
+                    delta = 15;
+                }
+                code[j] = ((v >> 15) << 11) | (delta << 7) | (v & 0x7f);
+            }
+            if (h->raw) break;
+            words[l * 3 + 0] = code[0] | (code[1] << 12) | ((code[2] & 0xff) << 24);
+            words[l * 3 + 1] = (code[2] >> 8) | (code[3] << 4) | (code[4] << 16) | ((code[5] & 0xf) << 28);
+            words[l * 3 + 2] = (code[5] >> 4) | (code[6] << 8) | (code[7] << 20);
+        }
+    }
+    h->n_exc = h->raw ? 0 : n_exc;
+    return TIDE_OK;
+}
+
+int tide_register_compressed(tide_ctx* ctx, int layer, const void* comp_host_blobs, uint64_t comp_stride) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    Layer& L = ctx->layers[layer];
+    if (!comp_host_blobs) {                               // back to the raw blobs
+        TIDE_HIP(ctx, hipDeviceSynchronize());
+        L.comp_blobs = nullptr;
+        return TIDE_OK;
+    }
+    if (!L.host_blobs) return fail(ctx, TIDE_E_STATE, "layer %d: register the raw blobs first (tide_register_experts)", layer);
+    if (comp_stride < tide_compressed_blob_bytes(&ctx->cfg) || (comp_stride & 63) || ((uintptr_t)comp_host_blobs & 63))
+        return fail(ctx, TIDE_E_INVAL, "comp_stride must be >= the compressed size; base and stride 64-byte aligned");
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, comp_host_blobs) != hipSuccess || attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr) {
+        (void)hipGetLastError();
+        return fail(ctx, TIDE_E_INVAL, "comp_host_blobs must be pinned host memory");
+    }
+    const uint32_t n_tiles = (uint32_t)(tide_expert_blob_bytes(&ctx->cfg) / 1024);
+    for (int e = 0; e < ctx->cfg.n_experts; ++e) {
+        const P12Header* h = reinterpret_cast<const P12Header*>(static_cast<const uint8_t*>(comp_host_blobs) + (uint64_t)e * comp_stride);
+        if (h->magic != kP12Magic || h->n_tiles != n_tiles || h->n_exc > n_tiles || h->raw > 1)
+            return fail(ctx, TIDE_E_INVAL, "expert %d: not a compressed blob of this configuration (tide_compress_expert)", e);
+    }
+    TIDE_HIP(ctx, hipDeviceSynchronize());
+    L.comp_blobs = static_cast<const uint8_t*>(comp_host_blobs);
+    L.comp_stride = comp_stride;
     return TIDE_OK;
 }
 
@@ -736,8 +826,12 @@ int refresh_impl(tide_ctx* ctx, int layer, const int32_t* counts_host, int capac
     TIDE_HIP(ctx, hipStreamSynchronize(stream));
     const int n = L.plan->n_copies;
     TIDE_HIP(ctx, hipEventRecord(L.copies_begin, ctx->side));
-    TIDE_HIP(ctx, launch_refresh_copies(L.host_blobs, L.host_stride, bytes,
-                                        deferred ? L.staging : reinterpret_cast<uint8_t*>(L.slots_owned), L.plan, n, deferred, ctx->side));
+    uint8_t* copy_dst = deferred ? L.staging : reinterpret_cast<uint8_t*>(L.slots_owned);
+    if (L.comp_blobs)
+        TIDE_HIP(ctx, launch_refresh_copies_p12(L.comp_blobs, L.comp_stride, L.host_blobs, L.host_stride, bytes, copy_dst, L.plan, n,
+                                                deferred, ctx->side));
+    else
+        TIDE_HIP(ctx, launch_refresh_copies(L.host_blobs, L.host_stride, bytes, copy_dst, L.plan, n, deferred, ctx->side));
     for (int i = 0; i < n; ++i) {
         const int e = L.plan->expert[i], s = L.plan->slot[i];
         if (plan_out) {
@@ -829,9 +923,19 @@ int tide_read_slot(tide_ctx* ctx, int layer, int slot, void* blob_host) {
 int tide_profile(tide_ctx* ctx, int enable) {
     if (!ctx) return TIDE_E_INVAL;
     TIDE_HIP(ctx, hipDeviceSynchronize());
-    ctx->profiling = enable != 0;
+    ctx->profiling = enable == 2 ? 2 : (enable != 0 ? 1 : 0);
     ctx->prof_spans.clear();
     ctx->prof_used = 0;
+    // events for 512 steps are made here, not inside the region being measured (more are made on demand)
+    if (ctx->profiling) {
+        const size_t want = (size_t)512 * 2 * TIDE_K_COUNT;
+        ctx->prof_spans.reserve(want / 2);
+        while (ctx->prof_pool.size() < want) {
+            hipEvent_t e = nullptr;
+            TIDE_HIP(ctx, hipEventCreate(&e));
+            ctx->prof_pool.push_back(e);
+        }
+    }
     return TIDE_OK;
 }
 

@@ -59,6 +59,7 @@ def main():
     ap.add_argument("--taus", default="1,2,4,8,16")
     ap.add_argument("--miss-path", choices=("device", "host"), default="host")
     ap.add_argument("--host-threads", type=int, default=16)
+    ap.add_argument("--refresh-source", choices=("raw", "packed12"), default="packed12")
     args = ap.parse_args()
     import torch
     import tide_inputs as ti
@@ -71,6 +72,8 @@ def main():
     t0 = time.time()
     sess.load_layer(0, lambda e: ti.expert_weights(wl, args.layer, e), ti.router_weights(wl, args.layer),
                     ti.router_bias(wl, args.layer), ti.initial_resident(wl), workers=16)
+    if args.refresh_source == "packed12":
+        sess.compress_layer(0, workers=16)
     hidden = [sess.to_device_bf16(h) for h in ti.hidden_stream(wl, args.layer)]
     T, B, pairs = len(hidden), wl.C, wl.N * wl.k
     print("loaded %s layer %d in %.1f s: T=%d steps, budget %d, %d pairs per step" % (wl.name, args.layer, time.time() - t0, T, B, pairs),
@@ -114,7 +117,7 @@ def main():
     for r in rows:
         r["measured_total_ms"] = r["copy_ms"] + r["miss_ms"]
     best = min(rows, key=lambda r: (r["measured_total_ms"], r["tau"]))
-    out = dict(workload=wl.name, miss_path=args.miss_path, measured_best_tau=best["tau"],
+    out = dict(workload=wl.name, miss_path=args.miss_path, refresh_source=args.refresh_source, measured_best_tau=best["tau"],
                measured_best_ms=best["measured_total_ms"], steps=T, budget=B, adjacent_similarity=float(np.mean([sim_h[t, t + 1] for t in range(T - 1)])),
                similarity_5_apart=float(np.mean([sim_h[t, t + 5] for t in range(T - 5)])),
                distinct_experts=[int(uniq.min().item()), int(uniq.max().item())], drift_eq4=d_eq4, drift_model=d_model,

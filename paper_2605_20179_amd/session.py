@@ -55,6 +55,19 @@ class TideSession:
             tb.tide_pack_expert(self.cfg, *expert_bits(self.E), sh)
         return blobs, sh
 
+    def compress_layer(self, layer: int, workers: int = 8) -> None:
+        """Builds the 12-bit form of the layer's registered blobs in pinned memory and makes it the source of
+        the layer's refresh copies (3/4 of the bytes over the host link, slots bit-identical)."""
+        comp_bytes = tb.tide_compressed_blob_bytes(self.cfg)
+        comp = torch.empty((self.E, comp_bytes), dtype=torch.uint8, pin_memory=True)
+        raw, out = self.host_blobs[layer].numpy(), comp.numpy()
+        with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as ex:
+            list(ex.map(lambda e: tb.tide_compress_expert(self.cfg, raw[e], out[e]), range(self.E)))
+        if not hasattr(self, "comp_blobs"):
+            self.comp_blobs = {}
+        self.comp_blobs[layer] = comp
+        tb.tide_register_compressed(self.ctx, layer, comp, comp_bytes)
+
     def load_layer(self, layer: int, expert_bits: Optional[ExpertBits], router_w: np.ndarray,
                    router_bias: Optional[np.ndarray], resident: Sequence[int], workers: int = 8, packed=None) -> None:
         blobs, sh = packed if packed is not None else self.pack_layer(expert_bits, workers)

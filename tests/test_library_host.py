@@ -143,6 +143,62 @@ def test_host_miss_path_matches_the_oracle(tb, n_tokens, n_experts, k, threads, 
     assert ei.value.code == tb.TIDE_E_INVAL and np.array_equal(again, base)
 
 
+def _p12_decode(comp: np.ndarray, n_tiles: int) -> np.ndarray:
+    """Decoder written from the format's description in include/tide.h and csrc/packed12.h, independent of the
+    library: header, one base exponent per tile, 12-bit elements (sign | base - exponent | mantissa) packed low bits
+    first, then the listed exceptions."""
+    hdr = comp[:64].view(np.uint32)
+    assert hdr[0] == 0x32315054 and hdr[1] == n_tiles
+    off_base = 64
+    off_payload = off_base + (n_tiles + 63) // 64 * 64
+    off_idx = off_payload + n_tiles * 768
+    off_val = off_idx + n_tiles * 4
+    base = comp[off_base:off_base + n_tiles].astype(np.int64)
+    payload = comp[off_payload:off_idx].reshape(-1, 3)                       # 3 bytes = 2 elements
+    two = payload[:, 0].astype(np.int64) | (payload[:, 1].astype(np.int64) << 8) | (payload[:, 2].astype(np.int64) << 16)
+    code = np.stack([two & 0xfff, two >> 12], axis=1).reshape(n_tiles, 512)
+    e = np.maximum(base[:, None] - ((code >> 7) & 15), 0)
+    vals = (((code >> 11) << 15) | (e << 7) | (code & 0x7f)).astype(np.uint16).reshape(-1)
+    n_exc = int(hdr[2])
+    idx = comp[off_idx:off_idx + 4 * n_exc].view(np.uint32)
+    vals[idx] = comp[off_val:off_val + 2 * n_exc].view(np.uint16)
+    return vals
+
+
+def test_compressed_blob_round_trip(tb):
+    """The 12-bit refresh source is lossless: decoding it (here, by hand) gives back the packed blob bit for bit,
+    for Gaussian weights, for weights with zeros / denormals / tiny values (exceptions), and an expert whose
+    exponents are spread too widely is marked raw instead."""
+    d, I = 256, 128
+    cfg = tb.make_config(d, 8, 2, I, 0, 1, 4, 8, 0, 0)
+    n_tiles = 3 * d * I // 512
+    cbytes = tb.tide_compressed_blob_bytes(cfg)
+    assert cbytes % 64 == 0 and cbytes < 0.77 * tb.tide_expert_blob_bytes(cfg)
+    rng = np.random.default_rng(12)
+    def bits(shape, scale):
+        return (np.ascontiguousarray(rng.normal(0, scale, size=shape), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    blob = np.zeros(tb.tide_expert_blob_bytes(cfg), dtype=np.uint8)
+    comp = np.zeros(cbytes, dtype=np.uint8)
+    # Gaussian weights
+    tb.tide_pack_expert(cfg, bits((I, d), 0.02), bits((I, d), 0.02), bits((d, I), 0.02), blob)
+    tb.tide_compress_expert(cfg, blob, comp)
+    hdr = comp[:64].view(np.uint32)
+    assert hdr[3] == 0 and hdr[2] < n_tiles // 4
+    assert np.array_equal(_p12_decode(comp, n_tiles), blob.view(np.uint16))
+    # zeros, negative zeros, denormals, tiny and huge values, infinities and NaNs sprinkled in (all exceptions)
+    raw = blob.view(np.uint16).copy()
+    at = rng.choice(raw.size, size=60, replace=False)
+    raw[at] = np.resize(np.array([0x0000, 0x8000, 0x0001, 0x807f, 0x0080, 0x7f7f, 0xff80, 0x7fc1, 0x1234, 0x3f80], dtype=np.uint16), 60)
+    tb.tide_compress_expert(cfg, raw.view(np.uint8), comp)
+    hdr = comp[:64].view(np.uint32)
+    assert hdr[3] == 0 and hdr[2] >= 6
+    assert np.array_equal(_p12_decode(comp, n_tiles), raw)
+    # exponents all over the range: more exceptions than the list holds -> marked raw
+    wild = rng.integers(0, 2 ** 16, size=raw.size, dtype=np.uint16)
+    tb.tide_compress_expert(cfg, wild.view(np.uint8), comp)
+    assert comp[:64].view(np.uint32)[3] == 1
+
+
 def test_config_validation_and_no_device(tb):
     ok = dict(d=256, n_experts=16, top_k=2, d_ff=128, n_shared=0, n_layers=1, capacity=8, max_tokens=8, gating=0, bias_mode=0)
     blob = np.zeros(3 * 256 * 128 * 2, dtype=np.uint8)
