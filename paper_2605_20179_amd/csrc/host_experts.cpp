@@ -263,8 +263,13 @@ Isa detect_isa() {
     return bf16 ? kAvx512Bf16 : avx2 ? kAvx2 : kGeneric;
 }
 
-void run_part(const PartArgs& a) {
+Isa host_isa() {
     static const Isa isa = detect_isa();
+    return isa;
+}
+
+void run_part(const PartArgs& a) {
+    const Isa isa = host_isa();
     if (isa == kAvx512Bf16) part_bf16(a);
     else if (isa == kAvx2) part_avx2(a);
     else part_generic(a);
@@ -376,7 +381,7 @@ void host_expert_forward(const void* blob, int d, int d_ff, const uint16_t* x, i
     std::vector<const float*> xp(m);
     std::vector<const uint16_t*> xbp(m);
     for (int t = 0; t < m; ++t) {
-        bf16_row_to_f32(x + (int64_t)t * d, xf.data() + (int64_t)t * d, d);
+        if (host_isa() != kAvx512Bf16) bf16_row_to_f32(x + (int64_t)t * d, xf.data() + (int64_t)t * d, d);
         xp[t] = xf.data() + (int64_t)t * d;
         xbp[t] = x + (int64_t)t * d;
     }
@@ -434,7 +439,8 @@ int host_apply_misses(HostPool* p, const uint8_t* blobs, uint64_t stride, int d,
     // fp32 copies of those tokens' states
     p->xf.resize((size_t)n_rows * d);
     float* xf = p->xf.data();
-    p->run(n_rows, [&](int r, int) { bf16_row_to_f32(x + (int64_t)tokens_out[r] * d, xf + (int64_t)r * d, d); });
+    if (host_isa() != kAvx512Bf16)          // the bf16 dot-product path reads the token states as they are
+        p->run(n_rows, [&](int r, int) { bf16_row_to_f32(x + (int64_t)tokens_out[r] * d, xf + (int64_t)r * d, d); });
     p->xptr.resize(n);
     p->xbptr.resize(n);
     for (int j = 0; j < n; ++j) {
