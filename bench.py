@@ -179,6 +179,9 @@ def main():
     ap.add_argument("--refresh-mode", choices=("immediate", "deferred"), default="immediate",
                     help="immediate: Alg. 1 as written, the refresh step's GEMMs wait for the copies (default, the headline figure); "
                          "deferred: the refresh step runs on the old placement while the copies land, the new one serves from the next step")
+    ap.add_argument("--refresh-call", choices=("sync", "async"), default="sync",
+                    help="immediate refresh through tide_refresh (the host waits for the plan, then queues the copies) or "
+                         "tide_refresh_async (everything queued at once; the plans are read after the timed region)")
     ap.add_argument("--commit-after", type=int, default=1,
                     help="deferred mode: steps that still run on the old placement before the new one is committed (1..refresh interval)")
     ap.add_argument("--tokens", type=int, default=0, help="tokens per step (0 = the workload's own; e.g. 4096 = batch 128 of block 32)")
@@ -280,14 +283,19 @@ def main():
             state["uncommitted"] = False
         if t > 0 and t % wl.K == 0:
             r0 = time.perf_counter()
-            _, plan = sess.refresh(0, deferred=args.refresh_mode == "deferred")
+            if args.refresh_call == "async" and args.refresh_mode == "immediate":
+                # the previous refresh's plan is read now, long after its selection ran: no wait
+                plan = sess.refresh_result(0)[1] if state.get("result_due") else []
+                sess.refresh_async(0)
+                state["result_due"] = timed
+            else:
+                _, plan = sess.refresh(0, deferred=args.refresh_mode == "deferred")
             state["uncommitted"] = args.refresh_mode == "deferred"
             state["commit_at"] = state["t"] + args.commit_after
             if timed:
                 state["refresh_s"] += time.perf_counter() - r0
                 state["copies"] += len(plan)
                 state["refreshes"] += 1
-                state["pending_copy_timing"] = bool(plan)
         sess.step(0, hidden[t], want_topk=False)
         state["t"] += 1
 
@@ -307,6 +315,9 @@ def main():
         state["uncommitted"] = False
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    if state.get("result_due"):                     # the last asynchronous refresh's plan (outside the timed region)
+        state["copies"] += len(sess.refresh_result(0)[1])
+        state["result_due"] = False
 
     prof = tb.tide_profile_read(sess.ctx) if not args.no_kernel_events else {}
     tb.tide_profile(sess.ctx, False)
@@ -478,7 +489,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "d": wl.d, "experts": wl.E, "top_k": wl.k, "d_ff": wl.I, "shared_experts": wl.n_shared,
                    "tokens_per_step": wl.N, "capacity": wl.C, "refresh_interval": wl.K, "steps_per_block": wl.S, "layers": 1,
-                   "refresh_source": args.refresh_source,
+                   "refresh_source": args.refresh_source, "refresh_call": args.refresh_call,
                    "refresh_mode": args.refresh_mode if args.refresh_mode == "immediate" else "deferred by %d step(s)" % args.commit_after},
         "roofline": roofline,
         "detail": {

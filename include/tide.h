@@ -257,6 +257,19 @@ int tide_interval_stats(tide_ctx* ctx, int layer, int32_t* counts_host, int rese
 int tide_refresh(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,
                  int32_t* resident_out, tide_copy* plan_out, int* n_copies_out, void* hip_stream);
 
+/* The same refresh without the host round trip: selection, plan, counter reset and copies are queued and the call
+ * returns at once.  Nothing on the host needs the plan to queue the copies -- the copy kernel reads the plan, and
+ * how many copies it holds, from the pinned block the selection kernel writes -- so hip_stream is NOT synchronised;
+ * the side stream waits (on the device) for the selection, i.e. for every earlier step queued on hip_stream.
+ * The placement, the tables, the next step's wait for the copies: as tide_refresh.  counts_host, if given, must
+ * stay valid until the call returns.  The new resident set and the plan are read later with tide_refresh_result. */
+int tide_refresh_async(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,
+                       void* hip_stream);
+/* resident_out / plan_out / n_copies_out of the layer's last refresh (any of the three forms), as tide_refresh
+ * returns them; after tide_refresh_async it first waits for that refresh's selection kernel.  Valid until the
+ * layer's next refresh.  TIDE_E_STATE if the layer has not been refreshed. */
+int tide_refresh_result(tide_ctx* ctx, int layer, int32_t* resident_out, tide_copy* plan_out, int* n_copies_out);
+
 /* The same refresh with its effect deferred, so that the host-link copies overlap with the steps that
  * follow instead of holding up the next one: the selection, the plan, the counter reset and the copies are
  * as above, but the newcomers land in staging blobs owned by the layer (allocated on first use: `ctx

@@ -26,6 +26,7 @@ EXPORTS = [
     "tide_step_histogram", "tide_routing_stability", "tide_interval_costs", "tide_optimal_interval", "tide_fit_drift", "tide_scale_counts", "tide_refresh_deferred", "tide_commit",
     "tide_host_experts", "tide_moe_apply_misses_host", "tide_host_miss_ms", "tide_host_expert", "tide_host_link_share", "tide_host_misses",
     "tide_compressed_blob_bytes", "tide_compress_expert", "tide_register_compressed",
+    "tide_refresh_async", "tide_refresh_result",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -85,6 +86,8 @@ def _load() -> C.CDLL:
     lib.tide_interval_stats.argtypes = [vp, C.c_int, vp, C.c_int, vp]
     lib.tide_refresh.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, vp, vp, C.POINTER(C.c_int), vp]
     lib.tide_refresh_deferred.argtypes = lib.tide_refresh.argtypes
+    lib.tide_refresh_async.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, vp]
+    lib.tide_refresh_result.argtypes = [vp, C.c_int, vp, vp, C.POINTER(C.c_int)]
     lib.tide_commit.argtypes = [vp, C.c_int, vp]
     lib.tide_wait_refresh.argtypes = [vp, C.c_int]
     lib.tide_get_table.argtypes = [vp, C.c_int, vp, vp]
@@ -259,6 +262,21 @@ def tide_refresh(ctx, layer: int, ctx_capacity: int, capacity: int, counts: Opti
     fn = lib.tide_refresh_deferred if deferred else lib.tide_refresh
     _check(fn(ctx, layer, _ptr(cnt), capacity, int(reset_counts), _ptr(resident),
               C.cast(plan, C.c_void_p), C.byref(n), _stream_ptr(stream)), ctx)
+    return resident, [(plan[i].expert, plan[i].slot, plan[i].host_offset, plan[i].bytes) for i in range(n.value)]
+
+
+def tide_refresh_async(ctx, layer: int, capacity: int, counts: Optional[np.ndarray] = None, reset_counts: bool = True,
+                       stream=None) -> None:
+    cnt = None if counts is None else np.ascontiguousarray(np.asarray(counts, dtype=np.int32))
+    _check(lib.tide_refresh_async(ctx, layer, _ptr(cnt), capacity, int(reset_counts), _stream_ptr(stream)), ctx)
+
+
+def tide_refresh_result(ctx, layer: int, ctx_capacity: int):
+    """(expert_in_slot, plan) of the layer's last refresh, as tide_refresh returns them."""
+    resident = np.full(ctx_capacity, -1, dtype=np.int32)
+    plan = (tide_copy * max(ctx_capacity, 1))()
+    n = C.c_int(0)
+    _check(lib.tide_refresh_result(ctx, layer, _ptr(resident), C.cast(plan, C.c_void_p), C.byref(n)), ctx)
     return resident, [(plan[i].expert, plan[i].slot, plan[i].host_offset, plan[i].bytes) for i in range(n.value)]
 
 

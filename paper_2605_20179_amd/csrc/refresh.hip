@@ -129,6 +129,7 @@ __global__ __launch_bounds__(kCopyThreads) void refresh_copy_kernel(const uint8_
                                                                    const RefreshOut* __restrict__ plan, int n, int dst_by_rank) {
     const uint64_t per_blob = blob_bytes / 16;
     const uint64_t stride = (uint64_t)gridDim.x * kCopyThreads;
+    if (n < 0) n = plan->n_copies;             // queued without the host knowing the plan
     for (int i = 0; i < n; ++i) {
         const uint4* src = reinterpret_cast<const uint4*>(host_blobs + (uint64_t)plan->expert[i] * host_stride);
         uint4* dst = reinterpret_cast<uint4*>(dst_base + (uint64_t)(dst_by_rank ? i : plan->slot[i]) * blob_bytes);
@@ -180,6 +181,7 @@ __global__ __launch_bounds__(kCopyThreads) void refresh_copy_p12_kernel(const ui
     const uint32_t wave = (blockIdx.x * kCopyThreads + threadIdx.x) >> 6, n_waves = gridDim.x * (kCopyThreads / 64);
     const uint32_t n_tiles = (uint32_t)(blob_bytes / 1024);
     const P12Layout lay = p12_layout(n_tiles);
+    if (n < 0) n = plan->n_copies;             // queued without the host knowing the plan
     for (int i = 0; i < n; ++i) {
         const uint8_t* comp = comp_blobs + (uint64_t)plan->expert[i] * comp_stride;
         uint8_t* dst = dst_base + (uint64_t)(dst_by_rank ? i : plan->slot[i]) * blob_bytes;
@@ -216,6 +218,7 @@ __global__ __launch_bounds__(256) void refresh_patch_p12_kernel(const uint8_t* _
                                                                 uint64_t blob_bytes, uint8_t* __restrict__ dst_base,
                                                                 const RefreshOut* __restrict__ plan, int dst_by_rank) {
     const int i = blockIdx.x;
+    if (i >= plan->n_copies) return;
     const uint8_t* comp = comp_blobs + (uint64_t)plan->expert[i] * comp_stride;
     const P12Header* h = reinterpret_cast<const P12Header*>(comp);
     if (h->raw) return;
@@ -239,7 +242,7 @@ __global__ void scale_counts_kernel(int32_t* hits, int n, int num, int den) {
 
 hipError_t launch_refresh_copies(const uint8_t* host_blobs, uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base,
                                  const RefreshOut* plan, int n, bool dst_by_rank, hipStream_t stream) {
-    if (n <= 0) return hipSuccess;
+    if (n == 0) return hipSuccess;
     hipLaunchKernelGGL(refresh_copy_kernel, dim3(kCopyBlocks), dim3(kCopyThreads), 0, stream, host_blobs, host_stride,
                        blob_bytes, dst_base, plan, n, dst_by_rank ? 1 : 0);
     return hipGetLastError();
@@ -247,11 +250,11 @@ hipError_t launch_refresh_copies(const uint8_t* host_blobs, uint64_t host_stride
 
 hipError_t launch_refresh_copies_p12(const uint8_t* comp_blobs, uint64_t comp_stride, const uint8_t* host_blobs,
                                      uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base, const RefreshOut* plan, int n,
-                                     bool dst_by_rank, hipStream_t stream) {
-    if (n <= 0) return hipSuccess;
+                                     int max_n, bool dst_by_rank, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
     hipLaunchKernelGGL(refresh_copy_p12_kernel, dim3(kCopyBlocks), dim3(kCopyThreads), 0, stream, comp_blobs, comp_stride,
                        host_blobs, host_stride, blob_bytes, dst_base, plan, n, dst_by_rank ? 1 : 0);
-    hipLaunchKernelGGL(refresh_patch_p12_kernel, dim3(n), dim3(256), 0, stream, comp_blobs, comp_stride, blob_bytes, dst_base,
+    hipLaunchKernelGGL(refresh_patch_p12_kernel, dim3(n < 0 ? max_n : n), dim3(256), 0, stream, comp_blobs, comp_stride, blob_bytes, dst_base,
                        plan, dst_by_rank ? 1 : 0);
     return hipGetLastError();
 }

@@ -35,6 +35,8 @@ struct Layer {
     bool shared_set = false;
     bool placed = false;
     hipEvent_t copies_begin = nullptr, copies_done = nullptr;
+    hipEvent_t select_done = nullptr;    // the plan of the last refresh is in pinned memory
+    bool result_pending = false;         // tide_refresh_async: the plan has not been read by the host yet
     bool copies_pending = false;         // a step must wait on copies_done before its GEMMs
     bool copies_recorded = false;
     RefreshOut* plan = nullptr;          // pinned, device-visible
@@ -370,7 +372,8 @@ int tide_create(const tide_config* cfg, tide_ctx** out) {
             return bail(fail(ctx, TIDE_E_HIP, "hipMemset failed"));
         if ((rc = ws_alloc(ctx, &L.slots_owned, (int64_t)(s.capacity + 1) * s.blob_elems))) return bail(rc);
         L.t.hits = hits; L.t.slot_of = slot_of; L.t.expert_in_slot = eis; L.t.slots = L.slots_owned;
-        if (hipEventCreate(&L.copies_begin) != hipSuccess || hipEventCreate(&L.copies_done) != hipSuccess)
+        if (hipEventCreate(&L.copies_begin) != hipSuccess || hipEventCreate(&L.copies_done) != hipSuccess ||
+            hipEventCreateWithFlags(&L.select_done, hipEventDisableTiming) != hipSuccess)
             return bail(fail(ctx, TIDE_E_HIP, "event"));
         void* plan = nullptr;
         if (hipHostMalloc(&plan, sizeof(RefreshOut), hipHostMallocDefault) != hipSuccess) return bail(fail(ctx, TIDE_E_NOMEM, "pinned plan buffer"));
@@ -388,6 +391,7 @@ int tide_destroy(tide_ctx* ctx) {
     for (Layer& L : ctx->layers) {
         if (L.copies_begin) (void)hipEventDestroy(L.copies_begin);
         if (L.copies_done) (void)hipEventDestroy(L.copies_done);
+        if (L.select_done) (void)hipEventDestroy(L.select_done);
         if (L.plan) (void)hipHostFree(L.plan);
         if (L.staging) (void)hipFree(L.staging);
         if (L.pend_slot_of) (void)hipFree(L.pend_slot_of);
@@ -782,7 +786,8 @@ namespace {
 // newcomers are copied into staging blobs, and the layer keeps serving from the old placement until
 // tide_commit moves the staged blobs into their slots and swaps the tables.
 int refresh_impl(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,
-                 int32_t* resident_out, tide_copy* plan_out, int* n_copies_out, void* hip_stream, bool deferred) {
+                 int32_t* resident_out, tide_copy* plan_out, int* n_copies_out, void* hip_stream, bool deferred,
+                 bool async = false) {
     int rc = layer_ok(ctx, layer);
     if (rc) return rc;
     if (capacity < 0 || capacity > ctx->cfg.capacity) return fail(ctx, TIDE_E_RANGE, "capacity %d outside 0..%d", capacity, ctx->cfg.capacity);
@@ -821,17 +826,33 @@ int refresh_impl(tide_ctx* ctx, int layer, const int32_t* counts_host, int capac
         sel.expert_in_slot = L.pend_eis;
     }
     TIDE_HIP(ctx, launch_refresh_select(ctx->shape, sel, counts, capacity, reset_counts, L.plan, stream));
-    // the plan is needed here to queue the copies; this also means every earlier step that
-    // could still read a slot (or a staging blob) about to be overwritten has finished
-    TIDE_HIP(ctx, hipStreamSynchronize(stream));
-    const int n = L.plan->n_copies;
-    TIDE_HIP(ctx, hipEventRecord(L.copies_begin, ctx->side));
     uint8_t* copy_dst = deferred ? L.staging : reinterpret_cast<uint8_t*>(L.slots_owned);
+    int n = -1;
+    if (async) {
+        // nothing here needs the plan on the host: the copy kernels read it, and the number of copies, from the pinned
+        // block the selection wrote.  The side stream waits for the selection, hence for every earlier step that could
+        // still read a slot about to be overwritten.
+        TIDE_HIP(ctx, hipEventRecord(L.select_done, stream));
+        TIDE_HIP(ctx, hipStreamWaitEvent(ctx->side, L.select_done, 0));
+    } else {
+        // the plan goes back to the caller; this also means every earlier step that could still read a slot (or a
+        // staging blob) about to be overwritten has finished
+        TIDE_HIP(ctx, hipStreamSynchronize(stream));
+        n = L.plan->n_copies;
+    }
+    L.result_pending = async;
+    TIDE_HIP(ctx, hipEventRecord(L.copies_begin, ctx->side));
     if (L.comp_blobs)
         TIDE_HIP(ctx, launch_refresh_copies_p12(L.comp_blobs, L.comp_stride, L.host_blobs, L.host_stride, bytes, copy_dst, L.plan, n,
-                                                deferred, ctx->side));
+                                                ctx->cfg.capacity, deferred, ctx->side));
     else
         TIDE_HIP(ctx, launch_refresh_copies(L.host_blobs, L.host_stride, bytes, copy_dst, L.plan, n, deferred, ctx->side));
+    if (async) {
+        TIDE_HIP(ctx, hipEventRecord(L.copies_done, ctx->side));
+        L.copies_recorded = true;
+        L.copies_pending = true;
+        return TIDE_OK;
+    }
     for (int i = 0; i < n; ++i) {
         const int e = L.plan->expert[i], s = L.plan->slot[i];
         if (plan_out) {
@@ -855,6 +876,30 @@ int refresh_impl(tide_ctx* ctx, int layer, const int32_t* counts_host, int capac
 int tide_refresh(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,
                  int32_t* resident_out, tide_copy* plan_out, int* n_copies_out, void* hip_stream) {
     return refresh_impl(ctx, layer, counts_host, capacity, reset_counts, resident_out, plan_out, n_copies_out, hip_stream, false);
+}
+
+int tide_refresh_async(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts, void* hip_stream) {
+    return refresh_impl(ctx, layer, counts_host, capacity, reset_counts, nullptr, nullptr, nullptr, hip_stream, false, true);
+}
+
+int tide_refresh_result(tide_ctx* ctx, int layer, int32_t* resident_out, tide_copy* plan_out, int* n_copies_out) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    Layer& L = ctx->layers[layer];
+    if (!L.copies_recorded) return fail(ctx, TIDE_E_STATE, "no refresh has run on layer %d", layer);
+    if (L.result_pending) TIDE_HIP(ctx, hipEventSynchronize(L.select_done));
+    L.result_pending = false;
+    const int n = L.plan->n_copies;
+    const uint64_t bytes = tide_expert_blob_bytes(&ctx->cfg);
+    for (int i = 0; i < n && plan_out; ++i) {
+        plan_out[i].expert = L.plan->expert[i];
+        plan_out[i].slot = L.plan->slot[i];
+        plan_out[i].host_offset = (uint64_t)L.plan->expert[i] * L.host_stride;
+        plan_out[i].bytes = bytes;
+    }
+    if (n_copies_out) *n_copies_out = n;
+    if (resident_out) memcpy(resident_out, L.plan->expert_in_slot, ctx->cfg.capacity * sizeof(int32_t));
+    return TIDE_OK;
 }
 
 int tide_refresh_deferred(tide_ctx* ctx, int layer, const int32_t* counts_host, int capacity, int reset_counts,

@@ -159,13 +159,15 @@ struct RefreshOut {           // lives in pinned host memory the kernel writes d
 hipError_t launch_refresh_select(const Shape& s, const LayerTables& t, const int32_t* counts, int capacity,
                                  int reset_counts, RefreshOut* out_hostmapped, hipStream_t stream);
 
-// a12: the plan's blobs from pinned host memory to their slots (or to staging blob i), one kernel
+// a12: the plan's blobs from pinned host memory to their slots (or to staging blob i), one kernel.  n < 0: the
+// kernel takes the number of copies from the plan itself (the host has not seen it); the p12 form then needs
+// max_n >= that number
 hipError_t launch_refresh_copies(const uint8_t* host_blobs, uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base,
                                  const RefreshOut* plan, int n, bool dst_by_rank, hipStream_t stream);
 // the same copies from the 12-bit form of the blobs (packed12.h), rebuilt bit for bit in the destination
 hipError_t launch_refresh_copies_p12(const uint8_t* comp_blobs, uint64_t comp_stride, const uint8_t* host_blobs,
                                      uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base, const RefreshOut* plan, int n,
-                                     bool dst_by_rank, hipStream_t stream);
+                                     int max_n, bool dst_by_rank, hipStream_t stream);
 // H[e] <- floor(H[e] * num / den)
 hipError_t launch_scale_counts(int32_t* hits, int n_experts, int num, int den, hipStream_t stream);
 // interval analysis (Sec. 3.2, Eq. 4-7): similarity / distinct experts / drift on the device, cost model on the host

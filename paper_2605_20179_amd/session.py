@@ -138,6 +138,14 @@ class TideSession:
         return tb.tide_refresh(self.ctx, layer, self.C, self.C if capacity is None else capacity, counts, reset_counts,
                                torch.cuda.current_stream(), deferred=deferred)
 
+    def refresh_async(self, layer: int, capacity: Optional[int] = None, counts: Optional[np.ndarray] = None,
+                      reset_counts: bool = True) -> None:
+        tb.tide_refresh_async(self.ctx, layer, self.C if capacity is None else capacity, counts, reset_counts,
+                              torch.cuda.current_stream())
+
+    def refresh_result(self, layer: int):
+        return tb.tide_refresh_result(self.ctx, layer, self.C)
+
     def commit(self, layer: int) -> None:
         tb.tide_commit(self.ctx, layer, torch.cuda.current_stream())
 
