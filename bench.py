@@ -2,7 +2,8 @@
 """Benchmark of the TIDE MoE-step hot path on one MI355X.
 
 A "step" is one denoise step of one MoE layer: (every tau-th step) the refresh --
-top-B selection, plan, pinned-host -> HBM expert copies -- followed by tide_moe_step
+top-B selection, plan, pinned-host -> HBM expert copies (by default from the lossless 12-bit
+form of the blobs; --refresh-source raw copies them as they are) -- followed by tide_moe_step
 (router, top-k, hit counts, hit/miss split + miss list, grouped SwiGLU expert GEMMs
 over the resident experts, weighted combine).  The workload is the LLaDA2.0-mini-shaped
 single layer (block of 32 tokens, batch 1, 256 experts top-8 + shared, capacity 64,
