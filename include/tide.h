@@ -317,8 +317,10 @@ int tide_refresh_copy_ms(tide_ctx* ctx, int layer, float* ms_out);
 
 /* enable != 0: from now on every kernel launch of a step carries a start and a stop HIP
  * event that the dispatch itself stamps when it begins and ends on its stream (no extra
- * packets between the kernels); enable == 2: only the expert GEMM launches (TIDE_K_GATE_UP,
- * TIDE_K_DOWN and their _BIG forms) do, which costs the host a fifth of the bookkeeping per step.
+ * packets between the kernels).  An event-stamped launch costs the host about 15 us, so a step of
+ * five stamped launches can become host-bound; enable == 2 stamps only the expert GEMM launches
+ * (TIDE_K_GATE_UP, TIDE_K_DOWN and their _BIG forms), enable == 3 only TIDE_K_GATE_UP(_BIG) and the
+ * launch right before it (TIDE_K_TOPK / TIDE_K_DISPATCH).
  * Synchronises the device and drops earlier samples. */
 int tide_profile(tide_ctx* ctx, int enable);
 /* Waits for the device, then writes per kernel id the summed start-to-stop time in

@@ -303,7 +303,7 @@ def tide_read_slot(ctx, layer: int, slot: int, blob_bytes: int) -> np.ndarray:
 
 
 def tide_profile(ctx, enable) -> None:
-    """False/0 off, True/1 every kernel of a step, 2 the expert GEMM kernels only."""
+    """False/0 off, True/1 every kernel of a step, 2 the expert GEMM kernels only, 3 gate/up and the kernel before it."""
     _check(lib.tide_profile(ctx, int(enable)), ctx)
 
 

@@ -64,7 +64,7 @@ struct tide_ctx {
     int max_rows = 0, max_tasks = 0;
     std::string err;
     // optional per-kernel timing: every kernel launch of a step stamps a start and a stop event
-    int profiling = 0;                      // 0 off, 1 every kernel of a step, 2 the expert GEMM kernels only
+    int profiling = 0;                      // 0 off, 1 every kernel of a step, 2 the expert GEMMs, 3 gate/up and the kernel before it
     std::vector<hipEvent_t> prof_pool;      // created on demand, reused
     size_t prof_used = 0;
     std::vector<std::pair<int, std::pair<hipEvent_t, hipEvent_t>>> prof_spans;   // (kernel id, begin, end)
@@ -120,7 +120,9 @@ template <typename F>
 hipError_t timed(tide_ctx* ctx, int kernel_id, F&& launch) {
     LaunchEvents ev;
     const bool gemm = kernel_id == TIDE_K_GATE_UP || kernel_id == TIDE_K_DOWN || kernel_id == TIDE_K_GATE_UP_BIG || kernel_id == TIDE_K_DOWN_BIG;
-    if (!ctx->profiling || (ctx->profiling == 2 && !gemm)) return launch(ev);
+    const bool gate_up_and_before = kernel_id == TIDE_K_GATE_UP || kernel_id == TIDE_K_GATE_UP_BIG || kernel_id == TIDE_K_TOPK ||
+                                    kernel_id == TIDE_K_DISPATCH;
+    if (!ctx->profiling || (ctx->profiling == 2 && !gemm) || (ctx->profiling == 3 && !gate_up_and_before)) return launch(ev);
     ev.start = prof_event(ctx);
     ev.stop = prof_event(ctx);
     if (!ev.start || !ev.stop) return hipErrorOutOfMemory;
@@ -968,7 +970,7 @@ int tide_read_slot(tide_ctx* ctx, int layer, int slot, void* blob_host) {
 int tide_profile(tide_ctx* ctx, int enable) {
     if (!ctx) return TIDE_E_INVAL;
     TIDE_HIP(ctx, hipDeviceSynchronize());
-    ctx->profiling = enable == 2 ? 2 : (enable != 0 ? 1 : 0);
+    ctx->profiling = (enable == 2 || enable == 3) ? enable : (enable != 0 ? 1 : 0);
     ctx->prof_spans.clear();
     ctx->prof_used = 0;
     // events for 512 steps are made here, not inside the region being measured (more are made on demand)
