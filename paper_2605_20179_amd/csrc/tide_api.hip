@@ -221,7 +221,11 @@ int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, 
         TIDE_HIP(ctx, launch_miss_export(miss_dev, cap, n_miss_dev, x, n_tokens, ctx->cfg.d, ctx->h_miss, ctx->h_n_miss,
                                          ctx->h_hidden, ctx->aux));
         TIDE_HIP(ctx, hipEventRecord(ctx->listed_ev, ctx->aux));
-        ctx->listed_valid = true;
+        // a step recorded into a HIP graph hands its list over at every replay, but the event above then belongs to
+        // the graph: the host path must not wait on it, it queues a hand-over of its own instead
+        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+        TIDE_HIP(ctx, hipStreamIsCapturing(stream, &capturing));
+        ctx->listed_valid = capturing == hipStreamCaptureStatusNone;
         ctx->listed_miss = miss_dev;
         ctx->listed_hidden = hidden_dev;
         ctx->listed_stream = stream;

@@ -108,6 +108,45 @@ def test_host_miss_path_is_deterministic_and_thread_count_changes_only_rounding(
     sess.close()
 
 
+def test_host_miss_path_after_a_graph_replay():
+    """A step recorded into a HIP graph while host workers exist (its list hand-over is part of the graph), replayed,
+    then completed by the host path: the same full output as the eager pair of calls, replay after replay."""
+    wl = ti.CONFIGS[1].replace(S=4)
+    sess = tp._session(wl)
+    tp.load(sess, wl, 0)
+    sess.host_experts(4)
+    hidden = [sess.to_device_bf16(h) for h in ti.hidden_stream(wl, 0, 4)]
+    eager = []
+    for h in hidden:
+        sess.step(0, h)
+        sess.apply_misses_host(0, h)
+        torch.cuda.synchronize()
+        eager.append(sess.out[:wl.N].clone())
+    assert int(sess.n_miss.item()) > 0
+    static_in = hidden[0].clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sess.step(0, static_in)                       # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sess.step(0, static_in)
+    for rep in range(2):
+        for i, h in enumerate(hidden):
+            static_in.copy_(h)
+            graph.replay()
+            sess.apply_misses_host(0, static_in)
+            torch.cuda.synchronize()
+            assert torch.equal(sess.out[:wl.N], eager[i]), "replay %d step %d" % (rep, i)
+        sess.step(0, hidden[rep])                     # eager work between the rounds
+        sess.apply_misses_host(0, hidden[rep])
+        torch.cuda.synchronize()
+        assert torch.equal(sess.out[:wl.N], eager[rep])
+    sess.close()
+
+
 def test_host_miss_path_rejects_a_bad_list():
     from paper_2605_20179_amd import binding as tb
     wl = ti.CONFIGS[0]
