@@ -1,0 +1,74 @@
+"""GPU parity on a seeded sweep of random valid shapes (hidden size, experts, top-k, intermediate size, shared expert,
+tokens per step, capacity, gating and bias mode drawn at random within the library's limits): a three-step block with
+one refresh per shape, compared with the oracle as in test_gpu_parity (routing, counters, tables, plans, miss lists
+bit-exact; outputs within tolerance), then the same block with the refresh copies read from the compressed blobs and
+the misses evaluated by the host workers."""
+import numpy as np
+import pytest
+import torch
+
+import tide_inputs as ti
+import test_gpu_parity as tp
+
+pytestmark = pytest.mark.gpu
+
+
+_check_nonzero = tp.check_out
+
+
+def _check_out(out, y_ref):
+    if not np.any(y_ref):                      # e.g. one slot, no shared expert, no token routed to it
+        assert not np.any(out)
+        return 0.0
+    return _check_nonzero(out, y_ref)
+
+
+def _draw(rng):
+    d = int(rng.choice([64, 128, 192, 256, 320, 384, 512]))
+    I = int(rng.choice([64, 128, 192, 256, 320]))
+    E = int(rng.choice([1, 2, 3, 5, 8, 13, 16, 17, 31, 33, 64, 65, 100, 130, 257, 300]))
+    k = int(rng.integers(1, min(E, 16) + 1))
+    sh = int(rng.integers(0, 2))
+    N = int(rng.choice([1, 2, 15, 16, 17, 31, 32, 33, 47, 64, 100, 255, 256, 257, 300, 520]))
+    C = int(rng.integers(1, E + 1))
+    gating = int(rng.choice([ti.GATING_SOFTMAX, ti.GATING_SIGMOID]))
+    bias = int(rng.choice([ti.BIAS_NONE, ti.BIAS_LOGIT, ti.BIAS_SELECT]))
+    return d, E, k, I, sh, N, C, gating, bias
+
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_random_shapes(seed, monkeypatch):
+    monkeypatch.setattr(tp, "check_out", lambda out, y_ref, rows=None: _check_out(out if rows is None else out[rows], y_ref))
+    rng = np.random.default_rng(seed)
+    for case in range(16):
+        shape = _draw(rng)
+        d, E, k, I, sh, N, C, gating, bias = shape
+        tp.say("random shape %d/%d: %s" % (seed, case, shape))
+        wl = ti.TideWorkload("random", d=d, E=E, k=k, I=I, n_shared=sh, N=N, S=3, K=2, C=C, L=1, gating=gating,
+                             bias_mode=bias, seed=1000 * seed + case)
+        log, hidden = tp.oracle_block(wl, 0, [0, 2])
+        for forced in (True, False):
+            sess = tp._session(wl)
+            tp.load(sess, wl, 0)
+            tp.run_block_on_gpu(wl, 0, sess, log, hidden, forced, [0, 2])
+            sess.close()
+        sess = tp._session(wl)
+        tp.load(sess, wl, 0)
+        sess.compress_layer(0, workers=4)
+        sess.host_experts(int(rng.integers(1, 6)))
+        for t, rec in enumerate(log):
+            if t > 0 and t % wl.K == 0:
+                eis, _ = sess.refresh(0)
+                assert eis.tolist() == rec["expert_in_slot"].tolist()
+            x = sess.to_device_bf16(hidden[t])
+            sess.step_routed(0, x, torch.from_numpy(rec["idx"]).to(sess.device),
+                             torch.from_numpy(rec["w"].astype(np.float32)).to(sess.device))
+            if "y_full" in rec:
+                sess.apply_misses_host(0, x)
+                torch.cuda.synchronize()
+                _check_out(sess.out[:wl.N].cpu().numpy(), rec["y_full"])
+        eis = log[-1]["expert_in_slot"]
+        for slot in range(min(C, 3)):
+            if eis[slot] >= 0:
+                assert np.array_equal(sess.read_slot(0, slot), sess.host_blobs[0][int(eis[slot])].numpy())
+        sess.close()
