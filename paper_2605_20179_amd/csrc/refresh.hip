@@ -240,10 +240,25 @@ __global__ void scale_counts_kernel(int32_t* hits, int n, int num, int den) {
 }
 }  // namespace
 
+// A copy workgroup asks for almost all of a compute unit's LDS without using it: no workgroup of the expert GEMM
+// kernels (which stage their token rows in LDS) then fits beside it, so the copy's host-link reads never sit in the
+// memory pipeline of a compute unit that a GEMM workgroup is waiting on.
+#ifndef TIDE_COPY_LDS_RESERVE
+#define TIDE_COPY_LDS_RESERVE (152 * 1024)
+#endif
+constexpr int kCopyLdsReserve = TIDE_COPY_LDS_RESERVE;
+template <typename K>
+hipError_t reserve_lds(K kernel) {
+    static hipError_t rc = kCopyLdsReserve > 0 ? hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kCopyLdsReserve)
+                                               : hipSuccess;
+    return rc;
+}
+
 hipError_t launch_refresh_copies(const uint8_t* host_blobs, uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base,
                                  const RefreshOut* plan, int n, bool dst_by_rank, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL(refresh_copy_kernel, dim3(kCopyBlocks), dim3(kCopyThreads), 0, stream, host_blobs, host_stride,
+    if (hipError_t rc = reserve_lds(refresh_copy_kernel); rc != hipSuccess) return rc;
+    hipLaunchKernelGGL(refresh_copy_kernel, dim3(kCopyBlocks), dim3(kCopyThreads), kCopyLdsReserve, stream, host_blobs, host_stride,
                        blob_bytes, dst_base, plan, n, dst_by_rank ? 1 : 0);
     return hipGetLastError();
 }
@@ -252,7 +267,8 @@ hipError_t launch_refresh_copies_p12(const uint8_t* comp_blobs, uint64_t comp_st
                                      uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base, const RefreshOut* plan, int n,
                                      int max_n, bool dst_by_rank, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL(refresh_copy_p12_kernel, dim3(kCopyBlocks), dim3(kCopyThreads), 0, stream, comp_blobs, comp_stride,
+    if (hipError_t rc = reserve_lds(refresh_copy_p12_kernel); rc != hipSuccess) return rc;
+    hipLaunchKernelGGL(refresh_copy_p12_kernel, dim3(kCopyBlocks), dim3(kCopyThreads), kCopyLdsReserve, stream, comp_blobs, comp_stride,
                        host_blobs, host_stride, blob_bytes, dst_base, plan, n, dst_by_rank ? 1 : 0);
     hipLaunchKernelGGL(refresh_patch_p12_kernel, dim3(n < 0 ? max_n : n), dim3(256), 0, stream, comp_blobs, comp_stride, blob_bytes, dst_base,
                        plan, dst_by_rank ? 1 : 0);
