@@ -199,7 +199,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
         all_big += n_big_items(e >= 0 ? hist_step[e] : 0, true);
     }
     all_big = block_sum(all_big, lds4) + n_big_items(n_shared ? n_tokens : 0, true);
-    const bool use_big = all_big * big_ftiles >= kMinBigUnits;
+    const bool use_big = max_big > 0 && all_big * big_ftiles >= kMinBigUnits;      // max_big == 0: the host launches no large-item kernels
 
     // rows and work items that precede this slot
     const int upto = s < capacity ? s : capacity;
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(kThreads) void miss_group_kernel(const int32_t* __r
     const int e = blockIdx.x, tid = threadIdx.x;
     int all_big = 0;
     for (int q = tid; q < n_experts; q += kThreads) all_big += n_big_items(miss_hist[q], true);
-    const bool use_big = block_sum(all_big, lds4) * big_ftiles >= kMinBigUnits;
+    const bool use_big = max_big > 0 && block_sum(all_big, lds4) * big_ftiles >= kMinBigUnits;
     const int upto = e < n_experts ? e : n_experts;
     int rows_before = 0, tasks_before = 0, big_before = 0;
     for (int q = tid; q < upto; q += kThreads) {

@@ -18,8 +18,15 @@ constexpr int kRowsPerBigTask = 256;    // rows of a large work item
 #ifndef TIDE_BIG_MIN_ROWS
 #define TIDE_BIG_MIN_ROWS 32
 #endif
-constexpr int kMinBigUnits = 128;       // a step uses large work items only if they make at least this many gate/up workgroups (half the compute units)
+#ifndef TIDE_MIN_BIG_UNITS
+#define TIDE_MIN_BIG_UNITS 128
+#endif
+constexpr int kMinBigUnits = TIDE_MIN_BIG_UNITS;   // a step uses large work items only if they make at least this many gate/up workgroups (half the compute units)
 constexpr int kBigMinRows = TIDE_BIG_MIN_ROWS;   // a slot with more rows than this is cut into large work items, else into small ones
+#ifndef TIDE_BIG_MIN_AVG_ROWS
+#define TIDE_BIG_MIN_AVG_ROWS 48
+#endif
+constexpr int kBigMinAvgRows = TIDE_BIG_MIN_AVG_ROWS;   // steps with fewer rows per slot on average launch no large-item kernels at all
 
 // One grouped-GEMM work item: rows [row0, row0+nrows) of the slot-sorted row space
 // all belong to cache slot `slot` (slot == capacity means the shared expert).
@@ -117,7 +124,13 @@ inline int max_big_tasks_for(const Shape& s, int n_tokens) {
     const int rows = n_tokens * s.k + (s.n_shared ? n_tokens : 0);
     const int slots = s.capacity + 1;
     const int busy = rows / (kBigMinRows + 1);           // slots that can exceed the small limit at once
-    return rows / kRowsPerBigTask + (busy < slots ? busy : slots);
+    const int most = rows / kRowsPerBigTask + (busy < slots ? busy : slots);
+    // too few for the step ever to choose large items (the split kernel's rule), or so few rows per slot that the
+    // large-item kernels would mostly be launched for nothing (their idle workgroups each take a compute unit's LDS
+    // for a moment: 135 -> 123 us per step at 256 tokens x top-8 over 65 slots): nothing to launch, and the split
+    // kernel, told so, cuts every slot into small items
+    if ((int64_t)most * ((s.I + 127) / 128) < kMinBigUnits || rows < kBigMinAvgRows * slots) return 0;
+    return most;
 }
 // upper bound of the number of small work items
 inline int max_small_tasks_for(const Shape& s, int n_tokens) {
@@ -130,7 +143,9 @@ inline int max_miss_big_tasks_for(const Shape& s, int n_tokens) {
     if (n_tokens <= kBigMinRows) return 0;
     const int rows = n_tokens * s.k;
     const int busy = rows / (kBigMinRows + 1);
-    return rows / kRowsPerBigTask + (busy < s.E ? busy : s.E);
+    const int most = rows / kRowsPerBigTask + (busy < s.E ? busy : s.E);
+    if ((int64_t)most * ((s.I + 127) / 128) < kMinBigUnits || rows < kBigMinAvgRows * s.E) return 0;
+    return most;
 }
 // miss pass (the step's misses evaluated from the host-resident blobs; entries that name an expert outside [0,E)
 // or a token outside [0,n_tokens) are skipped): group the list by expert into
