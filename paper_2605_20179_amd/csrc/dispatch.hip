@@ -79,7 +79,7 @@ __device__ inline void emit_tasks(int slot, int row0, int m, bool use_big, Task*
             t.slot = slot;
             t.row0 = row0 + c * kRowsPerTask;
             t.nrows = min(kRowsPerTask, m - c * kRowsPerTask);
-            t.pad = 0;
+            t.pad = ns > 1 ? 1 : 0;          // the slot's weights are streamed by several items: let them meet in L2
             small_out[c] = t;
         }
         return;

@@ -35,9 +35,13 @@ __device__ inline uint32_t f32_to_bf16_rne(float f) {
     return u >> 16;
 }
 
-// A weight tile is used once by the wave that fetches it: a non-temporal load keeps it from taking a line
-// of the vector cache (a plain streaming kernel reads 6.5 TB/s this way against 5.8 TB/s with ordinary loads).
+// A weight tile is normally used once by the wave that fetches it: a non-temporal load keeps it from taking a
+// line of the vector cache (a plain streaming kernel reads 6.5 TB/s this way against 5.8 TB/s with ordinary loads).
+// When a slot is cut into several small items (SHARED), their workgroups read the same tiles at about the same
+// time: ordinary loads let the later readers find them in L2.
+template <bool SHARED>
 __device__ inline bf16x8 load_weights(const uint16_t* p) {
+    if (SHARED) return *reinterpret_cast<const bf16x8*>(p);
     return __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(p));
 }
 
@@ -57,7 +61,7 @@ __device__ inline float silu(float g) { return g / (1.f + __expf(-g)); }
 // rows are shared by the workgroup's four waves, so they are staged through LDS, PC chunks of 32
 // columns at a time; the next stage's rows are already in flight while the current one is used.
 // Tokens sit on the MFMA's 16-wide N side, NT token tiles per work item.
-template <int PASS, int RT, int NT, int D, int PC, int NBUF>
+template <int PASS, int RT, int NT, int D, int PC, int NBUF, bool SHARED = false>
 __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile, bool active,
                                  const Task& task, const uint16_t* __restrict__ act_in,
                                  const int32_t* __restrict__ row_token, int K, int n_out,
@@ -143,7 +147,7 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
     for (int i = 0; i < D; ++i) {
         const int ci = min(i, kchunks - 1);
 #pragma unroll
-        for (int r = 0; r < RT; ++r) a[i][r] = load_weights(wt[r] + ci * cstep);
+        for (int r = 0; r < RT; ++r) a[i][r] = load_weights<SHARED>(wt[r] + ci * cstep);
     }
     f32x4 acc[RT][NT];
 #pragma unroll
@@ -169,7 +173,7 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
     auto refill = [&](int c, int i) {
         const int cn = min(c + D, kchunks - 1);
 #pragma unroll
-        for (int r = 0; r < RT; ++r) a[i][r] = load_weights(wt[r] + cn * cstep);
+        for (int r = 0; r < RT; ++r) a[i][r] = load_weights<SHARED>(wt[r] + cn * cstep);
     };
     using all_tiles = std::integral_constant<int, NT>;
 
@@ -317,10 +321,16 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
     const Task task = tasks[task_id];
     const uint16_t* blob = slots + (int64_t)task.slot * blob_elems;
     static_assert(kRowsPerTask == 32, "one or two 16-token tiles per small work item");
-    if (task.nrows <= 16)
+    if (task.pad) {                       // sibling items of one slot: cacheable weight loads
+        if (task.nrows <= 16)
+            gemm_task<PASS, RT, 1, D, kSmallPC, 1, true>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
+        else
+            gemm_task<PASS, RT, 2, D, kSmallPC, 1, true>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
+    } else if (task.nrows <= 16) {
         gemm_task<PASS, RT, 1, D, kSmallPC, 1>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
-    else
+    } else {
         gemm_task<PASS, RT, 2, D, kSmallPC, 1>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
+    }
 }
 
 // Large work items: up to 256 rows of a slot that holds more than 32.  A workgroup's tile is 256

@@ -34,7 +34,7 @@ struct Task {
     int32_t slot;
     int32_t row0;
     int32_t nrows;
-    int32_t pad;
+    int32_t pad;        // small items: 1 when the slot is cut into several items (they read the same weights)
 };
 
 // Device-side workspace of one context (shared by its layers; one step at a time).
