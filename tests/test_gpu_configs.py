@@ -115,3 +115,27 @@ def test_config4_flash_stack_layer(capacity):
     if capacity == 256:
         assert all(r["miss"] == [] for r in log) and all(not r["plan"] for r in log)
     sess.close()
+
+
+def test_maximum_tokens_per_step():
+    """The largest step the library accepts (max_tokens = 65535, a ragged last tile everywhere) on small matrices:
+    three steps with a refresh, every token's routing, the 160 000-entry miss lists, counters, tables and the copy
+    plan compared; outputs (resident part, then completed by the miss pass) on 12 sampled tokens."""
+    wl = ti.TideWorkload("max-tokens", d=64, E=32, k=4, I=64, n_shared=1, N=65535, S=3, K=2, C=8, L=1,
+                         gating=ti.GATING_SIGMOID, bias_mode=ti.BIAS_LOGIT, seed=91)
+    toks = sample_tokens(wl, 12, 5)
+    out_steps = [0, 2]
+    log, hidden = oracle_block(wl, 0, out_steps, tokens=toks)
+    say("max-tokens oracle done; near-ties per step %s, misses per step %s" %
+        ([int(r["ambiguous"].sum()) for r in log], [len(r["miss"]) for r in log]))
+    sess = _session(wl)
+    for forced in (True, False):
+        load(sess, wl, 0)
+        sess.stats(0, reset=True)
+        flips, worst = run_block_on_gpu(wl, 0, sess, log, hidden, forced, out_steps, tokens=toks)
+        say("max-tokens forced=%s flips=%d worst=%.2e" % (forced, flips, worst))
+    from paper_2605_20179_amd import binding as tb
+    with pytest.raises(tb.TideError) as ei:               # one token more is refused when the context is made
+        _session(wl.replace(N=65536))
+    assert ei.value.code == tb.TIDE_E_RANGE
+    sess.close()
