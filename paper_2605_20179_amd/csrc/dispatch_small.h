@@ -1,11 +1,12 @@
 // Hit/miss split for a small step (at most 32 tokens and 1024 (token, expert) pairs), run by a
-// single workgroup of 256 threads right after it has routed the step: same lists, same order and
+// single workgroup of kRouteThreads threads right after it has routed the step: same lists, same order and
 // same counters as dispatch_kernel produces with one block per slot.
 #pragma once
 #include "tide_internal.h"
 
 namespace tide {
 
+constexpr int kRouteThreads = 512;               // 16 lanes per token x 32 tokens: two waves per SIMD
 constexpr int kSmallDispatchMaxPairs = 1024;
 constexpr int kSmallDispatchMaxTokens = 32;      // token sets are 32-bit masks
 static_assert(kSmallDispatchMaxTokens <= kBigMinRows && kSmallDispatchMaxTokens <= kRowsPerTask,
@@ -41,7 +42,7 @@ __device__ inline void dispatch_small(const DispatchArgs& a, const unsigned* s_m
     int* s_row0 = s_m + kMaxExperts + 8;                     // first row of each slot
     int* s_task0 = s_row0 + kMaxExperts + 8;                 // first work item of each slot
 
-    for (int s = tid; s < n_slots; s += 256) {
+    for (int s = tid; s < n_slots; s += kRouteThreads) {
         int m;
         if (s == a.capacity) {
             m = a.n_shared ? a.n_tokens : 0;
@@ -93,7 +94,7 @@ __device__ inline void dispatch_small(const DispatchArgs& a, const unsigned* s_m
     __syncthreads();
 
     // work items and slot offsets
-    for (int s = tid; s < n_slots; s += 256) {
+    for (int s = tid; s < n_slots; s += kRouteThreads) {
         a.slot_off[s] = s_row0[s];
         const int m = s_m[s];
         const int items = (m + kRowsPerTask - 1) / kRowsPerTask;
@@ -108,10 +109,10 @@ __device__ inline void dispatch_small(const DispatchArgs& a, const unsigned* s_m
     }
     // shared expert: every token in token order
     if (a.n_shared)
-        for (int n = tid; n < a.n_tokens; n += 256) a.row_token[s_row0[a.capacity] + n] = n;
+        for (int n = tid; n < a.n_tokens; n += kRouteThreads) a.row_token[s_row0[a.capacity] + n] = n;
 
     // hit pairs: row = first row of the slot + number of lower-numbered tokens that chose the expert
-    for (int p = tid; p < n_pairs; p += 256) {
+    for (int p = tid; p < n_pairs; p += kRouteThreads) {
         const int e = s_idx[p];
         const int slot = (e < 0 || e >= a.n_experts) ? -1 : s_slot_of[e];
         if (slot >= 0) {

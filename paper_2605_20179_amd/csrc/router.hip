@@ -420,14 +420,17 @@ __global__ __launch_bounds__(256) void topk_gate_kernel(const float* __restrict_
 // A step of at most 32 tokens is routed by ONE workgroup: top-k of every token, the step's
 // histogram (in LDS), H += histogram, then the hit/miss split -- all without leaving the CU, so
 // nothing has to travel through memory between routing and split and no launch separates them.
+// 16 lanes per token: the 32 tokens fill eight waves, two per SIMD, whose selection rounds (the
+// kernel's longest phase, bound by vector-ALU issue) interleave.
 template <int V>
-__global__ __launch_bounds__(256) void route_small_kernel(const float* __restrict__ z_part, int k_splits, int e_pad,
+__global__ __launch_bounds__(kRouteThreads) void route_small_kernel(const float* __restrict__ z_part, int k_splits, int e_pad,
                                                           const float* __restrict__ bias, int n_experts, int gating,
                                                           int bias_mode, int32_t* __restrict__ topk_idx,
                                                           float* __restrict__ topk_w, int32_t* __restrict__ hist_step,
                                                           int32_t* __restrict__ hits,
                                                           int32_t* __restrict__ idx_copy, float* __restrict__ w_copy,
                                                           DispatchArgs da) {
+    static_assert(kRouteThreads == 16 * kSmallDispatchMaxTokens && kMaxExperts % kRouteThreads == 0, "one 16-lane group per token");
     __shared__ unsigned s_mask[kMaxExperts];     // per expert: bit n set when token n selected it
     __shared__ int s_slot_of[kMaxExperts];
     __shared__ int s_eis[kMaxExperts];
@@ -435,29 +438,28 @@ __global__ __launch_bounds__(256) void route_small_kernel(const float* __restric
     __shared__ float s_w[kSmallDispatchMaxPairs];
     __shared__ int s_work[kSmallDispatchLdsInts];
     // everything the workgroup needs from memory is requested up front -- the placement tables and the
-    // logits of both groups of 16 tokens -- because each dependent round trip to memory costs microseconds
-    int t_slot[kMaxExperts / 256], t_eis[kMaxExperts / 256];
+    // logits of every token -- because each dependent round trip to memory costs microseconds
+    int t_slot[kMaxExperts / kRouteThreads], t_eis[kMaxExperts / kRouteThreads];
 #pragma unroll
-    for (int q = 0; q < kMaxExperts / 256; ++q) {
-        const int e = threadIdx.x + 256 * q;
+    for (int q = 0; q < kMaxExperts / kRouteThreads; ++q) {
+        const int e = threadIdx.x + kRouteThreads * q;
         t_slot[q] = da.slot_of[min(e, n_experts - 1)];
         t_eis[q] = da.expert_in_slot[min(e, da.capacity - 1)];
     }
-    float z[2][V];
+    float z[1][V];
     load_logits16_any<V>(k_splits, 0, z_part, e_pad, bias, bias_mode, da.n_tokens, n_experts, z[0]);
-    load_logits16_any<V>(k_splits, 16, z_part, e_pad, bias, bias_mode, da.n_tokens, n_experts, z[1]);
 #pragma unroll
-    for (int q = 0; q < kMaxExperts / 256; ++q) {
-        const int e = threadIdx.x + 256 * q;
+    for (int q = 0; q < kMaxExperts / kRouteThreads; ++q) {
+        const int e = threadIdx.x + kRouteThreads * q;
         s_mask[e] = 0u;
         s_slot_of[e] = t_slot[q];
         s_eis[e] = t_eis[q];
     }
     __syncthreads();
-    select16<V, true, 2>(0, z, bias, da.n_tokens, n_experts, da.k, gating, bias_mode, topk_idx, topk_w, nullptr,
+    select16<V, true, 1>(0, z, bias, da.n_tokens, n_experts, da.k, gating, bias_mode, topk_idx, topk_w, nullptr,
                          idx_copy, w_copy, s_mask, s_idx, s_w);
     __syncthreads();
-    for (int e = threadIdx.x; e < n_experts; e += 256) {
+    for (int e = threadIdx.x; e < n_experts; e += kRouteThreads) {
         const int c = __popc(s_mask[e]);
         hist_step[e] = c;                                // the step's activation vector
         if (c) hits[e] += c;                             // this workgroup is the step's only writer of H
@@ -551,10 +553,10 @@ hipError_t launch_route_small(const Shape& s, const LayerTables& t, const Worksp
     da.slot_off = w.slot_off; da.tasks = w.tasks; da.n_tasks = w.n_tasks; da.miss = miss; da.miss_cap = miss_cap;
     da.n_miss = n_miss; da.counters = w.counters;
     if (s.E <= 256)
-        TIDE_LAUNCH(route_small_kernel<16>, dim3(1), dim3(256), stream, ev, w.logits, ks, e_pad, bias, s.E, s.gating,
+        TIDE_LAUNCH(route_small_kernel<16>, dim3(1), dim3(kRouteThreads), stream, ev, w.logits, ks, e_pad, bias, s.E, s.gating,
                     s.bias_mode, w.topk_idx, w.topk_w, w.hist_step, t.hits, idx_copy, w_copy, da);
     else
-        TIDE_LAUNCH(route_small_kernel<32>, dim3(1), dim3(256), stream, ev, w.logits, ks, e_pad, bias, s.E, s.gating,
+        TIDE_LAUNCH(route_small_kernel<32>, dim3(1), dim3(kRouteThreads), stream, ev, w.logits, ks, e_pad, bias, s.E, s.gating,
                     s.bias_mode, w.topk_idx, w.topk_w, w.hist_step, t.hits, idx_copy, w_copy, da);
     return hipGetLastError();
 }
