@@ -5,6 +5,8 @@
 #include "dispatch_small.h"
 #include "tide_internal.h"
 
+#include <type_traits>
+
 namespace tide {
 
 namespace {
@@ -212,16 +214,12 @@ __device__ inline float group16_max(float v) {
     v = fmaxf(v, row_ror_f<1>(v));
     return v;
 }
-// best = larger key, equal keys: lower expert id; the winner's logit rides along
-template <int N>
-__device__ inline void argmax_step(float& best, int& be, float& bz) {
-    const float ob = row_ror_f<N>(best);
-    const int oe = row_ror_i<N>(be);
-    const float oz = row_ror_f<N>(bz);
-    const bool take = (ob > best) | ((ob == best) & (oe < be));      // branch-free selects
-    best = take ? ob : best;
-    be = take ? oe : be;
-    bz = take ? oz : bz;
+__device__ inline int group16_min(int v) {
+    v = min(v, row_ror_i<8>(v));
+    v = min(v, row_ror_i<4>(v));
+    v = min(v, row_ror_i<2>(v));
+    v = min(v, row_ror_i<1>(v));
+    return v;
 }
 
 // sub-lane s owns experts s*4..s*4+3 of every group of 64, so that one 16-byte load per group and
@@ -340,41 +338,50 @@ __device__ inline void select16(int n_base, float (&z)[NG][V], const float* __re
     float my_z[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g) { my_e[g] = 0; my_z[g] = 0.f; }
-    for (int i = 0; i < k; ++i) {
-        // per-lane scan in ascending expert id with a strict compare keeps the lowest id among equals;
-        // experts past E hold -inf and never win; everything is select instructions, no branches
-        float best[NG], bz[NG];
-        int be[NG];
-#pragma unroll
-        for (int g = 0; g < NG; ++g) { best[g] = NEG; bz[g] = 0.f; be[g] = 0x7fffffff; }
-#pragma unroll
-        for (int j = 0; j < V; ++j)
+    // One selection round: the group's largest key (per-lane maximum, then four rotations), the lowest expert id
+    // that holds it (equal keys: the lower id wins, as in a stable descending sort), removal of that one value.
+    // Everything is select instructions, no branches; experts past E and values already taken hold -inf and never
+    // win.  SEL: the gate needs the winner's logit, which is not its key (selection score = gate score + bias).
+    auto rounds = [&](auto sel) {
+        constexpr bool SEL = decltype(sel)::value;
+        for (int i = 0; i < k; ++i) {
+            float gmax[NG];
+            int gid[NG];
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
-                const bool better = key[g][j] > best[g];
-                best[g] = better ? key[g][j] : best[g];
-                be[g] = better ? EXPERT_OF(j) : be[g];
-                bz[g] = better ? z[g][j] : bz[g];
+                float m = key[g][0];
+#pragma unroll
+                for (int j = 1; j < V; ++j) m = fmaxf(m, key[g][j]);
+                gmax[g] = m;
             }
 #pragma unroll
-        for (int g = 0; g < NG; ++g) argmax_step<8>(best[g], be[g], bz[g]);
+            for (int g = 0; g < NG; ++g) gmax[g] = group16_max(gmax[g]);
 #pragma unroll
-        for (int g = 0; g < NG; ++g) argmax_step<4>(best[g], be[g], bz[g]);
+            for (int g = 0; g < NG; ++g) {
+                int c = 0x7fffffff;
 #pragma unroll
-        for (int g = 0; g < NG; ++g) argmax_step<2>(best[g], be[g], bz[g]);
+                for (int j = V - 1; j >= 0; --j) c = (key[g][j] == gmax[g]) ? EXPERT_OF(j) : c;     // ascending in j = ascending id
+                gid[g] = (gmax[g] > NEG) ? c : 0x7fffffff;
+            }
 #pragma unroll
-        for (int g = 0; g < NG; ++g) argmax_step<1>(best[g], be[g], bz[g]);
+            for (int g = 0; g < NG; ++g) gid[g] = group16_min(gid[g]);
 #pragma unroll
-        for (int g = 0; g < NG; ++g) {
-            be[g] = (be[g] == 0x7fffffff) ? 0 : be[g];     // only with non-finite logits; keeps indexing in range
-            const bool mine = s == ((be[g] >> 2) & 15);
-            const int jsel = ((be[g] >> 6) << 2) + (be[g] & 3);
+            for (int g = 0; g < NG; ++g) {
+                float zw = NEG;
 #pragma unroll
-            for (int j = 0; j < V; ++j) key[g][j] = (mine & (j == jsel)) ? NEG : key[g][j];
-            my_e[g] = (s == i) ? be[g] : my_e[g];
-            my_z[g] = (s == i) ? bz[g] : my_z[g];
+                for (int j = 0; j < V; ++j) {
+                    const bool hit = EXPERT_OF(j) == gid[g];
+                    if (SEL) zw = hit ? z[g][j] : zw;
+                    key[g][j] = hit ? NEG : key[g][j];
+                }
+                const bool none = gid[g] == 0x7fffffff;      // only with non-finite logits; keeps indexing in range
+                const float bz = SEL ? group16_max(zw) : gmax[g];
+                my_e[g] = (s == i) ? (none ? 0 : gid[g]) : my_e[g];
+                my_z[g] = (s == i) ? (none ? 0.f : bz) : my_z[g];
+            }
         }
-    }
+    };
+    if (bias_mode == TIDE_BIAS_SELECT) rounds(std::true_type{}); else rounds(std::false_type{});
 
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
