@@ -405,7 +405,7 @@ __device__ inline void select16(int n_base, float (&z)[NG][V], const float* __re
                 s_idx[p] = my_e[g];
                 s_w[p] = w;
             } else {
-                atomicAdd(&hist_step[my_e[g]], 1);    // H += hist_step follows in the split kernel (one writer)
+                atomicAdd(&hist_step[my_e[g]], 1);    // the caller's per-workgroup counts
             }
         }
     }
@@ -418,10 +418,20 @@ __global__ __launch_bounds__(256) void topk_gate_kernel(const float* __restrict_
                                                         int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
                                                         int32_t* __restrict__ hist_step,
                                                         int32_t* __restrict__ idx_copy, float* __restrict__ w_copy) {
+    // the workgroup's 16 tokens are counted in LDS first: a popular expert then costs one global atomic per
+    // workgroup instead of one per token (thousands on one address at thousands of tokens per step)
+    __shared__ int32_t s_hist[kMaxExperts];
+    for (int e = threadIdx.x; e < n_experts; e += 256) s_hist[e] = 0;
     float z[1][V];
     load_logits16_any<V>(k_splits, blockIdx.x * 16, z_part, e_pad, bias, bias_mode, n_tokens, n_experts, z[0]);
+    __syncthreads();
     select16<V, false, 1>(blockIdx.x * 16, z, bias, n_tokens, n_experts, k, gating, bias_mode, topk_idx, topk_w,
-                          hist_step, idx_copy, w_copy, nullptr, nullptr, nullptr);
+                          s_hist, idx_copy, w_copy, nullptr, nullptr, nullptr);
+    __syncthreads();
+    for (int e = threadIdx.x; e < n_experts; e += 256) {
+        const int c = s_hist[e];
+        if (c) atomicAdd(&hist_step[e], c);           // H += hist_step follows in the split kernel (one writer)
+    }
 }
 
 // A step of at most 32 tokens is routed by ONE workgroup: top-k of every token, the step's
@@ -480,13 +490,23 @@ __global__ void clear_i32_kernel(int32_t* p, int n) {
     if (i < n) p[i] = 0;
 }
 
-__global__ void count_pairs_kernel(const int32_t* __restrict__ topk_idx, int n_pairs, int n_experts,
-                                   int32_t* hist_step) {
-    const int p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p < n_pairs) {
-        const int e = topk_idx[p];
-        if (e < 0 || e >= n_experts) return;
-        atomicAdd(&hist_step[e], 1);              // H += hist_step follows in the split kernel (one writer)
+// 256 threads, 1024 pairs per block, counted in LDS first (see topk_gate_kernel).
+__global__ __launch_bounds__(256) void count_pairs_kernel(const int32_t* __restrict__ topk_idx, int n_pairs, int n_experts,
+                                                          int32_t* hist_step) {
+    __shared__ int32_t s_hist[kMaxExperts];
+    for (int e = threadIdx.x; e < n_experts; e += 256) s_hist[e] = 0;
+    __syncthreads();
+    for (int q = 0; q < 4; ++q) {
+        const int p = blockIdx.x * 1024 + q * 256 + threadIdx.x;
+        if (p < n_pairs) {
+            const int e = topk_idx[p];
+            if (e >= 0 && e < n_experts) atomicAdd(&s_hist[e], 1);
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < n_experts; e += 256) {
+        const int c = s_hist[e];
+        if (c) atomicAdd(&hist_step[e], c);           // H += hist_step follows in the split kernel (one writer)
     }
 }
 
@@ -577,7 +597,7 @@ hipError_t launch_count_pairs(const Shape& s, const int32_t* topk_idx, int n_tok
                               hipStream_t stream) {
     hipLaunchKernelGGL(clear_i32_kernel, dim3((s.E + 255) / 256), dim3(256), 0, stream, hist_step, s.E);
     const int n_pairs = n_tokens * s.k;
-    hipLaunchKernelGGL(count_pairs_kernel, dim3((n_pairs + 255) / 256), dim3(256), 0, stream, topk_idx, n_pairs,
+    hipLaunchKernelGGL(count_pairs_kernel, dim3((n_pairs + 1023) / 1024), dim3(256), 0, stream, topk_idx, n_pairs,
                        s.E, hist_step);
     return hipGetLastError();
 }
