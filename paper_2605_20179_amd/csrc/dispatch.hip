@@ -23,6 +23,28 @@ __device__ inline int block_sum(int v, int* lds4) {
     return t;
 }
 
+// a and b summed over the block (fields packed by the caller must not overflow into each other).
+__device__ inline void block_sum2(unsigned long long& a, unsigned long long& b, unsigned long long* lds8) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        a += __shfl_xor(a, off);
+        b += __shfl_xor(b, off);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        lds8[2 * (threadIdx.x >> 6)] = a;
+        lds8[2 * (threadIdx.x >> 6) + 1] = b;
+    }
+    __syncthreads();
+    a = 0;
+    b = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) {
+        a += lds8[2 * w];
+        b += lds8[2 * w + 1];
+    }
+    __syncthreads();
+}
+
 // ids[0..3] = idx[p0 .. p0+3] (16-byte load when the four are in range; idx is 16-byte aligned).
 __device__ inline void load4(const int32_t* __restrict__ idx, int p0, int n, int (&ids)[4]) {
     if (p0 + 3 < n) {
@@ -147,6 +169,8 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     tide_miss* __restrict__ miss, int miss_cap, int32_t* __restrict__ n_miss, int64_t* __restrict__ counters,
     int max_big, int big_ftiles) {
     __shared__ int lds4[kThreads / 64];
+    __shared__ unsigned long long lds8[2 * (kThreads / 64)];
+    __shared__ int own[2];                   // this block's slot: expert and rows
     const int s = blockIdx.x;
     const int tid = threadIdx.x;
     const int n_pairs = n_tokens * k;
@@ -192,29 +216,34 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
         return;
     }
 
-    // large work items of the whole step (every block computes the same figure)
-    int all_big = 0;
-    for (int q = tid; q < capacity; q += kThreads) {
-        const int e = expert_in_slot[q];
-        all_big += n_big_items(e >= 0 ? hist_step[e] : 0, true);
-    }
-    all_big = block_sum(all_big, lds4) + n_big_items(n_shared ? n_tokens : 0, true);
-    const bool use_big = max_big > 0 && all_big * big_ftiles >= kMinBigUnits;      // max_big == 0: the host launches no large-item kernels
-
-    // rows and work items that precede this slot
+    // One thread per slot (capacity <= kMaxExperts <= kThreads) reads the slot's row count; a single block-wide
+    // sum of packed fields then gives everything that precedes this block's slot -- rows, work items, active
+    // slots -- and the large work items of the whole step (the same figure in every block).  The small-item
+    // count is carried for both outcomes of the step's small/large rule, which depends on that figure.
+    static_assert(kMaxExperts <= kThreads, "one thread per cache slot");
     const int upto = s < capacity ? s : capacity;
-    int rows_before = 0, tasks_before = 0, big_before = 0, active_before = 0;
-    for (int q = tid; q < upto; q += kThreads) {
-        const int e = expert_in_slot[q];
+    unsigned long long fa = 0, fb = 0;
+    if (tid < capacity) {
+        const int e = expert_in_slot[tid];
         const int m = e >= 0 ? hist_step[e] : 0;
-        rows_before += m;
-        tasks_before += n_small_items(m, use_big);
-        big_before += n_big_items(m, use_big);
-        active_before += m > 0 ? 1 : 0;
+        const unsigned long long big = n_big_items(m, true);
+        if (tid == s) {
+            own[0] = e;
+            own[1] = m;
+        }
+        fa = big;                                                        // bits 0-15: large items, all slots
+        if (tid < upto) {
+            fa |= (unsigned long long)(m > 0 ? 1 : 0) << 16 | (unsigned long long)m << 32;
+            fb = (unsigned long long)n_small_items(m, true) | (unsigned long long)n_small_items(m, false) << 21 | big << 42;
+        }
     }
-    rows_before = block_sum(rows_before, lds4);
-    tasks_before = block_sum(tasks_before, lds4);
-    big_before = block_sum(big_before, lds4);
+    block_sum2(fa, fb, lds8);
+    const int all_big = (int)(fa & 0xffff) + n_big_items(n_shared ? n_tokens : 0, true);
+    const bool use_big = max_big > 0 && all_big * big_ftiles >= kMinBigUnits;      // max_big == 0: the host launches no large-item kernels
+    const int active_before = (int)(fa >> 16 & 0xffff);
+    const int rows_before = (int)(fa >> 32);
+    const int tasks_before = use_big ? (int)(fb & 0x1fffff) : (int)(fb >> 21 & 0x1fffff);
+    const int big_before = use_big ? (int)(fb >> 42) : 0;
 
     if (s == capacity) {
         // the interval counter takes the step's histogram (Fig. 1 caption: every selected expert counts,
@@ -232,7 +261,6 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
             n_tasks[0] = tasks_before + n_small;
             n_tasks[1] = min(big_before + n_big, max_big);
         }
-        active_before = block_sum(active_before, lds4);
         if (tid == 0) {
             // running totals for throughput accounting; only this block of this kernel writes them
             counters[0] += 1;
@@ -242,8 +270,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
         return;
     }
 
-    const int e = expert_in_slot[s];
-    const int m = e >= 0 ? hist_step[e] : 0;
+    const int e = own[0], m = own[1];        // written before block_sum2's barriers
     if (tid == 0) slot_off[s] = rows_before;
     if (m == 0) return;
     emit_tasks(s, rows_before, m, use_big, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
