@@ -334,3 +334,54 @@ def test_two_layers_keep_separate_caches_and_counters():
             if "y_res" in rec:
                 check_out(out, rec["y_res"])
     sess.close()
+
+
+@pytest.mark.parametrize("n_tokens,n_experts,k,bias_mode", [(16, 64, 6, ti.BIAS_NONE), (32, 256, 8, ti.BIAS_LOGIT),
+                                                             (200, 64, 6, ti.BIAS_SELECT), (90, 300, 16, ti.BIAS_NONE)])
+def test_exactly_equal_scores_go_to_the_lower_expert_id(n_tokens, n_experts, k, bias_mode):
+    """Experts with identical router rows (and biases) have bit-identical scores for every token: among them the
+    selection must take the lower ids first, inside the top-k and at its boundary, and list them in id order --
+    the oracle's convention for equal keys.  Covers the one-workgroup path (<= 32 tokens) and the general one,
+    both register layouts (E <= 256, E > 256) and the three bias modes."""
+    wl = ti.TideWorkload("ties", d=128, E=n_experts, k=k, I=64, n_shared=0, N=n_tokens, S=1, K=1, C=min(8, n_experts),
+                         L=1, gating=ti.GATING_SIGMOID, bias_mode=bias_mode, seed=4242 + n_tokens)
+    rng = np.random.default_rng(wl.seed)
+    wr = ti.router_weights(wl, 0).copy()
+    bias = ti.router_bias(wl, 0)
+    bias = None if bias is None else bias.copy()
+    # families of 2, 3 and 5 identical experts, spread over the id range (different lanes and registers)
+    families = []
+    free = rng.permutation(n_experts).tolist()
+    for size in (2, 3, 5, 2, 3, 2):
+        fam = sorted(free.pop() for _ in range(size))
+        families.append(fam)
+        for e in fam[1:]:
+            wr[e] = wr[fam[0]]
+            if bias is not None:
+                bias[e] = bias[fam[0]]
+    # make the families attractive so that they reach the top-k and its boundary often
+    for fam in families:
+        wr[fam] *= 3.0
+    hidden = next(iter(ti.hidden_stream(wl, 0)))
+    idx_ref, w_ref, amb, key = orc.route(hidden, wr, bias, wl.gating, wl.bias_mode, wl.k)
+    sess = _session(wl)
+    sess.load_layer(0, lambda e: ti.expert_weights(wl, 0, e), wr, bias, ti.initial_resident(wl))
+    sess.step(0, sess.to_device_bf16(hidden))
+    _, idx, w, _, _ = sess.results(wl.N)
+    member = {e: f for f, fam in enumerate(families) for e in fam}
+    hit_families = 0
+    for n in range(wl.N):
+        chosen = idx[n].tolist()
+        assert len(set(chosen)) == wl.k
+        for f, fam in enumerate(families):
+            took = [e for e in fam if e in chosen]
+            assert took == fam[:len(took)], "token %d: family %s, selected %s" % (n, fam, took)
+            pos = [chosen.index(e) for e in took]
+            assert pos == list(range(pos[0], pos[0] + len(pos))) if pos else True, "token %d: equal scores out of id order" % n
+            hit_families += 0 < len(took) < len(fam)
+    assert hit_families > 0, "no family straddles the top-k boundary: the case tests nothing"
+    rec = {"idx": idx_ref, "w": w_ref, "ambiguous": amb, "key": key}
+    flips = check_routing(rec, idx, w, wl.k)
+    say("ties: %d tokens x top-%d of %d, %d family/token pairs cut by the boundary, %d near-tie flips elsewhere"
+        % (wl.N, wl.k, wl.E, hit_families, len(flips)))
+    sess.close()
