@@ -282,17 +282,18 @@ __device__ inline void load_logits16_any(int k_splits, int n_base, const float* 
     }
 }
 
-// Gate, top-k and weights of the 16 tokens whose (biased) logits are in z.
-// SMALL = true: the caller is the single workgroup that routes the whole step; selections are
-// mirrored into LDS (s_idx, s_w) and counted in an LDS histogram instead of global atomics.
+// Gate, top-k and weights of the tokens whose (biased) logits are in z: one token per 16 lanes, NG tokens per
+// 16-lane group (both callers use NG = 1 and fill the SIMDs with more waves instead: measured faster than two
+// interleaved tokens per group).
+// SMALL = true: the caller is the single workgroup that routes the whole step; selections are mirrored into LDS
+// (s_idx, s_w) and recorded as per-expert token masks (s_mask); otherwise hist_step[e] is incremented per
+// selection (the caller passes its workgroup's LDS counts).
 template <int V, bool SMALL, int NG>
 __device__ inline void select16(int n_base, float (&z)[NG][V], const float* __restrict__ bias, int n_tokens,
                                 int n_experts, int k, int gating, int bias_mode, int32_t* __restrict__ topk_idx,
                                 float* __restrict__ topk_w, int32_t* __restrict__ hist_step,
                                 int32_t* __restrict__ idx_copy,
                                 float* __restrict__ w_copy, unsigned* s_mask, int* s_idx, float* s_w) {
-    // NG groups of 16 tokens are worked on side by side: their dependency chains are independent,
-    // so the single wave per SIMD always has an instruction ready to issue
     const int s = threadIdx.x & 15;
     const float NEG = -__builtin_huge_valf();
     int n[NG];
