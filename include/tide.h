@@ -153,6 +153,29 @@ int tide_moe_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens
                   float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
                   int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream);
 
+/* tide_moe_step for callers that cannot allocate device memory or let a library do it on their behalf -- code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results
+ * (bit for bit) and same errors as tide_moe_step; the difference is where the step's workspace lives (partial
+ * router logits, routing tables, slot-sorted row lists, work items, SwiGLU activations, per-row expert outputs):
+ * not in the context's own allocation but in ONE array of TIDE_NOALLOC_SCRATCH_BYTES bytes that the library
+ * holds in each GPU's memory from load until the process ends.  The call performs no hipMalloc / hipFree and
+ * calls no allocating routine.
+ *   - A step whose workspace does not fit is refused with TIDE_E_RANGE and nothing is queued (the need grows with
+ *     n_tokens * (top_k + n_shared) * (4 d + 2 d_ff) bytes: 32 MiB hold e.g. 320 tokens at d = 2048, d_ff = 512,
+ *     top-8 + shared, or 192 tokens at d = 4096, d_ff = 1024).
+ *   - TIDE_E_STATE while tide_profile is on (event-stamped launches create events).
+ *   - Every context on a GPU shares that GPU's array and the array keeps the last call's contents; nothing in it has
+ *     to start at zero.  Calls that overlap in time on one GPU (two streams, two contexts, two threads) race: issue
+ *     them in stream order on one stream, like the other calls of a context.
+ *   - The step histogram (tide_step_histogram) and the running totals (tide_counters) stay with the context. */
+#define TIDE_NOALLOC_SCRATCH_BYTES (32u << 20)
+int tide_moe_step_noalloc(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens,
+                          const float* router_w_dev, const float* router_bias_dev,
+                          float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
+                          int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream);
+/* TIDE_NOALLOC_SCRATCH_BYTES as the loaded library was built with. */
+uint64_t tide_noalloc_scratch_bytes(void);
+
 /* The same step for token states that already carry their expert selections
  * (Alg. 1 takes X = {(x, E_x)} as given): topk_idx_dev / topk_w_dev are INPUTS
  * (expert ids must be in [0,E) and distinct per token; topk_idx_dev 16-byte aligned).  Counts, split, expert

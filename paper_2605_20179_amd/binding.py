@@ -27,6 +27,7 @@ EXPORTS = [
     "tide_host_experts", "tide_moe_apply_misses_host", "tide_host_miss_ms", "tide_host_expert", "tide_host_link_share", "tide_host_misses",
     "tide_compressed_blob_bytes", "tide_compress_expert", "tide_register_compressed",
     "tide_refresh_async", "tide_refresh_result",
+    "tide_moe_step_noalloc", "tide_noalloc_scratch_bytes",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -76,6 +77,9 @@ def _load() -> C.CDLL:
     lib.tide_set_resident.argtypes = [vp, C.c_int, vp, C.c_int]
     lib.tide_moe_step.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp, vp, vp]
     lib.tide_moe_step_routed.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp]
+    lib.tide_moe_step_noalloc.argtypes = lib.tide_moe_step.argtypes
+    lib.tide_noalloc_scratch_bytes.argtypes = []
+    lib.tide_noalloc_scratch_bytes.restype = C.c_uint64
     lib.tide_moe_apply_misses.argtypes = [vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, vp, vp]
     lib.tide_moe_apply_misses_host.argtypes = lib.tide_moe_apply_misses.argtypes
     lib.tide_host_experts.argtypes = [vp, C.c_int]
@@ -104,7 +108,7 @@ def _load() -> C.CDLL:
     lib.tide_optimal_interval.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, vp, C.POINTER(C.c_int),
                                           C.POINTER(C.c_double)]
     for name in EXPORTS:
-        if name not in ("tide_last_error", "tide_expert_blob_bytes", "tide_compressed_blob_bytes"):
+        if name not in ("tide_last_error", "tide_expert_blob_bytes", "tide_compressed_blob_bytes", "tide_noalloc_scratch_bytes"):
             getattr(lib, name).restype = C.c_int
     return lib
 
@@ -191,6 +195,16 @@ def tide_moe_step(ctx, layer: int, hidden, n_tokens: int, router_w, router_bias,
                   topk_idx=None, topk_w=None, stream=None) -> None:
     _check(lib.tide_moe_step(ctx, layer, _ptr(hidden), n_tokens, _ptr(router_w), _ptr(router_bias), _ptr(out),
                              _ptr(miss), miss_cap, _ptr(n_miss), _ptr(topk_idx), _ptr(topk_w), _stream_ptr(stream)), ctx)
+
+
+def tide_moe_step_noalloc(ctx, layer: int, hidden, n_tokens: int, router_w, router_bias, out, miss, miss_cap: int, n_miss,
+                          topk_idx=None, topk_w=None, stream=None) -> None:
+    _check(lib.tide_moe_step_noalloc(ctx, layer, _ptr(hidden), n_tokens, _ptr(router_w), _ptr(router_bias), _ptr(out),
+                                     _ptr(miss), miss_cap, _ptr(n_miss), _ptr(topk_idx), _ptr(topk_w), _stream_ptr(stream)), ctx)
+
+
+def tide_noalloc_scratch_bytes() -> int:
+    return int(lib.tide_noalloc_scratch_bytes())
 
 
 def tide_moe_step_routed(ctx, layer: int, hidden, n_tokens: int, topk_idx, topk_w, out, miss, miss_cap: int, n_miss,

@@ -6,8 +6,10 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include <chrono>
@@ -21,9 +23,33 @@ using namespace tide;
 static_assert(kHostGateUpGroup == kGateUpGroup && kHostDownGroup == kDownGroup,
               "the host experts and the GEMM kernels read the same packed layout");
 
+// Workspace of tide_moe_step_noalloc: one array per GPU, held until the process ends.  In host code the name is
+// only a handle for hipGetSymbolAddress; every use of the memory goes through the per-device pointer below.
+constexpr size_t kScratchBytes = (size_t)TIDE_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
 thread_local std::string g_create_error;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of `scratch` (looked up once per device, with that device current).
+hipError_t scratch_on_device(int device, unsigned char** out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p || ((uintptr_t)p & 255)) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 struct Layer {
     LayerTables t{};
@@ -62,6 +88,7 @@ struct tide_ctx {
     hipEvent_t fork_ev = nullptr, join_ev = nullptr;
     hipEvent_t compute_mark = nullptr;
     int max_rows = 0, max_tasks = 0;
+    unsigned char* scratch_dev = nullptr;   // this device's copy of the static scratch array (tide_moe_step_noalloc)
     std::string err;
     // optional per-kernel timing: every kernel launch of a step stamps a start and a stop event
     int profiling = 0;                      // 0 off, 1 every kernel of a step, 2 the expert GEMMs, 3 gate/up and the kernel before it
@@ -199,13 +226,13 @@ void pack_down(const uint16_t* wd, int d, int d_ff, uint16_t* dst) {
     }
 }
 
-int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const int32_t* idx,
+int common_step(tide_ctx* ctx, const Workspace& ws, int layer, const void* hidden_dev, int n_tokens, const int32_t* idx,
                 const float* w, float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
                 hipStream_t stream, bool split_done) {
     Layer& L = ctx->layers[layer];
     if (!split_done)
         TIDE_HIP(ctx, timed(ctx, TIDE_K_DISPATCH, [&](LaunchEvents ev) {
-            return launch_dispatch(ctx->shape, L.t, ctx->ws, idx, w, n_tokens, miss_dev, miss_cap, n_miss_dev, stream, ev); }));
+            return launch_dispatch(ctx->shape, L.t, ws, idx, w, n_tokens, miss_dev, miss_cap, n_miss_dev, stream, ev); }));
     const int max_tasks = max_small_tasks_for(ctx->shape, n_tokens);
     const int max_big = max_big_tasks_for(ctx->shape, n_tokens);
     const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
@@ -240,21 +267,21 @@ int common_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, 
     // Small and large work items touch disjoint rows: the large ones run on the second stream so that
     // the two kinds of kernels overlap on the chip (join before the combine).
     if (max_big > 0) {
-        TIDE_HIP(ctx, launch_plan_big(ctx->ws, max_big, ctx->aux));
+        TIDE_HIP(ctx, launch_plan_big(ws, max_big, ctx->aux));
         TIDE_HIP(ctx, timed(ctx, TIDE_K_GATE_UP_BIG, [&](LaunchEvents ev) {
-            return launch_expert_gemm_big(0, ctx->shape, L.t, ctx->ws, x, max_big, ctx->aux, ev); }));
+            return launch_expert_gemm_big(0, ctx->shape, L.t, ws, x, max_big, ctx->aux, ev); }));
         TIDE_HIP(ctx, timed(ctx, TIDE_K_DOWN_BIG, [&](LaunchEvents ev) {
-            return launch_expert_gemm_big(1, ctx->shape, L.t, ctx->ws, x, max_big, ctx->aux, ev); }));
+            return launch_expert_gemm_big(1, ctx->shape, L.t, ws, x, max_big, ctx->aux, ev); }));
         TIDE_HIP(ctx, hipEventRecord(ctx->join_ev, ctx->aux));
     }
     TIDE_HIP(ctx, timed(ctx, TIDE_K_GATE_UP, [&](LaunchEvents ev) {
-        return launch_expert_gemm(0, ctx->shape, L.t, ctx->ws, x, max_tasks, stream, ev); }));
+        return launch_expert_gemm(0, ctx->shape, L.t, ws, x, max_tasks, stream, ev); }));
     TIDE_HIP(ctx, timed(ctx, TIDE_K_DOWN, [&](LaunchEvents ev) {
-        return launch_expert_gemm(1, ctx->shape, L.t, ctx->ws, x, max_tasks, stream, ev); }));
+        return launch_expert_gemm(1, ctx->shape, L.t, ws, x, max_tasks, stream, ev); }));
     if (max_big > 0) TIDE_HIP(ctx, hipStreamWaitEvent(stream, ctx->join_ev, 0));
     else if (ctx->pool) TIDE_HIP(ctx, hipStreamWaitEvent(stream, ctx->listed_ev, 0));    // the export read hidden_dev
     TIDE_HIP(ctx, timed(ctx, TIDE_K_COMBINE, [&](LaunchEvents ev) {
-        return launch_combine(ctx->shape, ctx->ws, w, n_tokens, out_dev, stream, ev); }));
+        return launch_combine(ctx->shape, ws, w, n_tokens, out_dev, stream, ev); }));
     ctx->steps_issued++;
     return TIDE_OK;
 }
@@ -341,6 +368,9 @@ int tide_create(const tide_config* cfg, tide_ctx** out) {
     if (hipGetDeviceProperties(&prop, ctx->device) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "hipGetDeviceProperties failed"));
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
         return bail(fail(ctx, TIDE_E_HIP, "device is %s; libtide is built for gfx950 only", prop.gcnArchName));
+
+    if (hipError_t se = scratch_on_device(ctx->device, &ctx->scratch_dev); se != hipSuccess)
+        return bail(fail(ctx, TIDE_E_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(se)));
 
     const int64_t N = cfg->max_tokens, P = N * cfg->top_k;
     ctx->max_rows = (int)(P + (cfg->n_shared ? N : 0));
@@ -564,12 +594,11 @@ int tide_set_resident(tide_ctx* ctx, int layer, const int32_t* experts, int n) {
     return TIDE_OK;
 }
 
-int tide_moe_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const float* router_w_dev,
-                  const float* router_bias_dev, float* out_dev, tide_miss* miss_dev, int miss_cap,
-                  int32_t* n_miss_dev, int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream) {
-    int rc = step_args_ok(ctx, layer, hidden_dev, n_tokens, out_dev, miss_dev, miss_cap, n_miss_dev);
-    if (rc) return rc;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+namespace {
+// tide_moe_step on the workspace `ws` (the context's own, or one carved from the static scratch array).
+int moe_step_on(tide_ctx* ctx, const Workspace& ws, int layer, const void* hidden_dev, int n_tokens, const float* router_w_dev,
+                const float* router_bias_dev, float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
+                int32_t* topk_idx_dev, float* topk_w_dev, hipStream_t stream) {
     if (n_tokens == 0) {
         TIDE_HIP(ctx, launch_clear_i32(n_miss_dev, 1, stream));
         return TIDE_OK;
@@ -580,19 +609,77 @@ int tide_moe_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens
     Layer& L = ctx->layers[layer];
     const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
     TIDE_HIP(ctx, timed(ctx, TIDE_K_ROUTER, [&](LaunchEvents ev) {
-        return launch_router_logits(ctx->shape, x, n_tokens, router_w_dev, ctx->ws.logits, ctx->ws.hist_step, stream, ev); }));
+        return launch_router_logits(ctx->shape, x, n_tokens, router_w_dev, ws.logits, ws.hist_step, stream, ev); }));
     const bool one_wg = routes_in_one_workgroup(ctx->shape, n_tokens);
     if (one_wg) {
         TIDE_HIP(ctx, timed(ctx, TIDE_K_TOPK, [&](LaunchEvents ev) {
-            return launch_route_small(ctx->shape, L.t, ctx->ws, router_bias_dev, n_tokens, topk_idx_dev, topk_w_dev, miss_dev,
+            return launch_route_small(ctx->shape, L.t, ws, router_bias_dev, n_tokens, topk_idx_dev, topk_w_dev, miss_dev,
                                       miss_cap, n_miss_dev, stream, ev); }));
     } else {
         TIDE_HIP(ctx, timed(ctx, TIDE_K_TOPK, [&](LaunchEvents ev) {
-            return launch_topk_gate(ctx->shape, ctx->ws.logits, router_bias_dev, n_tokens, ctx->ws.topk_idx, ctx->ws.topk_w,
-                                    ctx->ws.hist_step, topk_idx_dev, topk_w_dev, stream, ev); }));
+            return launch_topk_gate(ctx->shape, ws.logits, router_bias_dev, n_tokens, ws.topk_idx, ws.topk_w,
+                                    ws.hist_step, topk_idx_dev, topk_w_dev, stream, ev); }));
     }
-    return common_step(ctx, layer, hidden_dev, n_tokens, ctx->ws.topk_idx, ctx->ws.topk_w, out_dev, miss_dev, miss_cap,
+    return common_step(ctx, ws, layer, hidden_dev, n_tokens, ws.topk_idx, ws.topk_w, out_dev, miss_dev, miss_cap,
                        n_miss_dev, stream, one_wg);
+}
+}  // namespace
+
+int tide_moe_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const float* router_w_dev,
+                  const float* router_bias_dev, float* out_dev, tide_miss* miss_dev, int miss_cap,
+                  int32_t* n_miss_dev, int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream) {
+    int rc = step_args_ok(ctx, layer, hidden_dev, n_tokens, out_dev, miss_dev, miss_cap, n_miss_dev);
+    if (rc) return rc;
+    return moe_step_on(ctx, ctx->ws, layer, hidden_dev, n_tokens, router_w_dev, router_bias_dev, out_dev, miss_dev, miss_cap,
+                       n_miss_dev, topk_idx_dev, topk_w_dev, static_cast<hipStream_t>(hip_stream));
+}
+
+namespace {
+// The per-step buffers of a step over n_tokens tokens laid out from `base` on (each piece 256-byte aligned, with the
+// same 256 bytes of slack behind it that tide_create gives its allocations); returns the bytes taken.  With base ==
+// nullptr only the size is computed.  What outlives a step -- the step histogram, the running totals -- stays with
+// the context, as do the buffers only the miss passes use.
+size_t carve_step_workspace(const Shape& s, int n_tokens, unsigned char* base, Workspace& w) {
+    size_t at = 0;
+    auto take = [&](auto** field, size_t count) {
+        using T = std::remove_pointer_t<std::remove_pointer_t<decltype(field)>>;
+        if (base) *field = reinterpret_cast<T*>(base + at);
+        at += (count * sizeof(T) + 256 + 255) / 256 * 256;
+    };
+    const size_t N = (size_t)n_tokens, P = N * s.k, rows = P + (s.n_shared ? N : 0);
+    const size_t max_big = (size_t)max_big_tasks_for(s, n_tokens);
+    take(&w.logits, (size_t)kMaxRouterSplits * N * ((s.E + 15) / 16 * 16));
+    take(&w.topk_idx, P);
+    take(&w.topk_w, P);
+    take(&w.row_token, rows);
+    take(&w.pair_row, P);
+    take(&w.slot_off, (size_t)s.capacity + 2);
+    take(&w.tasks, (size_t)max_small_tasks_for(s, n_tokens));
+    take(&w.big_tasks, max_big + 1);
+    take(&w.n_tasks, 2);
+    take(&w.big_order, max_big + 1);
+    take(&w.act, rows * s.I);
+    take(&w.y, rows * s.d);
+    return at;
+}
+}  // namespace
+
+uint64_t tide_noalloc_scratch_bytes(void) { return kScratchBytes; }
+
+int tide_moe_step_noalloc(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const float* router_w_dev,
+                          const float* router_bias_dev, float* out_dev, tide_miss* miss_dev, int miss_cap,
+                          int32_t* n_miss_dev, int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream) {
+    int rc = step_args_ok(ctx, layer, hidden_dev, n_tokens, out_dev, miss_dev, miss_cap, n_miss_dev);
+    if (rc) return rc;
+    if (ctx->profiling) return fail(ctx, TIDE_E_STATE, "tide_moe_step_noalloc does not run while tide_profile is on (stamped launches create events)");
+    Workspace ws = ctx->ws;
+    const size_t need = carve_step_workspace(ctx->shape, n_tokens, nullptr, ws);
+    if (need > kScratchBytes)
+        return fail(ctx, TIDE_E_RANGE, "a step of %d tokens needs %zu bytes of workspace; the static scratch array holds %zu",
+                    n_tokens, need, kScratchBytes);
+    carve_step_workspace(ctx->shape, n_tokens, ctx->scratch_dev, ws);
+    return moe_step_on(ctx, ws, layer, hidden_dev, n_tokens, router_w_dev, router_bias_dev, out_dev, miss_dev, miss_cap,
+                       n_miss_dev, topk_idx_dev, topk_w_dev, static_cast<hipStream_t>(hip_stream));
 }
 
 int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const int32_t* topk_idx_dev,
@@ -608,7 +695,7 @@ int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n
     if (!topk_idx_dev || !topk_w_dev) return fail(ctx, TIDE_E_INVAL, "topk_idx_dev / topk_w_dev is null");
     if ((uintptr_t)topk_idx_dev & 15) return fail(ctx, TIDE_E_INVAL, "topk_idx_dev must be 16-byte aligned");
     TIDE_HIP(ctx, launch_count_pairs(ctx->shape, topk_idx_dev, n_tokens, ctx->ws.hist_step, stream));
-    return common_step(ctx, layer, hidden_dev, n_tokens, topk_idx_dev, topk_w_dev, out_dev, miss_dev, miss_cap,
+    return common_step(ctx, ctx->ws, layer, hidden_dev, n_tokens, topk_idx_dev, topk_w_dev, out_dev, miss_dev, miss_cap,
                        n_miss_dev, stream, false);
 }
 
