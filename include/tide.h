@@ -178,8 +178,10 @@ uint64_t tide_noalloc_scratch_bytes(void);
 
 /* The same step for token states that already carry their expert selections
  * (Alg. 1 takes X = {(x, E_x)} as given): topk_idx_dev / topk_w_dev are INPUTS
- * (expert ids must be in [0,E) and distinct per token; topk_idx_dev 16-byte aligned).  Counts, split, expert
- * evaluation, combine and miss list exactly as tide_moe_step. */
+ * (expert ids in [0,E), distinct per token; topk_idx_dev 16-byte aligned).  Counts, split, expert evaluation,
+ * combine and miss list exactly as tide_moe_step.  An id outside [0,E) is reported as a miss and not counted.
+ * A token that names an expert more than once gets the sum the definition gives (each listed pair is evaluated
+ * with its own weight) and H counts pairs, not tokens, for it. */
 int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens,
                          const int32_t* topk_idx_dev, const float* topk_w_dev,
                          float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
@@ -263,6 +265,11 @@ int tide_host_expert(const tide_config* cfg, const void* blob_host, const uint16
  * hip_stream; reset != 0 zeroes it afterwards.  Synchronises hip_stream. */
 int tide_interval_stats(tide_ctx* ctx, int layer, int32_t* counts_host, int reset, void* hip_stream);
 
+/* Overwrites the layer's hit counter H[E] with counts_host (all >= 0), after all work queued on hip_stream:
+ * the counterpart of tide_interval_stats, so that a caller can snapshot (H, placement) and replay from it,
+ * or carry a counter over from another run.  Synchronises hip_stream. */
+int tide_set_counts(tide_ctx* ctx, int layer, const int32_t* counts_host, void* hip_stream);
+
 /* Refresh step (Alg. 1; Sec. 3.3: the GPU set becomes the current top-B by hits).
  * Experts are ranked by (hits descending, currently resident first, lower id first);
  * the first `capacity` form the new resident set.  Leaving experts, ordered by
@@ -309,6 +316,26 @@ int tide_commit(tide_ctx* ctx, int layer, void* hip_stream);
 
 /* Blocks until every refresh copy queued so far for the layer has landed. */
 int tide_wait_refresh(tide_ctx* ctx, int layer);
+/* The same wait queued on hip_stream instead of blocking the host: work queued on hip_stream afterwards runs
+ * once the layer's refresh copies have landed.  A step issued eagerly needs neither call -- it queues this wait
+ * ahead of its expert GEMMs itself.  A step REPLAYED from a captured HIP graph does not: the wait is decided
+ * when the step is issued, and a graph captured on a settled placement holds none.  After tide_refresh /
+ * tide_refresh_async, call tide_wait_refresh, or tide_queue_refresh_wait on the replay's stream, before
+ * replaying a captured step of that layer, or the replay may read slots the copies are still writing. */
+int tide_queue_refresh_wait(tide_ctx* ctx, int layer, void* hip_stream);
+
+/* Who moves a refresh's expert blobs across the host link (Alg. 1's asynchronous migration), for every later
+ * refresh on the context:
+ *   TIDE_COPY_KERNEL  one kernel on the side stream that reads pinned host memory in place (default; the only
+ *                     engine that can read the 12-bit form of tide_register_compressed, and the only one
+ *                     tide_refresh_async can use, because the host never sees that call's plan);
+ *   TIDE_COPY_DMA     one hipMemcpyAsync per entering expert on the side stream, raw blobs: the copy engines
+ *                     move the bytes and no compute unit takes part, which matters when steps run beside the
+ *                     copies (tide_refresh_deferred).
+ * Results are identical: the slots end up byte-equal to the host blobs either way. */
+#define TIDE_COPY_KERNEL 0
+#define TIDE_COPY_DMA    1
+int tide_refresh_engine(tide_ctx* ctx, int engine);
 
 /* Policy variant of the counter (the paper clears H at a refresh; Sec. 5 names counters with a longer
  * memory as future work): H[e] <- floor(H[e] * num / den) for every expert of the layer, on hip_stream.
@@ -320,6 +347,17 @@ int tide_scale_counts(tide_ctx* ctx, int layer, int num, int den, void* hip_stre
  * raw bytes of a cache slot (slot == capacity: the shared expert) to host. */
 int tide_get_table(tide_ctx* ctx, int layer, int32_t* slot_of_host, void* hip_stream);
 int tide_read_slot(tide_ctx* ctx, int layer, int slot, void* blob_host);
+
+/* Snapshot hook (tests): how the last tide_moe_step / tide_moe_step_routed on this context cut its hit pairs
+ * into grouped-GEMM work items.  Rows are the step's hit pairs (plus one row per token for the shared expert)
+ * sorted by cache slot, pairs of one slot in (token, rank) order; row_token_host[r] is the token of row r.  A
+ * work item is rows [row0, row0 + nrows) of one slot (slot == capacity: the shared expert); kind 0 = at most 32
+ * rows (a slot with more may be cut into several), kind 1 = up to 256 rows of a slot that holds more than 32.
+ * At most items_cap / rows_cap entries are written; *n_items_host / *n_rows_host are the full numbers.
+ * Synchronises hip_stream.  Not valid after tide_moe_apply_misses (it reuses the lists) or tide_moe_step_noalloc. */
+typedef struct { int32_t slot; int32_t row0; int32_t nrows; int32_t kind; } tide_work_item;
+int tide_read_work_items(tide_ctx* ctx, tide_work_item* items_host, int items_cap, int* n_items_host,
+                         int32_t* row_token_host, int rows_cap, int* n_rows_host, void* hip_stream);
 
 /* Per-call timing of the refresh copies of the LAST tide_refresh on the layer, in
  * milliseconds between the first copy starting and the last one landing; waits for them. */

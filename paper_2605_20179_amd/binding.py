@@ -27,7 +27,8 @@ EXPORTS = [
     "tide_host_experts", "tide_moe_apply_misses_host", "tide_host_miss_ms", "tide_host_expert", "tide_host_link_share", "tide_host_misses",
     "tide_compressed_blob_bytes", "tide_compress_expert", "tide_register_compressed",
     "tide_refresh_async", "tide_refresh_result",
-    "tide_moe_step_noalloc", "tide_noalloc_scratch_bytes",
+    "tide_moe_step_noalloc", "tide_noalloc_scratch_bytes", "tide_set_counts", "tide_read_work_items",
+    "tide_refresh_engine", "tide_queue_refresh_wait",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -88,12 +89,16 @@ def _load() -> C.CDLL:
     lib.tide_host_expert.argtypes = [cfgp, vp, vp, C.c_int, vp]
     lib.tide_host_misses.argtypes = [cfgp, vp, C.c_uint64, vp, C.c_int, vp, C.c_int, C.c_int, vp]
     lib.tide_interval_stats.argtypes = [vp, C.c_int, vp, C.c_int, vp]
+    lib.tide_set_counts.argtypes = [vp, C.c_int, vp, vp]
+    lib.tide_read_work_items.argtypes = [vp, vp, C.c_int, C.POINTER(C.c_int), vp, C.c_int, C.POINTER(C.c_int), vp]
     lib.tide_refresh.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, vp, vp, C.POINTER(C.c_int), vp]
     lib.tide_refresh_deferred.argtypes = lib.tide_refresh.argtypes
     lib.tide_refresh_async.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, vp]
     lib.tide_refresh_result.argtypes = [vp, C.c_int, vp, vp, C.POINTER(C.c_int)]
     lib.tide_commit.argtypes = [vp, C.c_int, vp]
     lib.tide_wait_refresh.argtypes = [vp, C.c_int]
+    lib.tide_queue_refresh_wait.argtypes = [vp, C.c_int, vp]
+    lib.tide_refresh_engine.argtypes = [vp, C.c_int]
     lib.tide_get_table.argtypes = [vp, C.c_int, vp, vp]
     lib.tide_read_slot.argtypes = [vp, C.c_int, C.c_int, vp]
     lib.tide_refresh_copy_ms.argtypes = [vp, C.c_int, C.POINTER(C.c_float)]
@@ -265,6 +270,25 @@ def tide_interval_stats(ctx, layer: int, n_experts: int, reset: bool, stream=Non
     return counts
 
 
+def tide_set_counts(ctx, layer: int, counts: np.ndarray, stream=None) -> None:
+    a = np.ascontiguousarray(np.asarray(counts, dtype=np.int32))
+    _check(lib.tide_set_counts(ctx, layer, _ptr(a), _stream_ptr(stream)), ctx)
+
+
+WORK_ITEM_DTYPE = np.dtype([("slot", np.int32), ("row0", np.int32), ("nrows", np.int32), ("kind", np.int32)])
+
+
+def tide_read_work_items(ctx, max_items: int, max_rows: int, stream=None):
+    """(work items of the last step as a WORK_ITEM_DTYPE array, row_token[rows])."""
+    items = np.zeros(max(max_items, 1), dtype=WORK_ITEM_DTYPE)
+    rows = np.zeros(max(max_rows, 1), dtype=np.int32)
+    n_items, n_rows = C.c_int(0), C.c_int(0)
+    _check(lib.tide_read_work_items(ctx, items.ctypes.data, max_items, C.byref(n_items), rows.ctypes.data, max_rows,
+                                    C.byref(n_rows), _stream_ptr(stream)), ctx)
+    assert n_items.value <= max_items and n_rows.value <= max_rows, "work-item snapshot truncated"
+    return items[:n_items.value].copy(), rows[:n_rows.value].copy()
+
+
 def tide_refresh(ctx, layer: int, ctx_capacity: int, capacity: int, counts: Optional[np.ndarray] = None,
                  reset_counts: bool = True, stream=None, deferred: bool = False):
     """Returns (expert_in_slot[ctx_capacity] int32, plan = list of (expert, slot, host_offset, bytes)).
@@ -296,6 +320,17 @@ def tide_refresh_result(ctx, layer: int, ctx_capacity: int):
 
 def tide_wait_refresh(ctx, layer: int) -> None:
     _check(lib.tide_wait_refresh(ctx, layer), ctx)
+
+
+TIDE_COPY_KERNEL, TIDE_COPY_DMA = 0, 1
+
+
+def tide_refresh_engine(ctx, engine: int) -> None:
+    _check(lib.tide_refresh_engine(ctx, engine), ctx)
+
+
+def tide_queue_refresh_wait(ctx, layer: int, stream=None) -> None:
+    _check(lib.tide_queue_refresh_wait(ctx, layer, _stream_ptr(stream)), ctx)
 
 
 def tide_refresh_copy_ms(ctx, layer: int) -> float:

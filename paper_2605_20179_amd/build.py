@@ -13,14 +13,12 @@ BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtide.so")
 
 SOURCES = ["router.hip", "dispatch.hip", "expert_gemm.hip", "combine.hip", "refresh.hip", "analysis.hip", "tide_api.hip"]
-HOST_SOURCES = ["host_experts.cpp"]      # plain C++ (the host cores' expert path), compiled by the host compiler
+HOST_SOURCES = ["host_experts.cpp", "host_pack.cpp"]      # plain C++ (the host cores' expert path), compiled by the host compiler
 HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-pthread", "-Wall", "-Wno-psabi", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
-if os.environ.get("TIDE_EXTRA_DEFINES"):          # e.g. "-DTIDE_BIG_MIN_ROWS=128" for tuning builds
-    FLAGS += os.environ["TIDE_EXTRA_DEFINES"].split()
 
 
 def _hipcc() -> str:

@@ -110,8 +110,9 @@ __device__ inline void emit_tasks(int slot, int row0, int m, bool use_big, Task*
     // 300 rows become 160 + 140, not 256 + 44, so the slot's work items finish together
     const int nb = (m + kRowsPerBigTask - 1) / kRowsPerBigTask;
     const int per = ((m + nb - 1) / nb + 15) / 16 * 16;      // <= kRowsPerBigTask, and (nb-1)*per < m
-    // big_room < nb only if the caller's routing repeats an expert inside a token (not allowed):
-    // the surplus rows are then left uncomputed rather than written out of bounds
+    // the host's bound on the step's large work items holds for any routing (rows / 256 plus one per slot that can
+    // exceed the small limit), so big_room >= nb; the clamp only keeps a bound that was computed for another token
+    // count from ever turning into a write out of bounds
     for (int c = threadIdx.x; c < nb && c < big_room; c += kThreads) {
         Task t;
         t.slot = slot;

@@ -291,20 +291,8 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
 // Small work items: up to 32 rows of one slot (the whole slot at block 32 / batch 1).
 // grid.x = feature tile, grid.y = work item (blocks past n_tasks[0] leave at once).
 constexpr int kSmallPC = 16;       // 512 columns per stage
-#ifndef TIDE_P0_RT
-#define TIDE_P0_RT 2
-#endif
-#ifndef TIDE_P0_D
-#define TIDE_P0_D 8
-#endif
-#ifndef TIDE_P1_RT
-#define TIDE_P1_RT 4
-#endif
-#ifndef TIDE_P1_D
-#define TIDE_P1_D 4
-#endif
-constexpr int kSmallRT0 = TIDE_P0_RT, kSmallD0 = TIDE_P0_D;   // gate/up: weight stripes per wave, ring depth
-constexpr int kSmallRT1 = TIDE_P1_RT, kSmallD1 = TIDE_P1_D;   // down
+constexpr int kSmallRT0 = 2, kSmallD0 = 8;   // gate/up: weight stripes per wave, ring depth
+constexpr int kSmallRT1 = 4, kSmallD1 = 4;   // down
 template <int PASS>
 __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
     const uint16_t* __restrict__ slots, int64_t blob_elems, int64_t off_w,

@@ -1,0 +1,14 @@
+// Host-side preparation of expert weights: the packed streaming layout of a blob and its lossless 12-bit
+// form.  Plain C++ with no HIP in it, so that it can also be built and run under the host sanitizers.
+#pragma once
+#include <stdint.h>
+
+namespace tide {
+
+// wg / wu [d_ff][d], wd [d][d_ff] row-major bf16 -> blob (3 * d * d_ff elements) in the layout tide_pack_expert documents.
+void pack_expert_blob(int d, int d_ff, const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, uint16_t* blob);
+
+// packed blob (blob_bytes, a multiple of 1024) -> its 12-bit form (packed12.h), p12_layout(blob_bytes / 1024).bytes long.
+void compress_expert_blob(uint64_t blob_bytes, const uint16_t* src, uint8_t* out);
+
+}  // namespace tide

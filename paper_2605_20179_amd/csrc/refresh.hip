@@ -148,10 +148,7 @@ __global__ __launch_bounds__(kCopyThreads) void refresh_copy_kernel(const uint8_
 // The same copies from the 12-bit form of the blobs (packed12.h): 3/4 of the bytes cross the host link.  A wave
 // decodes one tile per turn -- lane l reads 3 dwords at byte 12 l of the tile's payload and writes its 8 bf16
 // (16 bytes) -- and keeps six tiles in flight.  An expert whose header says "raw" is copied from the raw blob.
-#ifndef TIDE_P12_IN_FLIGHT
-#define TIDE_P12_IN_FLIGHT 6
-#endif
-constexpr int kP12InFlight = TIDE_P12_IN_FLIGHT;      // tiles a wave has in flight: 72 bytes per lane, as many as the raw copy's 64
+constexpr int kP12InFlight = 6;      // tiles a wave has in flight: 72 bytes per lane, as many as the raw copy's 64
 struct P12Words { uint32_t a, b, c; };
 __device__ inline uint4 p12_decode(P12Words w, uint32_t base) {
     uint32_t code[8];

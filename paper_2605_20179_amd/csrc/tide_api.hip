@@ -15,13 +15,14 @@
 #include <chrono>
 
 #include "host_experts.h"
+#include "host_pack.h"
 #include "packed12.h"
 #include "tide_internal.h"
 
 using namespace tide;
 
 static_assert(kHostGateUpGroup == kGateUpGroup && kHostDownGroup == kDownGroup,
-              "the host experts and the GEMM kernels read the same packed layout");
+              "the host packer, the host experts and the GEMM kernels agree on the packed layout");
 
 // Workspace of tide_moe_step_noalloc: one array per GPU, held until the process ends.  In host code the name is
 // only a handle for hipGetSymbolAddress; every use of the memory goes through the per-device pointer below.
@@ -110,6 +111,7 @@ struct tide_ctx {
     float* h_rows = nullptr;                // pinned, read by the device in place: [max_tokens][d]
     int32_t* h_tokens = nullptr;            // pinned, read by the device in place: [max_tokens]
     uint8_t* h_mask = nullptr;              // pinned, read by the device in place: [E] experts the GPU takes over the link
+    int copy_engine = TIDE_COPY_KERNEL;     // who moves a refresh's blobs: the copy kernel, or one DMA per blob
     int link_share = 0;                     // percent of a step's missed experts evaluated by the GPU over the host link
     float host_ms[3] = {0.f, 0.f, 0.f};     // last call: wait for the list, host compute, whole call
 };
@@ -190,41 +192,6 @@ int layer_ok(tide_ctx* ctx, int layer) {
 }
 
 uint16_t* slot_ptr(tide_ctx* ctx, Layer& L, int slot) { return L.slots_owned + (int64_t)slot * ctx->shape.blob_elems; }
-
-// One 16-row x 32-column tile of a row-major matrix -> 512 contiguous elements, lane-major:
-// lane l holds row stripe*16 + l%16, columns kc*32 + (l/16)*8 .. +7 (the A operand of the 16x16x32 MFMA).
-void pack_tile(const uint16_t* src, int cols, int stripe, int kc, uint16_t* tile) {
-    for (int l = 0; l < 64; ++l)
-        memcpy(tile + l * 8, src + (int64_t)(stripe * 16 + (l & 15)) * cols + kc * 32 + (l >> 4) * 8, 16);
-}
-
-// Streaming order of the tiles.  The 16-row stripes of a matrix are taken in groups -- the stripes one
-// workgroup of the GEMM kernels consumes together -- and inside a group the K chunk is the slow index,
-// so a workgroup walks one contiguous region front to back (16 KiB per chunk for a full group).
-//   gate/up: a group is 8 SwiGLU column blocks = their 8 gate stripes, then their 8 up stripes
-//   down:    a group is 16 stripes (256 output columns)
-// A last, partial group holds fewer stripes and is laid out the same way.
-void pack_gate_up(const uint16_t* wg, const uint16_t* wu, int d_ff, int d, uint16_t* dst) {
-    const int kchunks = d / 32, blocks = d_ff / 16;
-    for (int g = 0; g * kGateUpGroup < blocks; ++g) {
-        const int ng = std::min(kGateUpGroup, blocks - g * kGateUpGroup);
-        uint16_t* base = dst + (int64_t)g * 2 * kGateUpGroup * kchunks * 512;
-        for (int kc = 0; kc < kchunks; ++kc)
-            for (int j = 0; j < ng; ++j) {
-                pack_tile(wg, d, g * kGateUpGroup + j, kc, base + ((int64_t)kc * 2 * ng + j) * 512);
-                pack_tile(wu, d, g * kGateUpGroup + j, kc, base + ((int64_t)kc * 2 * ng + ng + j) * 512);
-            }
-    }
-}
-void pack_down(const uint16_t* wd, int d, int d_ff, uint16_t* dst) {
-    const int kchunks = d_ff / 32, stripes = d / 16;
-    for (int g = 0; g * kDownGroup < stripes; ++g) {
-        const int ng = std::min(kDownGroup, stripes - g * kDownGroup);
-        uint16_t* base = dst + (int64_t)g * kDownGroup * kchunks * 512;
-        for (int kc = 0; kc < kchunks; ++kc)
-            for (int j = 0; j < ng; ++j) pack_tile(wd, d_ff, g * kDownGroup + j, kc, base + ((int64_t)kc * ng + j) * 512);
-    }
-}
 
 int common_step(tide_ctx* ctx, const Workspace& ws, int layer, const void* hidden_dev, int n_tokens, const int32_t* idx,
                 const float* w, float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
@@ -339,10 +306,7 @@ int tide_pack_expert(const tide_config* cfg, const uint16_t* wg, const uint16_t*
     int rc = check_cfg(cfg);
     if (rc) return rc;
     if (!wg || !wu || !wd || !blob) return fail(nullptr, TIDE_E_INVAL, "null matrix or blob");
-    uint16_t* b = static_cast<uint16_t*>(blob);
-    const int64_t n = (int64_t)cfg->d * cfg->d_ff;
-    pack_gate_up(wg, wu, cfg->d_ff, cfg->d, b);
-    pack_down(wd, cfg->d, cfg->d_ff, b + 2 * n);
+    pack_expert_blob(cfg->d, cfg->d_ff, wg, wu, wd, static_cast<uint16_t*>(blob));
     return TIDE_OK;
 }
 
@@ -474,51 +438,7 @@ int tide_compress_expert(const tide_config* cfg, const void* blob_host, void* co
     int rc = check_cfg(cfg);
     if (rc) return rc;
     if (!blob_host || !comp_host) return fail(nullptr, TIDE_E_INVAL, "null matrix or blob pointer");
-    const uint32_t n_tiles = (uint32_t)(tide_expert_blob_bytes(cfg) / 1024);
-    const P12Layout lay = p12_layout(n_tiles);
-    uint8_t* out = static_cast<uint8_t*>(comp_host);
-    memset(out, 0, lay.bytes);
-    P12Header* h = reinterpret_cast<P12Header*>(out);
-    h->magic = kP12Magic;
-    h->n_tiles = n_tiles;
-    const uint16_t* src = static_cast<const uint16_t*>(blob_host);
-    uint32_t* exc_idx = reinterpret_cast<uint32_t*>(out + lay.off_exc_idx);
-    uint16_t* exc_val = reinterpret_cast<uint16_t*>(out + lay.off_exc_val);
-    uint32_t n_exc = 0;
-    for (uint32_t t = 0; t < n_tiles && !h->raw; ++t) {
-        const uint16_t* tile = src + (uint64_t)t * 512;
-        // base: the top of the 16-binade window that holds the most elements of the tile (the highest such window)
-        uint32_t hist[256 + 16] = {0};
-        for (int i = 0; i < 512; ++i) hist[(tile[i] >> 7) & 0xff]++;
-        uint32_t base = 15, in_window = 0, best = 0;
-        for (uint32_t e = 0; e < 16; ++e) in_window += hist[e];
-        best = in_window;
-        for (uint32_t top = 16; top < 256; ++top) {
-            in_window += hist[top] - hist[top - 16];
-            if (in_window >= best) { best = in_window; base = top; }
-        }
-        out[lay.off_base + t] = (uint8_t)base;
-        uint32_t* words = reinterpret_cast<uint32_t*>(out + lay.off_payload + (uint64_t)t * kP12TileBytes);
-        for (int l = 0; l < 64; ++l) {
-            uint32_t code[8];
-            for (int j = 0; j < 8; ++j) {
-                const uint32_t v = tile[l * 8 + j], e = (v >> 7) & 0xff;
-                uint32_t delta = base - e;             // wraps for an exponent above the window
-                if (delta > 15) {                      // outside the tile's 16-binade window: listed
-                    if (n_exc == n_tiles) { h->raw = 1; break; }
-                    exc_idx[n_exc] = t * 512 + l * 8 + j;
-                    exc_val[n_exc++] = (uint16_t)v;
-                    delta = 15;
-                }
-                code[j] = ((v >> 15) << 11) | (delta << 7) | (v & 0x7f);
-            }
-            if (h->raw) break;
-            words[l * 3 + 0] = code[0] | (code[1] << 12) | ((code[2] & 0xff) << 24);
-            words[l * 3 + 1] = (code[2] >> 8) | (code[3] << 4) | (code[4] << 16) | ((code[5] & 0xf) << 28);
-            words[l * 3 + 2] = (code[5] >> 4) | (code[6] << 8) | (code[7] << 20);
-        }
-    }
-    h->n_exc = h->raw ? 0 : n_exc;
+    compress_expert_blob(tide_expert_blob_bytes(cfg), static_cast<const uint16_t*>(blob_host), static_cast<uint8_t*>(comp_host));
     return TIDE_OK;
 }
 
@@ -874,6 +794,47 @@ int tide_interval_stats(tide_ctx* ctx, int layer, int32_t* counts_host, int rese
     return TIDE_OK;
 }
 
+int tide_set_counts(tide_ctx* ctx, int layer, const int32_t* counts_host, void* hip_stream) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    if (!counts_host) return fail(ctx, TIDE_E_INVAL, "counts_host is null");
+    for (int e = 0; e < ctx->cfg.n_experts; ++e)
+        if (counts_host[e] < 0) return fail(ctx, TIDE_E_RANGE, "counts_host[%d] is negative", e);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    TIDE_HIP(ctx, hipMemcpyAsync(ctx->layers[layer].t.hits, counts_host, (size_t)ctx->cfg.n_experts * 4, hipMemcpyHostToDevice, stream));
+    TIDE_HIP(ctx, hipStreamSynchronize(stream));
+    return TIDE_OK;
+}
+
+int tide_read_work_items(tide_ctx* ctx, tide_work_item* items_host, int items_cap, int* n_items_host, int32_t* row_token_host,
+                         int rows_cap, int* n_rows_host, void* hip_stream) {
+    if (!ctx) return TIDE_E_INVAL;
+    if (!n_items_host || !n_rows_host || items_cap < 0 || rows_cap < 0 || (items_cap > 0 && !items_host) || (rows_cap > 0 && !row_token_host))
+        return fail(ctx, TIDE_E_INVAL, "null output");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int32_t n_tasks[2] = {0, 0}, total_rows = 0;
+    TIDE_HIP(ctx, hipMemcpyAsync(n_tasks, ctx->ws.n_tasks, sizeof n_tasks, hipMemcpyDeviceToHost, stream));
+    TIDE_HIP(ctx, hipMemcpyAsync(&total_rows, ctx->ws.slot_off + ctx->cfg.capacity + 1, sizeof total_rows, hipMemcpyDeviceToHost, stream));
+    TIDE_HIP(ctx, hipStreamSynchronize(stream));
+    if (ctx->steps_issued == 0) n_tasks[0] = n_tasks[1] = total_rows = 0;
+    std::vector<Task> small((size_t)std::max(n_tasks[0], 0)), big((size_t)std::max(n_tasks[1], 0));
+    if (!small.empty()) TIDE_HIP(ctx, hipMemcpyAsync(small.data(), ctx->ws.tasks, small.size() * sizeof(Task), hipMemcpyDeviceToHost, stream));
+    if (!big.empty()) TIDE_HIP(ctx, hipMemcpyAsync(big.data(), ctx->ws.big_tasks, big.size() * sizeof(Task), hipMemcpyDeviceToHost, stream));
+    const int n_rows = std::min(std::max(total_rows, 0), ctx->max_rows);
+    if (std::min(n_rows, rows_cap) > 0)
+        TIDE_HIP(ctx, hipMemcpyAsync(row_token_host, ctx->ws.row_token, (size_t)std::min(n_rows, rows_cap) * 4, hipMemcpyDeviceToHost, stream));
+    TIDE_HIP(ctx, hipStreamSynchronize(stream));
+    int at = 0;
+    for (int kind = 0; kind < 2; ++kind)
+        for (const Task& t : (kind ? big : small)) {
+            if (at < items_cap) items_host[at] = tide_work_item{t.slot, t.row0, t.nrows, kind};
+            ++at;
+        }
+    *n_items_host = at;
+    *n_rows_host = n_rows;
+    return TIDE_OK;
+}
+
 namespace {
 // tide_refresh and tide_refresh_deferred.  Deferred: the selection runs on a copy of the tables, the
 // newcomers are copied into staging blobs, and the layer keeps serving from the old placement until
@@ -935,7 +896,13 @@ int refresh_impl(tide_ctx* ctx, int layer, const int32_t* counts_host, int capac
     }
     L.result_pending = async;
     TIDE_HIP(ctx, hipEventRecord(L.copies_begin, ctx->side));
-    if (L.comp_blobs)
+    if (ctx->copy_engine == TIDE_COPY_DMA && !async) {
+        // one DMA transfer per entering expert, raw blob to slot (or staging blob): the copy engines move the bytes,
+        // no compute unit is involved, so kernels that run beside the copies keep their memory pipelines to themselves
+        for (int i = 0; i < n; ++i)
+            TIDE_HIP(ctx, hipMemcpyAsync(copy_dst + (uint64_t)(deferred ? i : L.plan->slot[i]) * bytes,
+                                         L.host_blobs + (uint64_t)L.plan->expert[i] * L.host_stride, bytes, hipMemcpyHostToDevice, ctx->side));
+    } else if (L.comp_blobs)
         TIDE_HIP(ctx, launch_refresh_copies_p12(L.comp_blobs, L.comp_stride, L.host_blobs, L.host_stride, bytes, copy_dst, L.plan, n,
                                                 ctx->cfg.capacity, deferred, ctx->side));
     else
@@ -1015,6 +982,21 @@ int tide_commit(tide_ctx* ctx, int layer, void* hip_stream) {
     TIDE_HIP(ctx, hipMemcpyAsync(L.t.expert_in_slot, L.pend_eis, (size_t)ctx->cfg.capacity * 4, hipMemcpyDeviceToDevice, stream));
     L.pend_slots.clear();
     L.deferred_pending = false;
+    return TIDE_OK;
+}
+
+int tide_refresh_engine(tide_ctx* ctx, int engine) {
+    if (!ctx) return TIDE_E_INVAL;
+    if (engine != TIDE_COPY_KERNEL && engine != TIDE_COPY_DMA) return fail(ctx, TIDE_E_INVAL, "engine must be TIDE_COPY_KERNEL or TIDE_COPY_DMA");
+    ctx->copy_engine = engine;
+    return TIDE_OK;
+}
+
+int tide_queue_refresh_wait(tide_ctx* ctx, int layer, void* hip_stream) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    Layer& L = ctx->layers[layer];
+    if (L.copies_recorded) TIDE_HIP(ctx, hipStreamWaitEvent(static_cast<hipStream_t>(hip_stream), L.copies_done, 0));
     return TIDE_OK;
 }
 

@@ -15,18 +15,9 @@ constexpr int kMaxTopK = 16;             // one selection per lane of a 16-lane 
 constexpr int kMaxRouterSplits = 8;      // slices of the hidden dimension the router logits are computed in
 constexpr int kRowsPerTask = 32;        // rows of a small work item
 constexpr int kRowsPerBigTask = 256;    // rows of a large work item
-#ifndef TIDE_BIG_MIN_ROWS
-#define TIDE_BIG_MIN_ROWS 32
-#endif
-#ifndef TIDE_MIN_BIG_UNITS
-#define TIDE_MIN_BIG_UNITS 128
-#endif
-constexpr int kMinBigUnits = TIDE_MIN_BIG_UNITS;   // a step uses large work items only if they make at least this many gate/up workgroups (half the compute units)
-constexpr int kBigMinRows = TIDE_BIG_MIN_ROWS;   // a slot with more rows than this is cut into large work items, else into small ones
-#ifndef TIDE_BIG_MIN_AVG_ROWS
-#define TIDE_BIG_MIN_AVG_ROWS 48
-#endif
-constexpr int kBigMinAvgRows = TIDE_BIG_MIN_AVG_ROWS;   // steps with fewer rows per slot on average launch no large-item kernels at all
+constexpr int kMinBigUnits = 128;       // a step uses large work items only if they make at least this many gate/up workgroups (half the compute units)
+constexpr int kBigMinRows = 32;         // a slot with more rows than this is cut into large work items, else into small ones
+constexpr int kBigMinAvgRows = 48;      // steps with fewer rows per slot on average launch no large-item kernels at all
 
 // One grouped-GEMM work item: rows [row0, row0+nrows) of the slot-sorted row space
 // all belong to cache slot `slot` (slot == capacity means the shared expert).

@@ -63,3 +63,40 @@ def test_step_replayed_from_a_graph(wl):
     fresh.close()
     say("%s: 12 graph replays identical to the eager calls" % wl.name)
     sess.close()
+
+
+def test_replay_after_a_refresh_needs_the_queued_wait():
+    """A captured step holds no wait for refresh copies (the wait is decided when a step is issued).  After a
+    refresh, tide_queue_refresh_wait on the replay's stream orders the replay behind the copies: the replay then
+    equals the eager step on the new placement."""
+    from paper_2605_20179_amd import binding as tb
+    wl = ti.CONFIGS[1].replace(S=4)
+    sess = _session(wl)
+    load(sess, wl, 0)
+    hidden = [sess.to_device_bf16(h) for h in ti.hidden_stream(wl, 0, 2)]
+    static_in = hidden[0].clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sess.step(0, static_in)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sess.step(0, static_in)
+    # a refresh that replaces the whole budget: 64 blobs are in flight on the side stream when the replay is queued
+    counts = np.zeros(wl.E, dtype=np.int32)
+    counts[wl.C:2 * wl.C] = 1
+    eis, plan = sess.refresh(0, counts=counts)
+    assert len(plan) == wl.C
+    tb.tide_queue_refresh_wait(sess.ctx, 0, torch.cuda.current_stream())
+    static_in.copy_(hidden[1])
+    graph.replay()
+    torch.cuda.synchronize()
+    got = (sess.out[:wl.N].clone(), sess.miss[:int(sess.n_miss.item())].clone(), int(sess.n_miss.item()))
+    sess.step(0, hidden[1])                                # eager, on the settled new placement
+    torch.cuda.synchronize()
+    assert int(sess.n_miss.item()) == got[2] and torch.equal(sess.miss[:got[2]], got[1])
+    assert torch.equal(sess.out[:wl.N], got[0])
+    assert sorted(np.nonzero(sess.table(0) >= 0)[0].tolist()) == list(range(wl.C, 2 * wl.C))
+    sess.close()

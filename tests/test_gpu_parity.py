@@ -336,6 +336,38 @@ def test_two_layers_keep_separate_caches_and_counters():
     sess.close()
 
 
+@pytest.mark.parametrize("n_tokens,d_ff", [(24, 128), (600, 1024)])
+def test_routed_step_with_an_expert_repeated_inside_a_token(n_tokens, d_ff):
+    """tide_moe_step_routed documents distinct expert ids per token; a caller that repeats one still gets every row
+    evaluated and both weights applied (the sum the definition gives), hits counted per pair, nothing out of bounds --
+    also when the repeats pile more rows onto one slot than the step has tokens (1200 rows of 600 tokens, large work items)."""
+    wl = ti.TideWorkload("repeats", d=128, E=12, k=4, I=d_ff, n_shared=1, N=n_tokens, S=1, K=1, C=6, L=1,
+                         gating=ti.GATING_SIGMOID, bias_mode=ti.BIAS_NONE, seed=808)
+    hidden = next(iter(ti.hidden_stream(wl, 0)))
+    rng = np.random.default_rng(9)
+    idx = rng.integers(0, wl.E, size=(wl.N, wl.k)).astype(np.int32)
+    idx[:, 1] = idx[:, 0]                                   # every token names its first expert twice
+    idx[: wl.N // 2] = 3                                    # and half of the tokens name one resident expert four times
+    w = rng.random((wl.N, wl.k)).astype(np.float32)
+    w /= w.sum(axis=1, keepdims=True)
+    store = orc.ExpertStore(lambda e: ti.expert_weights(wl, 0, e))
+    shared = tuple(orc.bf16_to_f64(m) for m in ti.expert_weights(wl, 0, wl.E))
+    slot_of = orc.slot_table(ti.initial_resident(wl), wl.E)
+    y_res, y_full, miss = orc.moe_outputs(hidden, idx, w.astype(np.float64), slot_of, store, shared)
+    sess = _session(wl)
+    load(sess, wl, 0)
+    x = sess.to_device_bf16(hidden)
+    sess.step_routed(0, x, torch.from_numpy(idx).to(sess.device), torch.from_numpy(w).to(sess.device))
+    out, _, _, gmiss, n_miss = sess.results(wl.N)
+    check_miss(miss, gmiss, n_miss)
+    check_out(out, y_res)
+    assert np.array_equal(sess.stats(0), orc.step_histogram(idx, wl.E).astype(np.int32))
+    sess.apply_misses(0, x)
+    torch.cuda.synchronize()
+    check_out(sess.out[:wl.N].cpu().numpy(), y_full)
+    sess.close()
+
+
 @pytest.mark.parametrize("n_tokens,n_experts,k,bias_mode", [(16, 64, 6, ti.BIAS_NONE), (32, 256, 8, ti.BIAS_LOGIT),
                                                              (200, 64, 6, ti.BIAS_SELECT), (90, 300, 16, ti.BIAS_NONE)])
 def test_exactly_equal_scores_go_to_the_lower_expert_id(n_tokens, n_experts, k, bias_mode):

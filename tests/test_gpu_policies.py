@@ -104,8 +104,9 @@ def test_other_budgets_and_block_lengths(budget, block):
     sess.close()
 
 
-def test_deferred_refresh_and_commit():
-    """The overlapped variant: the refresh before step t only stages its newcomers; step t runs on the old
+@pytest.mark.parametrize("engine", [tb.TIDE_COPY_KERNEL, tb.TIDE_COPY_DMA], ids=["copy-kernel", "dma"])
+def test_deferred_refresh_and_commit(engine):
+    """Both copy engines (the side-stream copy kernel; one DMA transfer per entering expert).  The overlapped variant: the refresh before step t only stages its newcomers; step t runs on the old
     placement; tide_commit installs the new one before step t+1 (or, called later, before step t+j).  Counter, tables, plans, miss lists and the
     bytes of every cache slot are compared with the oracle's delayed placement."""
     wl = ti.CONFIGS[1].replace(S=14)
@@ -114,6 +115,10 @@ def test_deferred_refresh_and_commit():
             ti.initial_resident(wl))
     sess = _session(wl)
     load(sess, wl, 0)
+    tb.tide_refresh_engine(sess.ctx, engine)
+    with pytest.raises(tb.TideError) as err:
+        tb.tide_refresh_engine(sess.ctx, 2)
+    assert err.value.code == tb.TIDE_E_INVAL
     host = sess.host_blobs[0].numpy()
     with pytest.raises(tb.TideError) as err:
         sess.commit(0)
@@ -152,6 +157,15 @@ def test_deferred_refresh_and_commit():
             assert np.array_equal(sess.read_slot(0, s), host[final[s]]), "slot %d" % s
         say("deferred refresh K=%d, serving %d step(s) late: %d steps exact, miss rate %.4f"
             % (K, delay, len(log), sum(len(r["miss"]) for r in log) / (len(log) * wl.N * wl.k)))
+    # the immediate refresh through the same engine: slots byte-equal to the host blobs of the experts the table names
+    tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))
+    counts = np.zeros(wl.E, dtype=np.int32)
+    counts[wl.C:wl.C + 5] = 3
+    eis, plan = sess.refresh(0, counts=counts)
+    assert len(plan) == 5 and sorted(e for e, _, _, _ in plan) == list(range(wl.C, wl.C + 5))
+    tb.tide_wait_refresh(sess.ctx, 0)
+    for e, s_, off, nbytes in plan:
+        assert np.array_equal(sess.read_slot(0, s_), host[e]), "slot %d after an immediate refresh" % s_
     # a placement set by hand cancels a pending refresh
     sess.refresh(0, deferred=True)
     tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))
