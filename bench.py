@@ -111,6 +111,194 @@ def run_stack(args, wl, ti, tb, TideSession, torch):
     sess.close()
 
 
+def layer_rooflines(wl, blob, active, rows, gate_up_s, down_s, step_s):
+    """Fractions of the HBM and bf16-MFMA peaks for the two grouped GEMM passes and for the whole step, from the
+    step's own counters: `active` cache slots with at least one token (shared expert included), `rows` (token,
+    expert) rows evaluated.  Algorithmic bytes: every active slot's weights once, the hidden states once, the
+    activations / outputs a pass writes once.  The step figure is given twice: the algorithmic bytes alone, and
+    with the intermediates the implementation materialises (activations and per-row outputs, written once and
+    read once each)."""
+    def pass_(bytes_, flop, secs):
+        if not secs:
+            return None
+        return {"us": secs * 1e6, "algorithmic_bytes": bytes_, "flop": flop,
+                "hbm": {"achieved": bytes_ / secs / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes_ / secs / 1e9 / HBM_PEAK_GBS},
+                "mfma": {"achieved": flop / secs / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": flop / secs / 1e12 / MFMA_BF16_PEAK_TFLOPS}}
+    step_alg = active * blob + wl.E * wl.d * 4 + wl.N * wl.d * 2 + wl.N * wl.d * 4
+    step_mat = step_alg + 2 * rows * wl.I * 2 + 2 * rows * wl.d * 4
+    step_flop = rows * 6.0 * wl.d * wl.I + 2.0 * wl.N * wl.d * wl.E
+    return {"gate_up": pass_(active * (2 * blob / 3) + wl.N * wl.d * 2 + rows * wl.I * 2, rows * 4.0 * wl.d * wl.I, gate_up_s),
+            "down": pass_(active * (blob / 3) + rows * wl.I * 2 + rows * wl.d * 4, rows * 2.0 * wl.d * wl.I, down_s),
+            "step": {"us": step_s * 1e6, "algorithmic_bytes": step_alg, "flop": step_flop,
+                     "hbm_frac": step_alg / step_s / 1e9 / HBM_PEAK_GBS,
+                     "bytes_with_activation_and_row_output_round_trips": step_mat,
+                     "hbm_frac_with_round_trips": step_mat / step_s / 1e9 / HBM_PEAK_GBS,
+                     "mfma_frac": step_flop / step_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}}
+
+
+def pair_seconds(prof, small, big):
+    """Mean duration of one pass of a step: its small-item and large-item launches start together on two streams,
+    so the pass lasts as long as the longer of the two."""
+    ms_s, n_s = prof.get(small, (0.0, 0))
+    ms_b, n_b = prof.get(big, (0.0, 0))
+    cand = [ms / n for ms, n in ((ms_s, n_s), (ms_b, n_b)) if n]
+    return 1e-3 * max(cand) if cand else None
+
+
+def measure_layer(wl, ti, tb, TideSession, torch, packed, steps, warmup, refresh_source, comp=None):
+    """One layer of workload `wl` (any of the five configurations): tokens/s with the refresh every K steps (copies
+    from `refresh_source`, and once more from the raw blobs), tokens/s with the placement frozen, per-kernel
+    durations from event-stamped launches of a frozen pass, and the roofline fractions they give."""
+    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode)
+    sess.load_layer(0, None, ti.router_weights(wl, 0), ti.router_bias(wl, 0), ti.initial_resident(wl), packed=packed)
+    use_p12 = refresh_source == "packed12" and wl.C < wl.E
+    if use_p12:
+        if comp is None:
+            sess.compress_layer(0, workers=16)
+            comp = sess.comp_blobs[0]
+        else:
+            tb.tide_register_compressed(sess.ctx, 0, comp, tb.tide_compressed_blob_bytes(sess.cfg))
+    hidden = [sess.to_device_bf16(h) for h in ti.hidden_stream(wl, 0)]
+    torch.cuda.synchronize()
+
+    def block_loop(n_steps, warm):
+        tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))
+        sess.stats(0, reset=True)
+        copies = 0
+        for i in range(warm + n_steps):
+            if i == warm:
+                torch.cuda.synchronize()
+                tb.tide_counters(sess.ctx, reset=True)
+                copies = 0
+                t0 = time.perf_counter()
+            t = i % wl.S
+            if t > 0 and t % wl.K == 0:
+                copies += len(sess.refresh(0)[1])
+            sess.step(0, hidden[t], want_topk=False)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, copies, tb.tide_counters(sess.ctx)
+
+    dt, copies, cnt = block_loop(steps, warmup)
+    raw = None
+    if use_p12:
+        tb.tide_register_compressed(sess.ctx, 0, None, 0)
+        raw_dt, _, _ = block_loop(steps, warmup)
+        raw = wl.N * steps / raw_dt
+    # placement as the loop left it, no refresh: every kernel stamped, then the same steps unstamped
+    tb.tide_profile(sess.ctx, 1)
+    tb.tide_counters(sess.ctx, reset=True)
+    for i in range(steps):
+        sess.step(0, hidden[i % wl.S], want_topk=False)
+    prof = tb.tide_profile_read(sess.ctx)
+    fcnt = tb.tide_counters(sess.ctx)
+    tb.tide_profile(sess.ctx, False)
+    torch.cuda.synchronize()
+    f0 = time.perf_counter()
+    for i in range(steps):
+        sess.step(0, hidden[i % wl.S], want_topk=False)
+    torch.cuda.synchronize()
+    frozen_s = (time.perf_counter() - f0) / steps
+    active, rows = fcnt["active_slots"] / fcnt["steps"], fcnt["rows"] / fcnt["steps"]
+    res = {"workload": wl.name, "tokens_per_step": wl.N, "d": wl.d, "d_ff": wl.I, "capacity": wl.C, "layers_in_workload": wl.L,
+           "layers_measured": 1, "steps": steps, "warmup": warmup,
+           "tokens_per_s": wl.N * steps / dt, "ms_per_step": 1e3 * dt / steps, "refresh_source": refresh_source if use_p12 else "raw",
+           "tokens_per_s_raw_refresh_copies": raw if raw is not None else wl.N * steps / dt,
+           "experts_copied": copies, "hit_rate": 1.0 - cnt["misses"] / (wl.N * wl.k * cnt["steps"]),
+           "frozen_placement": {"us_per_step": frozen_s * 1e6, "tokens_per_s": wl.N / frozen_s, "hit_rate": 1.0 - fcnt["misses"] / (wl.N * wl.k * fcnt["steps"]),
+                                "active_slots_per_step": active, "rows_per_step": rows},
+           "kernels_us": {name: 1e3 * ms / n for name, (ms, n) in prof.items() if n},
+           "roofline": layer_rooflines(wl, sess.blob_bytes, active, rows, pair_seconds(prof, "gate_up_swiglu", "gate_up_swiglu_big"),
+                                       pair_seconds(prof, "down", "down_big"), frozen_s)}
+    sess.close()
+    return res, comp
+
+
+def measure_stack(wl, L, ti, tb, TideSession, torch, packed, steps, comp=None, refresh=True):
+    """The workload as the stack it is: L independent layers per denoise step in one context (own router, hidden
+    stream, cache, counter, refresh per layer; the layers share layer 0's expert values).  tokens/s = N / sum of
+    the layers' times, with the placement frozen and (refresh=True) with every layer refreshed every K steps, all
+    layers first so that later layers' copies run under earlier layers' compute."""
+    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, n_layers=L)
+    import concurrent.futures
+    n_hidden = min(wl.S, 2 * wl.K) if (refresh and wl.C < wl.E) else 2
+    with concurrent.futures.ThreadPoolExecutor(max_workers=16) as ex:
+        streams = list(ex.map(lambda l: list(ti.hidden_stream(wl, l, n_hidden)), range(L)))
+    hidden = []
+    for l in range(L):
+        sess.load_layer(l, None, ti.router_weights(wl, l), ti.router_bias(wl, l), ti.initial_resident(wl), packed=packed)
+        if comp is not None and wl.C < wl.E:
+            tb.tide_register_compressed(sess.ctx, l, comp, tb.tide_compressed_blob_bytes(sess.cfg))
+        hidden.append([sess.to_device_bf16(h) for h in streams[l]])
+    del streams
+    torch.cuda.synchronize()
+    free_b, total_b = torch.cuda.mem_get_info()
+    out = {"layers": L, "capacity": wl.C, "tokens_per_step": wl.N, "cache_slots_GiB": L * (wl.C + 1) * sess.blob_bytes / 2 ** 30,
+           "device_memory_in_use_GiB": (total_b - free_b) / 2 ** 30,
+           "note": "layers share layer 0's expert values in pinned host memory; routers, hidden streams, caches, counters and refreshes are per layer"}
+    copies = 0
+    if refresh and wl.C < wl.E:
+        def one(i):                                    # the hidden states cycle; the refresh schedule keeps counting
+            n = 0
+            if i > 0 and i % wl.K == 0:
+                for l in range(L):
+                    n += len(sess.refresh(l)[1])
+            for l in range(L):
+                sess.step(l, hidden[l][i % n_hidden], want_topk=False)
+            return n
+        for i in range(n_hidden):                     # one pass to leave the cold start behind
+            one(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n_hidden, n_hidden + steps):
+            copies += one(i)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        out.update({"tokens_per_s": wl.N / dt, "ms_per_stack_step": dt * 1e3, "experts_copied": copies, "steps": steps})
+    for l in range(L):
+        sess.step(l, hidden[l][0], want_topk=False)
+    torch.cuda.synchronize()
+    s0 = time.perf_counter()
+    for i in range(steps):
+        for l in range(L):
+            sess.step(l, hidden[l][i % n_hidden], want_topk=False)
+    torch.cuda.synchronize()
+    frozen = (time.perf_counter() - s0) / steps
+    out["frozen_placement"] = {"ms_per_stack_step": frozen * 1e3, "us_per_layer": frozen * 1e6 / L, "tokens_per_s": wl.N / frozen}
+    if "tokens_per_s" not in out:
+        out.update({"tokens_per_s": wl.N / frozen, "ms_per_stack_step": frozen * 1e3, "steps": steps, "experts_copied": 0})
+    sess.close()
+    return out
+
+
+def run_all_configs(args, ti, tb, TideSession, torch, cfg1_entry, packed_mini, comp_mini):
+    """The other configurations in the same run, short: one layer of each (tokens/s with refresh and with the placement
+    frozen, kernel durations, roofline fractions), and the two stack workloads at their depth (20 mini layers; 32 flash
+    layers with 64 slots per layer and with every expert resident).  Keyed by configuration id."""
+    out = {"1": cfg1_entry}
+    mini, flash = ti.CONFIGS[2], ti.CONFIGS[3]
+    t0 = time.perf_counter()
+    wl0 = ti.CONFIGS[0]
+    s0 = TideSession(wl0.d, wl0.E, wl0.k, wl0.I, wl0.n_shared, wl0.C, wl0.N, wl0.gating, wl0.bias_mode)
+    packed0 = s0.pack_layer(lambda e: ti.expert_weights(wl0, 0, e), workers=4)
+    s0.close()
+    out["0"], _ = measure_layer(wl0, ti, tb, TideSession, torch, packed0, 64, 16, args.refresh_source)
+    out["2"], comp_mini = measure_layer(mini, ti, tb, TideSession, torch, packed_mini, 64, 8, args.refresh_source, comp=comp_mini)
+    out["2"]["stack"] = measure_stack(mini, mini.L, ti, tb, TideSession, torch, packed_mini, 16, comp=comp_mini)
+    probe = TideSession(flash.d, flash.E, flash.k, flash.I, flash.n_shared, 1, 1, flash.gating, flash.bias_mode)
+    packed_flash = probe.pack_layer(lambda e: ti.expert_weights(flash, 0, e), workers=16)
+    probe.close()
+    out["3"], comp_flash = measure_layer(flash, ti, tb, TideSession, torch, packed_flash, 64, 8, args.refresh_source)
+    c4 = ti.CONFIGS[4]
+    out["4"], _ = measure_layer(c4, ti, tb, TideSession, torch, packed_flash, 64, 8, args.refresh_source, comp=comp_flash)
+    out["4"]["all_experts_resident"], _ = measure_layer(c4.replace(C=c4.E), ti, tb, TideSession, torch, packed_flash, 16, 4, "raw")
+    torch.cuda.empty_cache()
+    out["4"]["stack"] = measure_stack(c4, c4.L, ti, tb, TideSession, torch, packed_flash, 8, comp=comp_flash)
+    out["4"]["stack_all_experts_resident"] = measure_stack(c4.replace(C=c4.E), c4.L, ti, tb, TideSession, torch, packed_flash, 4, refresh=False)
+    out["seconds_spent_on_this_table"] = time.perf_counter() - t0
+    return out
+
+
 TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "cfg1_mini_layer_hbm_traffic.md")
 
 
@@ -204,6 +392,9 @@ def main():
                     help="comma list of percents: share of a step's missed experts the GPU evaluates over the host link while the host "
                          "workers do the rest (0 = all on the host cores, the paper's design); one 'host' measurement per value")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="only the headline workload: skip the per-configuration table (configurations 0, 2, 3, 4 and the two stacks "
+                         "at their depth) that the default run appends after it")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--events", choices=("all", "gemm", "gate-up"), default="gate-up",
                     help="which launches of the timed region carry start/stop events (an event-stamped launch costs the host ~15 us): "
@@ -270,8 +461,8 @@ def main():
         run_stack(args, wl, ti, tb, TideSession, torch)
         return
     sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode)
-    sess.load_layer(0, lambda e: ti.expert_weights(wl, 0, e), ti.router_weights(wl, 0), ti.router_bias(wl, 0),
-                    ti.initial_resident(wl), workers=16)
+    packed = sess.pack_layer(lambda e: ti.expert_weights(wl, 0, e), workers=16)
+    sess.load_layer(0, None, ti.router_weights(wl, 0), ti.router_bias(wl, 0), ti.initial_resident(wl), packed=packed)
     if args.refresh_source == "packed12":
         sess.compress_layer(0, workers=16)
     hidden = [sess.to_device_bf16(h) for h in ti.hidden_stream(wl, 0)]
@@ -492,9 +683,34 @@ def main():
                                        "avg_kernel_us": 1e3 * ms2 / n2,
                                        "measured_in": "frozen-placement pass" if "down" in from_frozen_pass else "timed region"}
 
-    if roofline is not None and args.config == 1:
-        roofline["traffic"], roofline["traffic_source"] = read_traffic_summary()
+    if roofline is not None and args.config == 1 and not (args.tokens or args.capacity):
+        roofline["traffic"], src = read_traffic_summary()
+        roofline["traffic_measured"] = ("offline, not by this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, "
+                                        "scaled by a plain copy of known size; summary in %s" % src)
     step_bytes = (cnt["active_slots"] / cnt["steps"]) * blob + wl.E * wl.d * 4 + wl.N * wl.d * 2 + wl.N * wl.d * 4
+    configs = None
+    if not args.headline_only and args.config == 1 and not (args.tokens or args.capacity):
+        comp1 = sess.comp_blobs[0] if args.refresh_source == "packed12" else None
+        sess.close()
+        this = {"workload": wl.name, "tokens_per_step": wl.N, "d": wl.d, "d_ff": wl.I, "capacity": wl.C, "layers_in_workload": 1,
+                "layers_measured": 1, "steps": args.steps, "warmup": args.warmup, "tokens_per_s": value, "ms_per_step": 1e3 * dt / args.steps,
+                "refresh_source": args.refresh_source,
+                "tokens_per_s_raw_refresh_copies": raw_source["tokens_per_s"] if raw_source else no_events["tokens_per_s"],
+                "frozen_placement": {"us_per_step": step_only_s * 1e6, "tokens_per_s": wl.N / step_only_s},
+                "kernels_us": {k_: v_["avg_us"] for k_, v_ in kernels.items()},
+                "roofline": None if frozen_cnt is None else layer_rooflines(
+                    wl, blob, frozen_cnt["active_slots"] / frozen_cnt["steps"], frozen_cnt["rows"] / frozen_cnt["steps"],
+                    1e-6 * kernels["gate_up_swiglu"]["avg_us"], 1e-6 * kernels["down"]["avg_us"], step_only_s)}
+        configs = run_all_configs(args, ti, tb, TideSession, torch, this, packed, comp1)
+        if roofline is not None and configs.get("4") and configs["4"].get("roofline"):
+            c4 = configs["4"]
+            roofline["cfg4"] = {"workload": c4["workload"], "tokens_per_step": c4["tokens_per_step"], "capacity": c4["capacity"],
+                                "layers_measured": 1, "tokens_per_s": c4["tokens_per_s"],
+                                "tokens_per_s_frozen_placement": c4["frozen_placement"]["tokens_per_s"],
+                                "kernel": "expert_gemm_big_kernel<0> beside expert_gemm_kernel<0> (grouped gate/up GEMM + SwiGLU)",
+                                "bound": "mfma", "mfma": c4["roofline"]["gate_up"]["mfma"], "hbm": c4["roofline"]["gate_up"]["hbm"],
+                                "avg_kernel_us": c4["roofline"]["gate_up"]["us"], "down_kernel": c4["roofline"]["down"],
+                                "step": c4["roofline"]["step"]}
     out = {
         "metric": "MoE-layer tokens/s per denoise step", "value": value, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True,
@@ -503,7 +719,10 @@ def main():
                    "tokens_per_step": wl.N, "capacity": wl.C, "refresh_interval": wl.K, "steps_per_block": wl.S, "layers": 1,
                    "refresh_source": args.refresh_source, "refresh_call": args.refresh_call,
                    "refresh_mode": args.refresh_mode if args.refresh_mode == "immediate" else "deferred by %d step(s)" % args.commit_after},
+        "value_refresh_source": args.refresh_source + (" (lossless 12-bit form of the blobs read over the host link)" if args.refresh_source == "packed12" else " blobs"),
+        "value_with_raw_refresh_copies": (raw_source or no_events)["tokens_per_s"],
         "roofline": roofline,
+        "configs": configs,
         "detail": {
             "kernels": kernels, "kernels_measured_in_frozen_placement_pass": from_frozen_pass,
             "step_hbm_roofline_us": step_bytes / (HBM_PEAK_GBS * 1e9) * 1e6,
@@ -524,7 +743,8 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, ti)
-    sess.close()
+    if sess.ctx:
+        sess.close()
     print(json.dumps(out))
 
 
