@@ -210,6 +210,9 @@ def measure_layer(wl, ti, tb, TideSession, torch, packed, steps, warmup, refresh
            "kernels_us": {name: 1e3 * ms / n for name, (ms, n) in prof.items() if n},
            "roofline": layer_rooflines(wl, sess.blob_bytes, active, rows, pair_seconds(prof, "gate_up_swiglu", "gate_up_swiglu_big"),
                                        pair_seconds(prof, "down", "down_big"), frozen_s)}
+    rate, nbytes = tb.tide_hbm_stream_probe(sess.ctx, 0, 8)
+    res["hbm_stream_probe"] = {"GB/s": rate, "bytes_per_launch": nbytes, "frac_of_peak": rate / HBM_PEAK_GBS,
+                               "what": "a kernel that only reads this layer's cache slots once, in the GEMMs' weight-stream shape"}
     sess.close()
     return res, comp
 
@@ -371,6 +374,9 @@ def main():
     ap.add_argument("--refresh-call", choices=("sync", "async"), default="sync",
                     help="immediate refresh through tide_refresh (the host waits for the plan, then queues the copies) or "
                          "tide_refresh_async (everything queued at once; the plans are read after the timed region)")
+    ap.add_argument("--copy-engine", choices=("kernel", "dma"), default="kernel",
+                    help="who moves a refresh's blobs over the host link: the library's copy kernel on the side stream (reads the 12-bit "
+                         "form when --refresh-source packed12), or one hipMemcpyAsync per entering expert (raw blobs, copy engines only)")
     ap.add_argument("--commit-after", type=int, default=1,
                     help="deferred mode: steps that still run on the old placement before the new one is committed (1..refresh interval)")
     ap.add_argument("--tokens", type=int, default=0, help="tokens per step (0 = the workload's own; e.g. 4096 = batch 128 of block 32)")
@@ -465,6 +471,8 @@ def main():
     sess.load_layer(0, None, ti.router_weights(wl, 0), ti.router_bias(wl, 0), ti.initial_resident(wl), packed=packed)
     if args.refresh_source == "packed12":
         sess.compress_layer(0, workers=16)
+    if args.copy_engine == "dma":
+        tb.tide_refresh_engine(sess.ctx, tb.TIDE_COPY_DMA)
     hidden = [sess.to_device_bf16(h) for h in ti.hidden_stream(wl, 0)]
     torch.cuda.synchronize()
 
@@ -683,6 +691,11 @@ def main():
                                        "avg_kernel_us": 1e3 * ms2 / n2,
                                        "measured_in": "frozen-placement pass" if "down" in from_frozen_pass else "timed region"}
 
+    if roofline is not None:
+        rate, nbytes = tb.tide_hbm_stream_probe(sess.ctx, 0, 8)
+        roofline["hbm_stream_probe"] = {"GB/s": rate, "bytes_per_launch": nbytes, "frac_of_peak": rate / HBM_PEAK_GBS,
+                                        "what": "a kernel that only reads this layer's cache slots once, in the GEMMs' weight-stream shape "
+                                                "(slot sets under the chip's 256 MB memory-side cache read faster than HBM delivers)"}
     if roofline is not None and args.config == 1 and not (args.tokens or args.capacity):
         roofline["traffic"], src = read_traffic_summary()
         roofline["traffic_measured"] = ("offline, not by this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, "
@@ -717,7 +730,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "d": wl.d, "experts": wl.E, "top_k": wl.k, "d_ff": wl.I, "shared_experts": wl.n_shared,
                    "tokens_per_step": wl.N, "capacity": wl.C, "refresh_interval": wl.K, "steps_per_block": wl.S, "layers": 1,
-                   "refresh_source": args.refresh_source, "refresh_call": args.refresh_call,
+                   "refresh_source": args.refresh_source if args.copy_engine == "kernel" else "raw", "refresh_call": args.refresh_call,
+                   "copy_engine": args.copy_engine,
                    "refresh_mode": args.refresh_mode if args.refresh_mode == "immediate" else "deferred by %d step(s)" % args.commit_after},
         "value_refresh_source": args.refresh_source + (" (lossless 12-bit form of the blobs read over the host link)" if args.refresh_source == "packed12" else " blobs"),
         "value_with_raw_refresh_copies": (raw_source or no_events)["tokens_per_s"],

@@ -388,6 +388,14 @@ int tide_profile(tide_ctx* ctx, int enable);
  * milliseconds (ms_sum_host[TIDE_K_COUNT]) and the number of launches
  * (launches_host[TIDE_K_COUNT]) since the last read, and clears the samples. */
 int tide_profile_read(tide_ctx* ctx, double* ms_sum_host, int64_t* launches_host);
+/* What this GPU's HBM delivers to a kernel that does nothing but read: the layer's cache slots (capacity +
+ * n_shared blobs) are read once per launch, in the access shape of the expert GEMMs' weight stream (whole 1 KiB
+ * tiles per wave, non-temporal, eight in flight, two workgroups per compute unit), `repeats` times after one
+ * warm-up launch.  *gbytes_per_s_host = bytes per launch / mean launch duration (dispatch-stamped events);
+ * *bytes_host (may be NULL) = bytes per launch.  A yardstick for the HBM fractions the step kernels reach:
+ * slot sets smaller than the chip's 256 MB memory-side cache read faster than HBM can deliver.
+ * Synchronises the device; touches no state. */
+int tide_hbm_stream_probe(tide_ctx* ctx, int layer, int repeats, double* gbytes_per_s_host, uint64_t* bytes_host);
 /* Running totals kept on the device by the step itself: out4_host = {steps, cache slots
  * (shared expert included) that had at least one token, expert rows evaluated, misses}.
  * Synchronises hip_stream; reset != 0 zeroes them afterwards. */

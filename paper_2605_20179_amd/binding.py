@@ -28,7 +28,7 @@ EXPORTS = [
     "tide_compressed_blob_bytes", "tide_compress_expert", "tide_register_compressed",
     "tide_refresh_async", "tide_refresh_result",
     "tide_moe_step_noalloc", "tide_noalloc_scratch_bytes", "tide_set_counts", "tide_read_work_items",
-    "tide_refresh_engine", "tide_queue_refresh_wait",
+    "tide_refresh_engine", "tide_queue_refresh_wait", "tide_hbm_stream_probe",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -105,6 +105,7 @@ def _load() -> C.CDLL:
     lib.tide_profile.argtypes = [vp, C.c_int]
     lib.tide_profile_read.argtypes = [vp, vp, vp]
     lib.tide_counters.argtypes = [vp, vp, C.c_int, vp]
+    lib.tide_hbm_stream_probe.argtypes = [vp, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
     lib.tide_step_histogram.argtypes = [vp, vp, C.c_int, vp]
     lib.tide_routing_stability.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp]
     lib.tide_interval_costs.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, vp, vp, vp]
@@ -369,6 +370,13 @@ def tide_counters(ctx, reset: bool = False, stream=None):
     out = np.zeros(4, dtype=np.int64)
     _check(lib.tide_counters(ctx, _ptr(out), int(reset), _stream_ptr(stream)), ctx)
     return dict(steps=int(out[0]), active_slots=int(out[1]), rows=int(out[2]), misses=int(out[3]))
+
+
+def tide_hbm_stream_probe(ctx, layer: int = 0, repeats: int = 8):
+    """(GB/s, bytes per launch) of a read-only pass over the layer's cache slots in the GEMMs' weight-stream shape."""
+    rate, nbytes = C.c_double(0.0), C.c_uint64(0)
+    _check(lib.tide_hbm_stream_probe(ctx, layer, repeats, C.byref(rate), C.byref(nbytes)), ctx)
+    return rate.value, nbytes.value
 
 
 def tide_step_histogram(ctx, n_experts: int, stream=None) -> np.ndarray:

@@ -231,6 +231,34 @@ __global__ __launch_bounds__(256) void refresh_patch_p12_kernel(const uint8_t* _
     }
 }
 
+// Measurement only: every workgroup reads its share of `bytes` once, front to back, with the access shape of the
+// expert GEMMs' weight stream -- each wave fetches whole 1 KiB tiles, 16 bytes per lane, non-temporal, eight tiles
+// in flight -- and folds what it read into one word per thread so that the loads cannot be dropped.
+constexpr int kProbeInFlight = 8;
+__global__ __launch_bounds__(256) void stream_probe_kernel(const uint8_t* __restrict__ base, uint64_t tiles, uint32_t* __restrict__ sink) {
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint64_t wave = ((uint64_t)blockIdx.x * 256 + threadIdx.x) >> 6, n_waves = (uint64_t)gridDim.x * 4;
+    // a wave owns a contiguous run of tiles (as a GEMM workgroup walks one contiguous region)
+    const uint64_t per = (tiles + n_waves - 1) / n_waves;
+    const uint64_t t0 = wave * per, t1 = t0 + per < tiles ? t0 + per : tiles;
+    uint32_t acc = 0;
+    uint64_t t = t0;
+    for (; t + kProbeInFlight <= t1; t += kProbeInFlight) {
+        u32x4 v[kProbeInFlight];
+#pragma unroll
+        for (int u = 0; u < kProbeInFlight; ++u)
+            v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (t + u) * 1024 + lane * 16));
+#pragma unroll
+        for (int u = 0; u < kProbeInFlight; ++u) acc ^= v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
+    }
+    for (; t < t1; ++t) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + t * 1024 + lane * 16));
+        acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;          // practically never true: the store only keeps the reads alive
+}
+
 __global__ void scale_counts_kernel(int32_t* hits, int n, int num, int den) {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e < n) hits[e] = (int32_t)(((int64_t)hits[e] * num) / den);
@@ -269,6 +297,11 @@ hipError_t launch_refresh_copies_p12(const uint8_t* comp_blobs, uint64_t comp_st
                        host_blobs, host_stride, blob_bytes, dst_base, plan, n, dst_by_rank ? 1 : 0);
     hipLaunchKernelGGL(refresh_patch_p12_kernel, dim3(n < 0 ? max_n : n), dim3(256), 0, stream, comp_blobs, comp_stride, blob_bytes, dst_base,
                        plan, dst_by_rank ? 1 : 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_probe(const uint8_t* base, uint64_t bytes, int workgroups, uint32_t* sink, hipStream_t stream, LaunchEvents ev) {
+    TIDE_LAUNCH(stream_probe_kernel, dim3(workgroups), dim3(256), stream, ev, base, bytes / 1024, sink);
     return hipGetLastError();
 }
 

@@ -1074,6 +1074,38 @@ int tide_profile_read(tide_ctx* ctx, double* ms_sum, int64_t* launches) {
     return TIDE_OK;
 }
 
+int tide_hbm_stream_probe(tide_ctx* ctx, int layer, int repeats, double* gbytes_per_s_host, uint64_t* bytes_host) {
+    int rc = layer_ok(ctx, layer);
+    if (rc) return rc;
+    if (!gbytes_per_s_host || repeats < 1 || repeats > 1000) return fail(ctx, TIDE_E_INVAL, "null output or repeats outside 1..1000");
+    Layer& L = ctx->layers[layer];
+    const uint64_t bytes = (uint64_t)(ctx->cfg.capacity + ctx->cfg.n_shared) * tide_expert_blob_bytes(&ctx->cfg) / 1024 * 1024;
+    hipDeviceProp_t prop;
+    TIDE_HIP(ctx, hipGetDeviceProperties(&prop, ctx->device));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    TIDE_HIP(ctx, hipEventCreate(&e0));
+    TIDE_HIP(ctx, hipEventCreate(&e1));
+    TIDE_HIP(ctx, hipDeviceSynchronize());
+    double best_ms = 0.0, sum_ms = 0.0;
+    for (int r = 0; r < repeats + 1; ++r) {                     // the first launch is a warm-up
+        LaunchEvents ev;
+        ev.start = e0;
+        ev.stop = e1;
+        hipError_t le = launch_stream_probe(reinterpret_cast<const uint8_t*>(L.slots_owned), bytes, 2 * prop.multiProcessorCount,
+                                            reinterpret_cast<uint32_t*>(ctx->ws.counts_tmp), nullptr, ev);
+        if (le != hipSuccess) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return fail(ctx, TIDE_E_HIP, "stream probe: %s", hipGetErrorString(le)); }
+        TIDE_HIP(ctx, hipDeviceSynchronize());
+        float ms = 0.f;
+        TIDE_HIP(ctx, hipEventElapsedTime(&ms, e0, e1));
+        if (r > 0) { sum_ms += ms; best_ms = (best_ms == 0.0 || ms < best_ms) ? ms : best_ms; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    *gbytes_per_s_host = (double)bytes / (sum_ms / repeats * 1e-3) / 1e9;
+    if (bytes_host) *bytes_host = bytes;
+    return TIDE_OK;
+}
+
 int tide_counters(tide_ctx* ctx, int64_t* out4, int reset, void* hip_stream) {
     if (!ctx || !out4) return ctx ? fail(ctx, TIDE_E_INVAL, "null output") : TIDE_E_INVAL;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);

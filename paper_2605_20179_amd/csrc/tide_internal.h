@@ -174,6 +174,8 @@ hipError_t launch_refresh_copies(const uint8_t* host_blobs, uint64_t host_stride
 hipError_t launch_refresh_copies_p12(const uint8_t* comp_blobs, uint64_t comp_stride, const uint8_t* host_blobs,
                                      uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base, const RefreshOut* plan, int n,
                                      int max_n, bool dst_by_rank, hipStream_t stream);
+// measurement: `bytes` (a multiple of 1024) from `base` read once by `workgroups` workgroups in the GEMMs' weight-stream shape
+hipError_t launch_stream_probe(const uint8_t* base, uint64_t bytes, int workgroups, uint32_t* sink, hipStream_t stream, LaunchEvents ev);
 // H[e] <- floor(H[e] * num / den)
 hipError_t launch_scale_counts(int32_t* hits, int n_experts, int num, int den, hipStream_t stream);
 // interval analysis (Sec. 3.2, Eq. 4-7): similarity / distinct experts / drift on the device, cost model on the host
