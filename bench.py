@@ -76,10 +76,13 @@ def run_stack(args, wl, ti, tb, TideSession, torch):
         if due and args.refresh_order == "all-first":
             for l in range(L):
                 state["copies"] += len(sess.refresh(l)[1])
-        for l in range(L):
-            if due and args.refresh_order == "per-layer":
-                state["copies"] += len(sess.refresh(l)[1])
-            sess.step(l, hidden[l][t], want_topk=False)
+        if args.refresh_order == "per-layer":
+            for l in range(L):
+                if due:
+                    state["copies"] += len(sess.refresh(l)[1])
+                sess.step(l, hidden[l][t], want_topk=False)
+        else:
+            sess.stack_step([hidden[l][t] for l in range(L)])
         state["t"] += 1
 
     for _ in range(args.warmup):
@@ -94,8 +97,7 @@ def run_stack(args, wl, ti, tb, TideSession, torch):
     torch.cuda.synchronize()
     s0 = time.perf_counter()
     for i in range(args.steps):
-        for l in range(L):
-            sess.step(l, hidden[l][i % wl.S], want_topk=False)
+        sess.stack_step([hidden[l][i % wl.S] for l in range(L)])
     torch.cuda.synchronize()
     frozen = (time.perf_counter() - s0) / args.steps
     print(json.dumps({
@@ -246,8 +248,7 @@ def measure_stack(wl, L, ti, tb, TideSession, torch, packed, steps, comp=None, r
             if i > 0 and i % wl.K == 0:
                 for l in range(L):
                     n += len(sess.refresh(l)[1])
-            for l in range(L):
-                sess.step(l, hidden[l][i % n_hidden], want_topk=False)
+            sess.stack_step([hidden[l][i % n_hidden] for l in range(L)])
             return n
         for i in range(n_hidden):                     # one pass to leave the cold start behind
             one(i)
@@ -258,16 +259,22 @@ def measure_stack(wl, L, ti, tb, TideSession, torch, packed, steps, comp=None, r
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / steps
         out.update({"tokens_per_s": wl.N / dt, "ms_per_stack_step": dt * 1e3, "experts_copied": copies, "steps": steps})
-    for l in range(L):
-        sess.step(l, hidden[l][0], want_topk=False)
+    sess.stack_step([hidden[l][0] for l in range(L)])
     torch.cuda.synchronize()
+    s0 = time.perf_counter()
+    for i in range(steps):
+        sess.stack_step([hidden[l][i % n_hidden] for l in range(L)])
+    torch.cuda.synchronize()
+    frozen = (time.perf_counter() - s0) / steps
+    out["frozen_placement"] = {"ms_per_stack_step": frozen * 1e3, "us_per_layer": frozen * 1e6 / L, "tokens_per_s": wl.N / frozen}
+    # the same steps as one tide_moe_step per layer, in turn on one stream (what the stack call overlaps)
     s0 = time.perf_counter()
     for i in range(steps):
         for l in range(L):
             sess.step(l, hidden[l][i % n_hidden], want_topk=False)
     torch.cuda.synchronize()
-    frozen = (time.perf_counter() - s0) / steps
-    out["frozen_placement"] = {"ms_per_stack_step": frozen * 1e3, "us_per_layer": frozen * 1e6 / L, "tokens_per_s": wl.N / frozen}
+    serial = (time.perf_counter() - s0) / steps
+    out["frozen_placement"]["ms_per_stack_step_layer_by_layer"] = serial * 1e3
     if "tokens_per_s" not in out:
         out.update({"tokens_per_s": wl.N / frozen, "ms_per_stack_step": frozen * 1e3, "steps": steps, "experts_copied": 0})
     sess.close()

@@ -18,7 +18,9 @@
  *   - bf16 = upper 16 bits of an IEEE fp32, carried as uint16_t.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls on one context must be issued in stream order on ONE stream: the
- *     context owns a single workspace shared by all of its layers.
+ *     context owns a single workspace shared by all of its layers (the layers of a
+ *     stack that do not depend on each other go through tide_moe_stack_step, which
+ *     overlaps them on streams and workspaces of its own).
  *   - Nothing is computed on the CPU: if no gfx950 device is usable,
  *     tide_create fails with TIDE_E_HIP.
  */
@@ -175,6 +177,22 @@ int tide_moe_step_noalloc(tide_ctx* ctx, int layer, const void* hidden_dev, int 
                           int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream);
 /* TIDE_NOALLOC_SCRATCH_BYTES as the loaded library was built with. */
 uint64_t tide_noalloc_scratch_bytes(void);
+
+/* One denoise step of a STACK of independent MoE layers (layers first_layer .. first_layer + n_layers - 1, each with
+ * its own router, hidden states, cache, counter and output): the same results, bit for bit, as tide_moe_step called
+ * for each layer in turn -- but the call states that the layers do not depend on each other within the step (no
+ * layer's input is another's output), so the library runs consecutive layers on two internal streams with a
+ * workspace each: one layer's routing, split and combine run beside the other's expert GEMMs, and the tail of one
+ * layer's GEMM launches is filled by the next layer's.  Everything is ordered behind the work already queued on
+ * hip_stream, and work queued on hip_stream afterwards runs behind all layers.
+ *   hidden_dev, router_w_dev, router_bias_dev, out_dev, miss_dev, n_miss_dev: HOST arrays of n_layers device
+ *   pointers, entry i for layer first_layer + i, each as tide_moe_step takes it (router_bias_dev may be NULL when
+ *   bias_mode == TIDE_BIAS_NONE; miss_dev may be NULL when miss_cap == 0); the arrays are read before the call returns.
+ * The lanes (two workspaces of the context's size, four streams) are allocated by the first call.  TIDE_E_STATE
+ * while host workers are active.  tide_step_histogram / tide_read_work_items afterwards describe the last layer. */
+int tide_moe_stack_step(tide_ctx* ctx, int first_layer, int n_layers, const void* const* hidden_dev, int n_tokens,
+                        const float* const* router_w_dev, const float* const* router_bias_dev, float* const* out_dev,
+                        tide_miss* const* miss_dev, int miss_cap, int32_t* const* n_miss_dev, void* hip_stream);
 
 /* The same step for token states that already carry their expert selections
  * (Alg. 1 takes X = {(x, E_x)} as given): topk_idx_dev / topk_w_dev are INPUTS

@@ -28,7 +28,7 @@ EXPORTS = [
     "tide_compressed_blob_bytes", "tide_compress_expert", "tide_register_compressed",
     "tide_refresh_async", "tide_refresh_result",
     "tide_moe_step_noalloc", "tide_noalloc_scratch_bytes", "tide_set_counts", "tide_read_work_items",
-    "tide_refresh_engine", "tide_queue_refresh_wait", "tide_hbm_stream_probe",
+    "tide_refresh_engine", "tide_queue_refresh_wait", "tide_hbm_stream_probe", "tide_moe_stack_step",
 ]
 KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "down", "combine", "gate_up_swiglu_big", "down_big"]
 
@@ -79,6 +79,7 @@ def _load() -> C.CDLL:
     lib.tide_moe_step.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp, vp, vp]
     lib.tide_moe_step_routed.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp]
     lib.tide_moe_step_noalloc.argtypes = lib.tide_moe_step.argtypes
+    lib.tide_moe_stack_step.argtypes = [vp, C.c_int, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp]
     lib.tide_noalloc_scratch_bytes.argtypes = []
     lib.tide_noalloc_scratch_bytes.restype = C.c_uint64
     lib.tide_moe_apply_misses.argtypes = [vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, vp, vp]
@@ -207,6 +208,21 @@ def tide_moe_step_noalloc(ctx, layer: int, hidden, n_tokens: int, router_w, rout
                           topk_idx=None, topk_w=None, stream=None) -> None:
     _check(lib.tide_moe_step_noalloc(ctx, layer, _ptr(hidden), n_tokens, _ptr(router_w), _ptr(router_bias), _ptr(out),
                                      _ptr(miss), miss_cap, _ptr(n_miss), _ptr(topk_idx), _ptr(topk_w), _stream_ptr(stream)), ctx)
+
+
+def _ptr_array(items):
+    """Host array of device (or host) addresses, one per item (None -> NULL)."""
+    return (C.c_void_p * len(items))(*[_ptr(t) for t in items])
+
+
+def tide_moe_stack_step(ctx, first_layer: int, hidden, n_tokens: int, router_w, router_bias, out, miss, miss_cap: int,
+                        n_miss, stream=None) -> None:
+    """hidden / router_w / router_bias / out / miss / n_miss: one entry per layer (router_bias may be None)."""
+    n = len(hidden)
+    assert len(router_w) == len(out) == len(n_miss) == n and (miss is None or len(miss) == n)
+    bias = None if router_bias is None or all(b is None for b in router_bias) else _ptr_array(router_bias)
+    _check(lib.tide_moe_stack_step(ctx, first_layer, n, _ptr_array(hidden), n_tokens, _ptr_array(router_w), bias, _ptr_array(out),
+                                   None if miss is None else _ptr_array(miss), miss_cap, _ptr_array(n_miss), _stream_ptr(stream)), ctx)
 
 
 def tide_noalloc_scratch_bytes() -> int:

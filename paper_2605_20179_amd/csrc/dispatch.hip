@@ -212,7 +212,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
         }
         if (tid == 0) {
             *n_miss = running;
-            counters[3] += running;
+            bump(counters + 3, running);
         }
         return;
     }
@@ -263,10 +263,10 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
             n_tasks[1] = min(big_before + n_big, max_big);
         }
         if (tid == 0) {
-            // running totals for throughput accounting; only this block of this kernel writes them
-            counters[0] += 1;
-            counters[1] += active_before + (m > 0 ? 1 : 0);
-            counters[2] += rows_before + m;
+            // running totals for throughput accounting (atomic: the layers of a stack step run on several streams)
+            bump(counters + 0, 1);
+            bump(counters + 1, active_before + (m > 0 ? 1 : 0));
+            bump(counters + 2, rows_before + m);
         }
         return;
     }

@@ -86,9 +86,9 @@ __device__ inline void dispatch_small(const DispatchArgs& a, const unsigned* s_m
             a.slot_off[n_slots] = rows_inc;
             a.n_tasks[0] = items_inc;
             a.n_tasks[1] = 0;                                // at most 32 tokens: no slot can exceed a small item
-            a.counters[0] += 1;
-            a.counters[1] += active_inc;
-            a.counters[2] += rows_inc;
+            bump(a.counters + 0, 1);
+            bump(a.counters + 1, active_inc);
+            bump(a.counters + 2, rows_inc);
         }
     }
     __syncthreads();
@@ -149,7 +149,7 @@ __device__ inline void dispatch_small(const DispatchArgs& a, const unsigned* s_m
         }
         if (lane == 0) {
             *a.n_miss = running;
-            a.counters[3] += running;
+            bump(a.counters + 3, running);
         }
     }
 }

@@ -324,9 +324,11 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
 // Large work items: up to 256 rows of a slot that holds more than 32.  A workgroup's tile is 256
 // weight rows x up to 256 tokens: what bounds these kernels is the rate at which a compute unit's
 // vector cache can be filled, so the tile is as large as the accumulators allow (256 of a wave's 512
-// registers).  Up to 128 rows: eight token tiles, 256-column stages, ring depth 8.  Above: up to 16
-// token tiles in two half sets, 128-column stages, ring depth 4 (the same lead in MFMA time).
-constexpr int kBigPC = 8, kBigD = 8;       // <= 8 token tiles
+// registers).  Up to 128 rows: eight token tiles, 256-column stages.  Above: up to 16 token tiles in two
+// half sets, 128-column stages.  Ring depth 4 for both: a deeper ring reads no faster (a read-only kernel
+// with this access shape and one workgroup per compute unit is slower at depth 8 than at 4) and measured
+// 1-3 % slower in the step.
+constexpr int kBigPC = 8, kBigD = 4;       // <= 8 token tiles
 constexpr int kWidePC = 4, kWideD = 4;     // 9..16 token tiles
 constexpr int kBigLdsElems = 2 * 128 * (kBigPC * 32 + 8) > 2 * 256 * (kWidePC * 32 + 8) ? 2 * 128 * (kBigPC * 32 + 8)
                                                                                       : 2 * 256 * (kWidePC * 32 + 8);

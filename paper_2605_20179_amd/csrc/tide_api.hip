@@ -77,6 +77,21 @@ struct Layer {
 
 }  // namespace
 
+// What one step in flight needs beyond its layer: a workspace, the second stream its large work items run on, and the
+// events that fork onto and join from that stream.  The context owns one set for its ordinary calls; a stack step
+// (tide_moe_stack_step) runs consecutive layers on several such sets ("lanes"), each with a stream of its own.
+struct StepRes {
+    Workspace ws{};
+    hipStream_t aux = nullptr;
+    hipEvent_t fork_ev = nullptr, join_ev = nullptr;
+};
+struct Lane {
+    StepRes res{};
+    hipStream_t stream = nullptr;
+    hipEvent_t done = nullptr;
+    std::vector<void*> allocs;
+};
+
 struct tide_ctx {
     tide_config cfg{};
     Shape shape{};
@@ -90,6 +105,9 @@ struct tide_ctx {
     hipEvent_t compute_mark = nullptr;
     int max_rows = 0, max_tasks = 0;
     unsigned char* scratch_dev = nullptr;   // this device's copy of the static scratch array (tide_moe_step_noalloc)
+    std::vector<Lane> lanes;                // tide_moe_stack_step: made on first use
+    hipEvent_t stack_begin = nullptr;
+    Workspace last{};                       // workspace of the most recent step (tide_step_histogram, tide_read_work_items)
     std::string err;
     // optional per-kernel timing: every kernel launch of a step stamps a start and a stop event
     int profiling = 0;                      // 0 off, 1 every kernel of a step, 2 the expert GEMMs, 3 gate/up and the kernel before it
@@ -117,6 +135,15 @@ struct tide_ctx {
 };
 
 namespace {
+
+StepRes own_res(const tide_ctx* ctx) {
+    StepRes r;
+    r.ws = ctx->ws;
+    r.aux = ctx->aux;
+    r.fork_ev = ctx->fork_ev;
+    r.join_ev = ctx->join_ev;
+    return r;
+}
 
 int fail(tide_ctx* ctx, int code, const char* fmt, ...) {
     char buf[512];
@@ -193,10 +220,11 @@ int layer_ok(tide_ctx* ctx, int layer) {
 
 uint16_t* slot_ptr(tide_ctx* ctx, Layer& L, int slot) { return L.slots_owned + (int64_t)slot * ctx->shape.blob_elems; }
 
-int common_step(tide_ctx* ctx, const Workspace& ws, int layer, const void* hidden_dev, int n_tokens, const int32_t* idx,
+int common_step(tide_ctx* ctx, const StepRes& res, int layer, const void* hidden_dev, int n_tokens, const int32_t* idx,
                 const float* w, float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
                 hipStream_t stream, bool split_done) {
     Layer& L = ctx->layers[layer];
+    const Workspace& ws = res.ws;
     if (!split_done)
         TIDE_HIP(ctx, timed(ctx, TIDE_K_DISPATCH, [&](LaunchEvents ev) {
             return launch_dispatch(ctx->shape, L.t, ws, idx, w, n_tokens, miss_dev, miss_cap, n_miss_dev, stream, ev); }));
@@ -207,14 +235,14 @@ int common_step(tide_ctx* ctx, const Workspace& ws, int layer, const void* hidde
     // and the token states it names to pinned host memory: the list is final long before the step's GEMMs
     // end, and the host cores can start on it at once.
     if (ctx->pool || max_big > 0) {
-        TIDE_HIP(ctx, hipEventRecord(ctx->fork_ev, stream));
-        TIDE_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_ev, 0));
+        TIDE_HIP(ctx, hipEventRecord(res.fork_ev, stream));
+        TIDE_HIP(ctx, hipStreamWaitEvent(res.aux, res.fork_ev, 0));
     }
     if (ctx->pool) {
         const int cap = std::min(miss_cap, n_tokens * ctx->cfg.top_k);
         TIDE_HIP(ctx, launch_miss_export(miss_dev, cap, n_miss_dev, x, n_tokens, ctx->cfg.d, ctx->h_miss, ctx->h_n_miss,
-                                         ctx->h_hidden, ctx->aux));
-        TIDE_HIP(ctx, hipEventRecord(ctx->listed_ev, ctx->aux));
+                                         ctx->h_hidden, res.aux));
+        TIDE_HIP(ctx, hipEventRecord(ctx->listed_ev, res.aux));
         // a step recorded into a HIP graph hands its list over at every replay, but the event above then belongs to
         // the graph: the host path must not wait on it, it queues a hand-over of its own instead
         hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
@@ -228,28 +256,29 @@ int common_step(tide_ctx* ctx, const Workspace& ws, int layer, const void* hidde
     }
     if (L.copies_pending) {                  // the GEMMs of both streams wait for a refresh's copies; nothing before them does
         TIDE_HIP(ctx, hipStreamWaitEvent(stream, L.copies_done, 0));
-        if (max_big > 0) TIDE_HIP(ctx, hipStreamWaitEvent(ctx->aux, L.copies_done, 0));
+        if (max_big > 0) TIDE_HIP(ctx, hipStreamWaitEvent(res.aux, L.copies_done, 0));
         L.copies_pending = false;
     }
     // Small and large work items touch disjoint rows: the large ones run on the second stream so that
     // the two kinds of kernels overlap on the chip (join before the combine).
     if (max_big > 0) {
-        TIDE_HIP(ctx, launch_plan_big(ws, max_big, ctx->aux));
+        TIDE_HIP(ctx, launch_plan_big(ws, max_big, res.aux));
         TIDE_HIP(ctx, timed(ctx, TIDE_K_GATE_UP_BIG, [&](LaunchEvents ev) {
-            return launch_expert_gemm_big(0, ctx->shape, L.t, ws, x, max_big, ctx->aux, ev); }));
+            return launch_expert_gemm_big(0, ctx->shape, L.t, ws, x, max_big, res.aux, ev); }));
         TIDE_HIP(ctx, timed(ctx, TIDE_K_DOWN_BIG, [&](LaunchEvents ev) {
-            return launch_expert_gemm_big(1, ctx->shape, L.t, ws, x, max_big, ctx->aux, ev); }));
-        TIDE_HIP(ctx, hipEventRecord(ctx->join_ev, ctx->aux));
+            return launch_expert_gemm_big(1, ctx->shape, L.t, ws, x, max_big, res.aux, ev); }));
+        TIDE_HIP(ctx, hipEventRecord(res.join_ev, res.aux));
     }
     TIDE_HIP(ctx, timed(ctx, TIDE_K_GATE_UP, [&](LaunchEvents ev) {
         return launch_expert_gemm(0, ctx->shape, L.t, ws, x, max_tasks, stream, ev); }));
     TIDE_HIP(ctx, timed(ctx, TIDE_K_DOWN, [&](LaunchEvents ev) {
         return launch_expert_gemm(1, ctx->shape, L.t, ws, x, max_tasks, stream, ev); }));
-    if (max_big > 0) TIDE_HIP(ctx, hipStreamWaitEvent(stream, ctx->join_ev, 0));
+    if (max_big > 0) TIDE_HIP(ctx, hipStreamWaitEvent(stream, res.join_ev, 0));
     else if (ctx->pool) TIDE_HIP(ctx, hipStreamWaitEvent(stream, ctx->listed_ev, 0));    // the export read hidden_dev
     TIDE_HIP(ctx, timed(ctx, TIDE_K_COMBINE, [&](LaunchEvents ev) {
         return launch_combine(ctx->shape, ws, w, n_tokens, out_dev, stream, ev); }));
     ctx->steps_issued++;
+    ctx->last = res.ws;
     return TIDE_OK;
 }
 
@@ -381,6 +410,7 @@ int tide_create(const tide_config* cfg, tide_ctx** out) {
         memset(L.plan, 0, sizeof(RefreshOut));
     }
     if (hipDeviceSynchronize() != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "synchronize after set-up failed"));
+    ctx->last = ctx->ws;
     *out = ctx;
     return TIDE_OK;
 }
@@ -396,6 +426,15 @@ int tide_destroy(tide_ctx* ctx) {
         if (L.staging) (void)hipFree(L.staging);
         if (L.pend_slot_of) (void)hipFree(L.pend_slot_of);
     }
+    for (Lane& ln : ctx->lanes) {
+        if (ln.done) (void)hipEventDestroy(ln.done);
+        if (ln.res.fork_ev) (void)hipEventDestroy(ln.res.fork_ev);
+        if (ln.res.join_ev) (void)hipEventDestroy(ln.res.join_ev);
+        if (ln.stream) (void)hipStreamDestroy(ln.stream);
+        if (ln.res.aux) (void)hipStreamDestroy(ln.res.aux);
+        for (void* q : ln.allocs) (void)hipFree(q);
+    }
+    if (ctx->stack_begin) (void)hipEventDestroy(ctx->stack_begin);
     host_pool_destroy(ctx->pool);
     if (ctx->listed_ev) (void)hipEventDestroy(ctx->listed_ev);
     for (void* q : {(void*)ctx->h_miss, (void*)ctx->h_n_miss, (void*)ctx->h_hidden, (void*)ctx->h_rows, (void*)ctx->h_tokens, (void*)ctx->h_mask})
@@ -516,7 +555,7 @@ int tide_set_resident(tide_ctx* ctx, int layer, const int32_t* experts, int n) {
 
 namespace {
 // tide_moe_step on the workspace `ws` (the context's own, or one carved from the static scratch array).
-int moe_step_on(tide_ctx* ctx, const Workspace& ws, int layer, const void* hidden_dev, int n_tokens, const float* router_w_dev,
+int moe_step_on(tide_ctx* ctx, const StepRes& res, int layer, const void* hidden_dev, int n_tokens, const float* router_w_dev,
                 const float* router_bias_dev, float* out_dev, tide_miss* miss_dev, int miss_cap, int32_t* n_miss_dev,
                 int32_t* topk_idx_dev, float* topk_w_dev, hipStream_t stream) {
     if (n_tokens == 0) {
@@ -527,6 +566,7 @@ int moe_step_on(tide_ctx* ctx, const Workspace& ws, int layer, const void* hidde
     if (ctx->cfg.bias_mode != TIDE_BIAS_NONE && !router_bias_dev) return fail(ctx, TIDE_E_INVAL, "router_bias_dev is null but bias_mode != NONE");
     if ((uintptr_t)router_w_dev & 15) return fail(ctx, TIDE_E_INVAL, "router_w_dev must be 16-byte aligned");
     Layer& L = ctx->layers[layer];
+    const Workspace& ws = res.ws;
     const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
     TIDE_HIP(ctx, timed(ctx, TIDE_K_ROUTER, [&](LaunchEvents ev) {
         return launch_router_logits(ctx->shape, x, n_tokens, router_w_dev, ws.logits, ws.hist_step, stream, ev); }));
@@ -540,7 +580,7 @@ int moe_step_on(tide_ctx* ctx, const Workspace& ws, int layer, const void* hidde
             return launch_topk_gate(ctx->shape, ws.logits, router_bias_dev, n_tokens, ws.topk_idx, ws.topk_w,
                                     ws.hist_step, topk_idx_dev, topk_w_dev, stream, ev); }));
     }
-    return common_step(ctx, ws, layer, hidden_dev, n_tokens, ws.topk_idx, ws.topk_w, out_dev, miss_dev, miss_cap,
+    return common_step(ctx, res, layer, hidden_dev, n_tokens, ws.topk_idx, ws.topk_w, out_dev, miss_dev, miss_cap,
                        n_miss_dev, stream, one_wg);
 }
 }  // namespace
@@ -550,7 +590,7 @@ int tide_moe_step(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens
                   int32_t* n_miss_dev, int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream) {
     int rc = step_args_ok(ctx, layer, hidden_dev, n_tokens, out_dev, miss_dev, miss_cap, n_miss_dev);
     if (rc) return rc;
-    return moe_step_on(ctx, ctx->ws, layer, hidden_dev, n_tokens, router_w_dev, router_bias_dev, out_dev, miss_dev, miss_cap,
+    return moe_step_on(ctx, own_res(ctx), layer, hidden_dev, n_tokens, router_w_dev, router_bias_dev, out_dev, miss_dev, miss_cap,
                        n_miss_dev, topk_idx_dev, topk_w_dev, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -592,14 +632,95 @@ int tide_moe_step_noalloc(tide_ctx* ctx, int layer, const void* hidden_dev, int 
     int rc = step_args_ok(ctx, layer, hidden_dev, n_tokens, out_dev, miss_dev, miss_cap, n_miss_dev);
     if (rc) return rc;
     if (ctx->profiling) return fail(ctx, TIDE_E_STATE, "tide_moe_step_noalloc does not run while tide_profile is on (stamped launches create events)");
-    Workspace ws = ctx->ws;
+    StepRes res = own_res(ctx);
+    Workspace& ws = res.ws;
     const size_t need = carve_step_workspace(ctx->shape, n_tokens, nullptr, ws);
     if (need > kScratchBytes)
         return fail(ctx, TIDE_E_RANGE, "a step of %d tokens needs %zu bytes of workspace; the static scratch array holds %zu",
                     n_tokens, need, kScratchBytes);
     carve_step_workspace(ctx->shape, n_tokens, ctx->scratch_dev, ws);
-    return moe_step_on(ctx, ws, layer, hidden_dev, n_tokens, router_w_dev, router_bias_dev, out_dev, miss_dev, miss_cap,
+    return moe_step_on(ctx, res, layer, hidden_dev, n_tokens, router_w_dev, router_bias_dev, out_dev, miss_dev, miss_cap,
                        n_miss_dev, topk_idx_dev, topk_w_dev, static_cast<hipStream_t>(hip_stream));
+}
+
+namespace {
+constexpr int kStackLanes = 2;
+
+// The lanes of tide_moe_stack_step: each a workspace of the context's size (the step histogram and the running totals
+// excepted, which stay the context's), a stream, a second stream for large work items and their events.
+int make_lanes(tide_ctx* ctx) {
+    if (!ctx->lanes.empty()) return TIDE_OK;
+    std::vector<Lane> lanes(kStackLanes);
+    auto undo = [&](int code) {
+        for (Lane& ln : lanes) {
+            if (ln.done) (void)hipEventDestroy(ln.done);
+            if (ln.res.fork_ev) (void)hipEventDestroy(ln.res.fork_ev);
+            if (ln.res.join_ev) (void)hipEventDestroy(ln.res.join_ev);
+            if (ln.stream) (void)hipStreamDestroy(ln.stream);
+            if (ln.res.aux) (void)hipStreamDestroy(ln.res.aux);
+            for (void* q : ln.allocs) (void)hipFree(q);
+        }
+        return code;
+    };
+    const size_t bytes = carve_step_workspace(ctx->shape, ctx->cfg.max_tokens, nullptr, lanes[0].res.ws) + (size_t)ctx->cfg.n_experts * 4 + 512;
+    for (Lane& ln : lanes) {
+        void* p = nullptr;
+        if (hipMalloc(&p, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return undo(fail(ctx, TIDE_E_NOMEM, "out of device memory for a stack lane's workspace (%zu bytes)", bytes));
+        }
+        ln.allocs.push_back(p);
+        ln.res.ws = ctx->ws;                       // counters and the miss-pass buffers stay the context's
+        const size_t used = carve_step_workspace(ctx->shape, ctx->cfg.max_tokens, static_cast<unsigned char*>(p), ln.res.ws);
+        ln.res.ws.hist_step = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(p) + used);
+        if (hipStreamCreateWithFlags(&ln.stream, hipStreamNonBlocking) != hipSuccess ||
+            hipStreamCreateWithFlags(&ln.res.aux, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&ln.done, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&ln.res.fork_ev, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&ln.res.join_ev, hipEventDisableTiming) != hipSuccess)
+            return undo(fail(ctx, TIDE_E_HIP, "stream / event creation for a stack lane failed"));
+    }
+    if (!ctx->stack_begin && hipEventCreateWithFlags(&ctx->stack_begin, hipEventDisableTiming) != hipSuccess)
+        return undo(fail(ctx, TIDE_E_HIP, "event creation failed"));
+    ctx->lanes = std::move(lanes);
+    return TIDE_OK;
+}
+}  // namespace
+
+int tide_moe_stack_step(tide_ctx* ctx, int first_layer, int n_layers, const void* const* hidden_dev, int n_tokens,
+                        const float* const* router_w_dev, const float* const* router_bias_dev, float* const* out_dev,
+                        tide_miss* const* miss_dev, int miss_cap, int32_t* const* n_miss_dev, void* hip_stream) {
+    if (!ctx) return TIDE_E_INVAL;
+    if (n_layers < 0 || first_layer < 0 || first_layer + n_layers > ctx->cfg.n_layers)
+        return fail(ctx, TIDE_E_INVAL, "layers %d..%d outside 0..%d", first_layer, first_layer + n_layers - 1, ctx->cfg.n_layers - 1);
+    if (n_layers == 0) return TIDE_OK;
+    if (!hidden_dev || !router_w_dev || !out_dev || !n_miss_dev || (miss_cap > 0 && !miss_dev))
+        return fail(ctx, TIDE_E_INVAL, "null pointer array");
+    if (ctx->cfg.bias_mode != TIDE_BIAS_NONE && !router_bias_dev) return fail(ctx, TIDE_E_INVAL, "router_bias_dev is null but bias_mode != NONE");
+    if (ctx->pool) return fail(ctx, TIDE_E_STATE, "tide_moe_stack_step does not run with host workers (tide_host_experts): their hand-over buffers serve one step at a time");
+    for (int i = 0; i < n_layers; ++i) {
+        int rc = step_args_ok(ctx, first_layer + i, hidden_dev[i], n_tokens, out_dev[i], miss_cap > 0 ? miss_dev[i] : nullptr, miss_cap, n_miss_dev[i]);
+        if (rc) return rc;
+        if (n_tokens > 0 && !router_w_dev[i]) return fail(ctx, TIDE_E_INVAL, "router_w_dev[%d] is null", i);
+    }
+    int rc = make_lanes(ctx);
+    if (rc) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // every lane starts behind what the caller has queued, and the caller's stream continues behind every lane
+    TIDE_HIP(ctx, hipEventRecord(ctx->stack_begin, stream));
+    const int used = std::min(n_layers, (int)ctx->lanes.size());
+    for (int j = 0; j < used; ++j) TIDE_HIP(ctx, hipStreamWaitEvent(ctx->lanes[j].stream, ctx->stack_begin, 0));
+    for (int i = 0; i < n_layers; ++i) {
+        Lane& ln = ctx->lanes[i % ctx->lanes.size()];
+        rc = moe_step_on(ctx, ln.res, first_layer + i, hidden_dev[i], n_tokens, router_w_dev[i], router_bias_dev ? router_bias_dev[i] : nullptr,
+                         out_dev[i], miss_cap > 0 ? miss_dev[i] : nullptr, miss_cap, n_miss_dev[i], nullptr, nullptr, ln.stream);
+        if (rc) break;
+    }
+    for (int j = 0; j < used; ++j) {
+        TIDE_HIP(ctx, hipEventRecord(ctx->lanes[j].done, ctx->lanes[j].stream));
+        TIDE_HIP(ctx, hipStreamWaitEvent(stream, ctx->lanes[j].done, 0));
+    }
+    return rc;
 }
 
 int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n_tokens, const int32_t* topk_idx_dev,
@@ -615,7 +736,7 @@ int tide_moe_step_routed(tide_ctx* ctx, int layer, const void* hidden_dev, int n
     if (!topk_idx_dev || !topk_w_dev) return fail(ctx, TIDE_E_INVAL, "topk_idx_dev / topk_w_dev is null");
     if ((uintptr_t)topk_idx_dev & 15) return fail(ctx, TIDE_E_INVAL, "topk_idx_dev must be 16-byte aligned");
     TIDE_HIP(ctx, launch_count_pairs(ctx->shape, topk_idx_dev, n_tokens, ctx->ws.hist_step, stream));
-    return common_step(ctx, ctx->ws, layer, hidden_dev, n_tokens, topk_idx_dev, topk_w_dev, out_dev, miss_dev, miss_cap,
+    return common_step(ctx, own_res(ctx), layer, hidden_dev, n_tokens, topk_idx_dev, topk_w_dev, out_dev, miss_dev, miss_cap,
                        n_miss_dev, stream, false);
 }
 
@@ -813,16 +934,16 @@ int tide_read_work_items(tide_ctx* ctx, tide_work_item* items_host, int items_ca
         return fail(ctx, TIDE_E_INVAL, "null output");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     int32_t n_tasks[2] = {0, 0}, total_rows = 0;
-    TIDE_HIP(ctx, hipMemcpyAsync(n_tasks, ctx->ws.n_tasks, sizeof n_tasks, hipMemcpyDeviceToHost, stream));
-    TIDE_HIP(ctx, hipMemcpyAsync(&total_rows, ctx->ws.slot_off + ctx->cfg.capacity + 1, sizeof total_rows, hipMemcpyDeviceToHost, stream));
+    TIDE_HIP(ctx, hipMemcpyAsync(n_tasks, ctx->last.n_tasks, sizeof n_tasks, hipMemcpyDeviceToHost, stream));
+    TIDE_HIP(ctx, hipMemcpyAsync(&total_rows, ctx->last.slot_off + ctx->cfg.capacity + 1, sizeof total_rows, hipMemcpyDeviceToHost, stream));
     TIDE_HIP(ctx, hipStreamSynchronize(stream));
     if (ctx->steps_issued == 0) n_tasks[0] = n_tasks[1] = total_rows = 0;
     std::vector<Task> small((size_t)std::max(n_tasks[0], 0)), big((size_t)std::max(n_tasks[1], 0));
-    if (!small.empty()) TIDE_HIP(ctx, hipMemcpyAsync(small.data(), ctx->ws.tasks, small.size() * sizeof(Task), hipMemcpyDeviceToHost, stream));
-    if (!big.empty()) TIDE_HIP(ctx, hipMemcpyAsync(big.data(), ctx->ws.big_tasks, big.size() * sizeof(Task), hipMemcpyDeviceToHost, stream));
+    if (!small.empty()) TIDE_HIP(ctx, hipMemcpyAsync(small.data(), ctx->last.tasks, small.size() * sizeof(Task), hipMemcpyDeviceToHost, stream));
+    if (!big.empty()) TIDE_HIP(ctx, hipMemcpyAsync(big.data(), ctx->last.big_tasks, big.size() * sizeof(Task), hipMemcpyDeviceToHost, stream));
     const int n_rows = std::min(std::max(total_rows, 0), ctx->max_rows);
     if (std::min(n_rows, rows_cap) > 0)
-        TIDE_HIP(ctx, hipMemcpyAsync(row_token_host, ctx->ws.row_token, (size_t)std::min(n_rows, rows_cap) * 4, hipMemcpyDeviceToHost, stream));
+        TIDE_HIP(ctx, hipMemcpyAsync(row_token_host, ctx->last.row_token, (size_t)std::min(n_rows, rows_cap) * 4, hipMemcpyDeviceToHost, stream));
     TIDE_HIP(ctx, hipStreamSynchronize(stream));
     int at = 0;
     for (int kind = 0; kind < 2; ++kind)
@@ -1127,7 +1248,7 @@ int tide_step_histogram(tide_ctx* ctx, int32_t* counts_host, int n_experts, void
     if (!ctx || !counts_host) return ctx ? fail(ctx, TIDE_E_INVAL, "null output") : TIDE_E_INVAL;
     if (n_experts != ctx->cfg.n_experts) return fail(ctx, TIDE_E_RANGE, "n_experts %d != configured %d", n_experts, ctx->cfg.n_experts);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    TIDE_HIP(ctx, hipMemcpyAsync(counts_host, ctx->ws.hist_step, (size_t)n_experts * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    TIDE_HIP(ctx, hipMemcpyAsync(counts_host, ctx->last.hist_step, (size_t)n_experts * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
     TIDE_HIP(ctx, hipStreamSynchronize(stream));
     return TIDE_OK;
 }

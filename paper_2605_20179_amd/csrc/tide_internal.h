@@ -19,6 +19,11 @@ constexpr int kMinBigUnits = 128;       // a step uses large work items only if 
 constexpr int kBigMinRows = 32;         // a slot with more rows than this is cut into large work items, else into small ones
 constexpr int kBigMinAvgRows = 48;      // steps with fewer rows per slot on average launch no large-item kernels at all
 
+// running totals (tide_counters): integer adds, so their order does not matter
+__device__ inline void bump(int64_t* counter, int64_t by) {
+    atomicAdd(reinterpret_cast<unsigned long long*>(counter), (unsigned long long)by);
+}
+
 // One grouped-GEMM work item: rows [row0, row0+nrows) of the slot-sorted row space
 // all belong to cache slot `slot` (slot == capacity means the shared expert).
 struct Task {

@@ -94,6 +94,21 @@ class TideSession:
                          self.miss, cap, self.n_miss, self.topk_idx if want_topk else None,
                          self.topk_w if want_topk else None, torch.cuda.current_stream())
 
+    def stack_step(self, hidden_devs, first_layer: int = 0, miss_cap: Optional[int] = None) -> None:
+        """One denoise step of the independent layers first_layer .. first_layer + len(hidden_devs) - 1 through
+        tide_moe_stack_step.  Results per layer in self.stack_out / stack_miss / stack_n_miss (made on first use)."""
+        n_layers = len(hidden_devs)
+        n = hidden_devs[0].shape[0]
+        if not hasattr(self, "stack_out"):
+            P = self.max_tokens * self.k
+            self.stack_out = [torch.empty((self.max_tokens, self.d), dtype=torch.float32, device=self.device) for _ in range(self.n_layers)]
+            self.stack_miss = [torch.empty((max(P, 1), 3), dtype=torch.int32, device=self.device) for _ in range(self.n_layers)]
+            self.stack_n_miss = [torch.zeros(1, dtype=torch.int32, device=self.device) for _ in range(self.n_layers)]
+        sl = slice(first_layer, first_layer + n_layers)
+        cap = n * self.k if miss_cap is None else miss_cap
+        tb.tide_moe_stack_step(self.ctx, first_layer, hidden_devs, n, self.router_w[sl], self.router_b[sl], self.stack_out[sl],
+                               self.stack_miss[sl], cap, self.stack_n_miss[sl], torch.cuda.current_stream())
+
     def step_routed(self, layer: int, hidden_dev: torch.Tensor, idx_dev: torch.Tensor, w_dev: torch.Tensor,
                     miss_cap: Optional[int] = None) -> None:
         n = hidden_dev.shape[0]

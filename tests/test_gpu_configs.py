@@ -250,14 +250,13 @@ def drive(sess, tb, runs, forced, out_checks=None):
 def stack_rate(sess, runs, steps):
     """tokens/s of the stack with the placement as the run left it (no refresh): N / sum over the layers."""
     xs = [[sess.to_device_bf16(run.hidden[t]) for t in range(min(steps, len(run.hidden)))] for run in runs]
+    assert [run.li for run in runs] == list(range(len(runs)))
     for _ in range(2):
-        for run, x in zip(runs, xs):
-            sess.step(run.li, x[0], want_topk=False)
+        sess.stack_step([x[0] for x in xs])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
-        for run, x in zip(runs, xs):
-            sess.step(run.li, x[i % len(x)], want_topk=False)
+        sess.stack_step([x[i % len(x)] for x in xs])
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / steps
     return {"layers": len(runs), "us_per_stack_step_frozen_placement": dt * 1e6, "tokens_per_s": runs[0].wl.N / dt}
