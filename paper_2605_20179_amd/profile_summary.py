@@ -1,4 +1,7 @@
-"""Summarise a rocprofv3 --kernel-trace CSV of a bench.py run: per kernel, launches and
+"""Measurement tooling, not part of the hot path (nothing in the library, the binding, the tests or bench.py imports
+it): it lives in the package only so that the commands quoted under profiles/ can name it with `python -m`.
+
+Summarise a rocprofv3 --kernel-trace CSV of a bench.py run: per kernel, launches and
 mean/min/max duration over (a) every launch and (b) the launches of bench.py's timed region
 (launch numbers warmup .. warmup+steps-1 of each step kernel).
 
