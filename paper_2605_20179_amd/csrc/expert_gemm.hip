@@ -61,6 +61,49 @@ __device__ inline float silu(float g) { return g / (1.f + __expf(-g)); }
 // rows are shared by the workgroup's four waves, so they are staged through LDS, PC chunks of 32
 // columns at a time; the next stage's rows are already in flight while the current one is used.
 // Tokens sit on the MFMA's 16-wide N side, NT token tiles per work item.
+// Where a wave finds its weight stripes: a wave's stripes all lie in one group of the packed layout, and inside a
+// group the K chunk is the slow index, so chunk c of stripe r sits at base + stripe_offset(r) + c * cstep (+ the lane's
+// 8 elements inside the tile).  Everything here is the same for all lanes of a wave: it lives in scalar registers.
+struct WeightStream {
+    const uint16_t* base;     // the wave's first stripe (PASS 0: its first gate stripe), chunk 0
+    int64_t cstep;            // elements from one K chunk to the next
+    int up;                   // PASS 0: elements from a gate stripe to the matching up stripe
+};
+
+template <int PASS, int RT>
+__device__ inline int64_t stripe_offset(const WeightStream& ws, int r) {
+    constexpr int G = RT / 2;
+    if (PASS == 0 && r >= G) return (int64_t)ws.up + (r - G) * kTileElems;
+    return (int64_t)r * kTileElems;
+}
+
+// wtile: the wave's tile of output features (wave-uniform).  A spare wave (columns past n_out) streams the last valid
+// wave's stripes and stores nothing: it stays in step with the barriers without a predicate around the loop.
+template <int PASS, int RT>
+__device__ inline void weight_stream(const uint16_t* blob, int64_t off_w, int wtile, bool active, int K, int n_out,
+                                     WeightStream& ws) {
+    constexpr int G = RT / 2;                        // PASS 0: gate stripes per wave
+    const int kchunks = K >> 5;
+    const int wsrc = active ? wtile : (n_out / (16 * (PASS == 0 ? G : RT)) - 1);
+    if (PASS == 0) {
+        static_assert(PASS != 0 || kGateUpGroup % (RT / 2) == 0, "a wave's column blocks share a group");
+        const int first = wsrc * G;                                  // the wave's first SwiGLU column block
+        const int g = first / kGateUpGroup, j0 = first % kGateUpGroup;
+        const int ng = min(kGateUpGroup, n_out / 16 - g * kGateUpGroup);
+        ws.base = blob + off_w + (int64_t)g * 2 * kGateUpGroup * kchunks * kTileElems + j0 * kTileElems;
+        ws.cstep = (int64_t)2 * ng * kTileElems;
+        ws.up = ng * kTileElems;
+    } else {
+        static_assert(PASS == 0 || kDownGroup % RT == 0, "a wave's stripes share a group");
+        const int first = wsrc * RT;
+        const int g = first / kDownGroup, j0 = first % kDownGroup;
+        const int ng = min(kDownGroup, n_out / 16 - g * kDownGroup);
+        ws.base = blob + off_w + (int64_t)g * kDownGroup * kchunks * kTileElems + j0 * kTileElems;
+        ws.cstep = (int64_t)ng * kTileElems;
+        ws.up = 0;
+    }
+}
+
 template <int PASS, int RT, int NT, int D, int PC, int NBUF, bool SHARED = false>
 __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile, bool active,
                                  const Task& task, const uint16_t* __restrict__ act_in,
@@ -78,32 +121,11 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
     const int kchunks = K >> 5;
     const int col0 = wtile * 16 * (PASS == 0 ? G : RT);
 
-    // a spare wave (columns past n_out) streams the last valid wave's stripes and stores nothing:
-    // it stays in step with the barriers without a predicate around the loop
-    const int wsrc = active ? wtile : (n_out / (16 * (PASS == 0 ? G : RT)) - 1);
-    // A wave's stripes all lie in one group of the packed layout; inside the group the K chunk is the
-    // slow index, so chunk c of stripe r sits at wt[r] + c * cstep.
-    const uint16_t* wt[RT];
-    int64_t cstep;
-    if (PASS == 0) {
-        static_assert(PASS != 0 || kGateUpGroup % (RT / 2) == 0, "a wave's column blocks share a group");
-        const int first = wsrc * G;                                  // the wave's first SwiGLU column block
-        const int g = first / kGateUpGroup, j0 = first % kGateUpGroup;
-        const int ng = min(kGateUpGroup, n_out / 16 - g * kGateUpGroup);
-        const uint16_t* base = blob + off_w + (int64_t)g * 2 * kGateUpGroup * kchunks * kTileElems + lane * 8;
-        cstep = (int64_t)2 * ng * kTileElems;
-#pragma unroll
-        for (int r = 0; r < RT; ++r) wt[r] = base + ((r < G ? 0 : ng) + j0 + (r % G)) * kTileElems;
-    } else {
-        static_assert(PASS == 0 || kDownGroup % RT == 0, "a wave's stripes share a group");
-        const int first = wsrc * RT;
-        const int g = first / kDownGroup, j0 = first % kDownGroup;
-        const int ng = min(kDownGroup, n_out / 16 - g * kDownGroup);
-        const uint16_t* base = blob + off_w + (int64_t)g * kDownGroup * kchunks * kTileElems + lane * 8;
-        cstep = (int64_t)ng * kTileElems;
-#pragma unroll
-        for (int r = 0; r < RT; ++r) wt[r] = base + (j0 + r) * kTileElems;
-    }
+    WeightStream ws;
+    weight_stream<PASS, RT>(blob, off_w, wtile, active, K, n_out, ws);
+    const int lane8 = lane * 8;
+    // chunk c of stripe r: scalar address arithmetic plus the lane's place in the tile
+    auto tile = [&](int r, int c) { return ws.base + (stripe_offset<PASS, RT>(ws, r) + c * ws.cstep) + lane8; };
 
     // staging map: piece q = tid + 256*j covers row q / kPPR of the item, columns (q % kPPR)*8 .. +7 of the
     // stage; kPPR divides 256, so a thread's pieces all sit at the same columns
@@ -147,7 +169,7 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
     for (int i = 0; i < D; ++i) {
         const int ci = min(i, kchunks - 1);
 #pragma unroll
-        for (int r = 0; r < RT; ++r) a[i][r] = load_weights<SHARED>(wt[r] + ci * cstep);
+        for (int r = 0; r < RT; ++r) a[i][r] = load_weights<SHARED>(tile(r, ci));
     }
     f32x4 acc[RT][NT];
 #pragma unroll
@@ -173,7 +195,7 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
     auto refill = [&](int c, int i) {
         const int cn = min(c + D, kchunks - 1);
 #pragma unroll
-        for (int r = 0; r < RT; ++r) a[i][r] = load_weights<SHARED>(wt[r] + cn * cstep);
+        for (int r = 0; r < RT; ++r) a[i][r] = load_weights<SHARED>(tile(r, cn));
     };
     using all_tiles = std::integral_constant<int, NT>;
 
@@ -304,7 +326,7 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
     __shared__ __attribute__((aligned(16))) uint16_t lds[kRowsPerTask * (kSmallPC * 32 + 8)];
     const int task_id = blockIdx.y;
     if (task_id >= n_tasks[0]) return;
-    const int wtile = blockIdx.x * kWaves + (threadIdx.x >> 6);
+    const int wtile = blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // the same for a wave's lanes: scalar
     const bool active = wtile * 16 * (PASS == 0 ? RT / 2 : RT) < n_out;      // spare waves still help staging
     const Task task = tasks[task_id];
     const uint16_t* blob = slots + (int64_t)task.slot * blob_elems;
@@ -384,7 +406,7 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_big_kernel(
     const int xcd = blockIdx.x % kXcds, unit = blockIdx.x / kXcds;
     if (unit >= list_tasks(xcd, n_big) * n_ftiles) return;
     const int task_id = order[list_rank(xcd, unit / n_ftiles)];
-    const int wtile = (unit % n_ftiles) * kWaves + (threadIdx.x >> 6);
+    const int wtile = (unit % n_ftiles) * kWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // scalar, as above
     const bool active = wtile * 16 * (PASS == 0 ? RT / 2 : RT) < n_out;
     const Task task = tasks[task_id];
     const uint16_t* blob = slots + (int64_t)task.slot * blob_elems;

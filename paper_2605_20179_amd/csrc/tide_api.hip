@@ -361,6 +361,7 @@ int tide_create(const tide_config* cfg, tide_ctx** out) {
     if (hipGetDeviceProperties(&prop, ctx->device) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "hipGetDeviceProperties failed"));
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
         return bail(fail(ctx, TIDE_E_HIP, "device is %s; libtide is built for gfx950 only", prop.gcnArchName));
+    s.n_cus = prop.multiProcessorCount;
 
     if (hipError_t se = scratch_on_device(ctx->device, &ctx->scratch_dev); se != hipSuccess)
         return bail(fail(ctx, TIDE_E_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(se)));

@@ -82,6 +82,7 @@ struct LaunchEvents {
 struct Shape {
     int d, E, k, I, n_shared, capacity, gating, bias_mode;
     int64_t blob_elems;       // 3*d*I
+    int n_cus;                // compute units of the device
 };
 
 // a1: z[n][e] = <x_n, W_r[e]>  (fp32)
