@@ -268,10 +268,7 @@ __global__ void scale_counts_kernel(int32_t* hits, int n, int num, int den) {
 // A copy workgroup asks for almost all of a compute unit's LDS without using it: no workgroup of the expert GEMM
 // kernels (which stage their token rows in LDS) then fits beside it, so the copy's host-link reads never sit in the
 // memory pipeline of a compute unit that a GEMM workgroup is waiting on.
-#ifndef TIDE_COPY_LDS_RESERVE
-#define TIDE_COPY_LDS_RESERVE (152 * 1024)
-#endif
-constexpr int kCopyLdsReserve = TIDE_COPY_LDS_RESERVE;
+constexpr int kCopyLdsReserve = 152 * 1024;
 template <typename K>
 hipError_t reserve_lds(K kernel) {
     static hipError_t rc = kCopyLdsReserve > 0 ? hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kCopyLdsReserve)

@@ -100,3 +100,42 @@ def test_replay_after_a_refresh_needs_the_queued_wait():
     assert torch.equal(sess.out[:wl.N], got[0])
     assert sorted(np.nonzero(sess.table(0) >= 0)[0].tolist()) == list(range(wl.C, 2 * wl.C))
     sess.close()
+
+
+def test_stack_step_replayed_from_a_graph():
+    """tide_moe_stack_step forks onto the library's lane streams and joins back by events: all of it is captured with
+    the caller's stream, and every replay equals the eager stack step."""
+    wl = ti.CONFIGS[2].replace(N=96, S=3, L=4, C=16)
+    from paper_2605_20179_amd.session import TideSession
+    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, n_layers=wl.L)
+    packed = sess.pack_layer(lambda e: ti.expert_weights(wl, 0, e), workers=16)
+    for l in range(wl.L):
+        sess.load_layer(l, None, ti.router_weights(wl, l), ti.router_bias(wl, l), ti.initial_resident(wl), packed=packed)
+    hidden = [[sess.to_device_bf16(h) for h in ti.hidden_stream(wl, l)] for l in range(wl.L)]
+    eager = []
+    for t in range(wl.S):
+        sess.stack_step([hidden[l][t] for l in range(wl.L)])
+        torch.cuda.synchronize()
+        eager.append([(sess.stack_out[l][:wl.N].clone(), int(sess.stack_n_miss[l].item())) for l in range(wl.L)])
+    static_in = [hidden[l][0].clone() for l in range(wl.L)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sess.stack_step(static_in)                     # warm-up outside the capture (the lanes exist already)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sess.stack_step(static_in)
+    for rep in range(2):
+        for t in range(wl.S):
+            for l in range(wl.L):
+                static_in[l].copy_(hidden[l][t])
+            graph.replay()
+            torch.cuda.synchronize()
+            for l in range(wl.L):
+                assert int(sess.stack_n_miss[l].item()) == eager[t][l][1]
+                assert torch.equal(sess.stack_out[l][:wl.N], eager[t][l][0]), "replay %d step %d layer %d" % (rep, t, l)
+        sess.step(0, hidden[0][rep], want_topk=False)      # eager work between the rounds of replays
+        torch.cuda.synchronize()
+    sess.close()
