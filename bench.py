@@ -30,10 +30,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 
 
-def cpu_baseline(wl, ti, sample_steps=512):
+def cpu_baseline(wl, ti, sample_steps=None):
     """The oracle as it stands, on `sample_steps` consecutive denoise steps (all tokens,
-    cold-start placement) of the benchmark workload."""
+    cold-start placement) of the benchmark workload.  The default sample is 512 steps of the
+    headline layer and as many steps of a larger one as cost about the same CPU time."""
     import numpy as np
+    if sample_steps is None:
+        sample_steps = max(2, min(512, int(512 * 32 * 2048 * 512 / (wl.N * wl.d * wl.I))))
     from oracle import tide_oracle as orc
     try:
         from threadpoolctl import threadpool_info
@@ -53,17 +56,22 @@ def cpu_baseline(wl, ti, sample_steps=512):
                       "%.1f s (includes bf16->fp64 weight conversion on first use)" % (sample_steps, wl.N, dt)}
 
 
+# --resident: the form the cache slots keep the blobs in (set once in main, read by every session made here)
+RESIDENT_P12 = False
+
+
 def run_stack(args, wl, ti, tb, TideSession, torch):
     """A stack of L independent MoE layers per denoise step (the stack workloads' metric: N / sum over the
     layers).  Detail measurement, not the headline: prints its own JSON line."""
     L = args.stack
-    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, n_layers=L)
+    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, n_layers=L, resident_p12=RESIDENT_P12)
     packed = sess.pack_layer(lambda e: ti.expert_weights(wl, 0, e), workers=16)
     hidden = []
-    for l in range(L):
-        sess.load_layer(l, None, ti.router_weights(wl, l), ti.router_bias(wl, l), ti.initial_resident(wl), packed=packed)
+    for l in range(L):                                 # the layers share layer 0's blobs, so one compressed copy serves all
+        sess.load_layer(l, None, ti.router_weights(wl, l), ti.router_bias(wl, l), ti.initial_resident(wl), packed=packed,
+                        workers=16, comp=sess.comp_blobs.get(0))
         hidden.append([sess.to_device_bf16(h) for h in ti.hidden_stream(wl, l)])
-    if args.refresh_source == "packed12":              # the layers share layer 0's blobs, so one compressed copy serves all
+    if args.refresh_source == "packed12" and not RESIDENT_P12:
         sess.compress_layer(0, workers=16)
         for l in range(1, L):
             tb.tide_register_compressed(sess.ctx, l, sess.comp_blobs[0], tb.tide_compressed_blob_bytes(sess.cfg))
@@ -106,7 +114,7 @@ def run_stack(args, wl, ti, tb, TideSession, torch):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "d": wl.d, "experts": wl.E, "top_k": wl.k, "d_ff": wl.I, "shared_experts": wl.n_shared,
                    "tokens_per_step": wl.N, "capacity": wl.C, "refresh_interval": wl.K, "steps_per_block": wl.S, "layers": L,
-                   "refresh_order": args.refresh_order, "refresh_source": args.refresh_source, "note": "layers share layer 0's expert values; routers, streams, caches differ"},
+                   "refresh_order": args.refresh_order, "refresh_source": args.refresh_source, "resident_format": args.resident, "note": "layers share layer 0's expert values; routers, streams, caches differ"},
         "detail": {"experts_copied": state["copies"], "blob_MiB": sess.blob_bytes / 2 ** 20,
                    "frozen_placement_us_per_step": frozen * 1e6, "frozen_placement_us_per_layer": frozen * 1e6 / L,
                    "us_per_layer": 1e6 * dt / args.steps / L}}))
@@ -152,9 +160,12 @@ def measure_layer(wl, ti, tb, TideSession, torch, packed, steps, warmup, refresh
     """One layer of workload `wl` (any of the five configurations): tokens/s with the refresh every K steps (copies
     from `refresh_source`, and once more from the raw blobs), tokens/s with the placement frozen, per-kernel
     durations from event-stamped launches of a frozen pass, and the roofline fractions they give."""
-    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode)
-    sess.load_layer(0, None, ti.router_weights(wl, 0), ti.router_bias(wl, 0), ti.initial_resident(wl), packed=packed)
-    use_p12 = refresh_source == "packed12" and wl.C < wl.E
+    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, resident_p12=RESIDENT_P12)
+    sess.load_layer(0, None, ti.router_weights(wl, 0), ti.router_bias(wl, 0), ti.initial_resident(wl), packed=packed,
+                    workers=16, comp=comp if RESIDENT_P12 else None)
+    use_p12 = refresh_source == "packed12" and wl.C < wl.E and not RESIDENT_P12
+    if RESIDENT_P12:
+        comp = sess.comp_blobs[0]
     if use_p12:
         if comp is None:
             sess.compress_layer(0, workers=16)
@@ -224,15 +235,16 @@ def measure_stack(wl, L, ti, tb, TideSession, torch, packed, steps, comp=None, r
     stream, cache, counter, refresh per layer; the layers share layer 0's expert values).  tokens/s = N / sum of
     the layers' times, with the placement frozen and (refresh=True) with every layer refreshed every K steps, all
     layers first so that later layers' copies run under earlier layers' compute."""
-    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, n_layers=L)
+    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, n_layers=L, resident_p12=RESIDENT_P12)
     import concurrent.futures
     n_hidden = min(wl.S, 2 * wl.K) if (refresh and wl.C < wl.E) else 2
     with concurrent.futures.ThreadPoolExecutor(max_workers=16) as ex:
         streams = list(ex.map(lambda l: list(ti.hidden_stream(wl, l, n_hidden)), range(L)))
     hidden = []
     for l in range(L):
-        sess.load_layer(l, None, ti.router_weights(wl, l), ti.router_bias(wl, l), ti.initial_resident(wl), packed=packed)
-        if comp is not None and wl.C < wl.E:
+        sess.load_layer(l, None, ti.router_weights(wl, l), ti.router_bias(wl, l), ti.initial_resident(wl), packed=packed,
+                        workers=16, comp=(comp if comp is not None else sess.comp_blobs.get(0)) if RESIDENT_P12 else None)
+        if comp is not None and wl.C < wl.E and not RESIDENT_P12:
             tb.tide_register_compressed(sess.ctx, l, comp, tb.tide_compressed_blob_bytes(sess.cfg))
         hidden.append([sess.to_device_bf16(h) for h in streams[l]])
     del streams
@@ -289,7 +301,7 @@ def run_all_configs(args, ti, tb, TideSession, torch, cfg1_entry, packed_mini, c
     mini, flash = ti.CONFIGS[2], ti.CONFIGS[3]
     t0 = time.perf_counter()
     wl0 = ti.CONFIGS[0]
-    s0 = TideSession(wl0.d, wl0.E, wl0.k, wl0.I, wl0.n_shared, wl0.C, wl0.N, wl0.gating, wl0.bias_mode)
+    s0 = TideSession(wl0.d, wl0.E, wl0.k, wl0.I, wl0.n_shared, wl0.C, wl0.N, wl0.gating, wl0.bias_mode)      # packs only
     packed0 = s0.pack_layer(lambda e: ti.expert_weights(wl0, 0, e), workers=4)
     s0.close()
     out["0"], _ = measure_layer(wl0, ti, tb, TideSession, torch, packed0, 64, 16, args.refresh_source)
@@ -394,6 +406,9 @@ def main():
                     help="--stack: at a refresh step, refresh each layer right before its own step, or all layers first so "
                          "that later layers' copies overlap earlier layers' compute")
     ap.add_argument("--capacity", type=int, default=0, help="cache slots (0 = the workload's own budget); 256 = every expert resident")
+    ap.add_argument("--resident", choices=("bf16", "p12"), default="bf16",
+                    help="the form a cache slot keeps its blob in: the bf16 blob, or its lossless 12-bit form decoded by the "
+                         "expert GEMMs in registers (3/4 of the HBM bytes per step; refresh copies then move compressed blobs)")
     ap.add_argument("--refresh-source", choices=("raw", "packed12"), default="packed12",
                     help="what the refresh copies read over the host link: the raw blobs, or their lossless 12-bit form "
                          "(3/4 of the bytes; slots bit-identical)")
@@ -473,10 +488,14 @@ def main():
     if args.stack:
         run_stack(args, wl, ti, tb, TideSession, torch)
         return
-    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode)
+    global RESIDENT_P12
+    RESIDENT_P12 = args.resident == "p12"
+    if RESIDENT_P12:
+        args.refresh_source = "packed12"               # 12-bit slots are filled with compressed blobs by every engine
+    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, resident_p12=RESIDENT_P12)
     packed = sess.pack_layer(lambda e: ti.expert_weights(wl, 0, e), workers=16)
-    sess.load_layer(0, None, ti.router_weights(wl, 0), ti.router_bias(wl, 0), ti.initial_resident(wl), packed=packed)
-    if args.refresh_source == "packed12":
+    sess.load_layer(0, None, ti.router_weights(wl, 0), ti.router_bias(wl, 0), ti.initial_resident(wl), packed=packed, workers=16)
+    if args.refresh_source == "packed12" and not RESIDENT_P12:
         sess.compress_layer(0, workers=16)
     if args.copy_engine == "dma":
         tb.tide_refresh_engine(sess.ctx, tb.TIDE_COPY_DMA)
@@ -628,7 +647,7 @@ def main():
 
     no_events = plain_pass()
     raw_source = None
-    if args.refresh_source == "packed12":
+    if args.refresh_source == "packed12" and not RESIDENT_P12:     # bf16 slots can also be refreshed from the raw blobs
         tb.tide_register_compressed(sess.ctx, 0, None, 0)
         raw_source = plain_pass()
         tb.tide_register_compressed(sess.ctx, 0, sess.comp_blobs[0], tb.tide_compressed_blob_bytes(sess.cfg))
@@ -737,8 +756,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "d": wl.d, "experts": wl.E, "top_k": wl.k, "d_ff": wl.I, "shared_experts": wl.n_shared,
                    "tokens_per_step": wl.N, "capacity": wl.C, "refresh_interval": wl.K, "steps_per_block": wl.S, "layers": 1,
-                   "refresh_source": args.refresh_source if args.copy_engine == "kernel" else "raw", "refresh_call": args.refresh_call,
-                   "copy_engine": args.copy_engine,
+                   "refresh_source": args.refresh_source if (args.copy_engine == "kernel" or RESIDENT_P12) else "raw", "refresh_call": args.refresh_call,
+                   "copy_engine": args.copy_engine, "resident_format": args.resident,
                    "refresh_mode": args.refresh_mode if args.refresh_mode == "immediate" else "deferred by %d step(s)" % args.commit_after},
         "value_refresh_source": args.refresh_source + (" (lossless 12-bit form of the blobs read over the host link)" if args.refresh_source == "packed12" else " blobs"),
         "value_with_raw_refresh_copies": (raw_source or no_events)["tokens_per_s"],

@@ -65,6 +65,7 @@ typedef struct {
     int32_t max_tokens;  /* largest n_tokens a step may carry, 1..65535                  */
     int32_t gating;      /* TIDE_GATING_*                                                */
     int32_t bias_mode;   /* TIDE_BIAS_*                                                  */
+    int32_t resident_format; /* TIDE_RESIDENT_*: the form a cache slot keeps its blob in  */
 } tide_config;
 
 /* ---- set-up --------------------------------------------------------------------- */
@@ -101,21 +102,32 @@ int tide_pack_expert(const tide_config* cfg, const uint16_t* wg_host, const uint
  * refused with TIDE_E_INVAL.  Borrowed, never written, never freed. */
 int tide_register_experts(tide_ctx* ctx, int layer, const void* host_blobs, uint64_t blob_stride);
 
-/* Optional: a lossless 12-bit form of the packed blobs as the SOURCE OF REFRESH COPIES, so that 3/4 of the
- * bytes cross the host link; the copy kernel rebuilds the blob bit for bit in the cache slot (or staging
- * blob).  Everything else (tide_set_resident, the miss paths) keeps reading the raw blobs, which must stay
- * registered.  Format: per 16 x 32 tile one exponent (the top of the 16-binade window that holds most of
- * the tile), per element sign | 4-bit distance below it | 7-bit mantissa; elements outside the window
- * are listed as exceptions (up to one per tile on average; an expert with more is marked "raw" and copied
- * from its raw blob).
+/* A lossless 12-bit form of the packed blobs: about 3/4 of the bytes, every weight rebuilt bit for bit.
+ * Format, per 16 x 32 tile: the low byte of every bf16 as it is (last exponent bit and mantissa), a table of
+ * the tile's distinct high bytes (sign and upper exponent bits; at most 16), and a 4-bit table index per
+ * element: 768 + 16 bytes instead of 1024.  A blob with a tile of more than 16 distinct high bytes (a few
+ * tiles in a million for Gaussian weights) is marked "raw" and used in its bf16 form everywhere.
+ * Two uses, both needing the raw blobs registered as well (the miss paths read those):
+ *   - resident_format == TIDE_RESIDENT_BF16: optional SOURCE OF REFRESH COPIES, so that 3/4 of the bytes
+ *     cross the host link; the copy kernel rebuilds the bf16 blob in the cache slot (or staging blob).
+ *   - resident_format == TIDE_RESIDENT_P12: required; the cache slots keep the compressed blob as it is
+ *     (tide_set_resident, tide_set_shared, every refresh copy and tide_read_slot then move compressed
+ *     blobs) and the expert GEMMs decode it in registers: the same outputs bit for bit from 3/4 of the
+ *     HBM bytes.  It pays where a step is bound by the weight bytes (small token counts); a large work
+ *     item then holds at most 192 rows instead of 256.
  *   tide_compressed_blob_bytes  size of one compressed blob (a multiple of 64)
  *   tide_compress_expert        host: packed blob (tide_pack_expert) -> compressed blob
+ *   tide_decompress_expert      host: the inverse; TIDE_E_INVAL for a blob marked raw or of another configuration
  *   tide_register_compressed    expert e at comp_host_blobs + e * comp_stride; pinned host memory, 64-byte
- *                               aligned, valid and unchanged until tide_destroy; NULL goes back to raw copies.
- *                               Synchronises the device.  TIDE_E_INVAL for pageable memory or a blob that is
- *                               not of this configuration, TIDE_E_STATE before tide_register_experts. */
+ *                               aligned, valid and unchanged until tide_destroy; NULL goes back to raw copies
+ *                               (bf16 slots only).  Synchronises the device.  TIDE_E_INVAL for pageable memory
+ *                               or a blob that is not of this configuration, TIDE_E_STATE before
+ *                               tide_register_experts, or with 12-bit slots after tide_set_resident. */
+#define TIDE_RESIDENT_BF16 0
+#define TIDE_RESIDENT_P12  1
 uint64_t tide_compressed_blob_bytes(const tide_config* cfg);
 int tide_compress_expert(const tide_config* cfg, const void* blob_host, void* comp_host);
+int tide_decompress_expert(const tide_config* cfg, const void* comp_host, void* blob_host);
 int tide_register_compressed(tide_ctx* ctx, int layer, const void* comp_host_blobs, uint64_t comp_stride);
 
 /* Copies one packed blob (host) into the layer's always-resident shared-expert slot.
@@ -345,12 +357,13 @@ int tide_queue_refresh_wait(tide_ctx* ctx, int layer, void* hip_stream);
 /* Who moves a refresh's expert blobs across the host link (Alg. 1's asynchronous migration), for every later
  * refresh on the context:
  *   TIDE_COPY_KERNEL  one kernel on the side stream that reads pinned host memory in place (default; the only
- *                     engine that can read the 12-bit form of tide_register_compressed, and the only one
- *                     tide_refresh_async can use, because the host never sees that call's plan);
- *   TIDE_COPY_DMA     one hipMemcpyAsync per entering expert on the side stream, raw blobs: the copy engines
- *                     move the bytes and no compute unit takes part, which matters when steps run beside the
- *                     copies (tide_refresh_deferred).
- * Results are identical: the slots end up byte-equal to the host blobs either way. */
+ *                     engine that can decode the 12-bit form of tide_register_compressed into bf16 slots, and the
+ *                     only one tide_refresh_async can use, because the host never sees that call's plan);
+ *   TIDE_COPY_DMA     one hipMemcpyAsync per entering expert on the side stream, of the bytes the slot keeps
+ *                     (the bf16 blob; with 12-bit slots the compressed blob): the copy engines move the bytes
+ *                     and no compute unit takes part, which matters when steps run beside the copies
+ *                     (tide_refresh_deferred).
+ * Results are identical: the slots end up byte-equal to the host's blobs of the resident form either way. */
 #define TIDE_COPY_KERNEL 0
 #define TIDE_COPY_DMA    1
 int tide_refresh_engine(tide_ctx* ctx, int engine);

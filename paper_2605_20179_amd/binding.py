@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libtide.so")
 TIDE_OK, TIDE_E_INVAL, TIDE_E_RANGE, TIDE_E_STATE, TIDE_E_HIP, TIDE_E_NOMEM = 0, -1, -2, -3, -4, -5
 TIDE_GATING_SOFTMAX, TIDE_GATING_SIGMOID = 0, 1
 TIDE_BIAS_NONE, TIDE_BIAS_LOGIT, TIDE_BIAS_SELECT = 0, 1, 2
+TIDE_RESIDENT_BF16, TIDE_RESIDENT_P12 = 0, 1
 
 EXPORTS = [
     "tide_create", "tide_destroy", "tide_last_error", "tide_expert_blob_bytes", "tide_pack_expert",
@@ -25,7 +26,7 @@ EXPORTS = [
     "tide_refresh_copy_ms", "tide_profile", "tide_profile_read", "tide_counters", "tide_moe_apply_misses",
     "tide_step_histogram", "tide_routing_stability", "tide_interval_costs", "tide_optimal_interval", "tide_fit_drift", "tide_scale_counts", "tide_refresh_deferred", "tide_commit",
     "tide_host_experts", "tide_moe_apply_misses_host", "tide_host_miss_ms", "tide_host_expert", "tide_host_link_share", "tide_host_misses",
-    "tide_compressed_blob_bytes", "tide_compress_expert", "tide_register_compressed",
+    "tide_compressed_blob_bytes", "tide_compress_expert", "tide_decompress_expert", "tide_register_compressed",
     "tide_refresh_async", "tide_refresh_result",
     "tide_moe_step_noalloc", "tide_noalloc_scratch_bytes", "tide_set_counts", "tide_read_work_items",
     "tide_refresh_engine", "tide_queue_refresh_wait", "tide_hbm_stream_probe", "tide_moe_stack_step",
@@ -35,7 +36,7 @@ KERNEL_NAMES = ["router_logits", "topk_gate", "dispatch", "gate_up_swiglu", "dow
 
 class tide_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d", "n_experts", "top_k", "d_ff", "n_shared", "n_layers", "capacity",
-                                          "max_tokens", "gating", "bias_mode")]
+                                          "max_tokens", "gating", "bias_mode", "resident_format")]
 
 
 class tide_miss(C.Structure):
@@ -72,6 +73,7 @@ def _load() -> C.CDLL:
     lib.tide_compressed_blob_bytes.argtypes = [cfgp]
     lib.tide_compressed_blob_bytes.restype = C.c_uint64
     lib.tide_compress_expert.argtypes = [cfgp, vp, vp]
+    lib.tide_decompress_expert.argtypes = [cfgp, vp, vp]
     lib.tide_register_compressed.argtypes = [vp, C.c_int, vp, C.c_uint64]
     lib.tide_register_experts.argtypes = [vp, C.c_int, vp, C.c_uint64]
     lib.tide_set_shared.argtypes = [vp, C.c_int, vp]
@@ -123,8 +125,9 @@ def _load() -> C.CDLL:
 lib = _load()
 
 
-def make_config(d, n_experts, top_k, d_ff, n_shared, n_layers, capacity, max_tokens, gating, bias_mode) -> tide_config:
-    return tide_config(d, n_experts, top_k, d_ff, n_shared, n_layers, capacity, max_tokens, gating, bias_mode)
+def make_config(d, n_experts, top_k, d_ff, n_shared, n_layers, capacity, max_tokens, gating, bias_mode,
+                resident_format=0) -> tide_config:
+    return tide_config(d, n_experts, top_k, d_ff, n_shared, n_layers, capacity, max_tokens, gating, bias_mode, resident_format)
 
 
 def _check(rc: int, ctx) -> None:
@@ -168,6 +171,11 @@ def tide_compressed_blob_bytes(cfg: tide_config) -> int:
 def tide_compress_expert(cfg: tide_config, blob, comp) -> None:
     """packed blob (host uint8 buffer) -> its 12-bit form (host uint8 buffer of tide_compressed_blob_bytes)."""
     _check(lib.tide_compress_expert(C.byref(cfg), _ptr(blob), _ptr(comp)), None)
+
+
+def tide_decompress_expert(cfg: tide_config, comp, blob) -> None:
+    """12-bit form (host uint8 buffer) -> the packed blob (host uint8 buffer of tide_expert_blob_bytes)."""
+    _check(lib.tide_decompress_expert(C.byref(cfg), _ptr(comp), _ptr(blob)), None)
 
 
 def tide_register_compressed(ctx, layer: int, comp_blobs, comp_stride: int) -> None:

@@ -87,12 +87,13 @@ __device__ inline int block_scan_excl(int v, int& total, int* lds4) {
 __device__ inline int n_small_items(int m, bool use_big) {
     return (m <= kBigMinRows || !use_big) ? (m + kRowsPerTask - 1) / kRowsPerTask : 0;
 }
-__device__ inline int n_big_items(int m, bool use_big) {
-    return (m > kBigMinRows && use_big) ? (m + kRowsPerBigTask - 1) / kRowsPerBigTask : 0;
+__device__ inline int n_big_items(int m, bool use_big, int big_rows) {
+    return (m > kBigMinRows && use_big) ? (m + big_rows - 1) / big_rows : 0;
 }
 
 // Work items of one slot whose m rows start at row0.
-__device__ inline void emit_tasks(int slot, int row0, int m, bool use_big, Task* small_out, Task* big_out, int big_room) {
+__device__ inline void emit_tasks(int slot, int row0, int m, bool use_big, Task* small_out, Task* big_out, int big_room, int fmt_flags,
+                                  int big_rows) {
     if (m <= 0) return;
     if (m <= kBigMinRows || !use_big) {
         const int ns = (m + kRowsPerTask - 1) / kRowsPerTask;
@@ -101,15 +102,15 @@ __device__ inline void emit_tasks(int slot, int row0, int m, bool use_big, Task*
             t.slot = slot;
             t.row0 = row0 + c * kRowsPerTask;
             t.nrows = min(kRowsPerTask, m - c * kRowsPerTask);
-            t.pad = ns > 1 ? 1 : 0;          // the slot's weights are streamed by several items: let them meet in L2
+            t.flags = (ns > 1 ? kTaskSiblings : 0) | fmt_flags;      // several items stream the slot's weights: let them meet in L2
             small_out[c] = t;
         }
         return;
     }
     // the fewest large work items that hold m rows, of even size (a whole number of 16-token tiles):
     // 300 rows become 160 + 140, not 256 + 44, so the slot's work items finish together
-    const int nb = (m + kRowsPerBigTask - 1) / kRowsPerBigTask;
-    const int per = ((m + nb - 1) / nb + 15) / 16 * 16;      // <= kRowsPerBigTask, and (nb-1)*per < m
+    const int nb = (m + big_rows - 1) / big_rows;
+    const int per = ((m + nb - 1) / nb + 15) / 16 * 16;      // <= big_rows (a multiple of 16), and (nb-1)*per < m
     // the host's bound on the step's large work items holds for any routing (rows / 256 plus one per slot that can
     // exceed the small limit), so big_room >= nb; the clamp only keeps a bound that was computed for another token
     // count from ever turning into a write out of bounds
@@ -118,7 +119,7 @@ __device__ inline void emit_tasks(int slot, int row0, int m, bool use_big, Task*
         t.slot = slot;
         t.row0 = row0 + c * per;
         t.nrows = min(per, m - c * per);
-        t.pad = 0;
+        t.flags = fmt_flags;
         big_out[c] = t;
     }
 }
@@ -164,11 +165,11 @@ __device__ inline void collect_rows(const int32_t* __restrict__ idx, const int32
 __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w, int n_tokens, int k, int capacity,
     int n_shared, int n_experts, const int32_t* __restrict__ slot_of, const int32_t* __restrict__ expert_in_slot,
-    const int32_t* __restrict__ hist_step, int32_t* __restrict__ hits, int32_t* __restrict__ row_token,
+    const uint8_t* __restrict__ expert_p12, const int32_t* __restrict__ hist_step, int32_t* __restrict__ hits, int32_t* __restrict__ row_token,
     int32_t* __restrict__ pair_row, int32_t* __restrict__ slot_off, Task* __restrict__ tasks, Task* __restrict__ big_tasks,
     int32_t* __restrict__ n_tasks,
     tide_miss* __restrict__ miss, int miss_cap, int32_t* __restrict__ n_miss, int64_t* __restrict__ counters,
-    int max_big, int big_ftiles) {
+    int max_big, int big_ftiles, int big_rows) {
     __shared__ int lds4[kThreads / 64];
     __shared__ unsigned long long lds8[2 * (kThreads / 64)];
     __shared__ int own[2];                   // this block's slot: expert and rows
@@ -227,7 +228,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     if (tid < capacity) {
         const int e = expert_in_slot[tid];
         const int m = e >= 0 ? hist_step[e] : 0;
-        const unsigned long long big = n_big_items(m, true);
+        const unsigned long long big = n_big_items(m, true, big_rows);
         if (tid == s) {
             own[0] = e;
             own[1] = m;
@@ -239,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
         }
     }
     block_sum2(fa, fb, lds8);
-    const int all_big = (int)(fa & 0xffff) + n_big_items(n_shared ? n_tokens : 0, true);
+    const int all_big = (int)(fa & 0xffff) + n_big_items(n_shared ? n_tokens : 0, true, big_rows);
     const bool use_big = max_big > 0 && all_big * big_ftiles >= kMinBigUnits;      // max_big == 0: the host launches no large-item kernels
     const int active_before = (int)(fa >> 16 & 0xffff);
     const int rows_before = (int)(fa >> 32);
@@ -254,8 +255,9 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
         const int m = n_shared ? n_tokens : 0;
         for (int n = tid; n < m; n += kThreads) row_token[rows_before + n] = n;
         const int n_small = n_small_items(m, use_big);
-        const int n_big = n_big_items(m, use_big);
-        emit_tasks(capacity, rows_before, m, use_big, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
+        const int n_big = n_big_items(m, use_big, big_rows);
+        emit_tasks(capacity, rows_before, m, use_big, tasks + tasks_before, big_tasks + big_before, max_big - big_before,
+                   expert_p12 && expert_p12[n_experts] ? kTaskP12 : 0, big_rows);
         if (tid == 0) {
             slot_off[capacity] = rows_before;
             slot_off[capacity + 1] = rows_before + m;
@@ -274,7 +276,8 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     const int e = own[0], m = own[1];        // written before block_sum2's barriers
     if (tid == 0) slot_off[s] = rows_before;
     if (m == 0) return;
-    emit_tasks(s, rows_before, m, use_big, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
+    emit_tasks(s, rows_before, m, use_big, tasks + tasks_before, big_tasks + big_before, max_big - big_before,
+               expert_p12 && expert_p12[e] ? kTaskP12 : 0, big_rows);
     collect_rows<false>(topk_idx, nullptr, n_pairs, k, e, rows_before, row_token, pair_row, lds4);
 }
 
@@ -310,11 +313,11 @@ __global__ __launch_bounds__(kThreads) void miss_group_kernel(const int32_t* __r
                                                              int32_t* __restrict__ row_token,
                                                              int32_t* __restrict__ pair_row, Task* __restrict__ tasks,
                                                              Task* __restrict__ big_tasks, int32_t* __restrict__ n_tasks,
-                                                             int max_big, int big_ftiles) {
+                                                             int max_big, int big_ftiles, int big_rows) {
     __shared__ int lds4[kThreads / 64];
     const int e = blockIdx.x, tid = threadIdx.x;
     int all_big = 0;
-    for (int q = tid; q < n_experts; q += kThreads) all_big += n_big_items(miss_hist[q], true);
+    for (int q = tid; q < n_experts; q += kThreads) all_big += n_big_items(miss_hist[q], true, big_rows);
     const bool use_big = max_big > 0 && block_sum(all_big, lds4) * big_ftiles >= kMinBigUnits;
     const int upto = e < n_experts ? e : n_experts;
     int rows_before = 0, tasks_before = 0, big_before = 0;
@@ -322,7 +325,7 @@ __global__ __launch_bounds__(kThreads) void miss_group_kernel(const int32_t* __r
         const int m = miss_hist[q];
         rows_before += m;
         tasks_before += n_small_items(m, use_big);
-        big_before += n_big_items(m, use_big);
+        big_before += n_big_items(m, use_big, big_rows);
     }
     rows_before = block_sum(rows_before, lds4);
     tasks_before = block_sum(tasks_before, lds4);
@@ -336,7 +339,8 @@ __global__ __launch_bounds__(kThreads) void miss_group_kernel(const int32_t* __r
     }
     const int m = miss_hist[e];
     if (m == 0) return;
-    emit_tasks(e, rows_before, m, use_big, tasks + tasks_before, big_tasks + big_before, max_big - big_before);
+    // the miss pass reads the host's bf16 blobs
+    emit_tasks(e, rows_before, m, use_big, tasks + tasks_before, big_tasks + big_before, max_big - big_before, 0, big_rows);
     collect_rows<true>(m_idx, m_tok, *m_count, 1, e, rows_before, row_token, pair_row, lds4);
 }
 
@@ -413,7 +417,7 @@ hipError_t launch_miss_group(const Shape& s, const Workspace& w, const tide_miss
     hipLaunchKernelGGL(miss_prepare_kernel, dim3((miss_cap + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, miss,
                        miss_cap, n_miss, s.E, n_tokens, expert_mask, w.m_idx, w.m_tok, w.m_w, w.miss_hist, w.m_count);
     hipLaunchKernelGGL(miss_group_kernel, dim3(s.E + 1), dim3(kThreads), 0, stream, w.m_idx, w.m_tok, w.m_count, s.E,
-                       w.miss_hist, w.row_token, w.pair_row, w.tasks, w.big_tasks, w.n_tasks, max_big, (s.I + 127) / 128);
+                       w.miss_hist, w.row_token, w.pair_row, w.tasks, w.big_tasks, w.n_tasks, max_big, (s.I + 127) / 128, s.big_rows);
     return hipGetLastError();
 }
 
@@ -427,9 +431,9 @@ hipError_t launch_dispatch(const Shape& s, const LayerTables& t, const Workspace
                            const float* topk_w, int n_tokens, tide_miss* miss, int miss_cap, int32_t* n_miss,
                            hipStream_t stream, LaunchEvents ev) {
     TIDE_LAUNCH(dispatch_kernel, dim3(s.capacity + 2), dim3(kThreads), stream, ev, topk_idx, topk_w,
-                       n_tokens, s.k, s.capacity, s.n_shared, s.E, t.slot_of, t.expert_in_slot, w.hist_step, t.hits,
+                       n_tokens, s.k, s.capacity, s.n_shared, s.E, t.slot_of, t.expert_in_slot, t.expert_p12, w.hist_step, t.hits,
                        w.row_token, w.pair_row, w.slot_off, w.tasks, w.big_tasks, w.n_tasks, miss, miss_cap, n_miss, w.counters,
-                max_big_tasks_for(s, n_tokens), (s.I + 127) / 128);
+                max_big_tasks_for(s, n_tokens), (s.I + 127) / 128, s.big_rows);
     return hipGetLastError();
 }
 

@@ -17,6 +17,7 @@ struct DispatchArgs {
     int n_tokens, k, capacity, n_shared, n_experts;
     const int32_t* slot_of;
     const int32_t* expert_in_slot;
+    const uint8_t* expert_p12;     // LayerTables::expert_p12
     int32_t* row_token;
     int32_t* pair_row;
     int32_t* slot_off;
@@ -98,12 +99,14 @@ __device__ inline void dispatch_small(const DispatchArgs& a, const unsigned* s_m
         a.slot_off[s] = s_row0[s];
         const int m = s_m[s];
         const int items = (m + kRowsPerTask - 1) / kRowsPerTask;
+        const int e = s < a.capacity ? s_eis[s] : a.n_experts;
+        const int fmt_flags = (items && a.expert_p12 && e >= 0 && a.expert_p12[e]) ? kTaskP12 : 0;
         for (int c = 0; c < items; ++c) {
             Task t;
             t.slot = s;
             t.row0 = s_row0[s] + c * kRowsPerTask;
             t.nrows = min(kRowsPerTask, m - c * kRowsPerTask);
-            t.pad = 0;
+            t.flags = fmt_flags;
             a.tasks[s_task0[s] + c] = t;
         }
     }

@@ -14,6 +14,7 @@
 // are stored K chunk by K chunk, so the workgroup reads one contiguous region front to
 // back (all memory channels in turn) instead of 16 streams 128 KiB apart.  Tokens sit
 // on the MFMA's 16-wide N side.
+#include "packed12_device.h"
 #include "tide_internal.h"
 
 #include <type_traits>
@@ -29,6 +30,27 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int kWaves = 4;            // independent waves per workgroup, each streaming its own weight rows
 constexpr int kTileElems = 16 * 32;  // one packed tile
 
+// The two forms a cache slot can hold its blob in.  bf16: tiles of 1 KiB, a lane's 16 bytes are its MFMA operand as they
+// are.  12-bit (packed12.h): tile payloads of 768 bytes, 12 per lane, plus a 16-byte table per tile; the wave decodes
+// its operand in registers, so 3/4 of the bytes leave HBM for the same weights.
+constexpr int kFmtBf16 = 0, kFmtP12 = 1;
+template <int FMT>
+struct WeightFormat;
+template <>
+struct WeightFormat<kFmtBf16> {
+    typedef bf16x8 Word;                                      // what a lane keeps in the ring per tile
+    static constexpr int kTileStride = kTileElems;            // uint16 units from one tile to the next
+    static constexpr int kLaneStride = 8;                     // uint16 units from one lane's piece to the next
+    static constexpr int kPayloadOff = 0;                     // uint16 units from the blob's start to tile 0
+};
+template <>
+struct WeightFormat<kFmtP12> {
+    typedef P12Words Word;
+    static constexpr int kTileStride = kP12TileBytes / 2;
+    static constexpr int kLaneStride = 6;
+    static constexpr int kPayloadOff = kP12HeaderBytes / 2;
+};
+
 __device__ inline uint32_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
     u += 0x7FFFu + ((u >> 16) & 1u);
@@ -40,9 +62,26 @@ __device__ inline uint32_t f32_to_bf16_rne(float f) {
 // When a slot is cut into several small items (SHARED), their workgroups read the same tiles at about the same
 // time: ordinary loads let the later readers find them in L2.
 template <bool SHARED>
-__device__ inline bf16x8 load_weights(const uint16_t* p) {
-    if (SHARED) return *reinterpret_cast<const bf16x8*>(p);
-    return __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(p));
+__device__ inline void load_weights(const uint16_t* p, bf16x8& w) {
+    if (SHARED) w = *reinterpret_cast<const bf16x8*>(p);
+    else w = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(p));
+}
+template <bool SHARED>
+__device__ inline void load_weights(const uint16_t* p, P12Words& w) {       // 12 bytes, dword-aligned
+    const uint32_t* q = reinterpret_cast<const uint32_t*>(p);
+    if (SHARED) {
+        w.a0 = q[0];
+        w.a1 = q[1];
+        w.b = q[2];
+    } else {
+        w.a0 = __builtin_nontemporal_load(q);
+        w.a1 = __builtin_nontemporal_load(q + 1);
+        w.b = __builtin_nontemporal_load(q + 2);
+    }
+}
+__device__ inline bf16x8 mfma_operand(const bf16x8& w, const uint4&) { return w; }
+__device__ inline bf16x8 mfma_operand(const P12Words& w, const uint4& table) {
+    return __builtin_bit_cast(bf16x8, p12_decode(w, table));
 }
 
 __device__ inline float silu(float g) { return g / (1.f + __expf(-g)); }
@@ -62,26 +101,26 @@ __device__ inline float silu(float g) { return g / (1.f + __expf(-g)); }
 // columns at a time; the next stage's rows are already in flight while the current one is used.
 // Tokens sit on the MFMA's 16-wide N side, NT token tiles per work item.
 // Where a wave finds its weight stripes: a wave's stripes all lie in one group of the packed layout, and inside a
-// group the K chunk is the slow index, so chunk c of stripe r sits at base + stripe_offset(r) + c * cstep (+ the lane's
-// 8 elements inside the tile).  Everything here is the same for all lanes of a wave: it lives in scalar registers.
+// group the K chunk is the slow index, so chunk c of stripe r is tile  first + stripe_tile(r) + c * cstep  of the blob.
+// Everything here is the same for all lanes of a wave: it lives in scalar registers.
 struct WeightStream {
-    const uint16_t* base;     // the wave's first stripe (PASS 0: its first gate stripe), chunk 0
-    int64_t cstep;            // elements from one K chunk to the next
-    int up;                   // PASS 0: elements from a gate stripe to the matching up stripe
+    int first;                // tile index of the wave's first stripe (PASS 0: its first gate stripe), chunk 0
+    int cstep;                // tiles from one K chunk to the next
+    int up;                   // PASS 0: tiles from a gate stripe to the matching up stripe
 };
 
 template <int PASS, int RT>
-__device__ inline int64_t stripe_offset(const WeightStream& ws, int r) {
+__device__ inline int stripe_tile(const WeightStream& ws, int r) {
     constexpr int G = RT / 2;
-    if (PASS == 0 && r >= G) return (int64_t)ws.up + (r - G) * kTileElems;
-    return (int64_t)r * kTileElems;
+    if (PASS == 0 && r >= G) return ws.up + (r - G);
+    return r;
 }
 
 // wtile: the wave's tile of output features (wave-uniform).  A spare wave (columns past n_out) streams the last valid
 // wave's stripes and stores nothing: it stays in step with the barriers without a predicate around the loop.
+// tile0: the blob's first tile of this pass (gate/up: 0, down: after the gate and up matrices).
 template <int PASS, int RT>
-__device__ inline void weight_stream(const uint16_t* blob, int64_t off_w, int wtile, bool active, int K, int n_out,
-                                     WeightStream& ws) {
+__device__ inline void weight_stream(int tile0, int wtile, bool active, int K, int n_out, WeightStream& ws) {
     constexpr int G = RT / 2;                        // PASS 0: gate stripes per wave
     const int kchunks = K >> 5;
     const int wsrc = active ? wtile : (n_out / (16 * (PASS == 0 ? G : RT)) - 1);
@@ -90,25 +129,25 @@ __device__ inline void weight_stream(const uint16_t* blob, int64_t off_w, int wt
         const int first = wsrc * G;                                  // the wave's first SwiGLU column block
         const int g = first / kGateUpGroup, j0 = first % kGateUpGroup;
         const int ng = min(kGateUpGroup, n_out / 16 - g * kGateUpGroup);
-        ws.base = blob + off_w + (int64_t)g * 2 * kGateUpGroup * kchunks * kTileElems + j0 * kTileElems;
-        ws.cstep = (int64_t)2 * ng * kTileElems;
-        ws.up = ng * kTileElems;
+        ws.first = tile0 + g * 2 * kGateUpGroup * kchunks + j0;
+        ws.cstep = 2 * ng;
+        ws.up = ng;
     } else {
         static_assert(PASS == 0 || kDownGroup % RT == 0, "a wave's stripes share a group");
         const int first = wsrc * RT;
         const int g = first / kDownGroup, j0 = first % kDownGroup;
         const int ng = min(kDownGroup, n_out / 16 - g * kDownGroup);
-        ws.base = blob + off_w + (int64_t)g * kDownGroup * kchunks * kTileElems + j0 * kTileElems;
-        ws.cstep = (int64_t)ng * kTileElems;
+        ws.first = tile0 + g * kDownGroup * kchunks + j0;
+        ws.cstep = ng;
         ws.up = 0;
     }
 }
 
-template <int PASS, int RT, int NT, int D, int PC, int NBUF, bool SHARED = false>
+template <int PASS, int RT, int NT, int D, int PC, int NBUF, bool SHARED = false, int FMT = kFmtBf16>
 __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile, bool active,
                                  const Task& task, const uint16_t* __restrict__ act_in,
-                                 const int32_t* __restrict__ row_token, int K, int n_out,
-                                 uint16_t* __restrict__ act_out, float* __restrict__ y_out, uint16_t* lds) {
+                                 const int32_t* __restrict__ row_token, int K, int n_out, int64_t blob_elems,
+                                 uint16_t* __restrict__ act_out, float* __restrict__ y_out, uint16_t* lds, uint4* wave_tables) {
     static_assert(PC % D == 0 || (NBUF == 2 && D % PC == 0), "stage boundaries must fall on whole chunks of a ring turn");
     constexpr int G = RT / 2;                        // PASS 0: gate stripes per wave
     constexpr int kCols = PC * 32;                   // columns per stage
@@ -121,11 +160,32 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
     const int kchunks = K >> 5;
     const int col0 = wtile * 16 * (PASS == 0 ? G : RT);
 
+    typedef WeightFormat<FMT> Fmt;
     WeightStream ws;
-    weight_stream<PASS, RT>(blob, off_w, wtile, active, K, n_out, ws);
-    const int lane8 = lane * 8;
+    weight_stream<PASS, RT>((int)(off_w / kTileElems), wtile, active, K, n_out, ws);
+    const uint16_t* lane_base = blob + Fmt::kPayloadOff + lane * Fmt::kLaneStride;
     // chunk c of stripe r: scalar address arithmetic plus the lane's place in the tile
-    auto tile = [&](int r, int c) { return ws.base + (stripe_offset<PASS, RT>(ws, r) + c * ws.cstep) + lane8; };
+    auto tile = [&](int r, int c) {
+        return lane_base + (int64_t)(ws.first + stripe_tile<PASS, RT>(ws, r) + c * ws.cstep) * Fmt::kTileStride;
+    };
+
+    // 12-bit form: the tables of the wave's next kTableChunks chunks (64 tiles: one per lane) come through a piece of
+    // LDS that only this wave touches -- one 16-byte load per lane a block ahead, one store at the block's start, and
+    // a broadcast read per tile when it is decoded.  A wave's LDS accesses complete in order: no barrier is needed.
+    constexpr int kTableChunks = 64 / RT;
+    static_assert(FMT == kFmtBf16 || (kTableChunks % D == 0 && D <= kTableChunks), "table blocks start on whole ring turns");
+    const uint8_t* table0 = reinterpret_cast<const uint8_t*>(blob) + kP12HeaderBytes + (blob_elems / kTileElems) * kP12TileBytes;
+    uint4 next_tables;
+    auto fetch_tables = [&](int block) {
+        const int c = min(block * kTableChunks + lane / RT, kchunks - 1), r = lane % RT;
+        const int t = ws.first + ((PASS == 0 && r >= G) ? ws.up + (r - G) : r) + c * ws.cstep;
+        next_tables = *reinterpret_cast<const uint4*>(table0 + (int64_t)t * kP12TableBytes);
+    };
+    auto table_block = [&](int block) {               // at the first chunk of a block
+        wave_tables[lane] = next_tables;
+        fetch_tables(block + 1);
+    };
+    if (FMT == kFmtP12) fetch_tables(0);
 
     // staging map: piece q = tid + 256*j covers row q / kPPR of the item, columns (q % kPPR)*8 .. +7 of the
     // stage; kPPR divides 256, so a thread's pieces all sit at the same columns
@@ -164,12 +224,12 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
     }
 
     // ring prologue (chunk indices past the end are clamped: a redundant in-bounds load, never used)
-    bf16x8 a[D][RT];
+    typename Fmt::Word a[D][RT];
 #pragma unroll
     for (int i = 0; i < D; ++i) {
         const int ci = min(i, kchunks - 1);
 #pragma unroll
-        for (int r = 0; r < RT; ++r) a[i][r] = load_weights<SHARED>(tile(r, ci));
+        for (int r = 0; r < RT; ++r) load_weights<SHARED>(tile(r, ci), a[i][r]);
     }
     f32x4 acc[RT][NT];
 #pragma unroll
@@ -185,17 +245,23 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
         for (int t = 0; t < decltype(cnt)::value; ++t)
             b[t] = *reinterpret_cast<const bf16x8*>(frag + (NBUF == 2 ? ((c / PC) & 1) * kBufElems : 0) + (t0 + t) * 16 * kRowElems + (c % PC) * 32);
     };
-    auto mfmas = [&](const bf16x8* b, int i, int t0, auto cnt) {
+    // chunk c (ring slot i) against token tiles t0 ..: a stripe's operand is the ring's word as it is, or is decoded
+    // with the tile's table right before the stripe's MFMAs (the decode of the next stripe runs under them)
+    auto mfmas = [&](const bf16x8* b, int c, int i, int t0, auto cnt) {
 #pragma unroll
-        for (int r = 0; r < RT; ++r)
+        for (int r = 0; r < RT; ++r) {
+            uint4 table{};
+            if (FMT == kFmtP12) table = wave_tables[(c % kTableChunks) * RT + r];
+            const bf16x8 w = mfma_operand(a[i][r], table);
 #pragma unroll
             for (int t = 0; t < decltype(cnt)::value; ++t)
-                acc[r][t0 + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][r], b[t], acc[r][t0 + t], 0, 0, 0);
+                acc[r][t0 + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, b[t], acc[r][t0 + t], 0, 0, 0);
+        }
     };
     auto refill = [&](int c, int i) {
         const int cn = min(c + D, kchunks - 1);
 #pragma unroll
-        for (int r = 0; r < RT; ++r) a[i][r] = load_weights<SHARED>(tile(r, cn));
+        for (int r = 0; r < RT; ++r) load_weights<SHARED>(tile(r, cn), a[i][r]);
     };
     using all_tiles = std::integral_constant<int, NT>;
 
@@ -211,17 +277,19 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
         auto chunk = [&](int c, int i) {
             bf16x8 b[NT];
             read_frags(b, c, 0, all_tiles{});
-            mfmas(b, i, 0, all_tiles{});
+            mfmas(b, c, i, 0, all_tiles{});
             refill(c, i);
         };
         // the main loop is straight-line (no per-chunk predicates): whole turns of the ring
         int base = 0;
         for (; base + D <= kchunks; base += D) {
+            if (FMT == kFmtP12 && base % kTableChunks == 0) table_block(base / kTableChunks);
             if (base % PC == 0) stage_switch(base);
 #pragma unroll
             for (int i = 0; i < D; ++i) chunk(base + i, i);
         }
         if (base < kchunks) {                        // a last partial turn (K not a multiple of 32*D)
+            if (FMT == kFmtP12 && base % kTableChunks == 0) table_block(base / kTableChunks);
             if (base % PC == 0) stage_switch(base);
 #pragma unroll
             for (int i = 0; i < D; ++i)
@@ -262,17 +330,19 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
                     read_frags(b[q ^ 1], c, NTH, half_tiles{});
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                mfmas(b[q], i, h * NTH, half_tiles{});
+                mfmas(b[q], c, i, h * NTH, half_tiles{});
                 if (h == NH - 1) refill(c, i);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
         int base = 0;
         for (; base + D <= kchunks; base += D) {
+            if (FMT == kFmtP12 && base % kTableChunks == 0) table_block(base / kTableChunks);
 #pragma unroll
             for (int i = 0; i < D; ++i) chunk(base + i, i);
         }
         if (base < kchunks) {
+            if (FMT == kFmtP12 && base % kTableChunks == 0) table_block(base / kTableChunks);
 #pragma unroll
             for (int i = 0; i < D; ++i)
                 if (base + i < kchunks) chunk(base + i, i);
@@ -324,23 +394,27 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
     constexpr int RT = PASS == 0 ? kSmallRT0 : kSmallRT1;
     constexpr int D = PASS == 0 ? kSmallD0 : kSmallD1;
     __shared__ __attribute__((aligned(16))) uint16_t lds[kRowsPerTask * (kSmallPC * 32 + 8)];
+    __shared__ uint4 tables[kWaves][64];               // 12-bit slots: each wave's tile tables
     const int task_id = blockIdx.y;
     if (task_id >= n_tasks[0]) return;
-    const int wtile = blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // the same for a wave's lanes: scalar
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // the same for a wave's lanes: scalar
+    const int wtile = blockIdx.x * kWaves + wave;
     const bool active = wtile * 16 * (PASS == 0 ? RT / 2 : RT) < n_out;      // spare waves still help staging
     const Task task = tasks[task_id];
     const uint16_t* blob = slots + (int64_t)task.slot * blob_elems;
     static_assert(kRowsPerTask == 32, "one or two 16-token tiles per small work item");
-    if (task.pad) {                       // sibling items of one slot: cacheable weight loads
-        if (task.nrows <= 16)
-            gemm_task<PASS, RT, 1, D, kSmallPC, 1, true>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
-        else
-            gemm_task<PASS, RT, 2, D, kSmallPC, 1, true>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
-    } else if (task.nrows <= 16) {
-        gemm_task<PASS, RT, 1, D, kSmallPC, 1>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
-    } else {
-        gemm_task<PASS, RT, 2, D, kSmallPC, 1>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, act_out, y_out, lds);
+    // sibling items of one slot (kTaskSiblings) use cacheable weight loads; up to 16 rows take one token tile
+#define TIDE_SMALL_CASE(NT_, SIB_, FMT_)                                                                                 \
+    gemm_task<PASS, RT, NT_, D, kSmallPC, 1, SIB_, FMT_>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, \
+                                                        blob_elems, act_out, y_out, lds, tables[wave])
+    const bool one = task.nrows <= 16;
+    switch (task.flags & (kTaskSiblings | kTaskP12)) {
+        case 0: if (one) TIDE_SMALL_CASE(1, false, kFmtBf16); else TIDE_SMALL_CASE(2, false, kFmtBf16); break;
+        case kTaskSiblings: if (one) TIDE_SMALL_CASE(1, true, kFmtBf16); else TIDE_SMALL_CASE(2, true, kFmtBf16); break;
+        case kTaskP12: if (one) TIDE_SMALL_CASE(1, false, kFmtP12); else TIDE_SMALL_CASE(2, false, kFmtP12); break;
+        default: if (one) TIDE_SMALL_CASE(1, true, kFmtP12); else TIDE_SMALL_CASE(2, true, kFmtP12); break;
     }
+#undef TIDE_SMALL_CASE
 }
 
 // Large work items: up to 256 rows of a slot that holds more than 32.  A workgroup's tile is 256
@@ -352,6 +426,7 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
 // 1-3 % slower in the step.
 constexpr int kBigPC = 8, kBigD = 4;       // <= 8 token tiles
 constexpr int kWidePC = 4, kWideD = 4;     // 9..16 token tiles
+constexpr int kBigPC12 = 4, kWidePC12 = 2; // the stages over a 12-bit slot (<= 8, 9..12 token tiles)
 constexpr int kBigLdsElems = 2 * 128 * (kBigPC * 32 + 8) > 2 * 256 * (kWidePC * 32 + 8) ? 2 * 128 * (kBigPC * 32 + 8)
                                                                                       : 2 * 256 * (kWidePC * 32 + 8);
 constexpr int kXcds = 8;           // accelerator complex dies, each with its own L2
@@ -402,11 +477,13 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_big_kernel(
     float* __restrict__ y_out, int n_ftiles) {
     constexpr int RT = 4;
     __shared__ __attribute__((aligned(16))) uint16_t lds[kBigLdsElems];
+    __shared__ uint4 tables[kWaves][64];               // 12-bit slots: each wave's tile tables
     const int n_big = n_tasks[1];
     const int xcd = blockIdx.x % kXcds, unit = blockIdx.x / kXcds;
     if (unit >= list_tasks(xcd, n_big) * n_ftiles) return;
     const int task_id = order[list_rank(xcd, unit / n_ftiles)];
-    const int wtile = (unit % n_ftiles) * kWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // scalar, as above
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // scalar, as above
+    const int wtile = (unit % n_ftiles) * kWaves + wave;
     const bool active = wtile * 16 * (PASS == 0 ? RT / 2 : RT) < n_out;
     const Task task = tasks[task_id];
     const uint16_t* blob = slots + (int64_t)task.slot * blob_elems;
@@ -414,22 +491,38 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_big_kernel(
     // only as many 16-token tiles as the item has rows: a 40-row item costs 3/8 of a 128-row one
 #define TIDE_BIG_CASE(NT_)                                                                                              \
     case NT_:                                                                                                           \
-        gemm_task<PASS, RT, NT_, kBigD, kBigPC, 2>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, \
-                                                   act_out, y_out, lds);                                               \
+        gemm_task<PASS, RT, NT_, kBigD, BPC, 2, false, FMT>(blob, off_w, wtile, active, task, act_in, row_token, K,      \
+                                                            n_out, blob_elems, act_out, y_out, lds, tables[wave]);     \
         break;
 #define TIDE_WIDE_CASE(NT_)                                                                                             \
     case NT_ - 1:                                                                                                       \
     case NT_:                                                                                                           \
-        gemm_task<PASS, RT, NT_, kWideD, kWidePC, 2>(blob, off_w, wtile, active, task, act_in, row_token, K,    \
-                                                     n_out, act_out, y_out, lds);                                      \
+        gemm_task<PASS, RT, NT_, kWideD, WPC, 2, false, FMT>(blob, off_w, wtile, active, task, act_in, row_token, K,     \
+                                                             n_out, blob_elems, act_out, y_out, lds, tables[wave]);    \
         break;
-    switch ((task.nrows + 15) >> 4) {
-        TIDE_BIG_CASE(1) TIDE_BIG_CASE(2) TIDE_BIG_CASE(3) TIDE_BIG_CASE(4) TIDE_BIG_CASE(5) TIDE_BIG_CASE(6) TIDE_BIG_CASE(7)
-        TIDE_BIG_CASE(8) TIDE_WIDE_CASE(10) TIDE_WIDE_CASE(12) TIDE_WIDE_CASE(14)
-        default:
-            gemm_task<PASS, RT, 16, kWideD, kWidePC, 2>(blob, off_w, wtile, active, task, act_in, row_token, K,
-                                                        n_out, act_out, y_out, lds);
-    }
+    auto run = [&](auto fmt) {
+        constexpr int FMT = decltype(fmt)::value;
+        // 12-bit slots: the decode's registers come out of the token staging (stages half as wide), and a work item
+        // has at most kRowsPerBigTaskP12 rows
+        constexpr int BPC = FMT == kFmtP12 ? kBigPC12 : kBigPC;
+        constexpr int WPC = FMT == kFmtP12 ? kWidePC12 : kWidePC;
+        static_assert(kRowsPerBigTaskP12 == 192, "twelve 16-token tiles per large work item over a 12-bit slot");
+        switch ((task.nrows + 15) >> 4) {
+            TIDE_BIG_CASE(1) TIDE_BIG_CASE(2) TIDE_BIG_CASE(3) TIDE_BIG_CASE(4) TIDE_BIG_CASE(5) TIDE_BIG_CASE(6) TIDE_BIG_CASE(7)
+            TIDE_BIG_CASE(8) TIDE_WIDE_CASE(10) TIDE_WIDE_CASE(12)
+            default:
+                if constexpr (FMT == kFmtBf16) {
+                    if (task.nrows <= 14 * 16)
+                        gemm_task<PASS, RT, 14, kWideD, WPC, 2, false, FMT>(blob, off_w, wtile, active, task, act_in, row_token, K,
+                                                                            n_out, blob_elems, act_out, y_out, lds, tables[wave]);
+                    else
+                        gemm_task<PASS, RT, 16, kWideD, WPC, 2, false, FMT>(blob, off_w, wtile, active, task, act_in, row_token, K,
+                                                                            n_out, blob_elems, act_out, y_out, lds, tables[wave]);
+                }
+        }
+    };
+    if (task.flags & kTaskP12) run(std::integral_constant<int, kFmtP12>{});
+    else run(std::integral_constant<int, kFmtBf16>{});
 #undef TIDE_BIG_CASE
 #undef TIDE_WIDE_CASE
 }

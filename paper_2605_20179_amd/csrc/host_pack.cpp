@@ -62,45 +62,52 @@ void compress_expert_blob(uint64_t blob_bytes, const uint16_t* src, uint8_t* out
     P12Header* h = reinterpret_cast<P12Header*>(out);
     h->magic = kP12Magic;
     h->n_tiles = n_tiles;
-    uint32_t* exc_idx = reinterpret_cast<uint32_t*>(out + lay.off_exc_idx);
-    uint16_t* exc_val = reinterpret_cast<uint16_t*>(out + lay.off_exc_val);
-    uint32_t n_exc = 0;
-    for (uint32_t t = 0; t < n_tiles && !h->raw; ++t) {
+    for (uint32_t t = 0; t < n_tiles; ++t) {
         const uint16_t* tile = src + (uint64_t)t * 512;
-        // base: the top of the 16-binade window that holds the most elements of the tile (the highest such window)
-        uint32_t hist[256 + 16] = {0};
-        for (int i = 0; i < 512; ++i) hist[(tile[i] >> 7) & 0xff]++;
-        uint32_t base = 15, in_window = 0, best = 0;
-        for (uint32_t e = 0; e < 16; ++e) in_window += hist[e];
-        best = in_window;
-        for (uint32_t top = 16; top < 256; ++top) {
-            in_window += hist[top] - hist[top - 16];
-            if (in_window >= best) { best = in_window; base = top; }
-        }
-        out[lay.off_base + t] = (uint8_t)base;
+        // the tile's table: its distinct high bytes in ascending order
+        bool seen[256] = {false};
+        for (int i = 0; i < 512; ++i) seen[tile[i] >> 8] = true;
+        uint8_t code_of[256];
+        uint8_t* table = out + lay.off_table + (uint64_t)t * kP12TableBytes;
+        int n = 0;
+        for (int v = 0; v < 256; ++v)
+            if (seen[v]) {
+                if (n == 16) {                 // a 17th high byte: this blob stays in its bf16 form
+                    memset(out + lay.off_payload, 0, lay.bytes - lay.off_payload);
+                    h->raw = 1;
+                    return;
+                }
+                code_of[v] = (uint8_t)n;
+                table[n++] = (uint8_t)v;
+            }
         uint32_t* words = reinterpret_cast<uint32_t*>(out + lay.off_payload + (uint64_t)t * kP12TileBytes);
         for (int l = 0; l < 64; ++l) {
-            uint32_t code[8];
+            uint32_t a[2] = {0, 0}, b = 0;
             for (int j = 0; j < 8; ++j) {
-                const uint32_t v = tile[l * 8 + j], e = (v >> 7) & 0xff;
-                uint32_t delta = base - e;             // wraps for an exponent above the window
-                if (delta > 15) {                      // outside the tile's 16-binade window: listed
-                    if (n_exc == n_tiles) { h->raw = 1; break; }
-                    exc_idx[n_exc] = t * 512 + l * 8 + j;
-                    exc_val[n_exc++] = (uint16_t)v;
-                    delta = 15;
-                }
-                code[j] = ((v >> 15) << 11) | (delta << 7) | (v & 0x7f);
+                const uint32_t v = tile[l * 8 + j];
+                a[j >> 2] |= (v & 0xffu) << (8 * (j & 3));
+                b |= (uint32_t)code_of[v >> 8] << (8 * (j & 3) + (j < 4 ? 0 : 4));
             }
-            if (h->raw) break;
-            words[l * 3 + 0] = code[0] | (code[1] << 12) | ((code[2] & 0xff) << 24);
-            words[l * 3 + 1] = (code[2] >> 8) | (code[3] << 4) | (code[4] << 16) | ((code[5] & 0xf) << 28);
-            words[l * 3 + 2] = (code[5] >> 4) | (code[6] << 8) | (code[7] << 20);
+            words[l * 3 + 0] = a[0];
+            words[l * 3 + 1] = a[1];
+            words[l * 3 + 2] = b;
         }
     }
-    h->n_exc = h->raw ? 0 : n_exc;
 }
 
-
+bool decompress_expert_blob(uint64_t blob_bytes, const uint8_t* comp, uint16_t* blob) {
+    const uint32_t n_tiles = (uint32_t)(blob_bytes / 1024);
+    const P12Layout lay = p12_layout(n_tiles);
+    const P12Header* h = reinterpret_cast<const P12Header*>(comp);
+    if (h->magic != kP12Magic || h->n_tiles != n_tiles || h->raw) return false;
+    for (uint32_t t = 0; t < n_tiles; ++t) {
+        const uint32_t* words = reinterpret_cast<const uint32_t*>(comp + lay.off_payload + (uint64_t)t * kP12TileBytes);
+        const uint8_t* table = comp + lay.off_table + (uint64_t)t * kP12TableBytes;
+        for (int l = 0; l < 64; ++l)
+            for (int j = 0; j < 8; ++j)
+                blob[(uint64_t)t * 512 + l * 8 + j] = p12_element(words[l * 3], words[l * 3 + 1], words[l * 3 + 2], table, j);
+    }
+    return true;
+}
 
 }  // namespace tide

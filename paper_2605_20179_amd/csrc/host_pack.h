@@ -11,4 +11,7 @@ void pack_expert_blob(int d, int d_ff, const uint16_t* wg, const uint16_t* wu, c
 // packed blob (blob_bytes, a multiple of 1024) -> its 12-bit form (packed12.h), p12_layout(blob_bytes / 1024).bytes long.
 void compress_expert_blob(uint64_t blob_bytes, const uint16_t* src, uint8_t* out);
 
+// the inverse: false (blob untouched) when `comp` is not a compressed blob of that size or is marked raw
+bool decompress_expert_blob(uint64_t blob_bytes, const uint8_t* comp, uint16_t* blob);
+
 }  // namespace tide

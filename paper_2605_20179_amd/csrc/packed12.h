@@ -1,17 +1,22 @@
-// Lossless 12-bit form of a packed expert blob, used only as the source of refresh copies: the bytes that
-// cross the host link shrink to 3/4, the copy kernel rebuilds the bf16 values bit for bit in the cache slot.
+// Lossless 12-bit form of a packed expert blob: 3/4 of the bytes (plus 16 per tile), every bf16 rebuilt bit for
+// bit.  It is what crosses the host link in a refresh copy and, when the context keeps its cache slots in this
+// form, what the expert GEMMs stream from HBM and decode in registers.
 //
-// A bf16 is sign(1) exponent(8) mantissa(7).  Inside one 16 x 32 tile of trained or Gaussian weights the
-// exponents span few binades, so a tile stores one exponent (base: the top of the 16-binade window that holds
-// most of its elements) and every element as sign(1) | base - exponent (4) | mantissa(7) = 12 bits.  The rare
-// element outside the window (a zero, a denormal, an outlier) goes to a per-expert exception list that is
-// applied after the tile decode.  Plain C++: included by the host-side encoder and by the device decoder.
+// A bf16 is sign(1) exponent(8) mantissa(7): its low byte is the exponent's last bit and the mantissa, its high
+// byte the sign and the upper seven exponent bits.  Inside one 16 x 32 tile of trained or Gaussian weights the
+// low bytes look random, but the high bytes take few distinct values (both signs of five to seven pairs of
+// binades).  A tile therefore stores the low byte of every element as it is, a table of up to 16 high bytes, and
+// per element a 4-bit index into that table.  A tile with more than 16 distinct high bytes cannot be encoded:
+// the whole blob is then marked raw and used in its bf16 form (Gaussian weights: a few tiles in a million).
 //
-//   [0, 64)                    header: magic, n_tiles, n_exceptions, raw (1 = not encoded: copy the raw blob)
-//   [64, 64 + pad64(T))        base exponent of each tile, one byte
-//   then T x 768 bytes         tile payloads: lane l's 8 elements are 3 dwords at byte 12 l
-//   then T x 4 bytes           exception element indices (uint32; capacity T entries)
-//   then T x 2 bytes           exception values (bf16 bits)
+//   [0, 64)                    header: magic, n_tiles, raw (1 = not encoded: use the bf16 blob)
+//   [64, 64 + 768 T)           tile payloads in tile order.  Lane l (the 8 consecutive elements 8l .. 8l+7 of the
+//                              tile) owns the 3 dwords at byte 12 l:
+//                                a0: low bytes of elements 0..3          a1: low bytes of elements 4..7
+//                                b : byte j = index of element j | index of element 4+j << 4
+//   then 16 T bytes            tables: 16 high bytes per tile, unused entries zero
+//
+// Plain C++: included by the host-side encoder / decoder and by the device code.
 #pragma once
 #include <stdint.h>
 
@@ -19,24 +24,31 @@ namespace tide {
 
 constexpr uint32_t kP12Magic = 0x32315054u;      // "TP12"
 constexpr int kP12TileBytes = 768;
+constexpr int kP12TableBytes = 16;
+constexpr int kP12HeaderBytes = 64;
 
 struct P12Header {
-    uint32_t magic, n_tiles, n_exc, raw;
-    uint32_t pad[12];
+    uint32_t magic, n_tiles, raw;
+    uint32_t pad[13];
 };
-static_assert(sizeof(P12Header) == 64, "header is one 64-byte line");
+static_assert(sizeof(P12Header) == kP12HeaderBytes, "header is one 64-byte line");
 
 struct P12Layout {
-    uint64_t off_base, off_payload, off_exc_idx, off_exc_val, bytes;
+    uint64_t off_payload, off_table, bytes;
 };
 constexpr P12Layout p12_layout(uint64_t n_tiles) {        // constexpr: callable from host and device code alike
     P12Layout l{};
-    l.off_base = 64;
-    l.off_payload = l.off_base + (n_tiles + 63) / 64 * 64;
-    l.off_exc_idx = l.off_payload + n_tiles * kP12TileBytes;
-    l.off_exc_val = l.off_exc_idx + n_tiles * 4;
-    l.bytes = (l.off_exc_val + n_tiles * 2 + 63) / 64 * 64;
+    l.off_payload = kP12HeaderBytes;
+    l.off_table = l.off_payload + n_tiles * kP12TileBytes;                  // 768 = 12 x 64: still 64-byte aligned
+    l.bytes = (l.off_table + n_tiles * kP12TableBytes + 63) / 64 * 64;
     return l;
+}
+
+// element j (0..7) of a lane from the lane's three dwords and the tile's table
+inline uint16_t p12_element(uint32_t a0, uint32_t a1, uint32_t b, const uint8_t* table, int j) {
+    const uint32_t low = ((j < 4 ? a0 : a1) >> (8 * (j & 3))) & 0xffu;
+    const uint32_t code = (b >> (8 * (j & 3) + (j < 4 ? 0 : 4))) & 0xfu;
+    return (uint16_t)(low | ((uint32_t)table[code] << 8));
 }
 
 }  // namespace tide

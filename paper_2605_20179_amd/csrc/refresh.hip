@@ -1,7 +1,7 @@
 // Refresh step: the resident set becomes the current top-B experts by hit count
 // (Alg. 1 refresh step: most-hit CPU experts in, least-hit GPU experts out; Sec. 3.3).
 // One workgroup, one expert per thread, all-pairs ranking (E <= 512).
-#include "packed12.h"
+#include "packed12_device.h"
 #include "tide_internal.h"
 
 namespace tide {
@@ -124,56 +124,42 @@ namespace {
 // unit that hosts one serves the step kernels' own loads slowly while the copy lasts (its vector memory
 // pipeline is full of host-link reads).  Each thread keeps four 16-byte reads in flight.
 constexpr int kCopyBlocks = 16, kCopyThreads = 256;
+// n16 16-byte pieces from src to dst, spread over the launch; each thread keeps four reads in flight
+__device__ inline void copy_blob(const uint8_t* src_bytes, uint8_t* dst_bytes, uint64_t n16) {
+    const uint4* src = reinterpret_cast<const uint4*>(src_bytes);
+    uint4* dst = reinterpret_cast<uint4*>(dst_bytes);
+    const uint64_t stride = (uint64_t)gridDim.x * kCopyThreads;
+    uint64_t q = (uint64_t)blockIdx.x * kCopyThreads + threadIdx.x;
+    for (; q + 3 * stride < n16; q += 4 * stride) {
+        const uint4 a = src[q], b = src[q + stride], c = src[q + 2 * stride], d = src[q + 3 * stride];
+        dst[q] = a;
+        dst[q + stride] = b;
+        dst[q + 2 * stride] = c;
+        dst[q + 3 * stride] = d;
+    }
+    for (; q < n16; q += stride) dst[q] = src[q];
+}
+
 __global__ __launch_bounds__(kCopyThreads) void refresh_copy_kernel(const uint8_t* __restrict__ host_blobs, uint64_t host_stride,
                                                                    uint64_t blob_bytes, uint8_t* __restrict__ dst_base,
                                                                    const RefreshOut* __restrict__ plan, int n, int dst_by_rank) {
-    const uint64_t per_blob = blob_bytes / 16;
-    const uint64_t stride = (uint64_t)gridDim.x * kCopyThreads;
     if (n < 0) n = plan->n_copies;             // queued without the host knowing the plan
-    for (int i = 0; i < n; ++i) {
-        const uint4* src = reinterpret_cast<const uint4*>(host_blobs + (uint64_t)plan->expert[i] * host_stride);
-        uint4* dst = reinterpret_cast<uint4*>(dst_base + (uint64_t)(dst_by_rank ? i : plan->slot[i]) * blob_bytes);
-        uint64_t q = (uint64_t)blockIdx.x * kCopyThreads + threadIdx.x;
-        for (; q + 3 * stride < per_blob; q += 4 * stride) {
-            const uint4 a = src[q], b = src[q + stride], c = src[q + 2 * stride], d = src[q + 3 * stride];
-            dst[q] = a;
-            dst[q + stride] = b;
-            dst[q + 2 * stride] = c;
-            dst[q + 3 * stride] = d;
-        }
-        for (; q < per_blob; q += stride) dst[q] = src[q];
-    }
+    for (int i = 0; i < n; ++i)
+        copy_blob(host_blobs + (uint64_t)plan->expert[i] * host_stride,
+                  dst_base + (uint64_t)(dst_by_rank ? i : plan->slot[i]) * blob_bytes, blob_bytes / 16);
 }
 
-// The same copies from the 12-bit form of the blobs (packed12.h): 3/4 of the bytes cross the host link.  A wave
-// decodes one tile per turn -- lane l reads 3 dwords at byte 12 l of the tile's payload and writes its 8 bf16
-// (16 bytes) -- and keeps six tiles in flight.  An expert whose header says "raw" is copied from the raw blob.
+// The same copies from the 12-bit form of the blobs (packed12.h): 3/4 of the bytes cross the host link.
+//   verbatim: the slots keep the 12-bit form (the expert GEMMs decode it): the compressed blob is copied as it is.
+//   else:     a wave decodes one tile per turn -- lane l reads its 3 dwords at byte 12 l of the tile's payload and the
+//             tile's 16-byte table, and writes its 8 bf16 (16 bytes) -- and keeps six tiles in flight.
+// An expert whose header says "raw" is copied from the raw blob either way.
 constexpr int kP12InFlight = 6;      // tiles a wave has in flight: 72 bytes per lane, as many as the raw copy's 64
-struct P12Words { uint32_t a, b, c; };
-__device__ inline uint4 p12_decode(P12Words w, uint32_t base) {
-    uint32_t code[8];
-    code[0] = w.a & 0xfff;
-    code[1] = (w.a >> 12) & 0xfff;
-    code[2] = (w.a >> 24) | ((w.b & 0xf) << 8);
-    code[3] = (w.b >> 4) & 0xfff;
-    code[4] = (w.b >> 16) & 0xfff;
-    code[5] = (w.b >> 28) | ((w.c & 0xff) << 4);
-    code[6] = (w.c >> 8) & 0xfff;
-    code[7] = w.c >> 20;
-    uint32_t v[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t delta = (code[j] >> 7) & 15;
-        const uint32_t e = base >= delta ? base - delta : 0;                  // an exception's place holder may undershoot
-        v[j] = ((code[j] >> 11) << 15) | (e << 7) | (code[j] & 0x7f);
-    }
-    return make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
-}
-
 __global__ __launch_bounds__(kCopyThreads) void refresh_copy_p12_kernel(const uint8_t* __restrict__ comp_blobs, uint64_t comp_stride,
                                                                        const uint8_t* __restrict__ host_blobs, uint64_t host_stride,
                                                                        uint64_t blob_bytes, uint8_t* __restrict__ dst_base,
-                                                                       const RefreshOut* __restrict__ plan, int n, int dst_by_rank) {
+                                                                       const RefreshOut* __restrict__ plan, int n, int dst_by_rank,
+                                                                       int verbatim) {
     const int lane = threadIdx.x & 63;
     const uint32_t wave = (blockIdx.x * kCopyThreads + threadIdx.x) >> 6, n_waves = gridDim.x * (kCopyThreads / 64);
     const uint32_t n_tiles = (uint32_t)(blob_bytes / 1024);
@@ -183,51 +169,32 @@ __global__ __launch_bounds__(kCopyThreads) void refresh_copy_p12_kernel(const ui
         const uint8_t* comp = comp_blobs + (uint64_t)plan->expert[i] * comp_stride;
         uint8_t* dst = dst_base + (uint64_t)(dst_by_rank ? i : plan->slot[i]) * blob_bytes;
         if (reinterpret_cast<const P12Header*>(comp)->raw) {
-            const uint4* src = reinterpret_cast<const uint4*>(host_blobs + (uint64_t)plan->expert[i] * host_stride);
-            const uint64_t stride = (uint64_t)gridDim.x * kCopyThreads;
-            for (uint64_t q = (uint64_t)blockIdx.x * kCopyThreads + threadIdx.x; q < blob_bytes / 16; q += stride)
-                reinterpret_cast<uint4*>(dst)[q] = src[q];
+            copy_blob(host_blobs + (uint64_t)plan->expert[i] * host_stride, dst, blob_bytes / 16);
             continue;
         }
-        const uint8_t* base = comp + lay.off_base;
+        if (verbatim) {
+            copy_blob(comp, dst, lay.bytes / 16);
+            continue;
+        }
+        const uint8_t* table = comp + lay.off_table;
         const uint8_t* payload = comp + lay.off_payload + lane * 12;
         uint32_t t = wave;
         for (; t + (kP12InFlight - 1) * n_waves < n_tiles; t += kP12InFlight * n_waves) {
             P12Words w[kP12InFlight];
-            uint32_t b[kP12InFlight];
+            uint4 tab[kP12InFlight];
 #pragma unroll
             for (int u = 0; u < kP12InFlight; ++u) {
                 w[u] = *reinterpret_cast<const P12Words*>(payload + (uint64_t)(t + u * n_waves) * kP12TileBytes);
-                b[u] = base[t + u * n_waves];
+                tab[u] = *reinterpret_cast<const uint4*>(table + (uint64_t)(t + u * n_waves) * kP12TableBytes);
             }
 #pragma unroll
             for (int u = 0; u < kP12InFlight; ++u)
-                *reinterpret_cast<uint4*>(dst + (uint64_t)(t + u * n_waves) * 1024 + lane * 16) = p12_decode(w[u], b[u]);
+                *reinterpret_cast<uint4*>(dst + (uint64_t)(t + u * n_waves) * 1024 + lane * 16) = p12_decode(w[u], tab[u]);
         }
         for (; t < n_tiles; t += n_waves)
             *reinterpret_cast<uint4*>(dst + (uint64_t)t * 1024 + lane * 16) =
-                p12_decode(*reinterpret_cast<const P12Words*>(payload + (uint64_t)t * kP12TileBytes), base[t]);
-    }
-}
-
-// After the tile decode: the listed exceptions of each copied expert, element by element.  grid = n plan entries.
-__global__ __launch_bounds__(256) void refresh_patch_p12_kernel(const uint8_t* __restrict__ comp_blobs, uint64_t comp_stride,
-                                                                uint64_t blob_bytes, uint8_t* __restrict__ dst_base,
-                                                                const RefreshOut* __restrict__ plan, int dst_by_rank) {
-    const int i = blockIdx.x;
-    if (i >= plan->n_copies) return;
-    const uint8_t* comp = comp_blobs + (uint64_t)plan->expert[i] * comp_stride;
-    const P12Header* h = reinterpret_cast<const P12Header*>(comp);
-    if (h->raw) return;
-    const uint32_t n_tiles = (uint32_t)(blob_bytes / 1024);
-    const P12Layout lay = p12_layout(n_tiles);
-    const uint32_t n_exc = min(h->n_exc, n_tiles);
-    const uint32_t* idx = reinterpret_cast<const uint32_t*>(comp + lay.off_exc_idx);
-    const uint16_t* val = reinterpret_cast<const uint16_t*>(comp + lay.off_exc_val);
-    uint16_t* dst = reinterpret_cast<uint16_t*>(dst_base + (uint64_t)(dst_by_rank ? i : plan->slot[i]) * blob_bytes);
-    for (uint32_t j = threadIdx.x; j < n_exc; j += 256) {
-        const uint32_t at = idx[j];
-        if (at < blob_bytes / 2) dst[at] = val[j];
+                p12_decode(*reinterpret_cast<const P12Words*>(payload + (uint64_t)t * kP12TileBytes),
+                           *reinterpret_cast<const uint4*>(table + (uint64_t)t * kP12TableBytes));
     }
 }
 
@@ -287,13 +254,11 @@ hipError_t launch_refresh_copies(const uint8_t* host_blobs, uint64_t host_stride
 
 hipError_t launch_refresh_copies_p12(const uint8_t* comp_blobs, uint64_t comp_stride, const uint8_t* host_blobs,
                                      uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base, const RefreshOut* plan, int n,
-                                     int max_n, bool dst_by_rank, hipStream_t stream) {
+                                     bool dst_by_rank, bool verbatim, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     if (hipError_t rc = reserve_lds(refresh_copy_p12_kernel); rc != hipSuccess) return rc;
     hipLaunchKernelGGL(refresh_copy_p12_kernel, dim3(kCopyBlocks), dim3(kCopyThreads), kCopyLdsReserve, stream, comp_blobs, comp_stride,
-                       host_blobs, host_stride, blob_bytes, dst_base, plan, n, dst_by_rank ? 1 : 0);
-    hipLaunchKernelGGL(refresh_patch_p12_kernel, dim3(n < 0 ? max_n : n), dim3(256), 0, stream, comp_blobs, comp_stride, blob_bytes, dst_base,
-                       plan, dst_by_rank ? 1 : 0);
+                       host_blobs, host_stride, blob_bytes, dst_base, plan, n, dst_by_rank ? 1 : 0, verbatim ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -577,7 +577,7 @@ hipError_t launch_route_small(const Shape& s, const LayerTables& t, const Worksp
     const int e_pad = (s.E + 15) / 16 * 16;
     DispatchArgs da;
     da.n_tokens = n_tokens; da.k = s.k; da.capacity = s.capacity; da.n_shared = s.n_shared; da.n_experts = s.E;
-    da.slot_of = t.slot_of; da.expert_in_slot = t.expert_in_slot; da.row_token = w.row_token; da.pair_row = w.pair_row;
+    da.slot_of = t.slot_of; da.expert_in_slot = t.expert_in_slot; da.expert_p12 = t.expert_p12; da.row_token = w.row_token; da.pair_row = w.pair_row;
     da.slot_off = w.slot_off; da.tasks = w.tasks; da.n_tasks = w.n_tasks; da.miss = miss; da.miss_cap = miss_cap;
     da.n_miss = n_miss; da.counters = w.counters;
     if (s.E <= 256)

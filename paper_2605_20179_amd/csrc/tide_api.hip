@@ -57,8 +57,9 @@ struct Layer {
     uint16_t* slots_owned = nullptr;     // capacity+1 blobs
     const uint8_t* host_blobs = nullptr;
     uint64_t host_stride = 0;
-    const uint8_t* comp_blobs = nullptr;  // optional 12-bit form of the same blobs: the source of refresh copies
+    const uint8_t* comp_blobs = nullptr;  // 12-bit form of the same blobs: the source of refresh copies (optional for bf16 slots)
     uint64_t comp_stride = 0;
+    uint8_t* expert_p12 = nullptr;        // device, [E + 1], 12-bit slots only: LayerTables::expert_p12
     bool shared_set = false;
     bool placed = false;
     hipEvent_t copies_begin = nullptr, copies_done = nullptr;
@@ -199,6 +200,7 @@ int check_cfg(const tide_config* c) {
     if (c->max_tokens < 1 || c->max_tokens > kMaxTokens) return fail(nullptr, TIDE_E_RANGE, "max_tokens must be 1..%d", kMaxTokens);
     if (c->gating != TIDE_GATING_SOFTMAX && c->gating != TIDE_GATING_SIGMOID) return fail(nullptr, TIDE_E_INVAL, "bad gating");
     if (c->bias_mode < TIDE_BIAS_NONE || c->bias_mode > TIDE_BIAS_SELECT) return fail(nullptr, TIDE_E_INVAL, "bad bias_mode");
+    if (c->resident_format != TIDE_RESIDENT_BF16 && c->resident_format != TIDE_RESIDENT_P12) return fail(nullptr, TIDE_E_INVAL, "bad resident_format");
     return TIDE_OK;
 }
 
@@ -305,6 +307,7 @@ int device_miss_pass(tide_ctx* ctx, Layer& L, const void* hidden_dev, int n_toke
     const uint16_t* x = static_cast<const uint16_t*>(hidden_dev);
     LayerTables host_view = L.t;
     host_view.slots = reinterpret_cast<const uint16_t*>(L.host_blobs);
+    host_view.expert_p12 = nullptr;                      // the host's blobs are bf16
     Shape shape = ctx->shape;
     shape.blob_elems = (int64_t)(L.host_stride / 2);
     const int max_small = max_miss_small_tasks_for(ctx->shape, n_tokens);
@@ -355,6 +358,8 @@ int tide_create(const tide_config* cfg, tide_ctx** out) {
     s.d = cfg->d; s.E = cfg->n_experts; s.k = cfg->top_k; s.I = cfg->d_ff; s.n_shared = cfg->n_shared;
     s.capacity = cfg->capacity; s.gating = cfg->gating; s.bias_mode = cfg->bias_mode;
     s.blob_elems = 3ll * cfg->d * cfg->d_ff;
+    s.resident_p12 = cfg->resident_format == TIDE_RESIDENT_P12;
+    s.big_rows = s.resident_p12 ? kRowsPerBigTaskP12 : kRowsPerBigTask;
     auto bail = [&](int code) { g_create_error = ctx->err; tide_destroy(ctx); return code; };
     if (hipGetDevice(&ctx->device) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "hipGetDevice failed"));
     hipDeviceProp_t prop;
@@ -402,6 +407,12 @@ int tide_create(const tide_config* cfg, tide_ctx** out) {
             return bail(fail(ctx, TIDE_E_HIP, "hipMemset failed"));
         if ((rc = ws_alloc(ctx, &L.slots_owned, (int64_t)(s.capacity + 1) * s.blob_elems))) return bail(rc);
         L.t.hits = hits; L.t.slot_of = slot_of; L.t.expert_in_slot = eis; L.t.slots = L.slots_owned;
+        if (s.resident_p12) {
+            // which experts are kept in the 12-bit form: none until tide_register_compressed / tide_set_shared say so
+            if ((rc = ws_alloc(ctx, &L.expert_p12, s.E + 1))) return bail(rc);
+            if (hipMemset(L.expert_p12, 0, s.E + 1) != hipSuccess) return bail(fail(ctx, TIDE_E_HIP, "hipMemset failed"));
+            L.t.expert_p12 = L.expert_p12;
+        }
         if (hipEventCreate(&L.copies_begin) != hipSuccess || hipEventCreate(&L.copies_done) != hipSuccess ||
             hipEventCreateWithFlags(&L.select_done, hipEventDisableTiming) != hipSuccess)
             return bail(fail(ctx, TIDE_E_HIP, "event"));
@@ -451,6 +462,22 @@ int tide_destroy(tide_ctx* ctx) {
     return TIDE_OK;
 }
 
+namespace {
+// What a cache slot receives for expert e, byte for byte: the bf16 blob, or -- when the slots keep the 12-bit form and
+// the expert has one -- its compressed blob.
+struct BlobSource {
+    const uint8_t* ptr;
+    uint64_t bytes;
+};
+BlobSource resident_source(const tide_ctx* ctx, const Layer& L, int e) {
+    if (ctx->shape.resident_p12) {
+        const uint8_t* comp = L.comp_blobs + (uint64_t)e * L.comp_stride;
+        if (!reinterpret_cast<const P12Header*>(comp)->raw) return {comp, tide_compressed_blob_bytes(&ctx->cfg)};
+    }
+    return {L.host_blobs + (uint64_t)e * L.host_stride, tide_expert_blob_bytes(&ctx->cfg)};
+}
+}  // namespace
+
 int tide_register_experts(tide_ctx* ctx, int layer, const void* host_blobs, uint64_t blob_stride) {
     int rc = layer_ok(ctx, layer);
     if (rc) return rc;
@@ -482,11 +509,21 @@ int tide_compress_expert(const tide_config* cfg, const void* blob_host, void* co
     return TIDE_OK;
 }
 
+int tide_decompress_expert(const tide_config* cfg, const void* comp_host, void* blob_host) {
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    if (!blob_host || !comp_host) return fail(nullptr, TIDE_E_INVAL, "null blob pointer");
+    if (!decompress_expert_blob(tide_expert_blob_bytes(cfg), static_cast<const uint8_t*>(comp_host), static_cast<uint16_t*>(blob_host)))
+        return fail(nullptr, TIDE_E_INVAL, "not a compressed blob of this configuration, or one marked raw");
+    return TIDE_OK;
+}
+
 int tide_register_compressed(tide_ctx* ctx, int layer, const void* comp_host_blobs, uint64_t comp_stride) {
     int rc = layer_ok(ctx, layer);
     if (rc) return rc;
     Layer& L = ctx->layers[layer];
     if (!comp_host_blobs) {                               // back to the raw blobs
+        if (ctx->shape.resident_p12) return fail(ctx, TIDE_E_STATE, "12-bit slots are filled from the compressed blobs: they cannot be unregistered");
         TIDE_HIP(ctx, hipDeviceSynchronize());
         L.comp_blobs = nullptr;
         return TIDE_OK;
@@ -502,10 +539,17 @@ int tide_register_compressed(tide_ctx* ctx, int layer, const void* comp_host_blo
     const uint32_t n_tiles = (uint32_t)(tide_expert_blob_bytes(&ctx->cfg) / 1024);
     for (int e = 0; e < ctx->cfg.n_experts; ++e) {
         const P12Header* h = reinterpret_cast<const P12Header*>(static_cast<const uint8_t*>(comp_host_blobs) + (uint64_t)e * comp_stride);
-        if (h->magic != kP12Magic || h->n_tiles != n_tiles || h->n_exc > n_tiles || h->raw > 1)
+        if (h->magic != kP12Magic || h->n_tiles != n_tiles || h->raw > 1)
             return fail(ctx, TIDE_E_INVAL, "expert %d: not a compressed blob of this configuration (tide_compress_expert)", e);
     }
     TIDE_HIP(ctx, hipDeviceSynchronize());
+    if (ctx->shape.resident_p12) {
+        if (L.placed) return fail(ctx, TIDE_E_STATE, "layer %d: register the compressed blobs before tide_set_resident", layer);
+        std::vector<uint8_t> flags(ctx->cfg.n_experts);
+        for (int e = 0; e < ctx->cfg.n_experts; ++e)
+            flags[e] = reinterpret_cast<const P12Header*>(static_cast<const uint8_t*>(comp_host_blobs) + (uint64_t)e * comp_stride)->raw ? 0 : 1;
+        TIDE_HIP(ctx, hipMemcpy(L.expert_p12, flags.data(), flags.size(), hipMemcpyHostToDevice));
+    }
     L.comp_blobs = static_cast<const uint8_t*>(comp_host_blobs);
     L.comp_stride = comp_stride;
     return TIDE_OK;
@@ -518,7 +562,21 @@ int tide_set_shared(tide_ctx* ctx, int layer, const void* blob_host) {
     if (!blob_host) return fail(ctx, TIDE_E_INVAL, "blob_host is null");
     Layer& L = ctx->layers[layer];
     TIDE_HIP(ctx, hipDeviceSynchronize());
-    TIDE_HIP(ctx, hipMemcpy(slot_ptr(ctx, L, ctx->cfg.capacity), blob_host, tide_expert_blob_bytes(&ctx->cfg), hipMemcpyHostToDevice));
+    const uint64_t bytes = tide_expert_blob_bytes(&ctx->cfg);
+    const void* src = blob_host;
+    uint64_t src_bytes = bytes;
+    std::vector<uint8_t> comp;
+    if (ctx->shape.resident_p12) {
+        comp.resize(tide_compressed_blob_bytes(&ctx->cfg));
+        compress_expert_blob(bytes, static_cast<const uint16_t*>(blob_host), comp.data());
+        const uint8_t is_p12 = reinterpret_cast<const P12Header*>(comp.data())->raw ? 0 : 1;
+        if (is_p12) {
+            src = comp.data();
+            src_bytes = comp.size();
+        }
+        TIDE_HIP(ctx, hipMemcpy(L.expert_p12 + ctx->cfg.n_experts, &is_p12, 1, hipMemcpyHostToDevice));
+    }
+    TIDE_HIP(ctx, hipMemcpy(slot_ptr(ctx, L, ctx->cfg.capacity), src, src_bytes, hipMemcpyHostToDevice));
     L.shared_set = true;
     return TIDE_OK;
 }
@@ -531,6 +589,8 @@ int tide_set_resident(tide_ctx* ctx, int layer, const int32_t* experts, int n) {
     if (n > 0 && !experts) return fail(ctx, TIDE_E_INVAL, "experts is null");
     Layer& L = ctx->layers[layer];
     if (!L.host_blobs) return fail(ctx, TIDE_E_STATE, "layer %d: experts not registered", layer);
+    if (ctx->shape.resident_p12 && !L.comp_blobs)
+        return fail(ctx, TIDE_E_STATE, "layer %d: 12-bit slots need the compressed blobs (tide_register_compressed)", layer);
     std::vector<int32_t> slot_of(E, -1), eis(C, -1);
     for (int s = 0; s < n; ++s) {
         const int e = experts[s];
@@ -541,10 +601,11 @@ int tide_set_resident(tide_ctx* ctx, int layer, const int32_t* experts, int n) {
         eis[s] = e;
     }
     TIDE_HIP(ctx, hipDeviceSynchronize());
-    const uint64_t bytes = tide_expert_blob_bytes(&ctx->cfg);
     for (int s = 0; s < C; ++s)
-        if (eis[s] >= 0)
-            TIDE_HIP(ctx, hipMemcpy(slot_ptr(ctx, L, s), L.host_blobs + (uint64_t)eis[s] * L.host_stride, bytes, hipMemcpyHostToDevice));
+        if (eis[s] >= 0) {
+            const BlobSource src = resident_source(ctx, L, eis[s]);
+            TIDE_HIP(ctx, hipMemcpy(slot_ptr(ctx, L, s), src.ptr, src.bytes, hipMemcpyHostToDevice));
+        }
     TIDE_HIP(ctx, hipMemcpy(L.t.slot_of, slot_of.data(), E * 4, hipMemcpyHostToDevice));
     TIDE_HIP(ctx, hipMemcpy(L.t.expert_in_slot, eis.data(), C * 4, hipMemcpyHostToDevice));
     L.placed = true;
@@ -970,6 +1031,8 @@ int refresh_impl(tide_ctx* ctx, int layer, const int32_t* counts_host, int capac
     Layer& L = ctx->layers[layer];
     if (!L.host_blobs) return fail(ctx, TIDE_E_STATE, "layer %d: experts not registered", layer);
     if (!L.placed) return fail(ctx, TIDE_E_STATE, "layer %d has no placement: call tide_set_resident first", layer);
+    if (ctx->shape.resident_p12 && !L.comp_blobs)
+        return fail(ctx, TIDE_E_STATE, "layer %d: 12-bit slots need the compressed blobs (tide_register_compressed)", layer);
     if (L.deferred_pending) return fail(ctx, TIDE_E_STATE, "layer %d: a deferred refresh awaits tide_commit", layer);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const uint64_t bytes = tide_expert_blob_bytes(&ctx->cfg);
@@ -1021,12 +1084,14 @@ int refresh_impl(tide_ctx* ctx, int layer, const int32_t* counts_host, int capac
     if (ctx->copy_engine == TIDE_COPY_DMA && !async) {
         // one DMA transfer per entering expert, raw blob to slot (or staging blob): the copy engines move the bytes,
         // no compute unit is involved, so kernels that run beside the copies keep their memory pipelines to themselves
-        for (int i = 0; i < n; ++i)
-            TIDE_HIP(ctx, hipMemcpyAsync(copy_dst + (uint64_t)(deferred ? i : L.plan->slot[i]) * bytes,
-                                         L.host_blobs + (uint64_t)L.plan->expert[i] * L.host_stride, bytes, hipMemcpyHostToDevice, ctx->side));
+        for (int i = 0; i < n; ++i) {
+            const BlobSource src = resident_source(ctx, L, L.plan->expert[i]);
+            TIDE_HIP(ctx, hipMemcpyAsync(copy_dst + (uint64_t)(deferred ? i : L.plan->slot[i]) * bytes, src.ptr, src.bytes,
+                                         hipMemcpyHostToDevice, ctx->side));
+        }
     } else if (L.comp_blobs)
         TIDE_HIP(ctx, launch_refresh_copies_p12(L.comp_blobs, L.comp_stride, L.host_blobs, L.host_stride, bytes, copy_dst, L.plan, n,
-                                                ctx->cfg.capacity, deferred, ctx->side));
+                                                deferred, ctx->shape.resident_p12 != 0, ctx->side));
     else
         TIDE_HIP(ctx, launch_refresh_copies(L.host_blobs, L.host_stride, bytes, copy_dst, L.plan, n, deferred, ctx->side));
     if (async) {

@@ -14,7 +14,8 @@ constexpr int kMaxTokens = 65535;       // tokens per step: the per-token kernel
 constexpr int kMaxTopK = 16;             // one selection per lane of a 16-lane group
 constexpr int kMaxRouterSplits = 8;      // slices of the hidden dimension the router logits are computed in
 constexpr int kRowsPerTask = 32;        // rows of a small work item
-constexpr int kRowsPerBigTask = 256;    // rows of a large work item
+constexpr int kRowsPerBigTask = 256;    // rows of a large work item (the kernels' limit)
+constexpr int kRowsPerBigTaskP12 = 192; // the same when the slots hold the 12-bit form: the decode needs the registers of four token tiles
 constexpr int kMinBigUnits = 128;       // a step uses large work items only if they make at least this many gate/up workgroups (half the compute units)
 constexpr int kBigMinRows = 32;         // a slot with more rows than this is cut into large work items, else into small ones
 constexpr int kBigMinAvgRows = 48;      // steps with fewer rows per slot on average launch no large-item kernels at all
@@ -30,8 +31,10 @@ struct Task {
     int32_t slot;
     int32_t row0;
     int32_t nrows;
-    int32_t pad;        // small items: 1 when the slot is cut into several items (they read the same weights)
+    int32_t flags;      // kTaskSiblings | kTaskP12
 };
+constexpr int kTaskSiblings = 1;   // small items: the slot is cut into several items (they read the same weights)
+constexpr int kTaskP12 = 2;        // the slot holds the 12-bit form of its blob (packed12.h), not the bf16 blob
 
 // Device-side workspace of one context (shared by its layers; one step at a time).
 struct Workspace {
@@ -62,6 +65,7 @@ struct LayerTables {
     int32_t* slot_of;         // [E]  slot of each expert, -1 = not resident
     int32_t* expert_in_slot;  // [capacity] expert in each slot, -1 = empty
     const uint16_t* slots;    // capacity (+1 shared) packed blobs, blob_elems apart
+    const uint8_t* expert_p12; // [E + n_shared] 1 = the expert's blob is kept in a slot in its 12-bit form; null: bf16 slots
 };
 
 // Optional timing of one kernel launch: when both events are set the launch goes through
@@ -83,6 +87,8 @@ struct Shape {
     int d, E, k, I, n_shared, capacity, gating, bias_mode;
     int64_t blob_elems;       // 3*d*I
     int n_cus;                // compute units of the device
+    int big_rows;             // most rows of a large work item: kRowsPerBigTask or kRowsPerBigTaskP12
+    int resident_p12;         // the cache slots hold the 12-bit form of the blobs (packed12.h)
 };
 
 // a1: z[n][e] = <x_n, W_r[e]>  (fp32)
@@ -121,7 +127,7 @@ inline int max_big_tasks_for(const Shape& s, int n_tokens) {
     const int rows = n_tokens * s.k + (s.n_shared ? n_tokens : 0);
     const int slots = s.capacity + 1;
     const int busy = rows / (kBigMinRows + 1);           // slots that can exceed the small limit at once
-    const int most = rows / kRowsPerBigTask + (busy < slots ? busy : slots);
+    const int most = rows / s.big_rows + (busy < slots ? busy : slots);
     // too few for the step ever to choose large items (the split kernel's rule), or so few rows per slot that the
     // large-item kernels would mostly be launched for nothing (their idle workgroups each take a compute unit's LDS
     // for a moment: 135 -> 123 us per step at 256 tokens x top-8 over 65 slots): nothing to launch, and the split
@@ -140,7 +146,7 @@ inline int max_miss_big_tasks_for(const Shape& s, int n_tokens) {
     if (n_tokens <= kBigMinRows) return 0;
     const int rows = n_tokens * s.k;
     const int busy = rows / (kBigMinRows + 1);
-    const int most = rows / kRowsPerBigTask + (busy < s.E ? busy : s.E);
+    const int most = rows / s.big_rows + (busy < s.E ? busy : s.E);
     if ((int64_t)most * ((s.I + 127) / 128) < kMinBigUnits || rows < kBigMinAvgRows * s.E) return 0;
     return most;
 }
@@ -172,14 +178,14 @@ hipError_t launch_refresh_select(const Shape& s, const LayerTables& t, const int
                                  int reset_counts, RefreshOut* out_hostmapped, hipStream_t stream);
 
 // a12: the plan's blobs from pinned host memory to their slots (or to staging blob i), one kernel.  n < 0: the
-// kernel takes the number of copies from the plan itself (the host has not seen it); the p12 form then needs
-// max_n >= that number
+// kernel takes the number of copies from the plan itself (the host has not seen it)
 hipError_t launch_refresh_copies(const uint8_t* host_blobs, uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base,
                                  const RefreshOut* plan, int n, bool dst_by_rank, hipStream_t stream);
-// the same copies from the 12-bit form of the blobs (packed12.h), rebuilt bit for bit in the destination
+// the same copies from the 12-bit form of the blobs (packed12.h): rebuilt bit for bit in the destination, or
+// (verbatim) copied as they are for slots that keep the 12-bit form
 hipError_t launch_refresh_copies_p12(const uint8_t* comp_blobs, uint64_t comp_stride, const uint8_t* host_blobs,
                                      uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base, const RefreshOut* plan, int n,
-                                     int max_n, bool dst_by_rank, hipStream_t stream);
+                                     bool dst_by_rank, bool verbatim, hipStream_t stream);
 // measurement: `bytes` (a multiple of 1024) from `base` read once by `workgroups` workgroups in the GEMMs' weight-stream shape
 hipError_t launch_stream_probe(const uint8_t* base, uint64_t bytes, int workgroups, uint32_t* sink, hipStream_t stream, LaunchEvents ev);
 // H[e] <- floor(H[e] * num / den)

@@ -16,12 +16,15 @@ ExpertBits = Callable[[int], Tuple[np.ndarray, np.ndarray, np.ndarray]]
 
 class TideSession:
     def __init__(self, d: int, E: int, k: int, I: int, n_shared: int, capacity: int, max_tokens: int,
-                 gating: int, bias_mode: int, n_layers: int = 1, device: str = "cuda:0"):
+                 gating: int, bias_mode: int, n_layers: int = 1, device: str = "cuda:0", resident_p12: bool = False):
         if not torch.cuda.is_available():
             raise RuntimeError("TideSession needs a GPU; there is no CPU path")
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
-        self.cfg = tb.make_config(d, E, k, I, n_shared, n_layers, capacity, max_tokens, gating, bias_mode)
+        self.resident_p12 = bool(resident_p12)
+        self.cfg = tb.make_config(d, E, k, I, n_shared, n_layers, capacity, max_tokens, gating, bias_mode,
+                                  tb.TIDE_RESIDENT_P12 if resident_p12 else tb.TIDE_RESIDENT_BF16)
+        self.comp_blobs = {}
         self.d, self.E, self.k, self.I, self.n_shared, self.C = d, E, k, I, n_shared, capacity
         self.max_tokens, self.n_layers = max_tokens, n_layers
         self.blob_bytes = tb.tide_expert_blob_bytes(self.cfg)
@@ -55,25 +58,29 @@ class TideSession:
             tb.tide_pack_expert(self.cfg, *expert_bits(self.E), sh)
         return blobs, sh
 
-    def compress_layer(self, layer: int, workers: int = 8) -> None:
-        """Builds the 12-bit form of the layer's registered blobs in pinned memory and makes it the source of
-        the layer's refresh copies (3/4 of the bytes over the host link, slots bit-identical)."""
+    def compress_layer(self, layer: int, workers: int = 8, comp: Optional[torch.Tensor] = None) -> None:
+        """Builds the 12-bit form of the layer's registered blobs in pinned memory (or takes one built earlier for the
+        same blobs) and registers it: the source of the layer's refresh copies (3/4 of the bytes over the host link)
+        and, in a session with 12-bit slots, what the slots hold."""
         comp_bytes = tb.tide_compressed_blob_bytes(self.cfg)
-        comp = torch.empty((self.E, comp_bytes), dtype=torch.uint8, pin_memory=True)
-        raw, out = self.host_blobs[layer].numpy(), comp.numpy()
-        with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as ex:
-            list(ex.map(lambda e: tb.tide_compress_expert(self.cfg, raw[e], out[e]), range(self.E)))
-        if not hasattr(self, "comp_blobs"):
-            self.comp_blobs = {}
+        if comp is None:
+            comp = torch.empty((self.E, comp_bytes), dtype=torch.uint8, pin_memory=True)
+            raw, out = self.host_blobs[layer].numpy(), comp.numpy()
+            with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as ex:
+                list(ex.map(lambda e: tb.tide_compress_expert(self.cfg, raw[e], out[e]), range(self.E)))
+        assert tuple(comp.shape) == (self.E, comp_bytes) and comp.is_pinned()
         self.comp_blobs[layer] = comp
         tb.tide_register_compressed(self.ctx, layer, comp, comp_bytes)
 
     def load_layer(self, layer: int, expert_bits: Optional[ExpertBits], router_w: np.ndarray,
-                   router_bias: Optional[np.ndarray], resident: Sequence[int], workers: int = 8, packed=None) -> None:
+                   router_bias: Optional[np.ndarray], resident: Sequence[int], workers: int = 8, packed=None,
+                   comp: Optional[torch.Tensor] = None) -> None:
         blobs, sh = packed if packed is not None else self.pack_layer(expert_bits, workers)
         assert tuple(blobs.shape) == (self.E, self.blob_bytes) and blobs.is_pinned()
         self.host_blobs[layer] = blobs
         tb.tide_register_experts(self.ctx, layer, blobs, self.blob_bytes)
+        if self.resident_p12 or comp is not None:        # 12-bit slots are filled from the compressed blobs
+            self.compress_layer(layer, workers, comp)
         if self.n_shared:
             tb.tide_set_shared(self.ctx, layer, sh)
         tb.tide_set_resident(self.ctx, layer, resident)

@@ -25,31 +25,23 @@ static float f32_of(uint16_t b) { uint32_t u = (uint32_t)b << 16; float f; memcp
         if (!(cond)) { fprintf(stderr, "FAILED %s:%d: %s\n", __FILE__, __LINE__, #cond); exit(1); } \
     } while (0)
 
+// decoder written from the format's description: a lane's two dwords of low bytes and its dword of 4-bit table
+// indices, the tile's table of high bytes
 static std::vector<uint16_t> decode_p12(const std::vector<uint8_t>& comp, uint64_t blob_bytes) {
     const uint32_t n_tiles = (uint32_t)(blob_bytes / 1024);
     const P12Layout lay = p12_layout(n_tiles);
-    const P12Header* h = reinterpret_cast<const P12Header*>(comp.data());
     std::vector<uint16_t> out(blob_bytes / 2);
     for (uint32_t t = 0; t < n_tiles; ++t) {
-        const uint32_t base = comp[lay.off_base + t];
+        const uint8_t* table = comp.data() + lay.off_table + (uint64_t)t * kP12TableBytes;
         for (int l = 0; l < 64; ++l) {
-            uint32_t w[3];
+            uint8_t w[12];
             memcpy(w, comp.data() + lay.off_payload + (uint64_t)t * kP12TileBytes + l * 12, 12);
-            const uint64_t lo = w[0] | ((uint64_t)w[1] << 32);
-            uint32_t code[8];
-            for (int j = 0; j < 5; ++j) code[j] = (uint32_t)(lo >> (12 * j)) & 0xfff;
-            code[5] = (w[1] >> 28) | ((w[2] & 0xff) << 4);
-            code[6] = (w[2] >> 8) & 0xfff;
-            code[7] = w[2] >> 20;
             for (int j = 0; j < 8; ++j) {
-                const uint32_t delta = (code[j] >> 7) & 15, e = base >= delta ? base - delta : 0;
-                out[(uint64_t)t * 512 + l * 8 + j] = (uint16_t)(((code[j] >> 11) << 15) | (e << 7) | (code[j] & 0x7f));
+                const uint32_t code = j < 4 ? (w[8 + j] & 15u) : (uint32_t)(w[8 + j - 4] >> 4);
+                out[(uint64_t)t * 512 + l * 8 + j] = (uint16_t)(w[j] | ((uint32_t)table[code] << 8));
             }
         }
     }
-    const uint32_t* idx = reinterpret_cast<const uint32_t*>(comp.data() + lay.off_exc_idx);
-    const uint16_t* val = reinterpret_cast<const uint16_t*>(comp.data() + lay.off_exc_val);
-    for (uint32_t i = 0; i < h->n_exc; ++i) out[idx[i]] = val[i];
     return out;
 }
 
@@ -62,7 +54,7 @@ int main() {
         wg[e].resize((size_t)d_ff * d); wu[e].resize((size_t)d_ff * d); wd[e].resize((size_t)d * d_ff);
         for (auto* m : {&wg[e], &wu[e], &wd[e]})
             for (auto& v : *m) v = bf16_of(next_unit() * 0.2f);
-        wg[e][7] = 0; wu[e][11] = 0x0001; wd[e][13] = 0x7f80;      // a zero, a denormal, an infinity: listed exceptions
+        wg[e][7] = 0; wu[e][11] = 0x0001; wd[e][13] = 0x7f80;      // a zero, a denormal, an infinity: table entries like any other
         pack_expert_blob(d, d_ff, wg[e].data(), wu[e].data(), wd[e].data(), blobs.data() + e * blob_elems);
     }
     wd[0][13] = bf16_of(0.01f);                                    // keep the arithmetic checks finite
@@ -78,15 +70,18 @@ int main() {
         CHECK(down[5 * 8 + 1] == wd[1][(size_t)5 * d_ff + 1]);
         (void)kch;
     }
-    // 12-bit form: bit-exact round trip, exceptions listed; a blob of arbitrary bits is marked raw
+    // 12-bit form: bit-exact round trip by hand and through the library's inverse; a blob of arbitrary bits is marked raw
     const uint64_t comp_bytes = p12_layout(blob_bytes / 1024).bytes;
     for (int e = 0; e < E; ++e) {
         std::vector<uint8_t> comp(comp_bytes);
         compress_expert_blob(blob_bytes, blobs.data() + e * blob_elems, comp.data());
         const P12Header* h = reinterpret_cast<const P12Header*>(comp.data());
-        CHECK(h->magic == kP12Magic && h->raw == 0 && h->n_exc >= 2);
+        CHECK(h->magic == kP12Magic && h->raw == 0 && h->n_tiles == blob_bytes / 1024);
         const std::vector<uint16_t> back = decode_p12(comp, blob_bytes);
         CHECK(memcmp(back.data(), blobs.data() + e * blob_elems, blob_bytes) == 0);
+        std::vector<uint16_t> again(blob_elems, 0xAAAA);
+        CHECK(decompress_expert_blob(blob_bytes, comp.data(), again.data()));
+        CHECK(memcmp(again.data(), blobs.data() + e * blob_elems, blob_bytes) == 0);
     }
     {
         std::vector<uint16_t> noise(blob_elems);
@@ -94,6 +89,7 @@ int main() {
         std::vector<uint8_t> comp(comp_bytes);
         compress_expert_blob(blob_bytes, noise.data(), comp.data());
         CHECK(reinterpret_cast<const P12Header*>(comp.data())->raw == 1);
+        CHECK(!decompress_expert_blob(blob_bytes, comp.data(), noise.data()));
     }
     // one expert on the calling thread against plain loops
     std::vector<uint16_t> x((size_t)n_tokens * d);

@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(tb):
 def test_struct_layouts_match_the_header(tb):
     assert ctypes.sizeof(tb.tide_miss) == 12
     assert ctypes.sizeof(tb.tide_copy) == 24
-    assert ctypes.sizeof(tb.tide_config) == 40
+    assert ctypes.sizeof(tb.tide_config) == 44
     assert tb.MISS_DTYPE.itemsize == 12
 
 
@@ -145,58 +145,67 @@ def test_host_miss_path_matches_the_oracle(tb, n_tokens, n_experts, k, threads, 
 
 def _p12_decode(comp: np.ndarray, n_tiles: int) -> np.ndarray:
     """Decoder written from the format's description in include/tide.h and csrc/packed12.h, independent of the
-    library: header, one base exponent per tile, 12-bit elements (sign | base - exponent | mantissa) packed low bits
-    first, then the listed exceptions."""
+    library: header; per tile 64 lanes x 3 dwords (the low bytes of the lane's elements 0..3 and 4..7, then one byte
+    per element pair j, 4+j holding their two 4-bit table indices); per tile a table of 16 high bytes."""
     hdr = comp[:64].view(np.uint32)
-    assert hdr[0] == 0x32315054 and hdr[1] == n_tiles
-    off_base = 64
-    off_payload = off_base + (n_tiles + 63) // 64 * 64
-    off_idx = off_payload + n_tiles * 768
-    off_val = off_idx + n_tiles * 4
-    base = comp[off_base:off_base + n_tiles].astype(np.int64)
-    payload = comp[off_payload:off_idx].reshape(-1, 3)                       # 3 bytes = 2 elements
-    two = payload[:, 0].astype(np.int64) | (payload[:, 1].astype(np.int64) << 8) | (payload[:, 2].astype(np.int64) << 16)
-    code = np.stack([two & 0xfff, two >> 12], axis=1).reshape(n_tiles, 512)
-    e = np.maximum(base[:, None] - ((code >> 7) & 15), 0)
-    vals = (((code >> 11) << 15) | (e << 7) | (code & 0x7f)).astype(np.uint16).reshape(-1)
-    n_exc = int(hdr[2])
-    idx = comp[off_idx:off_idx + 4 * n_exc].view(np.uint32)
-    vals[idx] = comp[off_val:off_val + 2 * n_exc].view(np.uint16)
-    return vals
+    assert hdr[0] == 0x32315054 and hdr[1] == n_tiles and hdr[2] == 0
+    off_table = 64 + n_tiles * 768
+    words = comp[64:off_table].view(np.uint32).reshape(n_tiles, 64, 3).astype(np.int64)
+    table = comp[off_table:off_table + 16 * n_tiles].reshape(n_tiles, 16).astype(np.int64)
+    vals = np.zeros((n_tiles, 64, 8), dtype=np.int64)
+    for j in range(8):
+        low = (words[:, :, j // 4] >> (8 * (j % 4))) & 0xff
+        code = (words[:, :, 2] >> (8 * (j % 4) + (0 if j < 4 else 4))) & 0xf
+        vals[:, :, j] = low | (np.take_along_axis(table, code, axis=1) << 8)
+    return vals.astype(np.uint16).reshape(-1)
 
 
 def test_compressed_blob_round_trip(tb):
-    """The 12-bit refresh source is lossless: decoding it (here, by hand) gives back the packed blob bit for bit,
-    for Gaussian weights, for weights with zeros / denormals / tiny values (exceptions), and an expert whose
-    exponents are spread too widely is marked raw instead."""
+    """The 12-bit form is lossless: decoding it (here by hand, and with the library's own inverse) gives back the
+    packed blob bit for bit -- for Gaussian weights, for weights with zeros / denormals / infinities / NaNs sprinkled
+    in, for a tile that uses all 16 table entries -- and a blob with a tile of 17 distinct high bytes is marked raw."""
     d, I = 256, 128
     cfg = tb.make_config(d, 8, 2, I, 0, 1, 4, 8, 0, 0)
     n_tiles = 3 * d * I // 512
     cbytes = tb.tide_compressed_blob_bytes(cfg)
-    assert cbytes % 64 == 0 and cbytes < 0.77 * tb.tide_expert_blob_bytes(cfg)
+    assert cbytes % 64 == 0 and cbytes == 64 + n_tiles * (768 + 16) and cbytes < 0.77 * tb.tide_expert_blob_bytes(cfg)
     rng = np.random.default_rng(12)
     def bits(shape, scale):
         return (np.ascontiguousarray(rng.normal(0, scale, size=shape), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
     blob = np.zeros(tb.tide_expert_blob_bytes(cfg), dtype=np.uint8)
     comp = np.zeros(cbytes, dtype=np.uint8)
+    back = np.zeros_like(blob)
+
+    def round_trip(src_u16):
+        tb.tide_compress_expert(cfg, src_u16.view(np.uint8), comp)
+        assert np.array_equal(_p12_decode(comp, n_tiles), src_u16)
+        back[:] = 0xAA
+        tb.tide_decompress_expert(cfg, comp, back)
+        assert np.array_equal(back.view(np.uint16), src_u16)
+
     # Gaussian weights
     tb.tide_pack_expert(cfg, bits((I, d), 0.02), bits((I, d), 0.02), bits((d, I), 0.02), blob)
-    tb.tide_compress_expert(cfg, blob, comp)
-    hdr = comp[:64].view(np.uint32)
-    assert hdr[3] == 0 and hdr[2] < n_tiles // 4
-    assert np.array_equal(_p12_decode(comp, n_tiles), blob.view(np.uint16))
-    # zeros, negative zeros, denormals, tiny and huge values, infinities and NaNs sprinkled in (all exceptions)
+    round_trip(blob.view(np.uint16))
+    # zeros, negative zeros, denormals, tiny and huge values, infinities and NaNs sprinkled in
     raw = blob.view(np.uint16).copy()
     at = rng.choice(raw.size, size=60, replace=False)
     raw[at] = np.resize(np.array([0x0000, 0x8000, 0x0001, 0x807f, 0x0080, 0x7f7f, 0xff80, 0x7fc1, 0x1234, 0x3f80], dtype=np.uint16), 60)
-    tb.tide_compress_expert(cfg, raw.view(np.uint8), comp)
-    hdr = comp[:64].view(np.uint32)
-    assert hdr[3] == 0 and hdr[2] >= 6
-    assert np.array_equal(_p12_decode(comp, n_tiles), raw)
-    # exponents all over the range: more exceptions than the list holds -> marked raw
+    round_trip(raw)
+    # a tile whose elements use exactly 16 distinct high bytes still encodes ...
+    full = blob.view(np.uint16).copy()
+    full[512 * 5:512 * 6] = (np.resize(np.arange(16, dtype=np.uint16) * 9 + 3, 512) << 8) | rng.integers(0, 256, 512, dtype=np.uint16)
+    round_trip(full)
+    # ... a 17th does not: the blob is marked raw, and the inverse refuses it
+    full[512 * 5 + 100] = 0xF1 << 8
+    tb.tide_compress_expert(cfg, full.view(np.uint8), comp)
+    assert comp[:64].view(np.uint32)[2] == 1
+    with pytest.raises(tb.TideError) as ei:
+        tb.tide_decompress_expert(cfg, comp, back)
+    assert ei.value.code == tb.TIDE_E_INVAL
+    # exponents all over the range: raw as well
     wild = rng.integers(0, 2 ** 16, size=raw.size, dtype=np.uint16)
     tb.tide_compress_expert(cfg, wild.view(np.uint8), comp)
-    assert comp[:64].view(np.uint32)[3] == 1
+    assert comp[:64].view(np.uint32)[2] == 1
 
 
 def test_config_validation_and_no_device(tb):
