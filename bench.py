@@ -56,8 +56,49 @@ def cpu_baseline(wl, ti, sample_steps=None):
                       "%.1f s (includes bf16->fp64 weight conversion on first use)" % (sample_steps, wl.N, dt)}
 
 
-# --resident: the form the cache slots keep the blobs in (set once in main, read by every session made here)
+# --resident: the form the cache slots keep the blobs in (set per workload, read by every session made here).
+# "auto": the 12-bit form where a step is bound by the weight bytes it streams (up to 256 tokens at these shapes: every
+# slot sees a handful of rows), bf16 blobs where the large-item kernels do most of the work (the decode costs them more
+# than the bytes it saves, and a 12-bit large item is capped at 192 rows).
 RESIDENT_P12 = False
+
+
+def resident_p12_for(args, wl):
+    policy = getattr(args, "resident_policy", args.resident)
+    return policy == "p12" or (policy == "auto" and wl.N <= 256)
+
+
+def choose_resident(args, wl):
+    global RESIDENT_P12
+    RESIDENT_P12 = resident_p12_for(args, wl)
+    return "p12" if RESIDENT_P12 else "bf16"
+
+
+def bf16_reference(wl, args, ti, tb, TideSession, torch, packed, comp, hidden_bits):
+    """The timed loop of the headline once more over bf16 slots, without event brackets: refresh copies from the raw blobs
+    (Alg. 1's copies as they are) and from the 12-bit form.  Reference figures beside a run over 12-bit slots."""
+    ref = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode)
+    ref.load_layer(0, None, ti.router_weights(wl, 0), ti.router_bias(wl, 0), ti.initial_resident(wl), packed=packed)
+    hidden = [ref.to_device_bf16(h) for h in hidden_bits]
+    out = {}
+    for source in ("raw", "packed12"):
+        if source == "packed12":
+            tb.tide_register_compressed(ref.ctx, 0, comp, tb.tide_compressed_blob_bytes(ref.cfg))
+        tb.tide_set_resident(ref.ctx, 0, ti.initial_resident(wl))
+        ref.stats(0, reset=True)
+        for phase, n in (("warm", args.warmup), ("timed", args.steps)):
+            torch.cuda.synchronize()
+            r0 = time.perf_counter()
+            for i in range(n):
+                t = (i if phase == "warm" else args.warmup + i) % wl.S
+                if t > 0 and t % wl.K == 0:
+                    ref.refresh(0)
+                ref.step(0, hidden[t], want_topk=False)
+            torch.cuda.synchronize()
+            rdt = time.perf_counter() - r0
+        out[source] = {"tokens_per_s": wl.N * args.steps / rdt, "us_per_step": rdt / args.steps * 1e6}
+    ref.close()
+    return out
 
 
 def run_stack(args, wl, ti, tb, TideSession, torch):
@@ -304,19 +345,31 @@ def run_all_configs(args, ti, tb, TideSession, torch, cfg1_entry, packed_mini, c
     s0 = TideSession(wl0.d, wl0.E, wl0.k, wl0.I, wl0.n_shared, wl0.C, wl0.N, wl0.gating, wl0.bias_mode)      # packs only
     packed0 = s0.pack_layer(lambda e: ti.expert_weights(wl0, 0, e), workers=4)
     s0.close()
-    out["0"], _ = measure_layer(wl0, ti, tb, TideSession, torch, packed0, 64, 16, args.refresh_source)
-    out["2"], comp_mini = measure_layer(mini, ti, tb, TideSession, torch, packed_mini, 64, 8, args.refresh_source, comp=comp_mini)
-    out["2"]["stack"] = measure_stack(mini, mini.L, ti, tb, TideSession, torch, packed_mini, 16, comp=comp_mini)
+    def layer(wl, *a, **kw):                           # one layer in the form of slots this run uses for its size
+        fmt = choose_resident(args, wl)
+        res, comp = measure_layer(wl, ti, tb, TideSession, torch, *a, **kw)
+        res["resident_format"] = fmt
+        return res, comp
+
+    def stack(wl, *a, **kw):
+        fmt = choose_resident(args, wl)
+        res = measure_stack(wl, wl.L, ti, tb, TideSession, torch, *a, **kw)
+        res["resident_format"] = fmt
+        return res
+
+    out["0"], _ = layer(wl0, packed0, 64, 16, args.refresh_source)
+    out["2"], comp_mini = layer(mini, packed_mini, 64, 8, args.refresh_source, comp=comp_mini)
+    out["2"]["stack"] = stack(mini, packed_mini, 16, comp=comp_mini)
     probe = TideSession(flash.d, flash.E, flash.k, flash.I, flash.n_shared, 1, 1, flash.gating, flash.bias_mode)
     packed_flash = probe.pack_layer(lambda e: ti.expert_weights(flash, 0, e), workers=16)
     probe.close()
-    out["3"], comp_flash = measure_layer(flash, ti, tb, TideSession, torch, packed_flash, 64, 8, args.refresh_source)
+    out["3"], comp_flash = layer(flash, packed_flash, 64, 8, args.refresh_source)
     c4 = ti.CONFIGS[4]
-    out["4"], _ = measure_layer(c4, ti, tb, TideSession, torch, packed_flash, 64, 8, args.refresh_source, comp=comp_flash)
-    out["4"]["all_experts_resident"], _ = measure_layer(c4.replace(C=c4.E), ti, tb, TideSession, torch, packed_flash, 16, 4, "raw")
+    out["4"], _ = layer(c4, packed_flash, 64, 8, args.refresh_source, comp=comp_flash)
+    out["4"]["all_experts_resident"], _ = layer(c4.replace(C=c4.E), packed_flash, 16, 4, "raw")
     torch.cuda.empty_cache()
-    out["4"]["stack"] = measure_stack(c4, c4.L, ti, tb, TideSession, torch, packed_flash, 8, comp=comp_flash)
-    out["4"]["stack_all_experts_resident"] = measure_stack(c4.replace(C=c4.E), c4.L, ti, tb, TideSession, torch, packed_flash, 4, refresh=False)
+    out["4"]["stack"] = stack(c4, packed_flash, 8, comp=comp_flash)
+    out["4"]["stack_all_experts_resident"] = stack(c4.replace(C=c4.E), packed_flash, 4, refresh=False)
     out["seconds_spent_on_this_table"] = time.perf_counter() - t0
     return out
 
@@ -406,9 +459,10 @@ def main():
                     help="--stack: at a refresh step, refresh each layer right before its own step, or all layers first so "
                          "that later layers' copies overlap earlier layers' compute")
     ap.add_argument("--capacity", type=int, default=0, help="cache slots (0 = the workload's own budget); 256 = every expert resident")
-    ap.add_argument("--resident", choices=("bf16", "p12"), default="bf16",
+    ap.add_argument("--resident", choices=("auto", "bf16", "p12"), default="auto",
                     help="the form a cache slot keeps its blob in: the bf16 blob, or its lossless 12-bit form decoded by the "
-                         "expert GEMMs in registers (3/4 of the HBM bytes per step; refresh copies then move compressed blobs)")
+                         "expert GEMMs in registers (3/4 of the HBM bytes per step; refresh copies then move compressed blobs); "
+                         "auto = 12-bit for steps of up to 256 tokens")
     ap.add_argument("--refresh-source", choices=("raw", "packed12"), default="packed12",
                     help="what the refresh copies read over the host link: the raw blobs, or their lossless 12-bit form "
                          "(3/4 of the bytes; slots bit-identical)")
@@ -485,13 +539,13 @@ def main():
         wl = wl.replace(C=args.capacity)
     if args.tokens:
         wl = wl.replace(N=args.tokens)
+    args.resident_policy = args.resident
+    args.resident = choose_resident(args, wl)                  # what this run uses, as the JSON line reports it
+    if RESIDENT_P12:
+        args.refresh_source = "packed12"                       # 12-bit slots are filled with compressed blobs by every engine
     if args.stack:
         run_stack(args, wl, ti, tb, TideSession, torch)
         return
-    global RESIDENT_P12
-    RESIDENT_P12 = args.resident == "p12"
-    if RESIDENT_P12:
-        args.refresh_source = "packed12"               # 12-bit slots are filled with compressed blobs by every engine
     sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, resident_p12=RESIDENT_P12)
     packed = sess.pack_layer(lambda e: ti.expert_weights(wl, 0, e), workers=16)
     sess.load_layer(0, None, ti.router_weights(wl, 0), ti.router_bias(wl, 0), ti.initial_resident(wl), packed=packed, workers=16)
@@ -651,6 +705,10 @@ def main():
         tb.tide_register_compressed(sess.ctx, 0, None, 0)
         raw_source = plain_pass()
         tb.tide_register_compressed(sess.ctx, 0, sess.comp_blobs[0], tb.tide_compressed_blob_bytes(sess.cfg))
+    bf16_ref = None
+    if RESIDENT_P12 and not args.headline_only and args.refresh_mode == "immediate" and args.refresh_call == "sync" and args.copy_engine == "kernel":
+        bf16_ref = bf16_reference(wl, args, ti, tb, TideSession, torch, packed, sess.comp_blobs[0], list(ti.hidden_stream(wl, 0)))
+        raw_source = bf16_ref["raw"]
     h2d_p12 = None
     if args.refresh_source == "packed12":
         cbytes = tb.tide_compressed_blob_bytes(sess.cfg)
@@ -700,7 +758,13 @@ def main():
         roofline = {"bound": "hbm", "kernel": "expert_gemm_kernel<0>%s (grouped gate/up GEMM + SwiGLU)" % (" + expert_gemm_big_kernel<0>" if n_big else ""),
                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                     "traffic": None, "avg_kernel_us": avg_s * 1e6, "algorithmic_bytes_per_launch": bytes_per_launch,
-                    "active_slots_per_launch": active_per_launch}
+                    "active_slots_per_launch": active_per_launch, "resident_format": args.resident}
+        if RESIDENT_P12:
+            # what the launch actually asks HBM for: the 12-bit form of the same matrices (768 + 16 bytes per 1 KiB
+            # tile); `achieved` stays the method's own bytes (bf16 weights) over the launch time, as for bf16 slots
+            streamed = active_per_launch * (2 * blob / 3) * 784.0 / 1024.0 + wl.N * wl.d * 2 + rows_per_launch * wl.I * 2
+            roofline["bytes_streamed_per_launch"] = streamed
+            roofline["streamed"] = {"achieved": streamed / avg_s / 1e9, "frac": streamed / avg_s / 1e9 / HBM_PEAK_GBS, "unit": "GB/s"}
         # the same launch against the matrix cores: 2 * rows * d * 2I flop (gate and up) on the bf16 MFMA peak
         roofline["mfma"] = {"achieved": rows_per_launch * 4.0 * wl.d * wl.I / avg_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                             "unit": "TFLOP/s", "frac": rows_per_launch * 4.0 * wl.d * wl.I / avg_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
@@ -734,13 +798,15 @@ def main():
         this = {"workload": wl.name, "tokens_per_step": wl.N, "d": wl.d, "d_ff": wl.I, "capacity": wl.C, "layers_in_workload": 1,
                 "layers_measured": 1, "steps": args.steps, "warmup": args.warmup, "tokens_per_s": value, "ms_per_step": 1e3 * dt / args.steps,
                 "refresh_source": args.refresh_source,
-                "tokens_per_s_raw_refresh_copies": raw_source["tokens_per_s"] if raw_source else no_events["tokens_per_s"],
+                "tokens_per_s_raw_refresh_copies": raw_source["tokens_per_s"] if raw_source else (None if RESIDENT_P12 else no_events["tokens_per_s"]),
                 "frozen_placement": {"us_per_step": step_only_s * 1e6, "tokens_per_s": wl.N / step_only_s},
                 "kernels_us": {k_: v_["avg_us"] for k_, v_ in kernels.items()},
                 "roofline": None if frozen_cnt is None else layer_rooflines(
                     wl, blob, frozen_cnt["active_slots"] / frozen_cnt["steps"], frozen_cnt["rows"] / frozen_cnt["steps"],
                     1e-6 * kernels["gate_up_swiglu"]["avg_us"], 1e-6 * kernels["down"]["avg_us"], step_only_s)}
+        this["resident_format"] = args.resident
         configs = run_all_configs(args, ti, tb, TideSession, torch, this, packed, comp1)
+        choose_resident(args, wl)
         if roofline is not None and configs.get("4") and configs["4"].get("roofline"):
             c4 = configs["4"]
             roofline["cfg4"] = {"workload": c4["workload"], "tokens_per_step": c4["tokens_per_step"], "capacity": c4["capacity"],
@@ -760,7 +826,9 @@ def main():
                    "copy_engine": args.copy_engine, "resident_format": args.resident,
                    "refresh_mode": args.refresh_mode if args.refresh_mode == "immediate" else "deferred by %d step(s)" % args.commit_after},
         "value_refresh_source": args.refresh_source + (" (lossless 12-bit form of the blobs read over the host link)" if args.refresh_source == "packed12" else " blobs"),
-        "value_with_raw_refresh_copies": (raw_source or no_events)["tokens_per_s"],
+        "value_with_raw_refresh_copies": raw_source["tokens_per_s"] if raw_source else (None if RESIDENT_P12 else no_events["tokens_per_s"]),
+        "value_resident_format": ("12-bit slots (the blobs' lossless 12-bit form, decoded in the expert GEMMs' registers)" if RESIDENT_P12 else "bf16 slots"),
+        "value_with_bf16_slots": None if bf16_ref is None else bf16_ref["packed12"]["tokens_per_s"],
         "roofline": roofline,
         "configs": configs,
         "detail": {
