@@ -122,7 +122,9 @@ int tide_register_experts(tide_ctx* ctx, int layer, const void* host_blobs, uint
  *                               aligned, valid and unchanged until tide_destroy; NULL goes back to raw copies
  *                               (bf16 slots only).  Synchronises the device.  TIDE_E_INVAL for pageable memory
  *                               or a blob that is not of this configuration, TIDE_E_STATE before
- *                               tide_register_experts, or with 12-bit slots after tide_set_resident. */
+ *                               tide_register_experts.  With 12-bit slots the call also withdraws the layer's
+ *                               placement (the slots were filled from the blobs registered before): call
+ *                               tide_set_resident again before the next step or refresh. */
 #define TIDE_RESIDENT_BF16 0
 #define TIDE_RESIDENT_P12  1
 uint64_t tide_compressed_blob_bytes(const tide_config* cfg);

@@ -385,16 +385,27 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
 constexpr int kSmallPC = 16;       // 512 columns per stage
 constexpr int kSmallRT0 = 2, kSmallD0 = 8;   // gate/up: weight stripes per wave, ring depth
 constexpr int kSmallRT1 = 4, kSmallD1 = 4;   // down
-template <int PASS>
+// The same for a context whose slots keep the 12-bit form (P12SLOTS): a 12-bit tile is 3 registers in the ring
+// instead of 4, and with a ring half as deep the gate/up kernel fits three waves per SIMD instead of two, which hides
+// some of the decode's latency (an LDS table read, then a chain of byte permutes): 34.4 -> 33.3 us on the 32-token
+// layer of 65 slots.  A deeper ring, or two stripes per wave in the down pass, measured no faster.  The bf16 cases of
+// this kernel (an expert stored raw) use the same parameters.
+constexpr int kP12RT0 = 2, kP12D0 = 4;
+constexpr int kP12RT1 = 4, kP12D1 = 4;
+template <int PASS, bool P12SLOTS>
+constexpr int small_rt() { return P12SLOTS ? (PASS == 0 ? kP12RT0 : kP12RT1) : (PASS == 0 ? kSmallRT0 : kSmallRT1); }
+template <int PASS, bool P12SLOTS>
+constexpr int small_depth() { return P12SLOTS ? (PASS == 0 ? kP12D0 : kP12D1) : (PASS == 0 ? kSmallD0 : kSmallD1); }
+template <int PASS, bool P12SLOTS>
 __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
     const uint16_t* __restrict__ slots, int64_t blob_elems, int64_t off_w,
     const Task* __restrict__ tasks, const int32_t* __restrict__ n_tasks, const uint16_t* __restrict__ act_in,
     const int32_t* __restrict__ row_token, int K, int n_out, uint16_t* __restrict__ act_out,
     float* __restrict__ y_out) {
-    constexpr int RT = PASS == 0 ? kSmallRT0 : kSmallRT1;
-    constexpr int D = PASS == 0 ? kSmallD0 : kSmallD1;
+    constexpr int RT = small_rt<PASS, P12SLOTS>();
+    constexpr int D = small_depth<PASS, P12SLOTS>();
     __shared__ __attribute__((aligned(16))) uint16_t lds[kRowsPerTask * (kSmallPC * 32 + 8)];
-    __shared__ uint4 tables[kWaves][64];               // 12-bit slots: each wave's tile tables
+    __shared__ uint4 tables[P12SLOTS ? kWaves : 1][64];     // 12-bit slots: each wave's tile tables
     const int task_id = blockIdx.y;
     if (task_id >= n_tasks[0]) return;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // the same for a wave's lanes: scalar
@@ -406,13 +417,20 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_kernel(
     // sibling items of one slot (kTaskSiblings) use cacheable weight loads; up to 16 rows take one token tile
 #define TIDE_SMALL_CASE(NT_, SIB_, FMT_)                                                                                 \
     gemm_task<PASS, RT, NT_, D, kSmallPC, 1, SIB_, FMT_>(blob, off_w, wtile, active, task, act_in, row_token, K, n_out, \
-                                                        blob_elems, act_out, y_out, lds, tables[wave])
+                                                        blob_elems, act_out, y_out, lds, tables[P12SLOTS ? wave : 0])
     const bool one = task.nrows <= 16;
-    switch (task.flags & (kTaskSiblings | kTaskP12)) {
-        case 0: if (one) TIDE_SMALL_CASE(1, false, kFmtBf16); else TIDE_SMALL_CASE(2, false, kFmtBf16); break;
-        case kTaskSiblings: if (one) TIDE_SMALL_CASE(1, true, kFmtBf16); else TIDE_SMALL_CASE(2, true, kFmtBf16); break;
-        case kTaskP12: if (one) TIDE_SMALL_CASE(1, false, kFmtP12); else TIDE_SMALL_CASE(2, false, kFmtP12); break;
-        default: if (one) TIDE_SMALL_CASE(1, true, kFmtP12); else TIDE_SMALL_CASE(2, true, kFmtP12); break;
+    // a context with bf16 slots never flags a work item kTaskP12: those cases are not compiled into its kernel
+    const int flags = task.flags & (P12SLOTS ? (kTaskSiblings | kTaskP12) : kTaskSiblings);
+    if (flags == 0) {
+        if (one) TIDE_SMALL_CASE(1, false, kFmtBf16); else TIDE_SMALL_CASE(2, false, kFmtBf16);
+    } else if (flags == kTaskSiblings) {
+        if (one) TIDE_SMALL_CASE(1, true, kFmtBf16); else TIDE_SMALL_CASE(2, true, kFmtBf16);
+    } else if constexpr (P12SLOTS) {
+        if (flags == kTaskP12) {
+            if (one) TIDE_SMALL_CASE(1, false, kFmtP12); else TIDE_SMALL_CASE(2, false, kFmtP12);
+        } else {
+            if (one) TIDE_SMALL_CASE(1, true, kFmtP12); else TIDE_SMALL_CASE(2, true, kFmtP12);
+        }
     }
 #undef TIDE_SMALL_CASE
 }
@@ -533,15 +551,23 @@ hipError_t launch_expert_gemm(int pass, const Shape& s, const LayerTables& t, co
                               int max_tasks, hipStream_t stream, LaunchEvents ev) {
     if (max_tasks <= 0) return hipSuccess;
     dim3 block(kWaves * 64);
-    if (pass == 0) {
-        TIDE_LAUNCH(expert_gemm_kernel<0>, dim3((s.I + 32 * kSmallRT0 - 1) / (32 * kSmallRT0), max_tasks), block, stream, ev, t.slots, s.blob_elems,
-                    blob_off_gate_up(s), w.tasks, w.n_tasks, x, w.row_token, s.d, s.I, w.act,
-                    (float*)nullptr);
-    } else {
-        TIDE_LAUNCH(expert_gemm_kernel<1>, dim3((s.d + 64 * kSmallRT1 - 1) / (64 * kSmallRT1), max_tasks), block, stream, ev, t.slots, s.blob_elems,
-                    blob_off_down(s), w.tasks, w.n_tasks, w.act, w.row_token, s.I, s.d,
-                    (uint16_t*)nullptr, w.y);
-    }
+    auto launch = [&](auto p12) {
+        constexpr bool P12 = decltype(p12)::value;
+        if (pass == 0) {
+            constexpr int cols = 16 * kWaves * (small_rt<0, P12>() / 2);      // SwiGLU columns per workgroup
+            TIDE_LAUNCH((expert_gemm_kernel<0, P12>), dim3((s.I + cols - 1) / cols, max_tasks), block, stream, ev, t.slots, s.blob_elems,
+                        blob_off_gate_up(s), w.tasks, w.n_tasks, x, w.row_token, s.d, s.I, w.act,
+                        (float*)nullptr);
+        } else {
+            constexpr int cols = 16 * kWaves * small_rt<1, P12>();            // output columns per workgroup
+            TIDE_LAUNCH((expert_gemm_kernel<1, P12>), dim3((s.d + cols - 1) / cols, max_tasks), block, stream, ev, t.slots, s.blob_elems,
+                        blob_off_down(s), w.tasks, w.n_tasks, w.act, w.row_token, s.I, s.d,
+                        (uint16_t*)nullptr, w.y);
+        }
+    };
+    // the miss pass reads the host's bf16 blobs through a table view without format flags: the bf16 kernel
+    if (t.expert_p12) launch(std::true_type{});
+    else launch(std::false_type{});
     return hipGetLastError();
 }
 

@@ -544,11 +544,15 @@ int tide_register_compressed(tide_ctx* ctx, int layer, const void* comp_host_blo
     }
     TIDE_HIP(ctx, hipDeviceSynchronize());
     if (ctx->shape.resident_p12) {
-        if (L.placed) return fail(ctx, TIDE_E_STATE, "layer %d: register the compressed blobs before tide_set_resident", layer);
         std::vector<uint8_t> flags(ctx->cfg.n_experts);
         for (int e = 0; e < ctx->cfg.n_experts; ++e)
             flags[e] = reinterpret_cast<const P12Header*>(static_cast<const uint8_t*>(comp_host_blobs) + (uint64_t)e * comp_stride)->raw ? 0 : 1;
         TIDE_HIP(ctx, hipMemcpy(L.expert_p12, flags.data(), flags.size(), hipMemcpyHostToDevice));
+        // what the slots hold was copied from the blobs registered before: the layer needs a placement again
+        L.placed = false;
+        L.copies_pending = false;
+        L.deferred_pending = false;
+        L.pend_slots.clear();
     }
     L.comp_blobs = static_cast<const uint8_t*>(comp_host_blobs);
     L.comp_stride = comp_stride;

@@ -39,6 +39,7 @@ REPORT = os.path.join(ROOT, "gpurun_out", "parity_report.json")
 
 _BITS = {}       # (d, I, E, seed, layer) -> list of E+1 (wg, wu, wd) bf16 bit triples
 _PACKED = {}     # same key -> (pinned blobs, shared blob)
+_COMP = {}       # same key -> pinned 12-bit form of the blobs (sessions with 12-bit slots)
 
 
 def _key(wl, layer):
@@ -65,9 +66,24 @@ def packed_layer(sess, wl, layer):
     return _PACKED[key]
 
 
+def compressed_layer(sess, wl, layer):
+    """Pinned 12-bit form of packed_layer's blobs, built once per test session."""
+    from paper_2605_20179_amd import binding as tb
+    key = _key(wl, layer)
+    if key not in _COMP:
+        raw = packed_layer(sess, wl, layer)[0].numpy()
+        comp = torch.empty((wl.E, tb.tide_compressed_blob_bytes(sess.cfg)), dtype=torch.uint8, pin_memory=True)
+        out = comp.numpy()
+        with concurrent.futures.ThreadPoolExecutor(max_workers=16) as ex:
+            list(ex.map(lambda e: tb.tide_compress_expert(sess.cfg, raw[e], out[e]), range(wl.E)))
+        _COMP[key] = comp
+    return _COMP[key]
+
+
 def forget(wl, layer):
     _BITS.pop(_key(wl, layer), None)
     _PACKED.pop(_key(wl, layer), None)
+    _COMP.pop(_key(wl, layer), None)
 
 
 def load_packed(sess, wl, layer, sess_layer=None, resident=None, values_of=None):
@@ -75,7 +91,8 @@ def load_packed(sess, wl, layer, sess_layer=None, resident=None, values_of=None)
     workload layer `values_of` (default: its own)."""
     sess.load_layer(layer if sess_layer is None else sess_layer, None, ti.router_weights(wl, layer),
                     ti.router_bias(wl, layer), ti.initial_resident(wl) if resident is None else resident,
-                    packed=packed_layer(sess, wl, layer if values_of is None else values_of))
+                    packed=packed_layer(sess, wl, layer if values_of is None else values_of),
+                    comp=compressed_layer(sess, wl, layer if values_of is None else values_of) if sess.resident_p12 else None)
 
 
 def report(section, payload):
@@ -269,7 +286,7 @@ def near_tie_summary(runs):
             "tokens_selected_differently_total": int(sum(sum(r.flips) for r in runs))}
 
 
-def run_config(name, wl, layers, own_values, out_checks, sample_rate_steps=0):
+def run_config(name, wl, layers, own_values, out_checks, sample_rate_steps=0, p12=False):
     """Context of len(layers) layers; forced-routing run (everything downstream of routing bit-exact, outputs),
     then a run with the library's own routing (selections, weights; downstream exact until a near-tie flips)."""
     from paper_2605_20179_amd import binding as tb
@@ -278,8 +295,9 @@ def run_config(name, wl, layers, own_values, out_checks, sample_rate_steps=0):
     runs = [LayerRun(wl, layer, li, with_outputs=layer in own_values, values_of=layer if layer in own_values else layers[0])
             for li, layer in enumerate(layers)]
     say("%s: oracle routing of %d layers x %d steps in %.1f s" % (name, len(runs), wl.S, time.perf_counter() - t0))
-    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, n_layers=len(layers))
-    summary = {}
+    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, n_layers=len(layers),
+                       resident_p12=p12)
+    summary = {"resident_format": "p12" if p12 else "bf16"}
     for forced in (True, False):
         for run in runs:
             load_packed(sess, wl, run.layer, sess_layer=run.li, values_of=run.values_of)
@@ -303,12 +321,15 @@ def run_config(name, wl, layers, own_values, out_checks, sample_rate_steps=0):
 
 
 # ----------------------------------------------------------------------------- configuration 2
-def test_config2_stack_at_depth():
+@pytest.mark.parametrize("p12", [False, True], ids=["bf16 slots", "12-bit slots"])
+def test_config2_stack_at_depth(p12):
     """Mini-shaped stack at its depth: 20 layers x 256 tokens x the 32-step block, K = 4.  Outputs on layers 0, 7
-    and 19 (own expert values) at a cold step, a refresh step, the step after it and the last one."""
+    and 19 (own expert values) at a cold step, a refresh step, the step after it and the last one.  Once over bf16
+    slots and once over 12-bit slots (the form bench.py times this configuration in)."""
     wl = ti.CONFIGS[2]
     checks = {(layer, t): 48 for layer in (0, 7, 19) for t in (0, 4, 5, 31)}
-    s = run_config("cfg2-mini-stack L=20", wl, list(range(wl.L)), {0, 7, 19}, checks, sample_rate_steps=16)
+    s = run_config("cfg2-mini-stack L=20" + (" 12-bit slots" if p12 else ""), wl, list(range(wl.L)), {0, 7, 19}, checks,
+                   sample_rate_steps=16, p12=p12)
     assert s["worst"] <= 1e-2
 
 

@@ -176,7 +176,8 @@ def test_large_work_items_over_12bit_slots():
 
 
 def test_12bit_slots_need_the_compressed_blobs():
-    """Error paths: no placement, no refresh and no unregistering without the compressed blobs."""
+    """Error paths: no placement and no unregistering without the compressed blobs; registering them again withdraws
+    the placement until tide_set_resident is called again."""
     from paper_2605_20179_amd import binding as tb
     from paper_2605_20179_amd.session import TideSession
     wl = ti.CONFIGS[0]
@@ -194,7 +195,22 @@ def test_12bit_slots_need_the_compressed_blobs():
     if wl.n_shared:
         tb.tide_set_shared(sess.ctx, 0, packed[1])
     tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))
-    with pytest.raises(tb.TideError) as ei:                  # the flags are fixed once slots have been filled
-        sess.compress_layer(0, workers=4)
+    sess.router_w[0] = torch.from_numpy(np.ascontiguousarray(ti.router_weights(wl, 0), dtype=np.float32)).to(sess.device)
+    bias = ti.router_bias(wl, 0)
+    sess.router_b[0] = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias, dtype=np.float32)).to(sess.device)
+    x = sess.to_device_bf16(next(iter(ti.hidden_stream(wl, 0))))
+    sess.step(0, x)
+    want = sess.results(wl.N)[0].copy()
+    # registering compressed blobs again withdraws the placement: the slots were filled from the earlier ones
+    sess.compress_layer(0, workers=4)
+    with pytest.raises(tb.TideError) as ei:
+        sess.step(0, x)
     assert ei.value.code == tb.TIDE_E_STATE
+    with pytest.raises(tb.TideError) as ei:
+        sess.refresh(0)
+    assert ei.value.code == tb.TIDE_E_STATE
+    tb.tide_set_resident(sess.ctx, 0, ti.initial_resident(wl))
+    sess.stats(0, reset=True)
+    sess.step(0, x)
+    assert np.array_equal(sess.results(wl.N)[0], want)
     sess.close()

@@ -19,17 +19,19 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("p12", [False, True], ids=["bf16 slots", "12-bit slots"])
 @pytest.mark.parametrize("name,wl", CASES, ids=[c[0] for c in CASES])
-def test_stack_step_equals_layer_by_layer(name, wl):
+def test_stack_step_equals_layer_by_layer(name, wl, p12):
     from paper_2605_20179_amd import binding as tb
     from paper_2605_20179_amd.session import TideSession
-    say("stack: " + name)
+    say("stack: %s, %s" % (name, "12-bit slots" if p12 else "bf16 slots"))
 
     def make():
-        sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, n_layers=wl.L)
+        sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, n_layers=wl.L, resident_p12=p12)
         packed = sess.pack_layer(lambda e: ti.expert_weights(wl, 0, e), workers=16)
-        for l in range(wl.L):
-            sess.load_layer(l, None, ti.router_weights(wl, l), ti.router_bias(wl, l), ti.initial_resident(wl), packed=packed)
+        for l in range(wl.L):                             # the layers share layer 0's blobs, compressed once
+            sess.load_layer(l, None, ti.router_weights(wl, l), ti.router_bias(wl, l), ti.initial_resident(wl), packed=packed,
+                            comp=sess.comp_blobs.get(0))
         return sess
 
     ref, stk = make(), make()

@@ -35,12 +35,13 @@ def _run(sess, tb, fn, x, n):
     return out.copy(), idx.copy(), w.copy(), raw_miss, n_miss, sess.stats(0).copy(), tb.tide_step_histogram(sess.ctx, sess.E)
 
 
+@pytest.mark.parametrize("p12", [False, True], ids=["bf16 slots", "12-bit slots"])
 @pytest.mark.parametrize("name,wl,token_counts", CASES, ids=[c[0] for c in CASES])
-def test_noalloc_step_equals_the_allocating_one(name, wl, token_counts):
+def test_noalloc_step_equals_the_allocating_one(name, wl, token_counts, p12):
     from paper_2605_20179_amd import binding as tb
     from paper_2605_20179_amd.session import TideSession
-    print("[noalloc] %s: %s" % (name, token_counts), flush=True)
-    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode)
+    print("[noalloc] %s: %s, %s" % (name, token_counts, "12-bit slots" if p12 else "bf16 slots"), flush=True)
+    sess = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, resident_p12=p12)
     sess.load_layer(0, lambda e: ti.expert_weights(wl, 0, e), ti.router_weights(wl, 0), ti.router_bias(wl, 0),
                     ti.initial_resident(wl), workers=16)
     hidden = sess.to_device_bf16(next(iter(ti.hidden_stream(wl, 0))))
