@@ -257,7 +257,7 @@ def measure_layer(wl, ti, tb, TideSession, torch, packed, steps, warmup, refresh
     res = {"workload": wl.name, "tokens_per_step": wl.N, "d": wl.d, "d_ff": wl.I, "capacity": wl.C, "layers_in_workload": wl.L,
            "layers_measured": 1, "steps": steps, "warmup": warmup,
            "tokens_per_s": wl.N * steps / dt, "ms_per_step": 1e3 * dt / steps, "refresh_source": refresh_source if use_p12 else "raw",
-           "tokens_per_s_raw_refresh_copies": raw if raw is not None else wl.N * steps / dt,
+           "tokens_per_s_raw_refresh_copies": raw if raw is not None else (None if RESIDENT_P12 else wl.N * steps / dt),
            "experts_copied": copies, "hit_rate": 1.0 - cnt["misses"] / (wl.N * wl.k * cnt["steps"]),
            "frozen_placement": {"us_per_step": frozen_s * 1e6, "tokens_per_s": wl.N / frozen_s, "hit_rate": 1.0 - fcnt["misses"] / (wl.N * wl.k * fcnt["steps"]),
                                 "active_slots_per_step": active, "rows_per_step": rows},

@@ -14,7 +14,7 @@ import collections
 
 def short(name: str) -> str:
     name = name.replace("tide::(anonymous namespace)::", "").replace("void ", "")
-    return name.split("(")[0]
+    return name.split("(")[0].replace(", ", ",")          # no blanks inside a name: the summaries are column text
 
 
 def pmc(path: str, warmup: int, steps: int) -> None:
