@@ -1,8 +1,8 @@
 """GPU parity on a seeded sweep of random valid shapes (hidden size, experts, top-k, intermediate size, shared expert,
 tokens per step, capacity, gating and bias mode drawn at random within the library's limits): a three-step block with
 one refresh per shape, compared with the oracle as in test_gpu_parity (routing, counters, tables, plans, miss lists
-bit-exact; outputs within tolerance), then the same block with the refresh copies read from the compressed blobs and
-the misses evaluated by the host workers."""
+bit-exact; outputs within tolerance), then the same block over 12-bit cache slots, and with the refresh copies read from
+the compressed blobs and the misses evaluated by the host workers."""
 import numpy as np
 import pytest
 import torch
@@ -38,6 +38,7 @@ def _draw(rng):
 
 @pytest.mark.parametrize("seed", [11, 12])
 def test_random_shapes(seed, monkeypatch):
+    from paper_2605_20179_amd.session import TideSession
     monkeypatch.setattr(tp, "check_out", lambda out, y_ref, rows=None: _check_out(out if rows is None else out[rows], y_ref))
     rng = np.random.default_rng(seed)
     for case in range(16):
@@ -52,6 +53,11 @@ def test_random_shapes(seed, monkeypatch):
             tp.load(sess, wl, 0)
             tp.run_block_on_gpu(wl, 0, sess, log, hidden, forced, [0, 2])
             sess.close()
+        # the same block over 12-bit cache slots (partial stripe groups, K chunks that do not fill a ring turn, ...)
+        p12 = TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, resident_p12=True)
+        tp.load(p12, wl, 0)
+        tp.run_block_on_gpu(wl, 0, p12, log, hidden, True, [0, 2])
+        p12.close()
         sess = tp._session(wl)
         tp.load(sess, wl, 0)
         sess.compress_layer(0, workers=4)
