@@ -11,7 +11,7 @@ rows in the sample; a seeded random draw fills the rest.  Beside the error again
 default (SwiGLU activation stored in bf16, as the kernels store it) the error against the un-rounded
 definition is computed and reported.  A step of every output-checked layer is run twice and must
 repeat bit for bit.  Near-tie tokens (selection keys closer than 1e-5, where fp32 and fp64 may order
-differently) and the errors are written to gpurun_out/parity_report.json (the un-rounded figure is a report, not
+differently) and the errors are written to a JSON report (REPORT below; the un-rounded figure is a report, not
 a bound: the bf16 store alone moves single outputs by up to about 1e-2 x RMS).
 
 Stacks: layers are independent (own router, hidden stream, cache, counter, refresh).  To bound host
@@ -96,7 +96,7 @@ def load_packed(sess, wl, layer, sess_layer=None, resident=None, values_of=None)
 
 
 def report(section, payload):
-    """Merges `payload` into gpurun_out/parity_report.json under `section`."""
+    """Merges `payload` into the JSON report under `section`."""
     os.makedirs(os.path.dirname(REPORT), exist_ok=True)
     try:
         doc = json.load(open(REPORT))
