@@ -9,8 +9,9 @@
 // per element a 4-bit index into that table.  A tile with more than 16 distinct high bytes cannot be encoded:
 // the whole blob is then marked raw and used in its bf16 form (Gaussian weights: a few tiles in a million).
 //
-//   [0, 64)                    header: magic, n_tiles, raw (1 = not encoded: use the bf16 blob)
-//   [64, 64 + 768 T)           tile payloads in tile order.  Lane l (the 8 consecutive elements 8l .. 8l+7 of the
+//   [0, 128)                   header: magic, n_tiles, raw (1 = not encoded: use the bf16 blob); one 128-byte cache
+//                              line, so that every 768-byte payload below is six whole lines
+//   [128, 128 + 768 T)         tile payloads in tile order.  Lane l (the 8 consecutive elements 8l .. 8l+7 of the
 //                              tile) owns the 3 dwords at byte 12 l:
 //                                a0: low bytes of elements 0..3          a1: low bytes of elements 4..7
 //                                b : byte j = index of element j | index of element 4+j << 4
@@ -25,13 +26,13 @@ namespace tide {
 constexpr uint32_t kP12Magic = 0x32315054u;      // "TP12"
 constexpr int kP12TileBytes = 768;
 constexpr int kP12TableBytes = 16;
-constexpr int kP12HeaderBytes = 64;
+constexpr int kP12HeaderBytes = 128;
 
 struct P12Header {
     uint32_t magic, n_tiles, raw;
-    uint32_t pad[13];
+    uint32_t pad[29];
 };
-static_assert(sizeof(P12Header) == kP12HeaderBytes, "header is one 64-byte line");
+static_assert(sizeof(P12Header) == kP12HeaderBytes, "header is one 128-byte line");
 
 struct P12Layout {
     uint64_t off_payload, off_table, bytes;
@@ -39,7 +40,7 @@ struct P12Layout {
 constexpr P12Layout p12_layout(uint64_t n_tiles) {        // constexpr: callable from host and device code alike
     P12Layout l{};
     l.off_payload = kP12HeaderBytes;
-    l.off_table = l.off_payload + n_tiles * kP12TileBytes;                  // 768 = 12 x 64: still 64-byte aligned
+    l.off_table = l.off_payload + n_tiles * kP12TileBytes;                  // 768 = 6 x 128: still 128-byte aligned
     l.bytes = (l.off_table + n_tiles * kP12TableBytes + 63) / 64 * 64;
     return l;
 }

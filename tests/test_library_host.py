@@ -145,12 +145,12 @@ def test_host_miss_path_matches_the_oracle(tb, n_tokens, n_experts, k, threads, 
 
 def _p12_decode(comp: np.ndarray, n_tiles: int) -> np.ndarray:
     """Decoder written from the format's description in include/tide.h and csrc/packed12.h, independent of the
-    library: header; per tile 64 lanes x 3 dwords (the low bytes of the lane's elements 0..3 and 4..7, then one byte
+    library: a 128-byte header; per tile 64 lanes x 3 dwords (the low bytes of the lane's elements 0..3 and 4..7, then one byte
     per element pair j, 4+j holding their two 4-bit table indices); per tile a table of 16 high bytes."""
     hdr = comp[:64].view(np.uint32)
     assert hdr[0] == 0x32315054 and hdr[1] == n_tiles and hdr[2] == 0
-    off_table = 64 + n_tiles * 768
-    words = comp[64:off_table].view(np.uint32).reshape(n_tiles, 64, 3).astype(np.int64)
+    off_table = 128 + n_tiles * 768
+    words = comp[128:off_table].view(np.uint32).reshape(n_tiles, 64, 3).astype(np.int64)
     table = comp[off_table:off_table + 16 * n_tiles].reshape(n_tiles, 16).astype(np.int64)
     vals = np.zeros((n_tiles, 64, 8), dtype=np.int64)
     for j in range(8):
@@ -168,7 +168,7 @@ def test_compressed_blob_round_trip(tb):
     cfg = tb.make_config(d, 8, 2, I, 0, 1, 4, 8, 0, 0)
     n_tiles = 3 * d * I // 512
     cbytes = tb.tide_compressed_blob_bytes(cfg)
-    assert cbytes % 64 == 0 and cbytes == 64 + n_tiles * (768 + 16) and cbytes < 0.77 * tb.tide_expert_blob_bytes(cfg)
+    assert cbytes % 64 == 0 and cbytes == 128 + n_tiles * (768 + 16) and cbytes < 0.77 * tb.tide_expert_blob_bytes(cfg)
     rng = np.random.default_rng(12)
     def bits(shape, scale):
         return (np.ascontiguousarray(rng.normal(0, scale, size=shape), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
