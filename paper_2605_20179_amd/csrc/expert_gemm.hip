@@ -107,6 +107,8 @@ struct WeightStream {
     int first;                // tile index of the wave's first stripe (PASS 0: its first gate stripe), chunk 0
     int cstep;                // tiles from one K chunk to the next
     int up;                   // PASS 0: tiles from a gate stripe to the matching up stripe
+    int table_first;          // 12-bit form: table slot of that first stripe, chunk 0 (tables are stored stripe first:
+                              // stripe r, chunk c of the wave at table_first + stripe_tile(r) * chunks + c)
 };
 
 template <int PASS, int RT>
@@ -132,6 +134,7 @@ __device__ inline void weight_stream(int tile0, int wtile, bool active, int K, i
         ws.first = tile0 + g * 2 * kGateUpGroup * kchunks + j0;
         ws.cstep = 2 * ng;
         ws.up = ng;
+        ws.table_first = tile0 + g * 2 * kGateUpGroup * kchunks + j0 * kchunks;
     } else {
         static_assert(PASS == 0 || kDownGroup % RT == 0, "a wave's stripes share a group");
         const int first = wsrc * RT;
@@ -140,6 +143,7 @@ __device__ inline void weight_stream(int tile0, int wtile, bool active, int K, i
         ws.first = tile0 + g * kDownGroup * kchunks + j0;
         ws.cstep = ng;
         ws.up = 0;
+        ws.table_first = tile0 + g * kDownGroup * kchunks + j0 * kchunks;
     }
 }
 
@@ -178,7 +182,7 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
     uint4 next_tables;
     auto fetch_tables = [&](int block) {
         const int c = min(block * kTableChunks + lane / RT, kchunks - 1), r = lane % RT;
-        const int t = ws.first + ((PASS == 0 && r >= G) ? ws.up + (r - G) : r) + c * ws.cstep;
+        const int t = ws.table_first + ((PASS == 0 && r >= G) ? ws.up + (r - G) : r) * kchunks + c;
         next_tables = *reinterpret_cast<const uint4*>(table0 + (int64_t)t * kP12TableBytes);
     };
     auto table_block = [&](int block) {               // at the first chunk of a block

@@ -55,8 +55,8 @@ void pack_expert_blob(int d, int d_ff, const uint16_t* wg, const uint16_t* wu, c
     pack_down(wd, d, d_ff, blob + 2 * (int64_t)d * d_ff);
 }
 
-void compress_expert_blob(uint64_t blob_bytes, const uint16_t* src, uint8_t* out) {
-    const uint32_t n_tiles = (uint32_t)(blob_bytes / 1024);
+void compress_expert_blob(int d, int d_ff, const uint16_t* src, uint8_t* out) {
+    const uint32_t n_tiles = (uint32_t)(3ull * d * d_ff / 512);
     const P12Layout lay = p12_layout(n_tiles);
     memset(out, 0, lay.bytes);
     P12Header* h = reinterpret_cast<P12Header*>(out);
@@ -68,7 +68,7 @@ void compress_expert_blob(uint64_t blob_bytes, const uint16_t* src, uint8_t* out
         bool seen[256] = {false};
         for (int i = 0; i < 512; ++i) seen[tile[i] >> 8] = true;
         uint8_t code_of[256];
-        uint8_t* table = out + lay.off_table + (uint64_t)t * kP12TableBytes;
+        uint8_t* table = out + lay.off_table + (uint64_t)p12_table_slot(t, d, d_ff) * kP12TableBytes;
         int n = 0;
         for (int v = 0; v < 256; ++v)
             if (seen[v]) {
@@ -95,14 +95,14 @@ void compress_expert_blob(uint64_t blob_bytes, const uint16_t* src, uint8_t* out
     }
 }
 
-bool decompress_expert_blob(uint64_t blob_bytes, const uint8_t* comp, uint16_t* blob) {
-    const uint32_t n_tiles = (uint32_t)(blob_bytes / 1024);
+bool decompress_expert_blob(int d, int d_ff, const uint8_t* comp, uint16_t* blob) {
+    const uint32_t n_tiles = (uint32_t)(3ull * d * d_ff / 512);
     const P12Layout lay = p12_layout(n_tiles);
     const P12Header* h = reinterpret_cast<const P12Header*>(comp);
     if (h->magic != kP12Magic || h->n_tiles != n_tiles || h->raw) return false;
     for (uint32_t t = 0; t < n_tiles; ++t) {
         const uint32_t* words = reinterpret_cast<const uint32_t*>(comp + lay.off_payload + (uint64_t)t * kP12TileBytes);
-        const uint8_t* table = comp + lay.off_table + (uint64_t)t * kP12TableBytes;
+        const uint8_t* table = comp + lay.off_table + (uint64_t)p12_table_slot(t, d, d_ff) * kP12TableBytes;
         for (int l = 0; l < 64; ++l)
             for (int j = 0; j < 8; ++j)
                 blob[(uint64_t)t * 512 + l * 8 + j] = p12_element(words[l * 3], words[l * 3 + 1], words[l * 3 + 2], table, j);

@@ -8,10 +8,11 @@ namespace tide {
 // wg / wu [d_ff][d], wd [d][d_ff] row-major bf16 -> blob (3 * d * d_ff elements) in the layout tide_pack_expert documents.
 void pack_expert_blob(int d, int d_ff, const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, uint16_t* blob);
 
-// packed blob (blob_bytes, a multiple of 1024) -> its 12-bit form (packed12.h), p12_layout(blob_bytes / 1024).bytes long.
-void compress_expert_blob(uint64_t blob_bytes, const uint16_t* src, uint8_t* out);
+// packed blob of an expert with hidden size d and intermediate size d_ff -> its 12-bit form (packed12.h),
+// p12_layout(3 * d * d_ff / 512).bytes long.
+void compress_expert_blob(int d, int d_ff, const uint16_t* src, uint8_t* out);
 
-// the inverse: false (blob untouched) when `comp` is not a compressed blob of that size or is marked raw
-bool decompress_expert_blob(uint64_t blob_bytes, const uint8_t* comp, uint16_t* blob);
+// the inverse: false (blob untouched) when `comp` is not a compressed blob of that shape or is marked raw
+bool decompress_expert_blob(int d, int d_ff, const uint8_t* comp, uint16_t* blob);
 
 }  // namespace tide

@@ -15,7 +15,10 @@
 //                              tile) owns the 3 dwords at byte 12 l:
 //                                a0: low bytes of elements 0..3          a1: low bytes of elements 4..7
 //                                b : byte j = index of element j | index of element 4+j << 4
-//   then 16 T bytes            tables: 16 high bytes per tile, unused entries zero
+//   then 16 T bytes            tables: 16 high bytes per tile, unused entries zero.  Inside a stripe group of the packed
+//                              layout the payloads are ordered K chunk first, the tables stripe first (table of stripe
+//                              j, chunk c of a group at the group's first tile + j * chunks + c): a wave of the expert
+//                              GEMMs walks the chunks of its own stripes, so the tables it needs next are contiguous
 //
 // Plain C++: included by the host-side encoder / decoder and by the device code.
 #pragma once
@@ -43,6 +46,21 @@ constexpr P12Layout p12_layout(uint64_t n_tiles) {        // constexpr: callable
     l.off_table = l.off_payload + n_tiles * kP12TileBytes;                  // 768 = 6 x 128: still 128-byte aligned
     l.bytes = (l.off_table + n_tiles * kP12TableBytes + 63) / 64 * 64;
     return l;
+}
+
+// Where the table of payload tile `tile` sits (in tables from the start of the table region), for a blob of an expert
+// with hidden size d and intermediate size d_ff: the packed layout's groups (8 SwiGLU column blocks = up to 16 gate and
+// up stripes; then 16 down stripes), a last group with fewer stripes included.
+constexpr uint32_t p12_table_slot(uint32_t tile, int d, int d_ff) {
+    const uint32_t kcd = d / 32, blocks = d_ff / 16, kci = d_ff / 32, stripes = d / 16, gate_up = 2 * blocks * kcd;
+    if (tile < gate_up) {
+        const uint32_t span = 2 * 8 * kcd, g = tile / span, base = g * span;
+        const uint32_t width = 2 * (blocks - 8 * g < 8 ? blocks - 8 * g : 8);
+        return base + ((tile - base) % width) * kcd + (tile - base) / width;
+    }
+    const uint32_t t = tile - gate_up, span = 16 * kci, g = t / span, base = g * span;
+    const uint32_t width = stripes - 16 * g < 16 ? stripes - 16 * g : 16;
+    return gate_up + base + ((t - base) % width) * kci + (t - base) / width;
 }
 
 // element j (0..7) of a lane from the lane's three dwords and the tile's table

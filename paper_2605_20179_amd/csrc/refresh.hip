@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kCopyThreads) void refresh_copy_p12_kernel(const ui
                                                                        const uint8_t* __restrict__ host_blobs, uint64_t host_stride,
                                                                        uint64_t blob_bytes, uint8_t* __restrict__ dst_base,
                                                                        const RefreshOut* __restrict__ plan, int n, int dst_by_rank,
-                                                                       int verbatim) {
+                                                                       int verbatim, int d, int d_ff) {
     const int lane = threadIdx.x & 63;
     const uint32_t wave = (blockIdx.x * kCopyThreads + threadIdx.x) >> 6, n_waves = gridDim.x * (kCopyThreads / 64);
     const uint32_t n_tiles = (uint32_t)(blob_bytes / 1024);
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(kCopyThreads) void refresh_copy_p12_kernel(const ui
 #pragma unroll
             for (int u = 0; u < kP12InFlight; ++u) {
                 w[u] = *reinterpret_cast<const P12Words*>(payload + (uint64_t)(t + u * n_waves) * kP12TileBytes);
-                tab[u] = *reinterpret_cast<const uint4*>(table + (uint64_t)(t + u * n_waves) * kP12TableBytes);
+                tab[u] = *reinterpret_cast<const uint4*>(table + (uint64_t)p12_table_slot(t + u * n_waves, d, d_ff) * kP12TableBytes);
             }
 #pragma unroll
             for (int u = 0; u < kP12InFlight; ++u)
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kCopyThreads) void refresh_copy_p12_kernel(const ui
         for (; t < n_tiles; t += n_waves)
             *reinterpret_cast<uint4*>(dst + (uint64_t)t * 1024 + lane * 16) =
                 p12_decode(*reinterpret_cast<const P12Words*>(payload + (uint64_t)t * kP12TileBytes),
-                           *reinterpret_cast<const uint4*>(table + (uint64_t)t * kP12TableBytes));
+                           *reinterpret_cast<const uint4*>(table + (uint64_t)p12_table_slot(t, d, d_ff) * kP12TableBytes));
     }
 }
 
@@ -254,11 +254,11 @@ hipError_t launch_refresh_copies(const uint8_t* host_blobs, uint64_t host_stride
 
 hipError_t launch_refresh_copies_p12(const uint8_t* comp_blobs, uint64_t comp_stride, const uint8_t* host_blobs,
                                      uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base, const RefreshOut* plan, int n,
-                                     bool dst_by_rank, bool verbatim, hipStream_t stream) {
+                                     bool dst_by_rank, bool verbatim, int d, int d_ff, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     if (hipError_t rc = reserve_lds(refresh_copy_p12_kernel); rc != hipSuccess) return rc;
     hipLaunchKernelGGL(refresh_copy_p12_kernel, dim3(kCopyBlocks), dim3(kCopyThreads), kCopyLdsReserve, stream, comp_blobs, comp_stride,
-                       host_blobs, host_stride, blob_bytes, dst_base, plan, n, dst_by_rank ? 1 : 0, verbatim ? 1 : 0);
+                       host_blobs, host_stride, blob_bytes, dst_base, plan, n, dst_by_rank ? 1 : 0, verbatim ? 1 : 0, d, d_ff);
     return hipGetLastError();
 }
 

@@ -505,7 +505,7 @@ int tide_compress_expert(const tide_config* cfg, const void* blob_host, void* co
     int rc = check_cfg(cfg);
     if (rc) return rc;
     if (!blob_host || !comp_host) return fail(nullptr, TIDE_E_INVAL, "null matrix or blob pointer");
-    compress_expert_blob(tide_expert_blob_bytes(cfg), static_cast<const uint16_t*>(blob_host), static_cast<uint8_t*>(comp_host));
+    compress_expert_blob(cfg->d, cfg->d_ff, static_cast<const uint16_t*>(blob_host), static_cast<uint8_t*>(comp_host));
     return TIDE_OK;
 }
 
@@ -513,7 +513,7 @@ int tide_decompress_expert(const tide_config* cfg, const void* comp_host, void* 
     int rc = check_cfg(cfg);
     if (rc) return rc;
     if (!blob_host || !comp_host) return fail(nullptr, TIDE_E_INVAL, "null blob pointer");
-    if (!decompress_expert_blob(tide_expert_blob_bytes(cfg), static_cast<const uint8_t*>(comp_host), static_cast<uint16_t*>(blob_host)))
+    if (!decompress_expert_blob(cfg->d, cfg->d_ff, static_cast<const uint8_t*>(comp_host), static_cast<uint16_t*>(blob_host)))
         return fail(nullptr, TIDE_E_INVAL, "not a compressed blob of this configuration, or one marked raw");
     return TIDE_OK;
 }
@@ -572,7 +572,7 @@ int tide_set_shared(tide_ctx* ctx, int layer, const void* blob_host) {
     std::vector<uint8_t> comp;
     if (ctx->shape.resident_p12) {
         comp.resize(tide_compressed_blob_bytes(&ctx->cfg));
-        compress_expert_blob(bytes, static_cast<const uint16_t*>(blob_host), comp.data());
+        compress_expert_blob(ctx->cfg.d, ctx->cfg.d_ff, static_cast<const uint16_t*>(blob_host), comp.data());
         const uint8_t is_p12 = reinterpret_cast<const P12Header*>(comp.data())->raw ? 0 : 1;
         if (is_p12) {
             src = comp.data();
@@ -1095,7 +1095,7 @@ int refresh_impl(tide_ctx* ctx, int layer, const int32_t* counts_host, int capac
         }
     } else if (L.comp_blobs)
         TIDE_HIP(ctx, launch_refresh_copies_p12(L.comp_blobs, L.comp_stride, L.host_blobs, L.host_stride, bytes, copy_dst, L.plan, n,
-                                                deferred, ctx->shape.resident_p12 != 0, ctx->side));
+                                                deferred, ctx->shape.resident_p12 != 0, ctx->shape.d, ctx->shape.I, ctx->side));
     else
         TIDE_HIP(ctx, launch_refresh_copies(L.host_blobs, L.host_stride, bytes, copy_dst, L.plan, n, deferred, ctx->side));
     if (async) {

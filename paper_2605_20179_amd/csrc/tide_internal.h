@@ -185,7 +185,7 @@ hipError_t launch_refresh_copies(const uint8_t* host_blobs, uint64_t host_stride
 // (verbatim) copied as they are for slots that keep the 12-bit form
 hipError_t launch_refresh_copies_p12(const uint8_t* comp_blobs, uint64_t comp_stride, const uint8_t* host_blobs,
                                      uint64_t host_stride, uint64_t blob_bytes, uint8_t* dst_base, const RefreshOut* plan, int n,
-                                     bool dst_by_rank, bool verbatim, hipStream_t stream);
+                                     bool dst_by_rank, bool verbatim, int d, int d_ff, hipStream_t stream);
 // measurement: `bytes` (a multiple of 1024) from `base` read once by `workgroups` workgroups in the GEMMs' weight-stream shape
 hipError_t launch_stream_probe(const uint8_t* base, uint64_t bytes, int workgroups, uint32_t* sink, hipStream_t stream, LaunchEvents ev);
 // H[e] <- floor(H[e] * num / den)

@@ -26,13 +26,13 @@ static float f32_of(uint16_t b) { uint32_t u = (uint32_t)b << 16; float f; memcp
     } while (0)
 
 // decoder written from the format's description: a lane's two dwords of low bytes and its dword of 4-bit table
-// indices, the tile's table of high bytes
-static std::vector<uint16_t> decode_p12(const std::vector<uint8_t>& comp, uint64_t blob_bytes) {
+// indices, the tile's table of high bytes (tables are stored stripe first inside a stripe group)
+static std::vector<uint16_t> decode_p12(const std::vector<uint8_t>& comp, uint64_t blob_bytes, int d, int d_ff) {
     const uint32_t n_tiles = (uint32_t)(blob_bytes / 1024);
     const P12Layout lay = p12_layout(n_tiles);
     std::vector<uint16_t> out(blob_bytes / 2);
     for (uint32_t t = 0; t < n_tiles; ++t) {
-        const uint8_t* table = comp.data() + lay.off_table + (uint64_t)t * kP12TableBytes;
+        const uint8_t* table = comp.data() + lay.off_table + (uint64_t)p12_table_slot(t, d, d_ff) * kP12TableBytes;
         for (int l = 0; l < 64; ++l) {
             uint8_t w[12];
             memcpy(w, comp.data() + lay.off_payload + (uint64_t)t * kP12TileBytes + l * 12, 12);
@@ -74,22 +74,22 @@ int main() {
     const uint64_t comp_bytes = p12_layout(blob_bytes / 1024).bytes;
     for (int e = 0; e < E; ++e) {
         std::vector<uint8_t> comp(comp_bytes);
-        compress_expert_blob(blob_bytes, blobs.data() + e * blob_elems, comp.data());
+        compress_expert_blob(d, d_ff, blobs.data() + e * blob_elems, comp.data());
         const P12Header* h = reinterpret_cast<const P12Header*>(comp.data());
         CHECK(h->magic == kP12Magic && h->raw == 0 && h->n_tiles == blob_bytes / 1024);
-        const std::vector<uint16_t> back = decode_p12(comp, blob_bytes);
+        const std::vector<uint16_t> back = decode_p12(comp, blob_bytes, d, d_ff);
         CHECK(memcmp(back.data(), blobs.data() + e * blob_elems, blob_bytes) == 0);
         std::vector<uint16_t> again(blob_elems, 0xAAAA);
-        CHECK(decompress_expert_blob(blob_bytes, comp.data(), again.data()));
+        CHECK(decompress_expert_blob(d, d_ff, comp.data(), again.data()));
         CHECK(memcmp(again.data(), blobs.data() + e * blob_elems, blob_bytes) == 0);
     }
     {
         std::vector<uint16_t> noise(blob_elems);
         for (auto& v : noise) v = (uint16_t)next_u32();
         std::vector<uint8_t> comp(comp_bytes);
-        compress_expert_blob(blob_bytes, noise.data(), comp.data());
+        compress_expert_blob(d, d_ff, noise.data(), comp.data());
         CHECK(reinterpret_cast<const P12Header*>(comp.data())->raw == 1);
-        CHECK(!decompress_expert_blob(blob_bytes, comp.data(), noise.data()));
+        CHECK(!decompress_expert_blob(d, d_ff, comp.data(), noise.data()));
     }
     // one expert on the calling thread against plain loops
     std::vector<uint16_t> x((size_t)n_tokens * d);

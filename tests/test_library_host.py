@@ -143,15 +143,34 @@ def test_host_miss_path_matches_the_oracle(tb, n_tokens, n_experts, k, threads, 
     assert ei.value.code == tb.TIDE_E_INVAL and np.array_equal(again, base)
 
 
-def _p12_decode(comp: np.ndarray, n_tiles: int) -> np.ndarray:
+def _p12_table_slots(d: int, I: int) -> np.ndarray:
+    """Table slot of every payload tile: payloads are ordered K chunk first inside a stripe group of the packed layout
+    (8 SwiGLU column blocks = up to 16 gate / up stripes; 16 down stripes), tables stripe first."""
+    slots = []
+    at = 0
+    for stripes_total, per_group, chunks in ((2 * (I // 16), 16, d // 32), (d // 16, 16, I // 32)):
+        done = 0
+        while done < stripes_total:
+            w = min(per_group, stripes_total - done)
+            for c in range(chunks):
+                for j in range(w):
+                    slots.append(at + j * chunks + c)
+            at += w * chunks
+            done += w
+    return np.asarray(slots, dtype=np.int64)
+
+
+def _p12_decode(comp: np.ndarray, n_tiles: int, d: int, I: int) -> np.ndarray:
     """Decoder written from the format's description in include/tide.h and csrc/packed12.h, independent of the
     library: a 128-byte header; per tile 64 lanes x 3 dwords (the low bytes of the lane's elements 0..3 and 4..7, then one byte
-    per element pair j, 4+j holding their two 4-bit table indices); per tile a table of 16 high bytes."""
+    per element pair j, 4+j holding their two 4-bit table indices); per tile a table of 16 high bytes, stored stripe first."""
     hdr = comp[:64].view(np.uint32)
     assert hdr[0] == 0x32315054 and hdr[1] == n_tiles and hdr[2] == 0
     off_table = 128 + n_tiles * 768
     words = comp[128:off_table].view(np.uint32).reshape(n_tiles, 64, 3).astype(np.int64)
-    table = comp[off_table:off_table + 16 * n_tiles].reshape(n_tiles, 16).astype(np.int64)
+    slots = _p12_table_slots(d, I)
+    assert len(slots) == n_tiles and len(set(slots.tolist())) == n_tiles
+    table = comp[off_table:off_table + 16 * n_tiles].reshape(n_tiles, 16).astype(np.int64)[slots]
     vals = np.zeros((n_tiles, 64, 8), dtype=np.int64)
     for j in range(8):
         low = (words[:, :, j // 4] >> (8 * (j % 4))) & 0xff
@@ -164,7 +183,7 @@ def test_compressed_blob_round_trip(tb):
     """The 12-bit form is lossless: decoding it (here by hand, and with the library's own inverse) gives back the
     packed blob bit for bit -- for Gaussian weights, for weights with zeros / denormals / infinities / NaNs sprinkled
     in, for a tile that uses all 16 table entries -- and a blob with a tile of 17 distinct high bytes is marked raw."""
-    d, I = 256, 128
+    d, I = 320, 192          # partial gate/up and down groups (12 column blocks, 20 down stripes)
     cfg = tb.make_config(d, 8, 2, I, 0, 1, 4, 8, 0, 0)
     n_tiles = 3 * d * I // 512
     cbytes = tb.tide_compressed_blob_bytes(cfg)
@@ -178,7 +197,7 @@ def test_compressed_blob_round_trip(tb):
 
     def round_trip(src_u16):
         tb.tide_compress_expert(cfg, src_u16.view(np.uint8), comp)
-        assert np.array_equal(_p12_decode(comp, n_tiles), src_u16)
+        assert np.array_equal(_p12_decode(comp, n_tiles, d, I), src_u16)
         back[:] = 0xAA
         tb.tide_decompress_expert(cfg, comp, back)
         assert np.array_equal(back.view(np.uint16), src_u16)
