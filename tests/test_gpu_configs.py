@@ -350,13 +350,17 @@ def test_config2_interval_sweep():
 
 
 # ----------------------------------------------------------------------------- configuration 3
-def test_config3_flash_layer():
+@pytest.mark.parametrize("p12", [False, True], ids=["bf16 slots", "12-bit slots"])
+def test_config3_flash_layer(p12):
     """Flash-shaped layer, 512 tokens per step, the whole 32-step block.  Outputs on EVERY token at step 0 (cold
-    placement, most misses) and step 4 (first refresh), on 64 stratified tokens at every other step."""
+    placement, most misses) and step 4 (first refresh), on 64 stratified tokens at every other step.  Over bf16 slots
+    and over 12-bit slots (the form bench.py times this configuration in; large work items of up to 192 rows)."""
     wl = ti.CONFIGS[3]
     checks = {(0, t): ("all" if t in (0, 4) else 64) for t in range(wl.S)}
-    s = run_config("cfg3-flash-layer", wl, [0], {0}, checks)
+    s = run_config("cfg3-flash-layer" + (" 12-bit slots" if p12 else ""), wl, [0], {0}, checks, p12=p12)
     assert s["worst"] <= 1e-2
+    if p12:
+        return
     # the host-core miss path at this size (over a thousand missed pairs over most of the 192 non-resident experts)
     log, hidden = oracle_block(wl.replace(S=1), 0, [])
     bits = layer_bits(wl, 0)
