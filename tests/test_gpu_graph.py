@@ -16,9 +16,17 @@ LARGE = ti.TideWorkload("graph-large", d=320, E=8, k=2, I=192, n_shared=1, N=700
                         gating=ti.GATING_SIGMOID, bias_mode=ti.BIAS_NONE, seed=5)
 
 
+def _make(wl, p12):
+    from paper_2605_20179_amd.session import TideSession
+    if not p12:
+        return _session(wl)
+    return TideSession(wl.d, wl.E, wl.k, wl.I, wl.n_shared, wl.C, wl.N, wl.gating, wl.bias_mode, resident_p12=True)
+
+
+@pytest.mark.parametrize("p12", [False, True], ids=["bf16 slots", "12-bit slots"])
 @pytest.mark.parametrize("wl", [ti.CONFIGS[1].replace(S=4), LARGE], ids=["small-step", "large-step"])
-def test_step_replayed_from_a_graph(wl):
-    sess = _session(wl)
+def test_step_replayed_from_a_graph(wl, p12):
+    sess = _make(wl, p12)
     load(sess, wl, 0)
     hidden = [sess.to_device_bf16(h) for h in ti.hidden_stream(wl, 0, 4)]
     eager = []
@@ -54,7 +62,7 @@ def test_step_replayed_from_a_graph(wl):
         torch.cuda.synchronize()
         assert torch.equal(sess.out[:wl.N], eager[rep % 4][0])
     # every replay and every eager call counted its step: 3 rounds x 4 steps, plus steps 0, 1, 2 once more
-    fresh = _session(wl)
+    fresh = _make(wl, p12)
     load(fresh, wl, 0)
     for i in range(3):
         fresh.step(0, hidden[i])
