@@ -391,9 +391,9 @@ constexpr int kSmallRT0 = 2, kSmallD0 = 8;   // gate/up: weight stripes per wave
 constexpr int kSmallRT1 = 4, kSmallD1 = 4;   // down
 // The same for a context whose slots keep the 12-bit form (P12SLOTS): a 12-bit tile is 3 registers in the ring
 // instead of 4, and with a ring half as deep the gate/up kernel fits three waves per SIMD instead of two, which hides
-// some of the decode's latency (an LDS table read, then a chain of byte permutes): 34.4 -> 33.3 us on the 32-token
-// layer of 65 slots.  A deeper ring, or two stripes per wave in the down pass, measured no faster.  The bf16 cases of
-// this kernel (an expert stored raw) use the same parameters.
+// some of the decode's latency (an LDS table read, then a chain of byte permutes): about 1 us of the 33 the launch
+// took on the 32-token layer of 65 slots.  A deeper ring (8, or 8 in the down pass) and two stripes per wave in the
+// down pass measured slower.  The bf16 cases of this kernel (an expert stored raw) use the same parameters.
 constexpr int kP12RT0 = 2, kP12D0 = 4;
 constexpr int kP12RT1 = 4, kP12D1 = 4;
 template <int PASS, bool P12SLOTS>
