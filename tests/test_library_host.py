@@ -227,6 +227,26 @@ def test_compressed_blob_round_trip(tb):
     assert comp[:64].view(np.uint32)[2] == 1
 
 
+@pytest.mark.parametrize("d,I", [(64, 64), (128, 192), (192, 448), (512, 320), (1024, 128)])
+def test_compressed_blob_table_order_on_other_shapes(tb, d, I):
+    """Whole and partial stripe groups in both matrices: the tables' stripe-first order is a permutation of the tiles
+    and the hand decoder, which applies it, gives back the blob."""
+    cfg = tb.make_config(d, 4, 2, I, 0, 1, 2, 8, 0, 0)
+    n_tiles = 3 * d * I // 512
+    slots = _p12_table_slots(d, I)
+    assert sorted(slots.tolist()) == list(range(n_tiles))
+    rng = np.random.default_rng(d * 7 + I)
+    blob = (np.ascontiguousarray(rng.normal(0, 0.05, size=3 * d * I), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    comp = np.zeros(tb.tide_compressed_blob_bytes(cfg), dtype=np.uint8)
+    tb.tide_compress_expert(cfg, blob.view(np.uint8), comp)
+    if comp[:64].view(np.uint32)[2]:
+        pytest.skip("this draw has a tile with more than 16 distinct high bytes")
+    assert np.array_equal(_p12_decode(comp, n_tiles, d, I), blob)
+    back = np.zeros(blob.size * 2, dtype=np.uint8)
+    tb.tide_decompress_expert(cfg, comp, back)
+    assert np.array_equal(back.view(np.uint16), blob)
+
+
 def test_config_validation_and_no_device(tb):
     ok = dict(d=256, n_experts=16, top_k=2, d_ff=128, n_shared=0, n_layers=1, capacity=8, max_tokens=8, gating=0, bias_mode=0)
     blob = np.zeros(3 * 256 * 128 * 2, dtype=np.uint8)
