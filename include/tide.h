@@ -70,10 +70,13 @@ typedef struct {
 
 /* ---- set-up --------------------------------------------------------------------- */
 
-/* Allocates the context on the current HIP device: per layer `capacity` weight slots,
+/* Allocates the context on the current HIP device: per layer `capacity` weight slots
+ * (one packed bf16 blob each, whatever resident_format says they will hold),
  * the hit counter H[E] (zero), the placement tables (all slots empty), and one
  * workspace sized by max_tokens.  Creates two streams of default priority: one for
- * refresh copies, one on which a step's large work items run beside the small ones. */
+ * refresh copies, one on which a step's large work items run beside the small ones.
+ * resident_format: TIDE_RESIDENT_BF16 (0; a zeroed field means this) or TIDE_RESIDENT_P12,
+ * both described with tide_register_compressed below. */
 int tide_create(const tide_config* cfg, tide_ctx** out);
 int tide_destroy(tide_ctx* ctx);
 /* Text of the last error on ctx (ctx == NULL: last error of a failed tide_create). */
