@@ -45,6 +45,8 @@ extern "C" {
 #define TIDE_BIAS_NONE   0
 #define TIDE_BIAS_LOGIT  1     /* bias added to the router logit before the gate */
 #define TIDE_BIAS_SELECT 2     /* bias added to the gate score for selection only, not to the weights */
+#define TIDE_RESIDENT_BF16 0   /* a cache slot holds the expert's packed bf16 blob */
+#define TIDE_RESIDENT_P12  1   /* a cache slot holds the blob's lossless 12-bit form (tide_compress_expert) */
 
 typedef struct tide_ctx tide_ctx;
 
@@ -128,8 +130,6 @@ int tide_register_experts(tide_ctx* ctx, int layer, const void* host_blobs, uint
  *                               tide_register_experts.  With 12-bit slots the call also withdraws the layer's
  *                               placement (the slots were filled from the blobs registered before): call
  *                               tide_set_resident again before the next step or refresh. */
-#define TIDE_RESIDENT_BF16 0
-#define TIDE_RESIDENT_P12  1
 uint64_t tide_compressed_blob_bytes(const tide_config* cfg);
 int tide_compress_expert(const tide_config* cfg, const void* blob_host, void* comp_host);
 int tide_decompress_expert(const tide_config* cfg, const void* comp_host, void* blob_host);
