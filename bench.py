@@ -367,6 +367,8 @@ def run_all_configs(args, ti, tb, TideSession, torch, cfg1_entry, packed_mini, c
     c4 = ti.CONFIGS[4]
     out["4"], _ = layer(c4, packed_flash, 64, 8, args.refresh_source, comp=comp_flash)
     out["4"]["all_experts_resident"], _ = layer(c4.replace(C=c4.E), packed_flash, 16, 4, "raw")
+    # the same layer at batch 256 (8192 tokens per step): every large work item then holds 256 rows
+    out["4"]["batch_256"], _ = layer(c4.replace(N=8192), packed_flash, 32, 32, args.refresh_source, comp=comp_flash)
     torch.cuda.empty_cache()
     out["4"]["stack"] = stack(c4, packed_flash, 8, comp=comp_flash)
     out["4"]["stack_all_experts_resident"] = stack(c4.replace(C=c4.E), packed_flash, 4, refresh=False)
@@ -816,6 +818,12 @@ def main():
                                 "bound": "mfma", "mfma": c4["roofline"]["gate_up"]["mfma"], "hbm": c4["roofline"]["gate_up"]["hbm"],
                                 "avg_kernel_us": c4["roofline"]["gate_up"]["us"], "down_kernel": c4["roofline"]["down"],
                                 "step": c4["roofline"]["step"]}
+            b256 = c4.get("batch_256")
+            if b256 and b256.get("roofline"):
+                roofline["cfg4"]["batch_256"] = {"tokens_per_step": b256["tokens_per_step"], "tokens_per_s": b256["tokens_per_s"],
+                                                 "tokens_per_s_frozen_placement": b256["frozen_placement"]["tokens_per_s"],
+                                                 "mfma": b256["roofline"]["gate_up"]["mfma"], "hbm": b256["roofline"]["gate_up"]["hbm"],
+                                                 "avg_kernel_us": b256["roofline"]["gate_up"]["us"], "down_kernel": b256["roofline"]["down"]}
     out = {
         "metric": "MoE-layer tokens/s per denoise step", "value": value, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True,
