@@ -119,7 +119,9 @@ int tide_register_experts(tide_ctx* ctx, int layer, const void* host_blobs, uint
  *     (tide_set_resident, tide_set_shared, every refresh copy and tide_read_slot then move compressed
  *     blobs) and the expert GEMMs decode it in registers: the same outputs bit for bit from 3/4 of the
  *     HBM bytes.  It pays where a step is bound by the weight bytes (small token counts); a large work
- *     item then holds at most 192 rows instead of 256.
+ *     item then holds at most 192 rows instead of 256.  The shared expert's slot keeps the 12-bit form
+ *     only when max_tokens <= 64: it sees every token of a step, and work items of more than four
+ *     16-token tiles run faster from the bf16 blob (tide_read_slot returns whichever form the slot holds).
  *   tide_compressed_blob_bytes  size of one compressed blob (a multiple of 64)
  *   tide_compress_expert        host: packed blob (tide_pack_expert) -> compressed blob
  *   tide_decompress_expert      host: the inverse; TIDE_E_INVAL for a blob marked raw or of another configuration

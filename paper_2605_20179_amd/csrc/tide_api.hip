@@ -573,7 +573,9 @@ int tide_set_shared(tide_ctx* ctx, int layer, const void* blob_host) {
     if (ctx->shape.resident_p12) {
         comp.resize(tide_compressed_blob_bytes(&ctx->cfg));
         compress_expert_blob(ctx->cfg.d, ctx->cfg.d_ff, static_cast<const uint16_t*>(blob_host), comp.data());
-        const uint8_t is_p12 = reinterpret_cast<const P12Header*>(comp.data())->raw ? 0 : 1;
+        // every token of a step reaches the shared expert: in a context of many tokens per step its work items are the
+        // widest of the step, and those are faster over the bf16 blob
+        const uint8_t is_p12 = (reinterpret_cast<const P12Header*>(comp.data())->raw || ctx->cfg.max_tokens > kSharedP12MaxTokens) ? 0 : 1;
         if (is_p12) {
             src = comp.data();
             src_bytes = comp.size();

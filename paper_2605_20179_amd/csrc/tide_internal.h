@@ -16,6 +16,7 @@ constexpr int kMaxRouterSplits = 8;      // slices of the hidden dimension the r
 constexpr int kRowsPerTask = 32;        // rows of a small work item
 constexpr int kRowsPerBigTask = 256;    // rows of a large work item (the kernels' limit)
 constexpr int kRowsPerBigTaskP12 = 192; // the same when the slots hold the 12-bit form: the decode needs the registers of four token tiles
+constexpr int kSharedP12MaxTokens = 64; // 12-bit slots: the shared expert keeps the 12-bit form only in contexts of at most this many tokens per step (its work items then have at most four token tiles; wider ones run faster from bf16)
 constexpr int kMinBigUnits = 128;       // a step uses large work items only if they make at least this many gate/up workgroups (half the compute units)
 constexpr int kBigMinRows = 32;         // a slot with more rows than this is cut into large work items, else into small ones
 constexpr int kBigMinAvgRows = 48;      // steps with fewer rows per slot on average launch no large-item kernels at all

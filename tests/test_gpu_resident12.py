@@ -25,6 +25,7 @@ def _sessions(wl, expert_bits=None, max_tokens=None):
         if packed is None:
             packed = sess.pack_layer(bits, workers=8)
         sess.load_layer(0, None, ti.router_weights(wl, 0), ti.router_bias(wl, 0), ti.initial_resident(wl), packed=packed)
+        sess.shared_blob = packed[1]
         pair.append(sess)
     return pair
 
@@ -45,6 +46,16 @@ def _check_slots(sess, eis):
             raw_experts.append(e)
         else:
             assert np.array_equal(got[:comp_bytes], comp[e]), "slot %d: compressed blob of expert %d" % (s, e)
+    if sess.n_shared:
+        # the shared expert's slot: the 12-bit form in a context of at most 64 tokens per step, else the bf16 blob
+        got = sess.read_slot(0, sess.C)
+        if sess.max_tokens <= 64:
+            want = np.empty(comp_bytes, dtype=np.uint8)
+            tb.tide_compress_expert(sess.cfg, sess.shared_blob, want)
+            assert not want[:64].view(np.uint32)[2]
+            assert np.array_equal(got[:comp_bytes], want), "shared expert's slot: its compressed blob"
+        else:
+            assert np.array_equal(got, sess.shared_blob), "shared expert's slot: its bf16 blob"
     return raw_experts
 
 
