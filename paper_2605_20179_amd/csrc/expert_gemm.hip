@@ -176,6 +176,9 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
     // 12-bit form: the tables of the wave's next kTableChunks chunks (64 tiles: one per lane) come through a piece of
     // LDS that only this wave touches -- one 16-byte load per lane a block ahead, one store at the block's start, and
     // a broadcast read per tile when it is decoded.  A wave's LDS accesses complete in order: no barrier is needed.
+    // Large items (kAhead) decode a chunk while the MFMAs of the chunk before it run: the decode of a block's first
+    // chunk then falls into the block before, so their table blocks alternate between two buffers.
+    constexpr bool kAhead = FMT == kFmtP12 && NBUF == 2;
     constexpr int kTableChunks = 64 / RT;
     static_assert(FMT == kFmtBf16 || (kTableChunks % D == 0 && D <= kTableChunks), "table blocks start on whole ring turns");
     const uint8_t* table0 = reinterpret_cast<const uint8_t*>(blob) + kP12HeaderBytes + (blob_elems / kTileElems) * kP12TileBytes;
@@ -185,9 +188,12 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
         const int t = ws.table_first + ((PASS == 0 && r >= G) ? ws.up + (r - G) : r) * kchunks + c;
         next_tables = *reinterpret_cast<const uint4*>(table0 + (int64_t)t * kP12TableBytes);
     };
-    auto table_block = [&](int block) {               // at the first chunk of a block
-        wave_tables[lane] = next_tables;
+    auto table_block = [&](int block) {               // before the first decode of a block's chunks
+        wave_tables[(kAhead ? (block & 1) * 64 : 0) + lane] = next_tables;
         fetch_tables(block + 1);
+    };
+    auto table_of = [&](int c, int r) {
+        return wave_tables[(kAhead ? ((c / kTableChunks) & 1) * 64 : 0) + (c % kTableChunks) * RT + r];
     };
     if (FMT == kFmtP12) fetch_tables(0);
 
@@ -255,7 +261,7 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
 #pragma unroll
         for (int r = 0; r < RT; ++r) {
             uint4 table{};
-            if (FMT == kFmtP12) table = wave_tables[(c % kTableChunks) * RT + r];
+            if (FMT == kFmtP12) table = table_of(c, r);
             const bf16x8 w = mfma_operand(a[i][r], table);
 #pragma unroll
             for (int t = 0; t < decltype(cnt)::value; ++t)
@@ -312,6 +318,17 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
         static_assert(PC % D == 0 || D % PC == 0, "stage boundaries must fall on whole chunks of a ring turn");
         using half_tiles = std::integral_constant<int, NTH>;
         bf16x8 b[2][NTH];
+        // kAhead: the decoded operands of this chunk and of the next.  A chunk's tiles are decoded, a stripe or two per
+        // half set, between the MFMAs of the chunk before it (a wave that keeps this many accumulators is alone on
+        // its SIMD: whatever it issues beside an MFMA in flight is free, whatever it issues between two costs), and
+        // the ring slot they came from is refilled at once.
+        bf16x8 wdec[kAhead ? 2 : 1][RT];
+        if constexpr (kAhead) {
+            table_block(0);
+#pragma unroll
+            for (int r = 0; r < RT; ++r) wdec[0][r] = mfma_operand(a[0][r], table_of(0, r));
+            refill(0, 0);
+        }
         __syncthreads();                             // stage 0 is complete
         read_frags(b[0], 0, 0, half_tiles{});
         auto chunk = [&](int c, int i) {
@@ -334,19 +351,48 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
                     read_frags(b[q ^ 1], c, NTH, half_tiles{});
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                mfmas(b[q], c, i, h * NTH, half_tiles{});
-                if (h == NH - 1) refill(c, i);
+                if constexpr (kAhead) {
+                    constexpr int RH = RT / NH;              // stripes of the next chunk decoded under this half set
+                    static_assert(RT % NH == 0, "the next chunk's stripes divide over the half sets");
+                    const int cn = min(c + 1, kchunks - 1), in = (i + 1) % D;
+#pragma unroll
+                    for (int r = 0; r < RT; ++r)
+#pragma unroll
+                        for (int t = 0; t < NTH; ++t)
+                            acc[r][h * NTH + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wdec[i & 1][r], b[q][t], acc[r][h * NTH + t], 0, 0, 0);
+#pragma unroll
+                    for (int r = h * RH; r < (h + 1) * RH; ++r) wdec[(i + 1) & 1][r] = mfma_operand(a[in][r], table_of(cn, r));
+                    if (h == NH - 1) refill(c + 1, in);
+                    // the order asked of the scheduler: the table reads first, then every MFMA followed by its share
+                    // of the decode's vector instructions
+                    constexpr int kMfmas = RT * NTH, kPerMfma = (RH * 20 + kMfmas - 1) / kMfmas;
+                    __builtin_amdgcn_sched_group_barrier(0x100, RH, 0);
+#pragma unroll
+                    for (int m = 0; m < kMfmas; ++m) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, kPerMfma, 0);
+                    }
+                } else {
+                    mfmas(b[q], c, i, h * NTH, half_tiles{});
+                    if (h == NH - 1) refill(c, i);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
+        // a table block is put in place at the top of the ring turn in which its first chunk is decoded: the turn
+        // that begins with it, or (kAhead) the turn before
+        auto tables_for_turn = [&](int base) {
+            const int first = kAhead ? base + D : base;
+            if (FMT == kFmtP12 && first % kTableChunks == 0) table_block(first / kTableChunks);
+        };
         int base = 0;
         for (; base + D <= kchunks; base += D) {
-            if (FMT == kFmtP12 && base % kTableChunks == 0) table_block(base / kTableChunks);
+            tables_for_turn(base);
 #pragma unroll
             for (int i = 0; i < D; ++i) chunk(base + i, i);
         }
         if (base < kchunks) {
-            if (FMT == kFmtP12 && base % kTableChunks == 0) table_block(base / kTableChunks);
+            tables_for_turn(base);
 #pragma unroll
             for (int i = 0; i < D; ++i)
                 if (base + i < kchunks) chunk(base + i, i);
@@ -499,7 +545,7 @@ __global__ __launch_bounds__(kWaves * 64) void expert_gemm_big_kernel(
     float* __restrict__ y_out, int n_ftiles) {
     constexpr int RT = 4;
     __shared__ __attribute__((aligned(16))) uint16_t lds[kBigLdsElems];
-    __shared__ uint4 tables[kWaves][64];               // 12-bit slots: each wave's tile tables
+    __shared__ uint4 tables[kWaves][2 * 64];           // 12-bit slots: each wave's tile tables, two blocks of them
     const int n_big = n_tasks[1];
     const int xcd = blockIdx.x % kXcds, unit = blockIdx.x / kXcds;
     if (unit >= list_tasks(xcd, n_big) * n_ftiles) return;
