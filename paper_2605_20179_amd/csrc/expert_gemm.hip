@@ -193,7 +193,8 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
         fetch_tables(block + 1);
     };
     auto table_of = [&](int c, int r) {
-        return wave_tables[(kAhead ? ((c / kTableChunks) & 1) * 64 : 0) + (c % kTableChunks) * RT + r];
+        const unsigned cu = (unsigned)c;              // chunk indices are never negative: unsigned / and % are a shift and a mask
+        return wave_tables[(kAhead ? ((cu / kTableChunks) & 1) * 64 : 0) + (cu % kTableChunks) * RT + r];
     };
     if (FMT == kFmtP12) fetch_tables(0);
 
@@ -251,9 +252,11 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
     const uint16_t* frag = lds + (lane & 15) * kRowElems + (lane >> 4) * 8;
     // fragments of token tiles t0 .. t0+CNT-1 for chunk c
     auto read_frags = [&](bf16x8* b, int c, int t0, auto cnt) {
+        const unsigned cu = (unsigned)c;
+        const uint16_t* from = frag + (NBUF == 2 ? ((cu / PC) & 1) * kBufElems : 0) + (cu % PC) * 32;
 #pragma unroll
         for (int t = 0; t < decltype(cnt)::value; ++t)
-            b[t] = *reinterpret_cast<const bf16x8*>(frag + (NBUF == 2 ? ((c / PC) & 1) * kBufElems : 0) + (t0 + t) * 16 * kRowElems + (c % PC) * 32);
+            b[t] = *reinterpret_cast<const bf16x8*>(from + (t0 + t) * 16 * kRowElems);
     };
     // chunk c (ring slot i) against token tiles t0 ..: a stripe's operand is the ring's word as it is, or is decoded
     // with the tile's table right before the stripe's MFMAs (the decode of the next stripe runs under them)
@@ -332,10 +335,10 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
         __syncthreads();                             // stage 0 is complete
         read_frags(b[0], 0, 0, half_tiles{});
         auto chunk = [&](int c, int i) {
-            if (c % PC == 0) {
+            if ((unsigned)c % PC == 0) {
                 // no branches in the loop body: past the last stage this stores a stage nobody reads into
                 // the buffer that is free, and fetches the last stage once more
-                const int stage = c / PC;
+                const int stage = (unsigned)c / PC;
                 store_stage((stage + 1) & 1);
                 fetch_stage(min(stage + 2, last_stage));
             }
@@ -345,7 +348,7 @@ __device__ inline void gemm_task(const uint16_t* blob, int64_t off_w, int wtile,
             for (int h = 0; h < NH; ++h) {
                 const int q = NH == 2 ? h : (i & 1);     // parity of this step
                 if (h == NH - 1) {
-                    if (c % PC == PC - 1) __syncthreads();
+                    if ((unsigned)c % PC == PC - 1) __syncthreads();
                     read_frags(b[q ^ 1], min(c + 1, kchunks - 1), 0, half_tiles{});
                 } else {
                     read_frags(b[q ^ 1], c, NTH, half_tiles{});
