@@ -19,7 +19,10 @@ constexpr int kRowsPerBigTaskP12 = 192; // the same when the slots hold the 12-b
 constexpr int kSharedP12MaxTokens = 64; // 12-bit slots: the shared expert keeps the 12-bit form only in contexts of at most this many tokens per step (its work items then have at most four token tiles; wider ones run faster from bf16)
 constexpr int kMinBigUnits = 128;       // a step uses large work items only if they make at least this many gate/up workgroups (half the compute units)
 constexpr int kBigMinRows = 32;         // a slot with more rows than this is cut into large work items, else into small ones
-constexpr int kBigMinAvgRows = 48;      // steps with fewer rows per slot on average launch no large-item kernels at all
+// Steps with fewer rows per slot on average launch no large-item kernels at all.  A large unit streams 256 weight rows
+// of length d: the shorter they are, the more of the unit is its fixed start and end, and the more rows it takes for
+// large items to pay (measured: from about 48 rows per slot at d = 4096, about 128 at d = 2048).
+constexpr int kBigMinAvgRows = 48, kBigMinAvgRowsShort = 96, kLongRow = 4096;
 
 // running totals (tide_counters): integer adds, so their order does not matter
 __device__ inline void bump(int64_t* counter, int64_t by) {
@@ -91,6 +94,7 @@ struct Shape {
     int big_rows;             // most rows of a large work item: kRowsPerBigTask or kRowsPerBigTaskP12
     int resident_p12;         // the cache slots hold the 12-bit form of the blobs (packed12.h)
 };
+inline int big_min_avg_rows(const Shape& s) { return s.d >= kLongRow ? kBigMinAvgRows : kBigMinAvgRowsShort; }
 
 // a1: z[n][e] = <x_n, W_r[e]>  (fp32)
 hipError_t launch_router_logits(const Shape& s, const uint16_t* x, int n_tokens, const float* w_r,
@@ -133,7 +137,7 @@ inline int max_big_tasks_for(const Shape& s, int n_tokens) {
     // large-item kernels would mostly be launched for nothing (their idle workgroups each take a compute unit's LDS
     // for a moment: 135 -> 123 us per step at 256 tokens x top-8 over 65 slots): nothing to launch, and the split
     // kernel, told so, cuts every slot into small items
-    if ((int64_t)most * ((s.I + 127) / 128) < kMinBigUnits || rows < kBigMinAvgRows * slots) return 0;
+    if ((int64_t)most * ((s.I + 127) / 128) < kMinBigUnits || rows < big_min_avg_rows(s) * slots) return 0;
     return most;
 }
 // upper bound of the number of small work items
@@ -148,7 +152,7 @@ inline int max_miss_big_tasks_for(const Shape& s, int n_tokens) {
     const int rows = n_tokens * s.k;
     const int busy = rows / (kBigMinRows + 1);
     const int most = rows / s.big_rows + (busy < s.E ? busy : s.E);
-    if ((int64_t)most * ((s.I + 127) / 128) < kMinBigUnits || rows < kBigMinAvgRows * s.E) return 0;
+    if ((int64_t)most * ((s.I + 127) / 128) < kMinBigUnits || rows < big_min_avg_rows(s) * s.E) return 0;
     return most;
 }
 // miss pass (the step's misses evaluated from the host-resident blobs; entries that name an expert outside [0,E)
