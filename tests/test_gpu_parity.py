@@ -417,3 +417,38 @@ def test_exactly_equal_scores_go_to_the_lower_expert_id(n_tokens, n_experts, k, 
     say("ties: %d tokens x top-%d of %d, %d family/token pairs cut by the boundary, %d near-tie flips elsewhere"
         % (wl.N, wl.k, wl.E, hit_families, len(flips)))
     sess.close()
+
+
+@pytest.mark.parametrize("d,n_tokens,large", [(2048, 512, False), (2048, 768, True), (4096, 512, True), (4096, 256, False)])
+def test_where_large_work_items_start(d, n_tokens, large):
+    """A step uses large work items from 48 rows per slot on average when the weight rows hold 4096 elements and from
+    96 when they are shorter (32 slots here, shared expert included, and 5 rows per token: 80 rows per slot at 512
+    tokens, 120 at 768, 40 at 256).  Every expert shares one blob: only the split is looked at."""
+    from paper_2605_20179_amd import binding as tb
+    from paper_2605_20179_amd.session import TideSession
+    say("large work items at d=%d, %d tokens" % (d, n_tokens))
+    E, C, k, I = 64, 31, 4, 512
+    wl = ti.TideWorkload("split-%d" % d, d=d, E=E, k=k, I=I, n_shared=1, N=n_tokens, S=1, K=1, C=C, L=1,
+                         gating=ti.GATING_SOFTMAX, bias_mode=ti.BIAS_NONE, seed=99)
+    sess = TideSession(d, E, k, I, 1, C, n_tokens, wl.gating, wl.bias_mode)
+    one = np.empty(sess.blob_bytes, dtype=np.uint8)
+    tb.tide_pack_expert(sess.cfg, *ti.expert_weights(wl, 0, 0), one)
+    blobs = torch.empty((E, sess.blob_bytes), dtype=torch.uint8, pin_memory=True)
+    blobs[:] = torch.from_numpy(one)
+    sess.load_layer(0, None, ti.router_weights(wl, 0), None, ti.initial_resident(wl), packed=(blobs, one))
+    rng = np.random.default_rng(3)
+    # every pair goes to a resident expert: 4 distinct ones per token
+    idx = np.stack([rng.choice(C, size=k, replace=False) for _ in range(n_tokens)]).astype(np.int32)
+    w = np.full((n_tokens, k), 1.0 / k, dtype=np.float32)
+    x = sess.to_device_bf16(next(iter(ti.hidden_stream(wl, 0))))
+    sess.step_routed(0, x, torch.from_numpy(idx).to(sess.device), torch.from_numpy(w).to(sess.device))
+    items, _ = tb.tide_read_work_items(sess.ctx, 4096, 65536, torch.cuda.current_stream())
+    kinds = {int(it["kind"]) for it in items}
+    rows = sum(int(it["nrows"]) for it in items)
+    assert rows == n_tokens * (k + 1)
+    if large:
+        assert 1 in kinds, "no large work items"
+        assert all(int(it["nrows"]) > 32 for it in items if it["kind"] == 1)
+    else:
+        assert kinds == {0}, "large work items in a step with few rows per slot"
+    sess.close()
