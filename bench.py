@@ -57,15 +57,17 @@ def cpu_baseline(wl, ti, sample_steps=None):
 
 
 # --resident: the form the cache slots keep the blobs in (set per workload, read by every session made here).
-# "auto": the 12-bit form where a step is bound by the weight bytes it streams (up to 512 tokens at these shapes: a
-# slot sees a handful to a few dozen rows), bf16 blobs where the large-item kernels do most of the work (the decode costs
+# "auto": the 12-bit form where a step is bound by the weight bytes it streams (up to 768 tokens at d = 4096, up to 1024 at d = 2048: a
+# slot sees a handful to a hundred rows), bf16 blobs where the large-item kernels do most of the work (the decode costs
 # them more than the bytes it saves, and a 12-bit large item is capped at 192 rows).
 RESIDENT_P12 = False
 
 
 def resident_p12_for(args, wl):
     policy = getattr(args, "resident_policy", args.resident)
-    return policy == "p12" or (policy == "auto" and wl.N <= 512)
+    # auto: the 12-bit form where it measured faster -- steps of up to 768 tokens, up to 1024 for layers whose steps
+    # of that size still run as small work items only (weight rows shorter than 4096)
+    return policy == "p12" or (policy == "auto" and wl.N <= (768 if wl.d >= 4096 else 1024))
 
 
 def choose_resident(args, wl):
@@ -464,7 +466,7 @@ def main():
     ap.add_argument("--resident", choices=("auto", "bf16", "p12"), default="auto",
                     help="the form a cache slot keeps its blob in: the bf16 blob, or its lossless 12-bit form decoded by the "
                          "expert GEMMs in registers (3/4 of the HBM bytes per step; refresh copies then move compressed blobs); "
-                         "auto = 12-bit for steps of up to 512 tokens")
+                         "auto = 12-bit for steps of up to 768 tokens (1024 when d < 4096)")
     ap.add_argument("--refresh-source", choices=("raw", "packed12"), default="packed12",
                     help="what the refresh copies read over the host link: the raw blobs, or their lossless 12-bit form "
                          "(3/4 of the bytes; slots bit-identical)")

@@ -21,8 +21,8 @@ constexpr int kMinBigUnits = 128;       // a step uses large work items only if 
 constexpr int kBigMinRows = 32;         // a slot with more rows than this is cut into large work items, else into small ones
 // Steps with fewer rows per slot on average launch no large-item kernels at all.  A large unit streams 256 weight rows
 // of length d: the shorter they are, the more of the unit is its fixed start and end, and the more rows it takes for
-// large items to pay (measured: from about 48 rows per slot at d = 4096, about 128 at d = 2048).
-constexpr int kBigMinAvgRows = 48, kBigMinAvgRowsShort = 96, kLongRow = 4096;
+// large items to pay (measured: from about 48 rows per slot at d = 4096, about 150 at d = 2048).
+constexpr int kBigMinAvgRows = 48, kBigMinAvgRowsShort = 144, kLongRow = 4096;
 
 // running totals (tide_counters): integer adds, so their order does not matter
 __device__ inline void bump(int64_t* counter, int64_t by) {

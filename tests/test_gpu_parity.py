@@ -419,11 +419,11 @@ def test_exactly_equal_scores_go_to_the_lower_expert_id(n_tokens, n_experts, k, 
     sess.close()
 
 
-@pytest.mark.parametrize("d,n_tokens,large", [(2048, 512, False), (2048, 768, True), (4096, 512, True), (4096, 256, False)])
+@pytest.mark.parametrize("d,n_tokens,large", [(2048, 768, False), (2048, 1024, True), (4096, 512, True), (4096, 256, False)])
 def test_where_large_work_items_start(d, n_tokens, large):
     """A step uses large work items from 48 rows per slot on average when the weight rows hold 4096 elements and from
-    96 when they are shorter (32 slots here, shared expert included, and 5 rows per token: 80 rows per slot at 512
-    tokens, 120 at 768, 40 at 256).  Every expert shares one blob: only the split is looked at."""
+    144 when they are shorter (32 slots here, shared expert included, and 5 rows per token: 40 rows per slot at 256
+    tokens, 80 at 512, 120 at 768, 160 at 1024).  Every expert shares one blob: only the split is looked at."""
     from paper_2605_20179_amd import binding as tb
     from paper_2605_20179_amd.session import TideSession
     say("large work items at d=%d, %d tokens" % (d, n_tokens))
